@@ -1,0 +1,18 @@
+"""fp64 CPU oracle for AdaS-Attn -- test infrastructure only.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package.  It imports nothing from the HIP package.
+"""
+from .adaspark_oracle import (  # noqa: F401
+    Shape,
+    build,
+    num_cubes,
+    cube_map,
+    cube_pool,
+    relevance,
+    top_p,
+    cube_select,
+    sparse_attn,
+    dense_attn,
+    num_threads,
+)

@@ -1,0 +1,202 @@
+"""ctypes front end of the fp64 C oracle (``adaspark_oracle.c``).
+
+TEST INFRASTRUCTURE, NOT PRODUCT CODE: argument marshalling only, every number
+is produced by the C file next to this one.  Arrays are numpy; bf16 tensors are
+passed as their uint16 bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "adaspark_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+class _CShape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in ("T", "H", "W", "ct", "ch", "cw", "Hq", "Hkv", "D")]
+
+
+@dataclass(frozen=True)
+class Shape:
+    """Token grid (frames, height, width), cube shape and head geometry."""
+
+    T: int
+    H: int
+    W: int
+    ct: int
+    ch: int
+    cw: int
+    Hq: int
+    Hkv: int
+    D: int
+
+    @property
+    def S(self) -> int:
+        return self.T * self.H * self.W
+
+    def _c(self) -> _CShape:
+        return _CShape(self.T, self.H, self.W, self.ct, self.ch, self.cw, self.Hq, self.Hkv, self.D)
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (fp64, OpenMP over rows, no fast-math)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"]
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.oracle_num_cubes.restype = ctypes.c_int
+        _lib.oracle_top_p.restype = ctypes.c_int
+    return _lib
+
+
+def _p(a, typ):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(typ))
+
+
+def _u16(a) -> np.ndarray:
+    """bf16 torch tensor or uint16 array -> contiguous uint16 numpy array."""
+    if isinstance(a, np.ndarray):
+        assert a.dtype == np.uint16
+        return np.ascontiguousarray(a)
+    import torch  # only to view a CPU bf16 tensor's bits
+
+    assert a.dtype == torch.bfloat16 and a.device.type == "cpu"
+    return a.contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def num_threads() -> int:
+    """Threads the OpenMP loops will use (OMP_NUM_THREADS or the affinity mask)."""
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env:
+        try:
+            return max(1, int(env.split(",")[0]))
+        except ValueError:
+            pass
+    return len(os.sched_getaffinity(0))
+
+
+def num_cubes(shape: Shape) -> int:
+    cs = shape._c()
+    return int(_load().oracle_num_cubes(ctypes.byref(cs)))
+
+
+def cube_map(shape: Shape):
+    """-> (cube_of[S], rank_of[S], size_of[N], start[N+1])  (Sec. 3.1)."""
+    lib, cs, N = _load(), shape._c(), num_cubes(shape)
+    cube_of = np.empty(shape.S, np.int32)
+    rank_of = np.empty(shape.S, np.int32)
+    size_of = np.empty(N, np.int32)
+    start = np.empty(N + 1, np.int64)
+    lib.oracle_cube_map(ctypes.byref(cs), _p(cube_of, ctypes.c_int32), _p(rank_of, ctypes.c_int32),
+                        _p(size_of, ctypes.c_int32), _p(start, ctypes.c_int64))
+    return cube_of, rank_of, size_of, start
+
+
+def cube_pool(shape: Shape, K) -> np.ndarray:
+    """Mean key per (cube, KV head): fp64 [N, Hkv, D]  (Eq. 1)."""
+    lib, cs, N = _load(), shape._c(), num_cubes(shape)
+    k = _u16(K)
+    assert k.size == shape.S * shape.Hkv * shape.D
+    kbar = np.empty((N, shape.Hkv, shape.D), np.float64)
+    lib.oracle_cube_pool(ctypes.byref(cs), _p(k, ctypes.c_uint16), _p(kbar, ctypes.c_double))
+    return kbar
+
+
+def relevance(q: np.ndarray, kbar_rows: np.ndarray):
+    """One row's logits and softmax over the given mean keys [n, D]  (Eq. 1)."""
+    lib = _load()
+    q = np.ascontiguousarray(q, np.float64)
+    kb = np.ascontiguousarray(kbar_rows, np.float64)
+    n, D = kb.shape
+    logits = np.empty(n, np.float64)
+    probs = np.empty(n, np.float64)
+    lib.oracle_relevance(_p(q, ctypes.c_double), _p(kb, ctypes.c_double), ctypes.c_int64(D),
+                         ctypes.c_int(n), ctypes.c_int(D), _p(logits, ctypes.c_double), _p(probs, ctypes.c_double))
+    return logits, probs
+
+
+def top_p(probs: np.ndarray, p: float):
+    """Nucleus rule on one distribution -> (keep[n] bool, order[n], cum[n])  (Eq. 2)."""
+    lib = _load()
+    pr = np.ascontiguousarray(probs, np.float64)
+    n = pr.size
+    keep = np.zeros(n, np.uint8)
+    order = np.zeros(n, np.int32)
+    cum = np.zeros(n, np.float64)
+    lib.oracle_top_p(_p(pr, ctypes.c_double), ctypes.c_int(n), ctypes.c_double(p), _p(keep, ctypes.c_uint8),
+                     _p(order, ctypes.c_int32), _p(cum, ctypes.c_double))
+    return keep.astype(bool), order, cum
+
+
+def _rows(rows):
+    if rows is None:
+        return None
+    return np.ascontiguousarray(rows, np.int64)
+
+
+def cube_select(shape: Shape, Q, kbar: np.ndarray, p: float, rows=None, eps: float = 1e-5):
+    """Selection for the given rows (all if None).
+
+    -> (sel_mask uint32 [nrows, ceil(N/32)], sel_count int32 [nrows], near_cut bool [nrows])
+    """
+    lib, cs, N = _load(), shape._c(), num_cubes(shape)
+    q = _u16(Q)
+    assert q.size == shape.S * shape.Hq * shape.D
+    kb = np.ascontiguousarray(kbar, np.float64)
+    assert kb.shape == (N, shape.Hkv, shape.D)
+    r = _rows(rows)
+    nrows = shape.S * shape.Hq if r is None else r.size
+    words = (N + 31) // 32
+    mask = np.zeros((nrows, words), np.uint32)
+    count = np.zeros(nrows, np.int32)
+    near = np.zeros(nrows, np.uint8)
+    lib.oracle_cube_select(ctypes.byref(cs), _p(q, ctypes.c_uint16), _p(kb, ctypes.c_double), ctypes.c_double(p),
+                           _p(r, ctypes.c_int64), ctypes.c_int64(nrows), _p(mask, ctypes.c_uint32),
+                           _p(count, ctypes.c_int32), _p(near, ctypes.c_uint8), ctypes.c_double(eps))
+    return mask, count, near.astype(bool)
+
+
+def sparse_attn(shape: Shape, Q, K, V, sel_mask: np.ndarray, rows=None):
+    """Eq. 3 on the given rows -> (out fp64 [nrows, D], n_keys int64 [nrows])."""
+    lib, cs, N = _load(), shape._c(), num_cubes(shape)
+    q, k, v = _u16(Q), _u16(K), _u16(V)
+    r = _rows(rows)
+    nrows = shape.S * shape.Hq if r is None else r.size
+    words = (N + 31) // 32
+    m = np.ascontiguousarray(sel_mask, np.uint32)
+    assert m.shape == (nrows, words)
+    out = np.empty((nrows, shape.D), np.float64)
+    nk = np.empty(nrows, np.int64)
+    lib.oracle_sparse_attn(ctypes.byref(cs), _p(q, ctypes.c_uint16), _p(k, ctypes.c_uint16), _p(v, ctypes.c_uint16),
+                           _p(r, ctypes.c_int64), ctypes.c_int64(nrows), _p(m, ctypes.c_uint32),
+                           _p(out, ctypes.c_double), _p(nk, ctypes.c_int64))
+    return out, nk
+
+
+def dense_attn(shape: Shape, Q, K, V, rows=None) -> np.ndarray:
+    """Causal attention in cube-major order on the given rows -> fp64 [nrows, D]."""
+    lib, cs = _load(), shape._c()
+    q, k, v = _u16(Q), _u16(K), _u16(V)
+    r = _rows(rows)
+    nrows = shape.S * shape.Hq if r is None else r.size
+    out = np.empty((nrows, shape.D), np.float64)
+    lib.oracle_dense_attn(ctypes.byref(cs), _p(q, ctypes.c_uint16), _p(k, ctypes.c_uint16), _p(v, ctypes.c_uint16),
+                          _p(r, ctypes.c_int64), ctypes.c_int64(nrows), _p(out, ctypes.c_double))
+    return out

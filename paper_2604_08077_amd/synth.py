@@ -1,0 +1,120 @@
+"""Seeded synthetic workloads (shapes and value distributions only).
+
+This module serves both the HIP path and the CPU oracle and therefore holds
+none of the method's arithmetic: no pooling, scoring, selection or attention,
+and no token->cube index function.  The per-cube key mean is laid onto the
+token grid by repeating a [cubes_t, cubes_h, cubes_w] field along each axis and
+cropping it to the grid.
+
+All tensors are drawn in fp32 on the CPU with ``torch.Generator`` and rounded to
+bf16 once; the bf16 buffers are the single source of truth for both sides.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Tuple
+
+import torch
+
+BASE_SEED = 20260408
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    config_id: int
+    T: int
+    H: int
+    W: int
+    ct: int
+    ch: int
+    cw: int
+    Hq: int
+    Hkv: int
+    D: int
+    top_p: Tuple[float, ...]
+    # scale of the per-cube key mean, one entry per KV head
+    k_mean_scale: Tuple[float, ...]
+
+    @property
+    def S(self) -> int:
+        return self.T * self.H * self.W
+
+    @property
+    def grid(self):
+        return (self.T, self.H, self.W)
+
+    @property
+    def cube(self):
+        return (self.ct, self.ch, self.cw)
+
+
+def _wl(name, cid, grid, cube, hq, hkv, d, top_p, scale):
+    if not isinstance(scale, tuple):
+        scale = (float(scale),) * hkv
+    if not isinstance(top_p, tuple):
+        top_p = (float(top_p),)
+    return Workload(name, cid, *grid, *cube, hq, hkv, d, top_p, scale)
+
+
+# The five benchmark configurations (token grid, cube, heads, head_dim, Top-p).
+WORKLOADS = {
+    "C1": _wl("C1", 1, (8, 16, 16), (2, 4, 4), 4, 4, 64, 0.9, 0.0),
+    "C2": _wl("C2", 2, (64, 16, 16), (4, 8, 8), 28, 4, 128, 0.9, 1.0),
+    "C3": _wl("C3", 3, (256, 16, 16), (4, 8, 8), 28, 4, 128, (0.5, 0.7, 0.9, 0.99), 1.0),
+    "C4": _wl("C4", 4, (1024, 16, 16), (4, 8, 8), 28, 4, 128, 0.9, 0.5),
+    # entropy stress: KV heads 0-3 flat scores, 4-7 sharply peaked scores
+    "C5": _wl("C5", 5, (100, 15, 20), (4, 8, 8), 32, 8, 128, 0.9, (0.0,) * 4 + (4.0,) * 4),
+}
+
+# Small cases for tests: ragged in every axis, GQA, both head dims.
+TEST_WORKLOADS = {
+    "T_tiny": _wl("T_tiny", 11, (3, 5, 6), (2, 2, 4), 4, 2, 64, 0.8, 1.0),
+    "T_ragged": _wl("T_ragged", 12, (9, 10, 12), (4, 4, 8), 6, 2, 128, 0.9, (0.0, 2.0)),
+    "T_mha64": _wl("T_mha64", 13, (6, 8, 8), (2, 4, 4), 3, 3, 64, 0.7, 0.5),
+    "T_gqa128": _wl("T_gqa128", 14, (12, 16, 16), (4, 8, 8), 14, 2, 128, 0.9, 1.0),
+    "T_manycubes": _wl("T_manycubes", 15, (40, 4, 4), (1, 2, 2), 4, 2, 64, 0.6, 1.0),
+}
+
+
+def _randn(shape, seed):
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    return torch.randn(shape, generator=g, dtype=torch.float32)
+
+
+def generate(w: Workload):
+    """-> (Q [S,Hq,D], K [S,Hkv,D], V [S,Hkv,D]) CPU bf16 tensors.
+
+    Q, V ~ N(0,1).  K = N(0,1) + scale[g] * mu, mu ~ N(0, I) drawn once per
+    (cube, KV head) and shared by all tokens of that cube.
+    """
+    seed = BASE_SEED + 1000 * w.config_id
+    S = w.S
+    Q = _randn((S, w.Hq, w.D), seed + 0).to(torch.bfloat16)
+    V = _randn((S, w.Hkv, w.D), seed + 2).to(torch.bfloat16)
+    K = _randn((S, w.Hkv, w.D), seed + 1)
+    if any(s != 0.0 for s in w.k_mean_scale):
+        nt, nh, nw = -(-w.T // w.ct), -(-w.H // w.ch), -(-w.W // w.cw)
+        mu = _randn((nt, nh, nw, w.Hkv, w.D), seed + 3)
+        mu = mu * torch.tensor(w.k_mean_scale, dtype=torch.float32).view(1, 1, 1, w.Hkv, 1)
+        field = mu.repeat_interleave(w.ct, 0).repeat_interleave(w.ch, 1).repeat_interleave(w.cw, 2)
+        field = field[: w.T, : w.H, : w.W].reshape(S, w.Hkv, w.D)
+        K = K + field
+    return Q, K.to(torch.bfloat16), V
+
+
+def sample_rows(w: Workload, n: int, seed: int = 7):
+    """A seeded sample of query row ids (row = token * Hq + head), sorted.
+
+    Always contains the first and last token's rows so that both ends of the
+    sequence are covered; the rest is uniform without replacement.
+    """
+    R = w.S * w.Hq
+    g = torch.Generator(device="cpu")
+    g.manual_seed(BASE_SEED + 77 * w.config_id + seed)
+    n = min(n, R)
+    picks = torch.randperm(R, generator=g)[:n]
+    fixed = torch.tensor([0, w.Hq - 1, R - w.Hq, R - 1], dtype=torch.int64)
+    rows = torch.unique(torch.cat([picks, fixed]))
+    return rows.numpy()
