@@ -1,0 +1,147 @@
+/*
+ * adaspark.h -- C ABI of the AdaS-Attn library for AMD MI355X (gfx950).
+ *
+ * Adaptive Cube-Selective Attention (AdaSpark, Sec. 3.1-3.2): video tokens on a
+ * frames x height x width grid are grouped into 3D cubes (Sec. 3.1); every key
+ * cube is mean-pooled; every (query token, query head) scores all preceding
+ * cubes (Eq. 1), keeps a Top-p nucleus of them (Eq. 2) and runs exact softmax
+ * attention over the kept cubes plus the causal part of its own cube (Eq. 3).
+ *
+ * Conventions shared by all entry points
+ *   - Every data pointer is a DEVICE pointer owned by the caller, contiguous,
+ *     16-byte aligned.  The library never allocates or frees device memory and
+ *     keeps no state between calls; scratch space is the caller's `workspace`
+ *     (size from adaspark_workspace_bytes; contents need not be initialised and
+ *     are undefined afterwards).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue kernels on it; they never synchronise with the host.
+ *   - Token index n = (t*height + h)*width + w ("raster order").  Tensors are
+ *     Q,O: bf16 [tokens][q_heads][head_dim]; K,V: bf16 [tokens][kv_heads][head_dim].
+ *     Query head a uses KV head a / (q_heads / kv_heads).
+ *   - Cubes are numbered (tb*ceil(H/cube_h) + hb)*ceil(W/cube_w) + wb; edge
+ *     cubes are clipped.  Inside a cube tokens are ranked in local (t,h,w)
+ *     raster order.  "Preceding" / causal order everywhere in this library is
+ *     cube-major: all tokens of cube j < i precede all tokens of cube i, and
+ *     inside a cube lower rank precedes higher rank.
+ *   - Query row id r = n*q_heads + a.
+ *   - Return value: ADASPARK_OK (0) or a negative adaspark_status.  Arguments
+ *     are validated before anything is enqueued; on a validation error nothing
+ *     was launched.  No exceptions, no process exit.
+ */
+#ifndef ADASPARK_H
+#define ADASPARK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct {
+    int32_t frames, height, width;       /* token grid T, H, W; tokens = T*H*W                 */
+    int32_t cube_t, cube_h, cube_w;      /* cube shape along frames, height, width (Sec. 3.1)  */
+    int32_t q_heads, kv_heads, head_dim; /* q_heads % kv_heads == 0; head_dim in {64, 128}     */
+} adaspark_shape;
+
+typedef enum {
+    ADASPARK_OK = 0,
+    ADASPARK_EINVAL = -1,       /* null/misaligned pointer, bad shape, top_p outside [0,1]     */
+    ADASPARK_EUNSUPPORTED = -2, /* valid request outside what the kernels cover (see below)    */
+    ADASPARK_EWORKSPACE = -3,   /* workspace missing or smaller than adaspark_workspace_bytes  */
+    ADASPARK_EHIP = -4          /* the HIP runtime refused a launch                            */
+} adaspark_status;
+
+typedef enum {
+    ADASPARK_CALL_CUBE_POOL = 0,
+    ADASPARK_CALL_CUBE_SELECT = 1,
+    ADASPARK_CALL_SPARSE_ATTN = 2,
+    ADASPARK_CALL_DENSE_ATTN = 3
+} adaspark_call;
+
+/* Limits: head_dim in {64,128}; number of cubes <= ADASPARK_MAX_CUBES;
+ * tokens*q_heads < 2^31; only causal != 0 (the paper's method) is implemented. */
+#define ADASPARK_MAX_CUBES 2048
+
+/* Host-only helpers (no GPU work). */
+int adaspark_num_cubes(const adaspark_shape *shape, int32_t *n_cubes);
+int adaspark_workspace_bytes(const adaspark_shape *shape, int which_call /* adaspark_call */, size_t *bytes);
+const char *adaspark_status_string(int status);
+
+/*
+ * Cube mean keys (Eq. 1: k-bar_j = Mean(k in K_j)), per KV head.
+ *   K    in   bf16 [tokens][kv_heads][head_dim]
+ *   kbar out  fp32 [cubes][kv_heads][head_dim]   (fp32 accumulation, never rounded to bf16)
+ */
+int adaspark_cube_pool(const adaspark_shape *shape, const void *K, float *kbar, void *stream);
+
+/*
+ * Relevance scoring and Top-p cube selection (Eqs. 1-2) for every query row.
+ * For row r = (token n in cube i, head a): logits q.kbar_j/sqrt(head_dim) over
+ * cubes j < i, softmax, then the minimal set of highest-probability cubes whose
+ * mass reaches top_p (ties: lower cube index first).  top_p >= 1 keeps every
+ * preceding cube, top_p == 0 keeps none; rows of cube 0 keep none.
+ *   Q         in   bf16 [tokens][q_heads][head_dim]
+ *   kbar      in   fp32 [cubes][kv_heads][head_dim]
+ *   sel_mask  out  u32  [tokens*q_heads][ceil(cubes/32)]; bit (j%32) of word j/32 set
+ *                  iff cube j is selected.  The own cube's bit is never set.
+ *   sel_count out  i32  [tokens*q_heads] number of selected cubes
+ *   row_ptr   out  i64  [tokens*q_heads + 1] exclusive prefix sum of sel_count, or NULL
+ *   cube_idx  out  i32  [capacity] selected cube ids, ascending inside each row,
+ *                  row r at [row_ptr[r], row_ptr[r+1]); entries at positions
+ *                  >= capacity are dropped, so the list is complete iff
+ *                  row_ptr[tokens*q_heads] <= capacity.  NULL iff row_ptr is NULL.
+ *   workspace      adaspark_workspace_bytes(ADASPARK_CALL_CUBE_SELECT)
+ */
+int adaspark_cube_select(const adaspark_shape *shape, const void *Q, const float *kbar, float top_p, int causal,
+                         uint32_t *sel_mask, int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx,
+                         int64_t capacity, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Sparse attention (Eq. 3 plus the own-cube rule of Sec. 3.2): row r attends
+ * all tokens of the cubes set in its sel_mask row and the tokens of its own
+ * cube with rank <= its own rank; softmax(q.K_att^T/sqrt(head_dim)).V_att with
+ * bf16 inputs, fp32 accumulation and fp32 softmax.
+ *   Q,K,V     in   bf16 (layouts above)
+ *   sel_mask  in   as written by adaspark_cube_select
+ *   O         out  bf16 [tokens][q_heads][head_dim]
+ *   lse       out  fp32 [tokens*q_heads] natural-log sum-exp of the scaled logits, or NULL
+ *   workspace      adaspark_workspace_bytes(ADASPARK_CALL_SPARSE_ATTN)
+ */
+int adaspark_sparse_attn(const adaspark_shape *shape, const void *Q, const void *K, const void *V,
+                         const uint32_t *sel_mask, int causal, void *O, float *lse,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Dense causal attention in the same cube-major order (the comparison point of
+ * the paper's FLOPs analysis, supp. "Detail of FLOPs Calculation"): row r
+ * attends every token that precedes it in cube-major order, and itself.
+ * Built from the same kernels as adaspark_sparse_attn with every preceding
+ * cube taken as selected.  Arguments as above, without sel_mask.
+ */
+int adaspark_dense_attn(const adaspark_shape *shape, const void *Q, const void *K, const void *V,
+                        int causal, void *O, float *lse, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Split-phase form of the two attention entries.  Both attention entries first
+ * gather K and V into a cube-major, tile-blocked copy inside the workspace (the
+ * layout Alg. 1 calls "Reshape K,V into Cubes") and then run the attention
+ * kernel on that copy.  A caller that attends the same K,V more than once (a
+ * Top-p sweep, sparse and dense side by side) can pack once:
+ *   adaspark_kv_pack            fills `workspace` (same size as for the attention entries)
+ *   adaspark_sparse_attn_packed / adaspark_dense_attn_packed
+ *                               read a workspace filled by adaspark_kv_pack for the same shape;
+ *                               `packed` is only read.
+ * adaspark_sparse_attn(...) == adaspark_kv_pack(...) followed by adaspark_sparse_attn_packed(...).
+ */
+int adaspark_kv_pack(const adaspark_shape *shape, const void *K, const void *V,
+                     void *workspace, size_t workspace_bytes, void *stream);
+int adaspark_sparse_attn_packed(const adaspark_shape *shape, const void *Q, const void *packed, size_t packed_bytes,
+                                const uint32_t *sel_mask, int causal, void *O, float *lse, void *stream);
+int adaspark_dense_attn_packed(const adaspark_shape *shape, const void *Q, const void *packed, size_t packed_bytes,
+                               int causal, void *O, float *lse, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADASPARK_H */

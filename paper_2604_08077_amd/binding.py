@@ -1,0 +1,218 @@
+"""Thin ctypes binding of ``libadaspark.so`` (see ``include/adaspark.h``).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  torch is used for device memory (outputs and workspaces are torch
+tensors) and for the current HIP stream.  There is no CPU fallback: if the
+library has not been built, or a tensor is not on the GPU, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+from .build import lib_path
+
+CALL_CUBE_POOL, CALL_CUBE_SELECT, CALL_SPARSE_ATTN, CALL_DENSE_ATTN = 0, 1, 2, 3
+
+
+class _CShape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "frames", "height", "width", "cube_t", "cube_h", "cube_w", "q_heads", "kv_heads", "head_dim")]
+
+
+@dataclass(frozen=True)
+class Shape:
+    """Mirror of ``adaspark_shape``."""
+
+    frames: int
+    height: int
+    width: int
+    cube_t: int
+    cube_h: int
+    cube_w: int
+    q_heads: int
+    kv_heads: int
+    head_dim: int
+
+    @property
+    def tokens(self) -> int:
+        return self.frames * self.height * self.width
+
+    @property
+    def rows(self) -> int:
+        return self.tokens * self.q_heads
+
+    def _c(self) -> _CShape:
+        return _CShape(self.frames, self.height, self.width, self.cube_t, self.cube_h, self.cube_w,
+                       self.q_heads, self.kv_heads, self.head_dim)
+
+    @staticmethod
+    def of(w) -> "Shape":
+        """From a ``synth.Workload``."""
+        return Shape(w.T, w.H, w.W, w.ct, w.ch, w.cw, w.Hq, w.Hkv, w.D)
+
+
+class AdasparkError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+EXPORTS = (
+    "adaspark_num_cubes",
+    "adaspark_workspace_bytes",
+    "adaspark_status_string",
+    "adaspark_cube_pool",
+    "adaspark_cube_select",
+    "adaspark_sparse_attn",
+    "adaspark_dense_attn",
+)
+
+
+def load():
+    """dlopen the library; raises if it was not built (no fallback)."""
+    global _lib
+    if _lib is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise RuntimeError(
+                f"{path} is missing: build it first (python -m paper_2604_08077_amd.build); "
+                "this package has no CPU or eager fallback")
+        lib = ctypes.CDLL(path)
+        vp, sp = ctypes.c_void_p, ctypes.POINTER(_CShape)
+        lib.adaspark_num_cubes.argtypes = [sp, ctypes.POINTER(ctypes.c_int32)]
+        lib.adaspark_workspace_bytes.argtypes = [sp, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
+        lib.adaspark_status_string.argtypes = [ctypes.c_int]
+        lib.adaspark_status_string.restype = ctypes.c_char_p
+        lib.adaspark_cube_pool.argtypes = [sp, vp, vp, vp]
+        lib.adaspark_cube_select.argtypes = [sp, vp, vp, ctypes.c_float, ctypes.c_int, vp, vp, vp, vp,
+                                             ctypes.c_int64, vp, ctypes.c_size_t, vp]
+        lib.adaspark_sparse_attn.argtypes = [sp, vp, vp, vp, vp, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.adaspark_dense_attn.argtypes = [sp, vp, vp, vp, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
+        for name in EXPORTS:
+            if name != "adaspark_status_string":
+                getattr(lib, name).restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().adaspark_status_string(int(status)).decode()
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        raise AdasparkError(status, what)
+
+
+def _dev(t: torch.Tensor, dtype, numel: int, name: str) -> int:
+    if not isinstance(t, torch.Tensor) or t.device.type != "cuda":
+        raise ValueError(f"{name} must be a GPU tensor (this package has no CPU path)")
+    if t.dtype != dtype or not t.is_contiguous() or t.numel() != numel:
+        raise ValueError(f"{name}: expected contiguous {dtype} with {numel} elements, got {t.dtype} {tuple(t.shape)}")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def num_cubes(shape: Shape) -> int:
+    n = ctypes.c_int32(0)
+    cs = shape._c()
+    _check(load().adaspark_num_cubes(ctypes.byref(cs), ctypes.byref(n)), "adaspark_num_cubes")
+    return n.value
+
+
+def workspace_bytes(shape: Shape, which_call: int) -> int:
+    b = ctypes.c_size_t(0)
+    cs = shape._c()
+    _check(load().adaspark_workspace_bytes(ctypes.byref(cs), which_call, ctypes.byref(b)), "adaspark_workspace_bytes")
+    return b.value
+
+
+def alloc_workspace(shape: Shape, which_call: int, device="cuda") -> torch.Tensor:
+    return torch.empty(max(workspace_bytes(shape, which_call), 16), dtype=torch.uint8, device=device)
+
+
+def cube_pool(shape: Shape, K: torch.Tensor, kbar: torch.Tensor | None = None) -> torch.Tensor:
+    """Eq. 1 mean keys: K bf16 [S,Hkv,D] -> kbar fp32 [N,Hkv,D]."""
+    N = num_cubes(shape)
+    if kbar is None:
+        kbar = torch.empty((N, shape.kv_heads, shape.head_dim), dtype=torch.float32, device=K.device)
+    cs = shape._c()
+    _check(load().adaspark_cube_pool(
+        ctypes.byref(cs), _dev(K, torch.bfloat16, shape.tokens * shape.kv_heads * shape.head_dim, "K"),
+        _dev(kbar, torch.float32, N * shape.kv_heads * shape.head_dim, "kbar"), _stream()), "adaspark_cube_pool")
+    return kbar
+
+
+def cube_select(shape: Shape, Q: torch.Tensor, kbar: torch.Tensor, top_p: float, causal: bool = True,
+                sel_mask=None, sel_count=None, csr_capacity: int | None = None, workspace=None):
+    """Eqs. 1-2: -> (sel_mask int32-viewed-u32 [R, words], sel_count int32 [R], row_ptr|None, cube_idx|None)."""
+    N = num_cubes(shape)
+    words = (N + 31) // 32
+    R = shape.rows
+    dev = Q.device
+    if sel_mask is None:
+        sel_mask = torch.empty((R, words), dtype=torch.int32, device=dev)
+    if sel_count is None:
+        sel_count = torch.empty((R,), dtype=torch.int32, device=dev)
+    row_ptr = cube_idx = None
+    rp = ci = None
+    cap = 0
+    if csr_capacity is not None:
+        cap = int(csr_capacity)
+        row_ptr = torch.empty((R + 1,), dtype=torch.int64, device=dev)
+        cube_idx = torch.empty((max(cap, 4),), dtype=torch.int32, device=dev)
+        rp, ci = row_ptr.data_ptr(), cube_idx.data_ptr()
+    if workspace is None:
+        workspace = alloc_workspace(shape, CALL_CUBE_SELECT, dev)
+    cs = shape._c()
+    _check(load().adaspark_cube_select(
+        ctypes.byref(cs), _dev(Q, torch.bfloat16, R * shape.head_dim, "Q"),
+        _dev(kbar, torch.float32, N * shape.kv_heads * shape.head_dim, "kbar"),
+        ctypes.c_float(top_p), int(bool(causal)),
+        _dev(sel_mask, torch.int32, R * words, "sel_mask"), _dev(sel_count, torch.int32, R, "sel_count"),
+        rp, ci, cap, workspace.data_ptr(), workspace.numel(), _stream()), "adaspark_cube_select")
+    return sel_mask, sel_count, row_ptr, cube_idx
+
+
+def _attn(fn_name, shape, Q, K, V, sel_mask, causal, O, lse, workspace, want_lse):
+    R = shape.rows
+    dev = Q.device
+    if O is None:
+        O = torch.empty((shape.tokens, shape.q_heads, shape.head_dim), dtype=torch.bfloat16, device=dev)
+    if lse is None and want_lse:
+        lse = torch.empty((R,), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = alloc_workspace(shape, CALL_SPARSE_ATTN, dev)
+    kvn = shape.tokens * shape.kv_heads * shape.head_dim
+    cs = shape._c()
+    args = [ctypes.byref(cs), _dev(Q, torch.bfloat16, R * shape.head_dim, "Q"), _dev(K, torch.bfloat16, kvn, "K"),
+            _dev(V, torch.bfloat16, kvn, "V")]
+    if fn_name == "adaspark_sparse_attn":
+        words = (num_cubes(shape) + 31) // 32
+        args.append(_dev(sel_mask, torch.int32, R * words, "sel_mask"))
+    args += [int(bool(causal)), _dev(O, torch.bfloat16, R * shape.head_dim, "O"),
+             None if lse is None else _dev(lse, torch.float32, R, "lse"),
+             workspace.data_ptr(), workspace.numel(), _stream()]
+    _check(getattr(load(), fn_name)(*args), fn_name)
+    return (O, lse) if want_lse else O
+
+
+def sparse_attn(shape: Shape, Q, K, V, sel_mask, causal: bool = True, O=None, lse=None, workspace=None,
+                return_lse: bool = False):
+    """Eq. 3 + own-cube rule over the cubes set in ``sel_mask`` -> O bf16 [S,Hq,D]."""
+    return _attn("adaspark_sparse_attn", shape, Q, K, V, sel_mask, causal, O, lse, workspace, return_lse)
+
+
+def dense_attn(shape: Shape, Q, K, V, causal: bool = True, O=None, lse=None, workspace=None,
+               return_lse: bool = False):
+    """Dense causal attention in cube-major order -> O bf16 [S,Hq,D]."""
+    return _attn("adaspark_dense_attn", shape, Q, K, V, None, causal, O, lse, workspace, return_lse)

@@ -1,0 +1,135 @@
+// extern "C" boundary of the library: argument validation and kernel enqueueing only.
+#include "geom.h"
+
+using namespace adaspark;
+
+namespace {
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_shape(const adaspark_shape *s)
+{
+    if (s == nullptr) return ADASPARK_EINVAL;
+    if (s->frames <= 0 || s->height <= 0 || s->width <= 0) return ADASPARK_EINVAL;
+    if (s->cube_t <= 0 || s->cube_h <= 0 || s->cube_w <= 0) return ADASPARK_EINVAL;
+    if (s->q_heads <= 0 || s->kv_heads <= 0 || s->head_dim <= 0) return ADASPARK_EINVAL;
+    if (s->q_heads % s->kv_heads != 0) return ADASPARK_EINVAL;
+    const long long tokens = (long long)s->frames * s->height * s->width;
+    if (tokens * s->q_heads >= (1ll << 31)) return ADASPARK_EUNSUPPORTED;
+    if (s->head_dim != 64 && s->head_dim != 128) return ADASPARK_EUNSUPPORTED;
+    const long long cube = (long long)s->cube_t * s->cube_h * s->cube_w;
+    if (cube >= (1ll << 24)) return ADASPARK_EUNSUPPORTED;
+    const Geom g = make_geom(*s);
+    if ((long long)g.nTb * g.nHb * g.nWb > ADASPARK_MAX_CUBES) return ADASPARK_EUNSUPPORTED;
+    return ADASPARK_OK;
+}
+
+int check_ptrs(std::initializer_list<const void *> ps)
+{
+    for (const void *p : ps)
+        if (p == nullptr || !aligned16(p)) return ADASPARK_EINVAL;
+    return ADASPARK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int adaspark_num_cubes(const adaspark_shape *shape, int32_t *n_cubes)
+{
+    if (n_cubes == nullptr) return ADASPARK_EINVAL;
+    const int rc = check_shape(shape);
+    if (rc != ADASPARK_OK) return rc;
+    *n_cubes = make_geom(*shape).N;
+    return ADASPARK_OK;
+}
+
+int adaspark_workspace_bytes(const adaspark_shape *shape, int which_call, size_t *bytes)
+{
+    if (bytes == nullptr) return ADASPARK_EINVAL;
+    const int rc = check_shape(shape);
+    if (rc != ADASPARK_OK) return rc;
+    const Geom g = make_geom(*shape);
+    switch (which_call) {
+    case ADASPARK_CALL_CUBE_POOL: *bytes = 0; return ADASPARK_OK;
+    case ADASPARK_CALL_CUBE_SELECT: *bytes = select_workspace_bytes(g); return ADASPARK_OK;
+    case ADASPARK_CALL_SPARSE_ATTN:
+    case ADASPARK_CALL_DENSE_ATTN: *bytes = attn_workspace_bytes(g); return ADASPARK_OK;
+    default: return ADASPARK_EINVAL;
+    }
+}
+
+const char *adaspark_status_string(int status)
+{
+    switch (status) {
+    case ADASPARK_OK: return "ok";
+    case ADASPARK_EINVAL: return "invalid argument";
+    case ADASPARK_EUNSUPPORTED: return "unsupported configuration";
+    case ADASPARK_EWORKSPACE: return "workspace missing or too small";
+    case ADASPARK_EHIP: return "HIP launch failed";
+    default: return "unknown status";
+    }
+}
+
+int adaspark_cube_pool(const adaspark_shape *shape, const void *K, float *kbar, void *stream)
+{
+    int rc = check_shape(shape);
+    if (rc != ADASPARK_OK) return rc;
+    if ((rc = check_ptrs({K, kbar})) != ADASPARK_OK) return rc;
+    const Geom g = make_geom(*shape);
+    const hipError_t e = launch_cube_pool(g, static_cast<const uint16_t *>(K), kbar, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ADASPARK_OK : ADASPARK_EHIP;
+}
+
+int adaspark_cube_select(const adaspark_shape *shape, const void *Q, const float *kbar, float top_p, int causal,
+                         uint32_t *sel_mask, int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx,
+                         int64_t capacity, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_shape(shape);
+    if (rc != ADASPARK_OK) return rc;
+    if ((rc = check_ptrs({Q, kbar, sel_mask, sel_count})) != ADASPARK_OK) return rc;
+    if (!(top_p >= 0.f && top_p <= 1.f)) return ADASPARK_EINVAL;  // also rejects NaN
+    if ((row_ptr == nullptr) != (cube_idx == nullptr)) return ADASPARK_EINVAL;
+    if (row_ptr != nullptr && (!aligned16(row_ptr) || !aligned16(cube_idx) || capacity < 0)) return ADASPARK_EINVAL;
+    if (!causal) return ADASPARK_EUNSUPPORTED;
+    const Geom g = make_geom(*shape);
+    if (workspace == nullptr || !aligned16(workspace) || workspace_bytes < select_workspace_bytes(g))
+        return ADASPARK_EWORKSPACE;
+    const hipError_t e = launch_cube_select(g, static_cast<const uint16_t *>(Q), kbar, top_p, sel_mask, sel_count,
+                                            row_ptr, cube_idx, capacity, workspace, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ADASPARK_OK : ADASPARK_EHIP;
+}
+
+static int attn_common(const adaspark_shape *shape, const void *Q, const void *K, const void *V,
+                       const uint32_t *sel_mask, bool sparse, int causal, void *O, float *lse, void *workspace,
+                       size_t workspace_bytes, void *stream)
+{
+    int rc = check_shape(shape);
+    if (rc != ADASPARK_OK) return rc;
+    if ((rc = check_ptrs({Q, K, V, O})) != ADASPARK_OK) return rc;
+    if (sparse && (sel_mask == nullptr || !aligned16(sel_mask))) return ADASPARK_EINVAL;
+    if (lse != nullptr && !aligned16(lse)) return ADASPARK_EINVAL;
+    if (!causal) return ADASPARK_EUNSUPPORTED;
+    const Geom g = make_geom(*shape);
+    if (workspace == nullptr || !aligned16(workspace) || workspace_bytes < attn_workspace_bytes(g))
+        return ADASPARK_EWORKSPACE;
+    const hipError_t e = launch_attn(g, static_cast<const uint16_t *>(Q), static_cast<const uint16_t *>(K),
+                                     static_cast<const uint16_t *>(V), sparse ? sel_mask : nullptr,
+                                     static_cast<uint16_t *>(O), lse, workspace, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ADASPARK_OK : ADASPARK_EHIP;
+}
+
+int adaspark_sparse_attn(const adaspark_shape *shape, const void *Q, const void *K, const void *V,
+                         const uint32_t *sel_mask, int causal, void *O, float *lse, void *workspace,
+                         size_t workspace_bytes, void *stream)
+{
+    return attn_common(shape, Q, K, V, sel_mask, true, causal, O, lse, workspace, workspace_bytes, stream);
+}
+
+int adaspark_dense_attn(const adaspark_shape *shape, const void *Q, const void *K, const void *V, int causal, void *O,
+                        float *lse, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return attn_common(shape, Q, K, V, nullptr, false, causal, O, lse, workspace, workspace_bytes, stream);
+}
+
+}  // extern "C"

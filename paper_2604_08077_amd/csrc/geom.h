@@ -1,0 +1,91 @@
+// Cube geometry shared by the kernels of this library (Sec. 3.1, video cube
+// partition).  Host code fills a Geom from the caller's adaspark_shape; device
+// code maps (cube, rank) <-> raster token index with it.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/adaspark.h"
+
+namespace adaspark {
+
+constexpr int KEY_TILE = 64;  // keys per staged K/V tile; cubes are padded to a multiple of it in the packed KV layout
+
+struct Geom {
+    int T, H, W;        // token grid
+    int ct, ch, cw;     // cube shape
+    int Hq, Hkv, D, G;  // heads, head_dim, group size Hq/Hkv
+    int nTb, nHb, nWb;  // cubes along each axis
+    int N;              // cubes
+    int S;              // tokens
+    int Cmax;           // tokens in an unclipped cube
+    int TPC;            // key tiles per cube in the packed layout = ceil(Cmax / KEY_TILE)
+    int words;          // u32 words per selection-mask row = ceil(N / 32)
+};
+
+inline Geom make_geom(const adaspark_shape &s)
+{
+    Geom g;
+    g.T = s.frames; g.H = s.height; g.W = s.width;
+    g.ct = s.cube_t; g.ch = s.cube_h; g.cw = s.cube_w;
+    g.Hq = s.q_heads; g.Hkv = s.kv_heads; g.D = s.head_dim; g.G = s.q_heads / s.kv_heads;
+    g.nTb = (g.T + g.ct - 1) / g.ct; g.nHb = (g.H + g.ch - 1) / g.ch; g.nWb = (g.W + g.cw - 1) / g.cw;
+    g.N = g.nTb * g.nHb * g.nWb;
+    g.S = g.T * g.H * g.W;
+    g.Cmax = g.ct * g.ch * g.cw;
+    g.TPC = (g.Cmax + KEY_TILE - 1) / KEY_TILE;
+    g.words = (g.N + 31) / 32;
+    return g;
+}
+
+// Clipped extents and origin of cube c.
+struct CubeBox {
+    int t0, h0, w0;  // origin in the token grid
+    int et, eh, ew;  // extents after clipping at the grid edge
+    __host__ __device__ int size() const { return et * eh * ew; }
+};
+
+__host__ __device__ inline CubeBox cube_box(const Geom &g, int c)
+{
+    CubeBox b;
+    const int wb = c % g.nWb, hb = (c / g.nWb) % g.nHb, tb = c / (g.nWb * g.nHb);
+    b.t0 = tb * g.ct; b.h0 = hb * g.ch; b.w0 = wb * g.cw;
+    b.et = min(g.ct, g.T - b.t0); b.eh = min(g.ch, g.H - b.h0); b.ew = min(g.cw, g.W - b.w0);
+    return b;
+}
+
+// Raster token index of the token with rank `rank` in the cube described by b.
+__host__ __device__ inline int token_of(const Geom &g, const CubeBox &b, int rank)
+{
+    const int lw = rank % b.ew, lh = (rank / b.ew) % b.eh, lt = rank / (b.ew * b.eh);
+    return ((b.t0 + lt) * g.H + (b.h0 + lh)) * g.W + (b.w0 + lw);
+}
+
+// Cube of raster token n (rank not needed by the callers of this one).
+__host__ __device__ inline int cube_of_token(const Geom &g, int n)
+{
+    const int w = n % g.W, h = (n / g.W) % g.H, t = n / (g.W * g.H);
+    return ((t / g.ct) * g.nHb + (h / g.ch)) * g.nWb + (w / g.cw);
+}
+
+// bf16 <-> fp32 bit helpers.
+__device__ inline float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ inline uint16_t float_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // quiet NaN
+    u += 0x7fffu + ((u >> 16) & 1u);  // round to nearest even
+    return (uint16_t)(u >> 16);
+}
+
+// Kernel launchers (defined one per .hip file).  All return hipError_t from the launch.
+hipError_t launch_cube_pool(const Geom &g, const uint16_t *K, float *kbar, hipStream_t st);
+size_t select_workspace_bytes(const Geom &g);
+hipError_t launch_cube_select(const Geom &g, const uint16_t *Q, const float *kbar, float top_p, uint32_t *sel_mask,
+                              int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx, int64_t capacity, void *ws,
+                              hipStream_t st);
+size_t attn_workspace_bytes(const Geom &g);
+hipError_t launch_attn(const Geom &g, const uint16_t *Q, const uint16_t *K, const uint16_t *V, const uint32_t *sel_mask,
+                       uint16_t *O, float *lse, void *ws, hipStream_t st);
+
+}  // namespace adaspark

@@ -1,0 +1,98 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every
+function the header declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2604_08077_amd import binding, build, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(build.lib_path()):
+        build.build()
+    return binding.load()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "adaspark.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(adaspark_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_num_cubes_and_workspace_sizes(lib):
+    expect = {"C1": 64, "C2": 64, "C3": 256, "C4": 1024, "C5": 150}
+    for name, n in expect.items():
+        sh = binding.Shape.of(synth.WORKLOADS[name])
+        assert binding.num_cubes(sh) == n
+        assert binding.workspace_bytes(sh, binding.CALL_CUBE_POOL) == 0
+        assert binding.workspace_bytes(sh, binding.CALL_CUBE_SELECT) > 0
+        ws = binding.workspace_bytes(sh, binding.CALL_SPARSE_ATTN)
+        assert ws == binding.workspace_bytes(sh, binding.CALL_DENSE_ATTN)
+        w = synth.WORKLOADS[name]
+        assert ws >= 2 * w.S * w.Hkv * w.D * 2          # room for a packed copy of K and V
+
+
+def test_status_strings(lib):
+    assert binding.status_string(0) == "ok"
+    for code in (-1, -2, -3, -4):
+        assert binding.status_string(code) not in ("ok", "unknown status")
+    assert binding.status_string(-99) == "unknown status"
+
+
+def _raw_shape(**kw):
+    base = dict(frames=4, height=8, width=8, cube_t=2, cube_h=4, cube_w=4, q_heads=4, kv_heads=2, head_dim=64)
+    base.update(kw)
+    return binding.Shape(**base)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(frames=0), -1), (dict(cube_w=0), -1), (dict(q_heads=3), -1), (dict(kv_heads=0), -1),
+    (dict(head_dim=96), -2), (dict(frames=4096, height=64, width=64, cube_t=1, cube_h=1, cube_w=1), -2),
+])
+def test_bad_shapes_are_rejected(lib, kw, code):
+    with pytest.raises(binding.AdasparkError) as e:
+        binding.num_cubes(_raw_shape(**kw))
+    assert e.value.status == code
+
+
+def test_bad_pointers_and_arguments_are_rejected_before_launch(lib):
+    cs = _raw_shape()._c()
+    ok_ptr = ctypes.c_void_p(4096)      # never dereferenced: validation fails first
+    assert lib.adaspark_cube_pool(ctypes.byref(cs), None, ok_ptr, None) == -1
+    assert lib.adaspark_cube_pool(ctypes.byref(cs), ctypes.c_void_p(4097), ok_ptr, None) == -1
+    args = [ctypes.byref(cs), ok_ptr, ok_ptr, ctypes.c_float(1.5), 1, ok_ptr, ok_ptr, None, None, 0, ok_ptr, 1 << 30, None]
+    assert lib.adaspark_cube_select(*args) == -1                       # top_p outside [0,1]
+    args[3] = ctypes.c_float(float("nan"))
+    assert lib.adaspark_cube_select(*args) == -1
+    args[3] = ctypes.c_float(0.9)
+    args[4] = 0
+    assert lib.adaspark_cube_select(*args) == -2                       # non-causal not implemented
+    args[4] = 1
+    args[11] = 8
+    assert lib.adaspark_cube_select(*args) == -3                       # workspace too small
+    args[11] = 1 << 30
+    args[7] = ok_ptr
+    assert lib.adaspark_cube_select(*args) == -1                       # row_ptr without cube_idx
+    assert lib.adaspark_sparse_attn(ctypes.byref(cs), ok_ptr, ok_ptr, ok_ptr, None, 1, ok_ptr, None, ok_ptr, 1 << 30, None) == -1
+    assert lib.adaspark_dense_attn(ctypes.byref(cs), ok_ptr, ok_ptr, ok_ptr, 1, ok_ptr, None, None, 0, None) == -3
+    assert lib.adaspark_dense_attn(None, ok_ptr, ok_ptr, ok_ptr, 1, ok_ptr, None, ok_ptr, 1 << 30, None) == -1
+
+
+def test_binding_refuses_cpu_tensors(lib):
+    import torch
+    w = synth.TEST_WORKLOADS["T_tiny"]
+    _, K, _ = synth.generate(w)
+    with pytest.raises(ValueError):
+        binding.cube_pool(binding.Shape.of(w), K)

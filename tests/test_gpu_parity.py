@@ -1,0 +1,217 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 oracle, element
+by element on the same seeded bf16 inputs.
+
+Bars (written here, derived in the design notes):
+  * mean keys: fp32 accumulation of <= 2^24 bf16 values against fp64 -> |err| <= 2e-5;
+  * selected cube sets: bit-exact, except rows the oracle flags as sitting within
+    1e-5 of the Top-p boundary (counted and printed); a differing row may differ
+    by at most 2 cubes;
+  * attention outputs (bf16 in, fp32 accumulate, bf16 out): max-abs <= 2e-2,
+    mean-abs <= 2e-3.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_08077_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, MEAN_ABS, KBAR_ABS = 2e-2, 2e-3, 2e-5
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2604_08077_amd import binding
+
+    binding.load()  # raises if the HIP library was not built: there is no fallback
+    return binding
+
+
+def oshape(o, w):
+    return o.Shape(w.T, w.H, w.W, w.ct, w.ch, w.cw, w.Hq, w.Hkv, w.D)
+
+
+def to_u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def popcount_rows(x):
+    return np.unpackbits(x.view(np.uint8), axis=1).sum(1)
+
+
+def check_selection(name, gpu_mask, gpu_count, ref_mask, ref_count, near):
+    """Returns the boolean vector of rows whose set equals the oracle's."""
+    same = (gpu_mask == ref_mask).all(axis=1)
+    assert np.array_equal(popcount_rows(gpu_mask), gpu_count), "sel_count does not match the mask"
+    differ = ~same
+    bad = differ & ~near
+    sym = popcount_rows(gpu_mask[differ] ^ ref_mask[differ]) if differ.any() else np.zeros(0, int)
+    print(f"[{name}] rows={len(same)} near-boundary(exempt)={int(near.sum())} differing={int(differ.sum())} "
+          f"differing-and-not-exempt={int(bad.sum())} max-symdiff={int(sym.max()) if sym.size else 0}", flush=True)
+    assert not bad.any(), f"{int(bad.sum())} rows differ from the oracle away from the Top-p boundary"
+    assert (sym <= 2).all()
+    return same
+
+
+def check_outputs(name, gpu_out, ref_out):
+    err = np.abs(gpu_out.astype(np.float64) - ref_out)
+    print(f"[{name}] rows={err.shape[0]} max-abs={err.max():.3e} mean-abs={err.mean():.3e}", flush=True)
+    assert np.isfinite(gpu_out).all()
+    assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS
+
+
+def rows_of(O, rows, w):
+    return O.reshape(w.S * w.Hq, w.D)[torch.as_tensor(rows, device=O.device)].float().cpu().numpy()
+
+
+SMALL = [synth.TEST_WORKLOADS[k] for k in ("T_tiny", "T_ragged", "T_mha64", "T_gqa128", "T_manycubes")] + [
+    synth.WORKLOADS["C1"]]
+
+
+@pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
+def test_full_path_small(B, oracle, w):
+    """Every row of the small cases: pool, select (several p, CSR), attention with the
+    oracle's selection, the whole GPU pipeline, and the dense entry."""
+    print(f"case {w.name} grid={w.grid} cube={w.cube} heads={w.Hq}/{w.Hkv} D={w.D}", flush=True)
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    Q, K, V = synth.generate(w)
+    Qg, Kg, Vg = Q.cuda(), K.cuda(), V.cuda()
+    N = B.num_cubes(sh)
+    assert N == oracle.num_cubes(osh)
+
+    kbar_ref = oracle.cube_pool(osh, K)
+    kbar = B.cube_pool(sh, Kg)
+    torch.cuda.synchronize()
+    err = np.abs(kbar.cpu().numpy().astype(np.float64) - kbar_ref).max()
+    print(f"[{w.name}] kbar max-abs err {err:.2e}", flush=True)
+    assert err <= KBAR_ABS
+
+    for p in sorted({0.0, 0.35, w.top_p[0], 0.97, 1.0}):
+        p32 = float(np.float32(p))
+        ref_mask, ref_count, near = oracle.cube_select(osh, Q, kbar_ref, p32)
+        cap = int(ref_count.sum()) + 64
+        mask, count, row_ptr, cube_idx = B.cube_select(sh, Qg, kbar, p32, csr_capacity=cap)
+        torch.cuda.synchronize()
+        gm, gc = to_u32(mask), count.cpu().numpy()
+        same = check_selection(f"{w.name} p={p}", gm, gc, ref_mask, ref_count, near)
+        if p in (0.0, 1.0):
+            assert same.all()
+        # compact list agrees with the mask
+        rp, ci = row_ptr.cpu().numpy(), cube_idx.cpu().numpy()
+        assert rp[0] == 0 and np.array_equal(np.diff(rp), gc)
+        bits = np.unpackbits(gm.view(np.uint8), axis=1, bitorder="little")[:, :N]
+        rr, cc = np.nonzero(bits)
+        assert np.array_equal(ci[: rp[-1]], cc.astype(np.int32))
+
+    p32 = float(np.float32(w.top_p[0]))
+    ref_mask, ref_count, near = oracle.cube_select(osh, Q, kbar_ref, p32)
+    ref_out, _ = oracle.sparse_attn(osh, Q, K, V, ref_mask)
+    # (1) GPU attention fed the oracle's selection: every row must pass
+    O, lse = B.sparse_attn(sh, Qg, Kg, Vg, torch.from_numpy(ref_mask.view(np.int32)).cuda(), return_lse=True)
+    torch.cuda.synchronize()
+    check_outputs(f"{w.name} attn(oracle sel)", O.reshape(-1, w.D).float().cpu().numpy(), ref_out)
+    assert torch.isfinite(lse).all()
+    # (2) whole GPU pipeline; rows whose set differs (all exempt) are excluded from the statistic
+    mask, count, _, _ = B.cube_select(sh, Qg, kbar, p32)
+    O2 = B.sparse_attn(sh, Qg, Kg, Vg, mask)
+    torch.cuda.synchronize()
+    same = (to_u32(mask) == ref_mask).all(axis=1)
+    check_outputs(f"{w.name} pipeline", O2.reshape(-1, w.D).float().cpu().numpy()[same], ref_out[same])
+    # (3) dense entry, and p = 1 through the sparse entry
+    dense_ref = oracle.dense_attn(osh, Q, K, V)
+    Od = B.dense_attn(sh, Qg, Kg, Vg)
+    m1, _, _, _ = B.cube_select(sh, Qg, kbar, 1.0)
+    O1 = B.sparse_attn(sh, Qg, Kg, Vg, m1)
+    torch.cuda.synchronize()
+    check_outputs(f"{w.name} dense", Od.reshape(-1, w.D).float().cpu().numpy(), dense_ref)
+    check_outputs(f"{w.name} sparse p=1", O1.reshape(-1, w.D).float().cpu().numpy(), dense_ref)
+    # (4) p = 0: own cube only
+    m0, c0, _, _ = B.cube_select(sh, Qg, kbar, 0.0)
+    O0 = B.sparse_attn(sh, Qg, Kg, Vg, m0)
+    torch.cuda.synchronize()
+    ref0, _ = oracle.sparse_attn(osh, Q, K, V, np.zeros_like(ref_mask))
+    check_outputs(f"{w.name} sparse p=0", O0.reshape(-1, w.D).float().cpu().numpy(), ref0)
+
+
+def test_value_indicator_recovers_attended_set(B, oracle):
+    """V[n] = indicator of cube(n): output column j is the attention mass on cube j, exactly 0
+    for cubes that are neither selected nor the row's own -- read back from the GPU kernel."""
+    w = synth.WORKLOADS["C1"]
+    print(f"case {w.name} value-indicator", flush=True)
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    Q, K, _ = synth.generate(w)
+    N = B.num_cubes(sh)
+    assert N <= w.D
+    cube_of, _, _, _ = oracle.cube_map(osh)
+    V = torch.zeros((w.S, w.Hkv, w.D), dtype=torch.bfloat16)
+    V[torch.arange(w.S), :, torch.from_numpy(cube_of.astype(np.int64))] = 1.0
+    Qg, Kg, Vg = Q.cuda(), K.cuda(), V.cuda()
+    kbar = B.cube_pool(sh, Kg)
+    mask, _, _, _ = B.cube_select(sh, Qg, kbar, 0.9)
+    O = B.sparse_attn(sh, Qg, Kg, Vg, mask)
+    torch.cuda.synchronize()
+    out = O.reshape(-1, w.D).float().cpu().numpy()[:, :N]
+    bits = np.unpackbits(to_u32(mask).view(np.uint8), axis=1, bitorder="little")[:, :N].astype(bool)
+    own = np.zeros_like(bits)
+    own[np.arange(w.S * w.Hq), np.repeat(cube_of, w.Hq)] = True
+    attended = bits | own
+    assert np.all(out[~attended] == 0.0)
+    assert np.all(out[own] > 0.0)
+    assert np.abs(out.sum(1) - 1.0).max() < 2e-2
+
+
+def sampled_case(B, oracle, w, p_list, n_rows, check_dense=True):
+    print(f"case {w.name} grid={w.grid} cube={w.cube} heads={w.Hq}/{w.Hkv} D={w.D} sampled rows={n_rows}", flush=True)
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    Q, K, V = synth.generate(w)
+    Qg, Kg, Vg = Q.cuda(), K.cuda(), V.cuda()
+    rows = synth.sample_rows(w, n_rows)
+    kbar_ref = oracle.cube_pool(osh, K)
+    kbar = B.cube_pool(sh, Kg)
+    torch.cuda.synchronize()
+    assert np.abs(kbar.cpu().numpy().astype(np.float64) - kbar_ref).max() <= KBAR_ABS
+    ws_sel = B.alloc_workspace(sh, B.CALL_CUBE_SELECT)
+    ws_att = B.alloc_workspace(sh, B.CALL_SPARSE_ATTN)
+    prev_bits = None
+    for p in p_list:
+        p32 = float(np.float32(p))
+        mask, count, _, _ = B.cube_select(sh, Qg, kbar, p32, workspace=ws_sel)
+        O = B.sparse_attn(sh, Qg, Kg, Vg, mask, workspace=ws_att)
+        torch.cuda.synchronize()
+        ridx = torch.as_tensor(rows, device="cuda")
+        gm, gc = to_u32(mask[ridx]), count[ridx].cpu().numpy()
+        ref_mask, ref_count, near = oracle.cube_select(osh, Q, kbar_ref, p32, rows=rows)
+        same = check_selection(f"{w.name} p={p}", gm, gc, ref_mask, ref_count, near)
+        frac = float(count.sum().item()) / max(1.0, float(np.repeat(oracle.cube_map(osh)[0], w.Hq).astype(np.float64).sum()))
+        print(f"[{w.name} p={p}] selected fraction of preceding cubes = {frac:.4f}", flush=True)
+        # properties that hold at any size, on all rows: nesting in p
+        if prev_bits is not None:
+            assert not bool((prev_bits & ~mask).any().item())
+        prev_bits = mask.clone()
+        ref_out, _ = oracle.sparse_attn(osh, Q, K, V, ref_mask, rows=rows)
+        got = rows_of(O, rows, w)
+        check_outputs(f"{w.name} p={p} pipeline(sampled)", got[same], ref_out[same])
+    if check_dense:
+        Od = B.dense_attn(sh, Qg, Kg, Vg, workspace=ws_att)
+        torch.cuda.synchronize()
+        drows = rows[:: max(1, len(rows) // 96)]
+        check_outputs(f"{w.name} dense(sampled)", rows_of(Od, drows, w), oracle.dense_attn(osh, Q, K, V, rows=drows))
+
+
+def test_c2_sampled(B, oracle):
+    sampled_case(B, oracle, synth.WORKLOADS["C2"], (0.9,), 768)
+
+
+def test_c5_entropy_stress_sampled(B, oracle):
+    sampled_case(B, oracle, synth.WORKLOADS["C5"], (0.9,), 512)
+
+
+def test_c3_p_sweep_sampled(B, oracle):
+    sampled_case(B, oracle, synth.WORKLOADS["C3"], (0.5, 0.7, 0.9, 0.99), 384)
+
+
+def test_c4_sampled(B, oracle):
+    sampled_case(B, oracle, synth.WORKLOADS["C4"], (0.9,), 192, check_dense=False)
