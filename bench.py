@@ -1,0 +1,243 @@
+#!/usr/bin/env python3
+"""Benchmark of the AdaS-Attn hot path on one MI355X.
+
+A "step" is one pass of the whole path over one synthetic batch already resident
+in HBM: cube mean-pool -> relevance scoring + Top-p selection -> KV pack ->
+sparse attention.  The default workload is the 64K-token configuration the
+headline metric is quoted on (256 frames x 16x16 tokens, cube 4x8x8, 28 query /
+4 KV heads, head_dim 128, Top-p 0.9).
+
+Prints ONE JSON line (see the field list in main()).  Besides the contract
+fields it carries
+  roofline     -- the dominant kernel (sparse attention) against bf16 MFMA peak:
+                  algorithmic FLOPs = 4 * head_dim * (attended keys summed over
+                  all query rows, from the selection actually produced) divided
+                  by the kernel's mean duration, timed with HIP events on the
+                  stream the kernels are launched on;
+  cpu_baseline -- the fp64 oracle timed on this machine's host cores on a bounded
+                  sample of the same workload (a reported baseline, not a target).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from paper_2604_08077_amd import synth  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+# HBM traffic of one sparse-attention launch (bytes), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# scaled by a copy kernel of known size; keyed by (workload, top_p).  See profiles/.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def cube_tables(w):
+    """Host-side sizes of all cubes and rank of every token (measurement bookkeeping only)."""
+    t, h, x = np.meshgrid(np.arange(w.T), np.arange(w.H), np.arange(w.W), indexing="ij")
+    nH, nW = -(-w.H // w.ch), -(-w.W // w.cw)
+    tb, hb, wb = t // w.ct, h // w.ch, x // w.cw
+    cube = ((tb * nH + hb) * nW + wb).reshape(-1)
+    eh = np.minimum(w.ch, w.H - hb * w.ch)
+    ew = np.minimum(w.cw, w.W - wb * w.cw)
+    rank = (((t - tb * w.ct) * eh + (h - hb * w.ch)) * ew + (x - wb * w.cw)).reshape(-1)
+    sizes = np.bincount(cube)
+    return cube, rank, sizes
+
+
+def attended_keys_total(w, mask, sizes, rank):
+    """Sum over all query rows of the number of attended keys, from the GPU's own selection mask."""
+    R, words = mask.shape
+    shifts = torch.arange(32, device=mask.device, dtype=torch.int32).view(1, 1, 32)
+    colsum = torch.zeros(words * 32, dtype=torch.int64, device=mask.device)
+    chunk = max(1, (1 << 25) // (words * 32))
+    for r0 in range(0, R, chunk):
+        bits = (mask[r0:r0 + chunk].unsqueeze(-1) >> shifts) & 1
+        colsum += bits.sum(dim=0, dtype=torch.int64).reshape(-1)
+    colsum = colsum[: len(sizes)].cpu().numpy()
+    selected_keys = int((colsum * sizes.astype(np.int64)).sum())
+    own_keys = int((rank.astype(np.int64) + 1).sum()) * w.Hq
+    return selected_keys + own_keys, int(colsum.sum())
+
+
+def timed(fn, n):
+    """Mean duration in ms of fn() over n launches, HIP events on the current stream."""
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(n):
+        fn()
+    ev1.record()
+    ev1.synchronize()
+    return ev0.elapsed_time(ev1) / n
+
+
+def cpu_baseline(w, p, Q, K, V, budget_rows_sel=262144, budget_rows_attn=24576):
+    """The fp64 oracle on a bounded row sample of the same workload, extrapolated to tokens/s."""
+    import oracle
+
+    osh = oracle.Shape(w.T, w.H, w.W, w.ct, w.ch, w.cw, w.Hq, w.Hkv, w.D)
+    R = w.S * w.Hq
+    t0 = time.perf_counter()
+    kbar = oracle.cube_pool(osh, K)
+    t_pool = time.perf_counter() - t0
+    rows_sel = synth.sample_rows(w, budget_rows_sel, seed=101)
+    t0 = time.perf_counter()
+    mask, _, _ = oracle.cube_select(osh, Q, kbar, p, rows=rows_sel)
+    t_sel = time.perf_counter() - t0
+    rows_att = synth.sample_rows(w, budget_rows_attn, seed=102)
+    mask_att, _, _ = oracle.cube_select(osh, Q, kbar, p, rows=rows_att)
+    t0 = time.perf_counter()
+    oracle.sparse_attn(osh, Q, K, V, mask_att, rows=rows_att)
+    t_att = time.perf_counter() - t0
+    total = t_pool + t_sel / len(rows_sel) * R + t_att / len(rows_att) * R
+    return {
+        "value": w.S / total,
+        "unit": "tokens/s",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": (f"pool on all {w.S} tokens ({t_pool:.2f}s) + select on {len(rows_sel)} of {R} rows ({t_sel:.2f}s) "
+                   f"+ attention on {len(rows_att)} of {R} rows ({t_att:.2f}s), uniform seeded row samples, "
+                   f"per-row cost scaled to all rows"),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="C3", choices=sorted(synth.WORKLOADS))
+    ap.add_argument("--top-p", type=float, default=0.9)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+
+    from paper_2604_08077_amd import binding as B
+
+    B.load()
+    w = synth.WORKLOADS[args.workload]
+    p = float(np.float32(args.top_p))
+    sh = B.Shape.of(w)
+    N = B.num_cubes(sh)
+    Q, K, V = synth.generate(w)
+    Qg, Kg, Vg = Q.cuda(), K.cuda(), V.cuda()
+    R, words = sh.rows, (N + 31) // 32
+    kbar = torch.empty((N, w.Hkv, w.D), dtype=torch.float32, device="cuda")
+    mask = torch.empty((R, words), dtype=torch.int32, device="cuda")
+    count = torch.empty((R,), dtype=torch.int32, device="cuda")
+    O = torch.empty((w.S, w.Hq, w.D), dtype=torch.bfloat16, device="cuda")
+    ws_sel = B.alloc_workspace(sh, B.CALL_CUBE_SELECT)
+    ws_att = B.alloc_workspace(sh, B.CALL_SPARSE_ATTN)
+
+    def f_pool():
+        B.cube_pool(sh, Kg, kbar)
+
+    def f_select():
+        B.cube_select(sh, Qg, kbar, p, sel_mask=mask, sel_count=count, workspace=ws_sel)
+
+    def f_pack():
+        B.kv_pack(sh, Kg, Vg, ws_att)
+
+    def f_attn():
+        B.sparse_attn_packed(sh, Qg, ws_att, mask, O=O)
+
+    def f_dense():
+        B.dense_attn_packed(sh, Qg, ws_att, O=O)
+
+    def step():
+        f_pool()
+        f_select()
+        f_pack()
+        f_attn()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-kernel means (HIP events on the launch stream), same inputs, same launch configuration
+    k_ms = {name: timed(fn, args.steps) for name, fn in
+            (("cube_pool", f_pool), ("cube_select", f_select), ("kv_pack", f_pack), ("sparse_attn", f_attn))}
+    dense_ms = None
+    if not args.no_dense:
+        f_dense()
+        torch.cuda.synchronize()
+        dense_ms = timed(f_dense, max(1, min(args.steps, 3)))
+
+    cube, rank, sizes = cube_tables(w)
+    keys_total, pairs = attended_keys_total(w, mask, sizes, rank)
+    eff_flops = 4.0 * w.D * keys_total
+    dense_keys = int((np.cumsum(np.concatenate([[0], sizes[:-1]]))[cube] + rank + 1).sum()) * w.Hq
+    dense_flops = 4.0 * w.D * dense_keys
+    preceding = int(cube.astype(np.int64).sum()) * w.Hq
+    attn_tflops = eff_flops / (k_ms["sparse_attn"] * 1e-3) / 1e12
+
+    hbm_bytes = {
+        "cube_pool": w.S * w.Hkv * w.D * 2 + N * w.Hkv * w.D * 4,
+        "cube_select": R * w.D * 2 + R * words * 4 + R * 4,
+        "kv_pack": 2 * w.S * w.Hkv * w.D * 2 + ws_att.numel(),
+    }
+    out = {
+        "metric": "AdaS-Attn tokens/s at 64K video tokens" if args.workload == "C3" else f"AdaS-Attn tokens/s ({w.name})",
+        "value": w.S / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{w.name}: {w.T}x{w.H}x{w.W} tokens={w.S}, cube {w.ct}x{w.ch}x{w.cw} ({N} cubes), "
+                        f"{w.Hq}q/{w.Hkv}kv heads, head_dim {w.D}, top_p {args.top_p}, causal, batch 1",
+            "top_p": args.top_p,
+        },
+        "effective_tflops": attn_tflops,
+        "effective_flops_per_step": eff_flops,
+        "dense_flops": dense_flops,
+        "selected_fraction_of_preceding_cubes": pairs / max(1, preceding),
+        "kernel_ms": k_ms,
+        "kernel_hbm_gbs": {k: hbm_bytes[k] / (k_ms[k] * 1e-3) / 1e9 for k in hbm_bytes},
+        "dense_attn_ms": dense_ms,
+        "dense_tflops": None if dense_ms is None else dense_flops / (dense_ms * 1e-3) / 1e12,
+        "speedup_vs_dense": None if dense_ms is None else (k_ms["kv_pack"] + dense_ms) / ms_per_step,
+        "roofline": {
+            "kernel": "attn_kernel<128,sparse>" if w.D == 128 else "attn_kernel<64,sparse>",
+            "bound": "mfma",
+            "achieved": attn_tflops,
+            "peak": PEAK_BF16_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": attn_tflops / PEAK_BF16_TFLOPS,
+            "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, args.top_p)),
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, p, Q, K, V)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

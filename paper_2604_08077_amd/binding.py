@@ -71,6 +71,9 @@ EXPORTS = (
     "adaspark_cube_select",
     "adaspark_sparse_attn",
     "adaspark_dense_attn",
+    "adaspark_kv_pack",
+    "adaspark_sparse_attn_packed",
+    "adaspark_dense_attn_packed",
 )
 
 
@@ -94,6 +97,9 @@ def load():
                                              ctypes.c_int64, vp, ctypes.c_size_t, vp]
         lib.adaspark_sparse_attn.argtypes = [sp, vp, vp, vp, vp, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
         lib.adaspark_dense_attn.argtypes = [sp, vp, vp, vp, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.adaspark_kv_pack.argtypes = [sp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.adaspark_sparse_attn_packed.argtypes = [sp, vp, vp, ctypes.c_size_t, vp, ctypes.c_int, vp, vp, vp]
+        lib.adaspark_dense_attn_packed.argtypes = [sp, vp, vp, ctypes.c_size_t, ctypes.c_int, vp, vp, vp]
         for name in EXPORTS:
             if name != "adaspark_status_string":
                 getattr(lib, name).restype = ctypes.c_int
@@ -216,3 +222,42 @@ def dense_attn(shape: Shape, Q, K, V, causal: bool = True, O=None, lse=None, wor
                return_lse: bool = False):
     """Dense causal attention in cube-major order -> O bf16 [S,Hq,D]."""
     return _attn("adaspark_dense_attn", shape, Q, K, V, None, causal, O, lse, workspace, return_lse)
+
+
+def kv_pack(shape: Shape, K, V, workspace=None) -> torch.Tensor:
+    """Gather K,V into the cube-major tiled copy the attention kernels read; returns the workspace."""
+    if workspace is None:
+        workspace = alloc_workspace(shape, CALL_SPARSE_ATTN, K.device)
+    kvn = shape.tokens * shape.kv_heads * shape.head_dim
+    cs = shape._c()
+    _check(load().adaspark_kv_pack(ctypes.byref(cs), _dev(K, torch.bfloat16, kvn, "K"), _dev(V, torch.bfloat16, kvn, "V"),
+                                   workspace.data_ptr(), workspace.numel(), _stream()), "adaspark_kv_pack")
+    return workspace
+
+
+def _attn_packed(fn_name, shape, Q, packed, sel_mask, causal, O, lse, want_lse):
+    R = shape.rows
+    if O is None:
+        O = torch.empty((shape.tokens, shape.q_heads, shape.head_dim), dtype=torch.bfloat16, device=Q.device)
+    if lse is None and want_lse:
+        lse = torch.empty((R,), dtype=torch.float32, device=Q.device)
+    if packed.device.type != "cuda":
+        raise ValueError("packed must be a GPU tensor")
+    cs = shape._c()
+    args = [ctypes.byref(cs), _dev(Q, torch.bfloat16, R * shape.head_dim, "Q"), packed.data_ptr(), packed.numel()]
+    if fn_name == "adaspark_sparse_attn_packed":
+        words = (num_cubes(shape) + 31) // 32
+        args.append(_dev(sel_mask, torch.int32, R * words, "sel_mask"))
+    args += [int(bool(causal)), _dev(O, torch.bfloat16, R * shape.head_dim, "O"),
+             None if lse is None else _dev(lse, torch.float32, R, "lse"), _stream()]
+    _check(getattr(load(), fn_name)(*args), fn_name)
+    return (O, lse) if want_lse else O
+
+
+def sparse_attn_packed(shape: Shape, Q, packed, sel_mask, causal: bool = True, O=None, lse=None,
+                       return_lse: bool = False):
+    return _attn_packed("adaspark_sparse_attn_packed", shape, Q, packed, sel_mask, causal, O, lse, return_lse)
+
+
+def dense_attn_packed(shape: Shape, Q, packed, causal: bool = True, O=None, lse=None, return_lse: bool = False):
+    return _attn_packed("adaspark_dense_attn_packed", shape, Q, packed, None, causal, O, lse, return_lse)

@@ -100,36 +100,86 @@ int adaspark_cube_select(const adaspark_shape *shape, const void *Q, const float
     return e == hipSuccess ? ADASPARK_OK : ADASPARK_EHIP;
 }
 
-static int attn_common(const adaspark_shape *shape, const void *Q, const void *K, const void *V,
-                       const uint32_t *sel_mask, bool sparse, int causal, void *O, float *lse, void *workspace,
-                       size_t workspace_bytes, void *stream)
+static int attn_check(const adaspark_shape *shape, const void *Q, const uint32_t *sel_mask, bool sparse, int causal,
+                      void *O, float *lse)
 {
     int rc = check_shape(shape);
     if (rc != ADASPARK_OK) return rc;
-    if ((rc = check_ptrs({Q, K, V, O})) != ADASPARK_OK) return rc;
+    if ((rc = check_ptrs({Q, O})) != ADASPARK_OK) return rc;
     if (sparse && (sel_mask == nullptr || !aligned16(sel_mask))) return ADASPARK_EINVAL;
     if (lse != nullptr && !aligned16(lse)) return ADASPARK_EINVAL;
     if (!causal) return ADASPARK_EUNSUPPORTED;
-    const Geom g = make_geom(*shape);
+    return ADASPARK_OK;
+}
+
+static int workspace_check(const Geom &g, const void *workspace, size_t workspace_bytes)
+{
     if (workspace == nullptr || !aligned16(workspace) || workspace_bytes < attn_workspace_bytes(g))
         return ADASPARK_EWORKSPACE;
-    const hipError_t e = launch_attn(g, static_cast<const uint16_t *>(Q), static_cast<const uint16_t *>(K),
-                                     static_cast<const uint16_t *>(V), sparse ? sel_mask : nullptr,
-                                     static_cast<uint16_t *>(O), lse, workspace, static_cast<hipStream_t>(stream));
+    return ADASPARK_OK;
+}
+
+int adaspark_kv_pack(const adaspark_shape *shape, const void *K, const void *V, void *workspace,
+                     size_t workspace_bytes, void *stream)
+{
+    int rc = check_shape(shape);
+    if (rc != ADASPARK_OK) return rc;
+    if ((rc = check_ptrs({K, V})) != ADASPARK_OK) return rc;
+    const Geom g = make_geom(*shape);
+    if ((rc = workspace_check(g, workspace, workspace_bytes)) != ADASPARK_OK) return rc;
+    const hipError_t e = launch_kv_pack(g, static_cast<const uint16_t *>(K), static_cast<const uint16_t *>(V), workspace,
+                                        static_cast<hipStream_t>(stream));
     return e == hipSuccess ? ADASPARK_OK : ADASPARK_EHIP;
+}
+
+static int attn_packed(const adaspark_shape *shape, const void *Q, const void *packed, size_t packed_bytes,
+                       const uint32_t *sel_mask, bool sparse, int causal, void *O, float *lse, void *stream)
+{
+    int rc = attn_check(shape, Q, sel_mask, sparse, causal, O, lse);
+    if (rc != ADASPARK_OK) return rc;
+    const Geom g = make_geom(*shape);
+    if ((rc = workspace_check(g, packed, packed_bytes)) != ADASPARK_OK) return rc;
+    const hipError_t e = launch_attn(g, static_cast<const uint16_t *>(Q), packed, sparse ? sel_mask : nullptr,
+                                     static_cast<uint16_t *>(O), lse, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ADASPARK_OK : ADASPARK_EHIP;
+}
+
+int adaspark_sparse_attn_packed(const adaspark_shape *shape, const void *Q, const void *packed, size_t packed_bytes,
+                                const uint32_t *sel_mask, int causal, void *O, float *lse, void *stream)
+{
+    return attn_packed(shape, Q, packed, packed_bytes, sel_mask, true, causal, O, lse, stream);
+}
+
+int adaspark_dense_attn_packed(const adaspark_shape *shape, const void *Q, const void *packed, size_t packed_bytes,
+                               int causal, void *O, float *lse, void *stream)
+{
+    return attn_packed(shape, Q, packed, packed_bytes, nullptr, false, causal, O, lse, stream);
+}
+
+static int attn_full(const adaspark_shape *shape, const void *Q, const void *K, const void *V,
+                     const uint32_t *sel_mask, bool sparse, int causal, void *O, float *lse, void *workspace,
+                     size_t workspace_bytes, void *stream)
+{
+    // validate everything before the first launch
+    int rc = attn_check(shape, Q, sel_mask, sparse, causal, O, lse);
+    if (rc != ADASPARK_OK) return rc;
+    if ((rc = check_ptrs({K, V})) != ADASPARK_OK) return rc;
+    if ((rc = workspace_check(make_geom(*shape), workspace, workspace_bytes)) != ADASPARK_OK) return rc;
+    if ((rc = adaspark_kv_pack(shape, K, V, workspace, workspace_bytes, stream)) != ADASPARK_OK) return rc;
+    return attn_packed(shape, Q, workspace, workspace_bytes, sel_mask, sparse, causal, O, lse, stream);
 }
 
 int adaspark_sparse_attn(const adaspark_shape *shape, const void *Q, const void *K, const void *V,
                          const uint32_t *sel_mask, int causal, void *O, float *lse, void *workspace,
                          size_t workspace_bytes, void *stream)
 {
-    return attn_common(shape, Q, K, V, sel_mask, true, causal, O, lse, workspace, workspace_bytes, stream);
+    return attn_full(shape, Q, K, V, sel_mask, true, causal, O, lse, workspace, workspace_bytes, stream);
 }
 
 int adaspark_dense_attn(const adaspark_shape *shape, const void *Q, const void *K, const void *V, int causal, void *O,
                         float *lse, void *workspace, size_t workspace_bytes, void *stream)
 {
-    return attn_common(shape, Q, K, V, nullptr, false, causal, O, lse, workspace, workspace_bytes, stream);
+    return attn_full(shape, Q, K, V, nullptr, false, causal, O, lse, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

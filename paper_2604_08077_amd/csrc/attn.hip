@@ -258,12 +258,20 @@ size_t attn_workspace_bytes(const Geom &g)
 }
 
 template <int D>
-static hipError_t launch_attn_d(const Geom &g, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
-                                const uint32_t *sel_mask, uint16_t *O, float *lse, void *ws, hipStream_t st)
+static hipError_t launch_pack_d(const Geom &g, const uint16_t *K, const uint16_t *V, void *ws, hipStream_t st)
 {
     uint16_t *Kp = reinterpret_cast<uint16_t *>(ws);
     uint16_t *Vt = Kp + (size_t)g.Hkv * g.N * g.TPC * KEY_TILE * D;
     hipLaunchKernelGGL((kv_pack_kernel<D>), dim3(g.TPC, g.N, g.Hkv), dim3(256), 0, st, g, K, V, Kp, Vt);
+    return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_attn_d(const Geom &g, const uint16_t *Q, const void *packed, const uint32_t *sel_mask,
+                                uint16_t *O, float *lse, hipStream_t st)
+{
+    const uint16_t *Kp = reinterpret_cast<const uint16_t *>(packed);
+    const uint16_t *Vt = Kp + (size_t)g.Hkv * g.N * g.TPC * KEY_TILE * D;
     const int chunks_per_cube = (g.Cmax + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
     const dim3 grid((unsigned)((size_t)g.N * g.Hq * chunks_per_cube));
     if (sel_mask != nullptr)
@@ -273,11 +281,17 @@ static hipError_t launch_attn_d(const Geom &g, const uint16_t *Q, const uint16_t
     return hipGetLastError();
 }
 
-hipError_t launch_attn(const Geom &g, const uint16_t *Q, const uint16_t *K, const uint16_t *V, const uint32_t *sel_mask,
-                       uint16_t *O, float *lse, void *ws, hipStream_t st)
+hipError_t launch_kv_pack(const Geom &g, const uint16_t *K, const uint16_t *V, void *ws, hipStream_t st)
 {
-    if (g.D == 64) return launch_attn_d<64>(g, Q, K, V, sel_mask, O, lse, ws, st);
-    return launch_attn_d<128>(g, Q, K, V, sel_mask, O, lse, ws, st);
+    if (g.D == 64) return launch_pack_d<64>(g, K, V, ws, st);
+    return launch_pack_d<128>(g, K, V, ws, st);
+}
+
+hipError_t launch_attn(const Geom &g, const uint16_t *Q, const void *packed, const uint32_t *sel_mask, uint16_t *O,
+                       float *lse, hipStream_t st)
+{
+    if (g.D == 64) return launch_attn_d<64>(g, Q, packed, sel_mask, O, lse, st);
+    return launch_attn_d<128>(g, Q, packed, sel_mask, O, lse, st);
 }
 
 }  // namespace adaspark

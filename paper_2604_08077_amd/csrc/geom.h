@@ -85,7 +85,9 @@ hipError_t launch_cube_select(const Geom &g, const uint16_t *Q, const float *kba
                               int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx, int64_t capacity, void *ws,
                               hipStream_t st);
 size_t attn_workspace_bytes(const Geom &g);
-hipError_t launch_attn(const Geom &g, const uint16_t *Q, const uint16_t *K, const uint16_t *V, const uint32_t *sel_mask,
-                       uint16_t *O, float *lse, void *ws, hipStream_t st);
+hipError_t launch_kv_pack(const Geom &g, const uint16_t *K, const uint16_t *V, void *ws, hipStream_t st);
+// sel_mask == nullptr: dense (every preceding cube attended)
+hipError_t launch_attn(const Geom &g, const uint16_t *Q, const void *packed, const uint32_t *sel_mask, uint16_t *O,
+                       float *lse, hipStream_t st);
 
 }  // namespace adaspark
