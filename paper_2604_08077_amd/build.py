@@ -23,6 +23,7 @@ HIPCC_FLAGS = [
     "-fPIC",
     "-Wall",
     "-Wno-unused-result",
+    "-Wno-inline-asm",
     # packed-fp32 instruction selection is switched off for all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]

@@ -5,22 +5,21 @@
 // mask-based tile kernel would execute dense FLOPs.  Here a workgroup owns up to MMAX query rows of one
 // (query cube i, KV head) -- all query heads of the GQA group, token-major -- and keeps their online-softmax
 // state (fp32 O, m, l) in LDS (MI355X: 160 KB per CU).  It walks the key cubes j <= i that any of its rows
-// attends.  For each cube
-//   1. every wavefront ballots the selection bits of all rows and so knows the (sorted) list of rows that
-//      attend j (dense mode, own cube: all rows); no LDS list and no extra barrier are needed,
-//   2. the list is cut into 16-row slabs, dealt round-robin to the eight wavefronts (two per SIMD, so one
-//      wavefront's softmax can overlap the other's MFMA),
+// attends.  The rows are split into two halves, each served by four wavefronts (one per SIMD).  For each cube
+//   1. every wavefront ballots the selection bits of its half's rows and so knows the (sorted) list of rows
+//      that attend j (dense mode, own cube: all rows); no extra barrier is needed,
+//   2. the list is cut into 16-row slabs, dealt round-robin to the half's wavefronts,
 //   3. per slab the Q operands are gathered (prefetched under the previous cube's last tile), the rows' state
 //      moves from LDS into MFMA accumulators, flash attention runs over the cube's 64-key tiles with
 //      mfma_f32_16x16x32_bf16 (S^T = K.Q^T, O^T += V^T.P^T: a lane owns one query row and a quarter of the
 //      keys of a tile), and the state moves back.
-// Executed MFMA work is the selected (row, cube) pairs rounded up to 16 rows per workgroup and cube.  In dense
-// mode the row set never changes and the state stays in registers.
+// Executed MFMA work is the selected (row, cube) pairs rounded up to 16 rows per half and cube.  In dense mode
+// the row set never changes and the state stays in registers.
 //
-// K and V^T tiles come from the packed, pre-swizzled copy (kvtile.h).  The tile stream K0 V0 K1 V1 ... rotates
-// through three LDS buffers; a tile is fetched into registers two phases before it is needed and written to
-// the buffer that was read two phases ago, so one barrier per phase (two per key tile) is enough and no wave
-// ever waits on a load it has just issued.
+// K and V^T tiles come from the packed, pre-swizzled copy (kvtile.h) by direct-to-LDS loads.  The tile stream
+// K0 V0 K1 V1 ... rotates through four LDS buffers; a tile is requested two phases before it is needed.  The two
+// halves run one phase apart: on every SIMD one wavefront is in its S^T + softmax phase while the other runs its
+// P.V MFMAs.
 #include <type_traits>
 
 #include "kvtile.h"
@@ -29,44 +28,77 @@ namespace adaspark {
 
 constexpr int FWD_WAVES = 8;  // two wavefronts per SIMD
 constexpr int FWD_THREADS = 64 * FWD_WAVES;
-constexpr int FWD_NS = 2;     // 16-row slabs a wavefront works on at a time
+constexpr int FWD_NS = 2;  // 16-row slabs a wavefront works on at a time
 
 template <int D, bool SPARSE>
 struct Fwd {
     static constexpr int WAVES = FWD_WAVES;
+    static constexpr int HWAVES = WAVES / 2;  // wavefronts per half
     static constexpr int THREADS = FWD_THREADS;
     static constexpr int NS = FWD_NS;
-    static constexpr int MMAX = SPARSE ? 192 : 16 * NS * WAVES;  // rows per workgroup (sparse: what LDS can hold)
-    static constexpr int GROUPS = (MMAX + 63) / 64;              // 64-row ballot groups
+    static constexpr int MMAX = SPARSE ? 168 : 16 * NS * WAVES;  // rows per workgroup (sparse: what LDS can hold)
+    static constexpr int GROUPS = (MMAX / 2 + 63) / 64;          // 64-row ballot groups of a half
     static constexpr int CHUNK = KEY_TILE * D * 2;               // bytes of a K tile (= bytes of a V^T tile)
-    static constexpr int CPT = CHUNK / 16 / THREADS;             // 16-byte pieces of a tile per thread
+    static constexpr int NBUF = 4;                               // LDS buffers the tile stream rotates through
+    static constexpr int DMA = CHUNK / 1024 / WAVES;             // 1 KB direct-to-LDS loads per wavefront and tile
     static constexpr int OST = D + 4;  // floats per state row (padded: 16 rows start in 16 different bank groups)
     static constexpr int SMALL = (((MMAX + 1) * 4 + 15) / 16) * 16;
     static constexpr int OFF_KV = 0;
-    static constexpr int OFF_ROWID = OFF_KV + 3 * CHUNK;
+    static constexpr int OFF_ROWID = OFF_KV + NBUF * CHUNK;
     static constexpr int OFF_RANK = OFF_ROWID + SMALL;
-    static constexpr int OFF_UMASK = OFF_RANK + SMALL;
-    static constexpr int OFF_M = OFF_UMASK + (ADASPARK_MAX_CUBES / 32) * 4;
+    static constexpr int OFF_MISC = OFF_RANK + SMALL;  // 16 bytes of workgroup scalars
+    static constexpr int OFF_UMASK = OFF_MISC + 16;
+    static constexpr int OFF_LIST = OFF_UMASK + (ADASPARK_MAX_CUBES / 32) * 4;  // per wavefront: 64*GROUPS bytes
+    static constexpr int OFF_CUBES = OFF_LIST + WAVES * 64 * GROUPS;            // attended cubes, u16 each
+    static constexpr int OFF_M = OFF_CUBES + ADASPARK_MAX_CUBES * 2;
     static constexpr int OFF_L = OFF_M + SMALL;
     static constexpr int OFF_O = OFF_L + SMALL;
-    static constexpr int BYTES = SPARSE ? OFF_O + (MMAX + 1) * OST * 4 : OFF_M;
-    static_assert(MMAX <= 16 * NS * WAVES, "every attending row needs a slab");
-    static_assert(CPT >= 1, "tile smaller than one 16-byte piece per thread");
+    static constexpr int BYTES = SPARSE ? OFF_O + (MMAX + 1) * OST * 4 : OFF_UMASK;
+    static_assert(MMAX <= 16 * NS * WAVES && MMAX % 2 == 0, "every attending row needs a slab");
+    static_assert(DMA >= 1 && DMA <= 2, "phase_barrier() leaves DMA loads in flight: keep the two in step");
+    static_assert(BYTES <= 160 * 1024, "LDS of one CU");
 };
 
-// waits for this wavefront's LDS traffic, then the workgroup barrier; global loads in flight stay in flight
-__device__ __forceinline__ void lds_barrier()
+// Phase barrier.  Waits for this wavefront's LDS traffic and for all but its youngest N vector-memory operations
+// (the direct-to-LDS loads issued in the phase that is ending stay in flight; older ones have landed), then the
+// workgroup barrier.
+template <int N>
+__device__ __forceinline__ void phase_barrier()
 {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    if constexpr (N == 2) asm volatile("s_waitcnt vmcnt(2) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(1) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// One wavefront copies 1 KB from global memory straight into LDS: lane l moves the 16 bytes at src (its own
+// address) to lds_addr + 16*l.  lds_addr is wave-uniform.  Completion is counted by vmcnt like any vector load.
+__device__ __forceinline__ void dma_1k(uint32_t lds_addr, const void *src)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(src)
+                 : "memory", "m0");
+}
+
+// Plain hardware max.  fmaxf() would first canonicalise each operand (one extra instruction per MFMA result);
+// the scores are never signalling NaNs, and -inf (masked keys) orders as it should.
+__device__ __forceinline__ float vmax(float a, float b)
+{
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ float vmax3(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
 }
 
 // max / sum over the four lanes {n, n+16, n+32, n+48} that share a query row
 __device__ __forceinline__ float quad_max(float x)
 {
     const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    const float y = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    const float y = vmax(__uint_as_float(a[0]), __uint_as_float(a[1]));
     const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(y), __float_as_uint(y), false, false);
-    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+    return vmax(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 __device__ __forceinline__ float quad_sum(float x)
 {
@@ -74,20 +106,6 @@ __device__ __forceinline__ float quad_sum(float x)
     const float y = __uint_as_float(a[0]) + __uint_as_float(a[1]);
     const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(y), __float_as_uint(y), false, false);
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
-}
-
-// Position of the k-th (0-based) set bit of m; k < popcount(m).
-__device__ __forceinline__ int kth_set_bit(unsigned long long m, int k)
-{
-    int pos = 0;
-#pragma unroll
-    for (int w = 32; w > 0; w >>= 1) {
-        const unsigned long long low = m & ((1ull << w) - 1ull);
-        const int c = __popcll(low);
-        if (k >= c) { k -= c; m >>= w; pos += w; }
-        else m = low;
-    }
-    return pos;
 }
 
 // S^T = K.Q^T for one 64-key tile and slabs S0..S1-1 of a wavefront.  MFMA M-row m of key group kg carries
@@ -130,21 +148,31 @@ __device__ __forceinline__ void softmax_tile(f32x4 (&sacc)[NS][4], bf16x8 (&pf)[
                     if (kr > lim[s]) sacc[s][kg][v] = -INFINITY;
                 }
         }
-        float mx = fmaxf(fmaxf(sacc[s][0][0], sacc[s][0][1]), fmaxf(sacc[s][0][2], sacc[s][0][3]));
-#pragma unroll
-        for (int kg = 1; kg < 4; ++kg)
-            mx = fmaxf(fmaxf(mx, fmaxf(sacc[s][kg][0], sacc[s][kg][1])), fmaxf(sacc[s][kg][2], sacc[s][kg][3]));
+        float mx = vmax3(sacc[s][0][0], sacc[s][0][1], sacc[s][0][2]);
+        mx = vmax3(mx, sacc[s][0][3], sacc[s][1][0]);
+        mx = vmax3(mx, sacc[s][1][1], sacc[s][1][2]);
+        mx = vmax3(mx, sacc[s][1][3], sacc[s][2][0]);
+        mx = vmax3(mx, sacc[s][2][1], sacc[s][2][2]);
+        mx = vmax3(mx, sacc[s][2][3], sacc[s][3][0]);
+        mx = vmax3(mx, sacc[s][3][1], sacc[s][3][2]);
+        mx = vmax(mx, sacc[s][3][3]);
         mx = quad_max(mx);
-        const float m_new = fmaxf(m_run[s], mx * c2);
+        const float m_new = vmax(m_run[s], mx * c2);
         const float alpha = __builtin_amdgcn_exp2f(m_run[s] - m_new);
-        float rs = 0.f;
 #pragma unroll
         for (int kg = 0; kg < 4; ++kg)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(sacc[s][kg][v], c2, -m_new));
-                rs += p;
-                pf[s][kg >> 1][4 * (kg & 1) + v] = (__bf16)p;
+            for (int v = 0; v < 4; ++v)
+                pf[s][kg >> 1][4 * (kg & 1) + v] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[s][kg][v], c2, -m_new));
+        // the row sum is taken over the rounded probabilities, the very weights P.V uses, two per instruction
+        float rs = 0.f;
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const bf16x2 pr = {pf[s][sl][2 * t], pf[s][sl][2 * t + 1]};
+                rs = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs, false);
             }
         rs = quad_sum(rs);
         l_run[s] = l_run[s] * alpha + rs;
@@ -174,7 +202,8 @@ __device__ __forceinline__ void pv_tile(const unsigned char *vt, int n16, int q4
 }
 
 struct TilePos {
-    int j;   // key cube (> i: past the end)
+    int k;   // position in the workgroup's list of attended cubes
+    int j;   // the cube
     int t;   // 64-key tile inside the cube
     int nt;  // tiles of cube j this workgroup reads
 };
@@ -182,24 +211,29 @@ struct TilePos {
 template <int D, bool SPARSE>
 __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(
     Geom g, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Kp, const uint16_t *__restrict__ Vt,
-    const uint32_t *__restrict__ sel_mask, uint16_t *__restrict__ O, float *__restrict__ lse)
+    const int32_t *__restrict__ csize, const uint32_t *__restrict__ sel_mask, uint16_t *__restrict__ O,
+    float *__restrict__ lse)
 {
     using C = Fwd<D, SPARSE>;
-    constexpr int NS = C::NS, MMAX = C::MMAX, OST = C::OST, CPT = C::CPT, THREADS = C::THREADS;
-    constexpr int WAVES = C::WAVES, GROUPS = C::GROUPS;
+    constexpr int NS = C::NS, MMAX = C::MMAX, OST = C::OST, THREADS = C::THREADS;
+    constexpr int HWAVES = C::HWAVES, GROUPS = C::GROUPS;
     constexpr int KSTEPS = D / 32;  // MFMA k-steps of S^T (32 head-dim elements each)
     constexpr int DT = D / 16;      // 16-wide tiles of O^T
     extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
     unsigned char *kvbuf = smem + C::OFF_KV;
     int *rowid = reinterpret_cast<int *>(smem + C::OFF_ROWID);
     int *rrank = reinterpret_cast<int *>(smem + C::OFF_RANK);
+    int *misc = reinterpret_cast<int *>(smem + C::OFF_MISC);
     uint32_t *umask = reinterpret_cast<uint32_t *>(smem + C::OFF_UMASK);
+    uint16_t *cubes = reinterpret_cast<uint16_t *>(smem + C::OFF_CUBES);
     float *mst = reinterpret_cast<float *>(smem + C::OFF_M);
     float *lst = reinterpret_cast<float *>(smem + C::OFF_L);
     float *ost = reinterpret_cast<float *>(smem + C::OFF_O);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n16 = lane & 15, q4 = lane >> 4;
+    const int half = wave / HWAVES, hw = wave % HWAVES;  // half-workgroup, wavefront inside it (one per SIMD)
+    unsigned char *clist = smem + C::OFF_LIST + wave * 64 * GROUPS;  // this wavefront's list of attending rows
 
     // workgroup -> (query cube, KV head, row block).  The row blocks of one (cube, KV head) stream the same K/V
     // tiles, so they are placed on the same XCD (hardware deals consecutive workgroup ids round-robin to the
@@ -220,6 +254,11 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(
     const int row0 = (int)((long long)blk * P / nblk), row1 = (int)((long long)(blk + 1) * P / nblk);
     const int Mrows = row1 - row0;
     const int max_rank = (row1 - 1) / g.G;
+    const int own_tiles = min((qsize + KEY_TILE - 1) / KEY_TILE, max_rank / KEY_TILE + 1);
+    // rows [hbase, hbase + hrows) of the workgroup belong to this half
+    const int hsplit = (Mrows + 1) / 2;
+    const int hbase = half ? hsplit : 0;
+    const int hrows = half ? Mrows - hsplit : hsplit;
 
     for (int r = tid; r < Mrows; r += THREADS) {
         const int rho = row0 + r, rank = rho / g.G, hg = rho % g.G;
@@ -234,17 +273,15 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(
         }
     }
     if (SPARSE) {
-        for (int x = tid; x < (MMAX + 1) * OST; x += THREADS) ost[x] = 0.f;
+        for (int x = tid; x < (MMAX + 1) * OST / 4; x += THREADS)
+            reinterpret_cast<f32x4 *>(ost)[x] = f32x4{0.f, 0.f, 0.f, 0.f};
         for (int w = tid; w < g.words; w += THREADS) umask[w] = 0;
     }
+    if (tid == 0) misc[0] = 0;
     __syncthreads();
-    // every wavefront tracks the selection bits of all rows: lane l speaks for rows l, l+64, ...
-    int mrid[GROUPS];  // global row id behind (group, lane); -1: no such row
-#pragma unroll
-    for (int gq = 0; gq < GROUPS; ++gq) {
-        const int r = 64 * gq + lane;
-        mrid[gq] = r < Mrows ? rowid[r] : -1;
-    }
+
+    // ---- the cubes this workgroup attends (union over its rows), in order; the own cube i is always last
+    int ncubes = i + 1;
     if (SPARSE) {
         for (int r = tid; r < Mrows; r += THREADS) {
             const uint32_t *mr = sel_mask + (size_t)rowid[r] * g.words;
@@ -254,59 +291,95 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(
             }
         }
         __syncthreads();
+        // word w holds cubes 32w..32w+31; only cubes below i count
+        auto below_i = [&](int w) -> uint32_t {
+            const int lo = 32 * w;
+            const uint32_t keep = i >= lo + 32 ? 0xffffffffu : (i > lo ? (1u << (i - lo)) - 1u : 0u);
+            return umask[w] & keep;
+        };
+        for (int w = tid; w < g.words; w += THREADS) {
+            int base = 0;
+            for (int w2 = 0; w2 < w; ++w2) base += __popc(below_i(w2));
+            uint32_t bits = below_i(w);
+            while (bits) {
+                const int b = __ffs(bits) - 1;
+                bits &= bits - 1;
+                cubes[base++] = (uint16_t)(32 * w + b);
+            }
+        }
+        int nsel = 0;
+        for (int w = 0; w < g.words; ++w) nsel += __popc(below_i(w));
+        if (tid == 0) cubes[nsel] = (uint16_t)i;
+        ncubes = nsel + 1;
+        __syncthreads();
     }
-
-    // ---- the tile stream of this workgroup
+    auto cube_at = [&](int k) -> int {
+        return SPARSE ? __builtin_amdgcn_readfirstlane((int)cubes[k]) : k;
+    };
     auto tiles_of = [&](int j) -> int {
-        if (j == i) return min((qsize + KEY_TILE - 1) / KEY_TILE, max_rank / KEY_TILE + 1);
-        return (cube_box(g, j).size() + KEY_TILE - 1) / KEY_TILE;
+        if (j == i) return own_tiles;
+        return g.ragged ? (csize[j] + KEY_TILE - 1) / KEY_TILE : g.TPC;
     };
-    // next key cube after j that some row of this workgroup attends (the own cube i always is); i+1: none
-    auto next_cube = [&](int j) -> int {
-        if (!SPARSE) return j + 1;
-        int c = j + 1;
-        while (c < i) {
-            const uint32_t w = umask[c >> 5] >> (c & 31);
-            if (w) return min(c + __ffs(w) - 1, i);
-            c = (c | 31) + 1;
+    // length of the tile stream
+    {
+        int part = 0;
+        for (int k = tid; k < ncubes; k += THREADS) part += tiles_of(SPARSE ? (int)cubes[k] : k);
+        for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
+        if (lane == 0) atomicAdd(&misc[0], part);
+        __syncthreads();
+    }
+    const int ntiles = __builtin_amdgcn_readfirstlane(misc[0]);
+
+    auto first_tile = [&]() -> TilePos {
+        TilePos p;
+        p.k = 0;
+        p.j = cube_at(0);
+        p.t = 0;
+        p.nt = tiles_of(p.j);
+        return p;
+    };
+    auto advance = [&](TilePos &p) __attribute__((always_inline)) {
+        if (p.t + 1 < p.nt) ++p.t;
+        else if (p.k + 1 < ncubes) {
+            ++p.k;
+            p.j = cube_at(p.k);
+            p.t = 0;
+            p.nt = tiles_of(p.j);
+        } else {
+            p.k = ncubes;  // past the end
         }
-        return j < i ? i : i + 1;
     };
-    auto advance = [&](const TilePos &p) -> TilePos {
-        TilePos n;
-        if (p.t + 1 < p.nt) { n.j = p.j; n.t = p.t + 1; n.nt = p.nt; }
-        else {
-            n.j = next_cube(p.j);
-            n.t = 0;
-            n.nt = n.j <= i ? tiles_of(n.j) : 0;
+    // this wavefront's share of a tile: DMA pieces of 1 KB, lane l moves 16 bytes
+    auto issue = [&](const uint16_t *base, const TilePos &p, int buf) __attribute__((always_inline)) {
+        const unsigned char *src = reinterpret_cast<const unsigned char *>(
+            base + ((((size_t)kv * g.N + p.j) * g.TPC) + p.t) * (size_t)(KEY_TILE * D));
+#pragma unroll
+        for (int u = 0; u < C::DMA; ++u) {
+            const int piece = wave * C::DMA + u;
+            const uint32_t dst = __builtin_amdgcn_readfirstlane(
+                (uint32_t)(uintptr_t)(kvbuf + buf * C::CHUNK + piece * 1024));
+            dma_1k(dst, src + piece * 1024 + lane * 16);
         }
-        return n;
-    };
-    auto tile_ptr = [&](const uint16_t *base, const TilePos &p) -> const u32x4 * {
-        return reinterpret_cast<const u32x4 *>(base + ((((size_t)kv * g.N + p.j) * g.TPC) + p.t) * (size_t)(KEY_TILE * D));
-    };
-    auto fetch = [&](u32x4 (&r)[CPT], const u32x4 *src) {
-#pragma unroll
-        for (int u = 0; u < CPT; ++u) r[u] = src[tid + THREADS * u];
-    };
-    auto stash = [&](const u32x4 (&r)[CPT], int buf) {
-        u32x4 *dst = reinterpret_cast<u32x4 *>(kvbuf + buf * C::CHUNK);
-#pragma unroll
-        for (int u = 0; u < CPT; ++u) dst[tid + THREADS * u] = r[u];
     };
 
-    // ---- slabs of this wavefront for cube j.  The rows that attend j, in row order, are cut into 16-row slabs;
-    // slab k goes to wavefront k % WAVES as its slot k / WAVES.  lr[s]: workgroup row in column n16 of slot s
-    // (MMAX: padding column); ns: slots in use; lo/hi: smallest/largest rank among the wavefront's rows.
+    // ---- slabs of this wavefront for cube j.  The rows of the half that attend j, in row order, are cut into
+    // 16-row slabs; slab k goes to the half's wavefront k % HWAVES as its slot k / HWAVES.  lr[s]: workgroup row
+    // in column n16 of slot s (MMAX: padding column); ns: slots in use; lo/hi: smallest/largest rank among the
+    // wavefront's rows (own cube only).
+    int mrid[GROUPS];  // global row id behind (group, lane) of this half; -1: no such row
+#pragma unroll
+    for (int gq = 0; gq < GROUPS; ++gq) {
+        const int r = 64 * gq + lane;
+        mrid[gq] = r < hrows ? rowid[hbase + r] : -1;
+    }
     int cw = -1;  // mask word index cached in wbits
     uint32_t wbits[GROUPS];
 #pragma unroll
     for (int gq = 0; gq < GROUPS; ++gq) wbits[gq] = 0;
-    auto slab_rows = [&](int j, int (&lr)[NS], int &ns, int &lo, int &hi) {
+    auto slab_rows = [&](int j, int (&lr)[NS], int &ns, int &lo, int &hi) __attribute__((always_inline)) {
         int total;
-        unsigned long long bal[GROUPS];
         const bool all = !SPARSE || j == i;
-        if (all) total = Mrows;
+        if (all) total = hrows;
         else {
             if ((j >> 5) != cw) {
                 cw = j >> 5;
@@ -314,68 +387,63 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(
                 for (int gq = 0; gq < GROUPS; ++gq)
                     wbits[gq] = mrid[gq] >= 0 ? sel_mask[(size_t)mrid[gq] * g.words + cw] : 0u;
             }
+            // every attending row writes its index (inside the half) at its position in the list: the number
+            // of attending rows below it.  The list is private to the wavefront: no barrier.
             total = 0;
 #pragma unroll
             for (int gq = 0; gq < GROUPS; ++gq) {
-                bal[gq] = __ballot((wbits[gq] >> (j & 31)) & 1u);
-                total += __popcll(bal[gq]);
+                const bool sel = (wbits[gq] >> (j & 31)) & 1u;
+                const unsigned long long bal = __ballot(sel);
+                const int below = __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32),
+                                                            __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0));
+                if (sel) clist[total + below] = (unsigned char)(64 * gq + lane);
+                total += __popcll(bal);
             }
         }
         const int nslab = (total + 15) >> 4;
-        ns = nslab > wave ? (nslab - wave + WAVES - 1) / WAVES : 0;
+        ns = nslab > hw ? (nslab - hw + HWAVES - 1) / HWAVES : 0;
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            int idx = 16 * (wave + WAVES * s) + n16;
+            const int idx = 16 * (hw + HWAVES * s) + n16;
             int r = MMAX;
-            if (idx < total) {
-                if (all) r = idx;
-                else {
-                    int base = 0;
-#pragma unroll
-                    for (int gq = 0; gq < GROUPS; ++gq) {
-                        const int c = __popcll(bal[gq]);
-                        if (r == MMAX) {
-                            if (idx < c) r = base + kth_set_bit(bal[gq], idx);
-                            else { idx -= c; base += 64; }
-                        }
-                    }
-                }
-            }
+            if (idx < total) r = hbase + (all ? idx : (int)clist[idx]);
             lr[s] = r;
         }
         // rows are sorted by rank: the first column of slot 0 and the last used column of the last slot bound them
         lo = hi = 0;
         if (all && ns > 0) {
-            lo = rrank[16 * wave];
-            hi = rrank[min(16 * (wave + WAVES * (ns - 1)) + 15, total - 1)];
+            lo = rrank[hbase + 16 * hw];
+            hi = rrank[hbase + min(16 * (hw + HWAVES * (ns - 1)) + 15, total - 1)];
         }
     };
-    auto load_q = [&](const int (&lr)[NS], int ns, bf16x8 (&qf)[NS][KSTEPS]) {
+    // Q operands of one slab: lane (n16, q4) takes head-dim elements 32c + 8*q4 .. +7 of its column's row
+    auto load_q = [&](int row, bf16x8 (&q)[KSTEPS]) __attribute__((always_inline)) {
+        const uint16_t *qrow = Q + (size_t)rowid[row] * D + 8 * q4;
 #pragma unroll
-        for (int s = 0; s < NS; ++s)
-            if (s < ns) {
-                const uint16_t *qrow = Q + (size_t)rowid[lr[s]] * D + 8 * q4;
+        for (int c = 0; c < KSTEPS; ++c) q[c] = *reinterpret_cast<const bf16x8 *>(qrow + 32 * c);
+    };
+    // The compiler places the wait for a load in front of the first use of its result.  Naming the registers
+    // here puts that wait here, once, instead of in front of every S^T of the main loop (where it would also
+    // hold up the direct-to-LDS loads in flight).
+    auto settle_q = [&](bf16x8 (&q)[KSTEPS]) __attribute__((always_inline)) {
 #pragma unroll
-                for (int c = 0; c < KSTEPS; ++c) qf[s][c] = *reinterpret_cast<const bf16x8 *>(qrow + 32 * c);
-            }
+        for (int c = 0; c < KSTEPS; ++c) asm volatile("" : "+v"(q[c]));
     };
 
     const float c2 = 1.44269504088896340736f / sqrtf((float)D);
 
-    TilePos cur, nxt;
-    cur.j = SPARSE ? next_cube(-1) : 0;
-    cur.t = 0;
-    cur.nt = tiles_of(cur.j);
-    nxt = advance(cur);
-
-    u32x4 gk[CPT], gv[CPT];
-    fetch(gk, tile_ptr(Kp, cur));
-    fetch(gv, tile_ptr(Vt, cur));
+    TilePos sc = first_tile();  // staging cursor: the tile whose K and V^T are being brought in
+    TilePos cc = sc;            // compute cursor of this wavefront
+    issue(Kp, sc, 0);           // chunk 0
+    issue(Vt, sc, 1);           // chunk 1
 
     int lr[NS], ns, rank_lo, rank_hi;
     bf16x8 qf[NS][KSTEPS];
-    slab_rows(cur.j, lr, ns, rank_lo, rank_hi);
-    load_q(lr, ns, qf);
+    slab_rows(cc.j, lr, ns, rank_lo, rank_hi);
+#pragma unroll
+    for (int s = 0; s < NS; ++s) load_q(lr[s], qf[s]);
+#pragma unroll
+    for (int s = 0; s < NS; ++s) settle_q(qf[s]);
 
     // online-softmax state of the slabs being worked on
     int lim[NS];
@@ -388,13 +456,14 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(
 #pragma unroll
         for (int e = 0; e < DT; ++e) oacc[s][e] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    auto set_limits = [&](int j) {
+    auto set_limits = [&](int j) __attribute__((always_inline)) -> int {
         const bool own = (j == i);
-        const int jsize = own ? qsize : cube_box(g, j).size();
+        const int jsize = own ? qsize : (g.ragged ? csize[j] : g.Cmax);
 #pragma unroll
         for (int s = 0; s < NS; ++s) lim[s] = own ? min(rrank[lr[s]], jsize - 1) : jsize - 1;
+        return jsize;
     };
-    auto state_in = [&]() {
+    auto state_in = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int s = 0; s < NS; ++s)
             if (s < ns) {
@@ -405,7 +474,7 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(
                     oacc[s][e] = *reinterpret_cast<const f32x4 *>(&ost[lr[s] * OST + 16 * e + 4 * q4]);
             }
     };
-    auto state_out = [&]() {
+    auto state_out = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int s = 0; s < NS; ++s)
             if (s < ns) {
@@ -418,90 +487,117 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(
                 }
             }
     };
-    set_limits(cur.j);  // first cube: the state registers already hold the initial state
+    int jsize = set_limits(cc.j);  // first cube: the state registers already hold the initial state
+    bool new_slabs = false;        // the slabs changed at the last cube boundary: their state is still in LDS
+    int lr_n[NS], ns_n = 0, lo_n = 0, hi_n = 0;
+    bf16x8 qf_n[KSTEPS];
+    f32x4 sacc[NS][4];
+    bf16x8 pf[NS][2];
 
-    stash(gk, 0);
-    if (nxt.j <= i) fetch(gk, tile_ptr(Kp, nxt));
-    int bk = 0;             // LDS buffer of K(cur); V(cur) -> bk+1, K(nxt) -> bk+2 (mod 3)
-    bool new_slabs = false;  // the slabs changed at the last cube boundary: their state is still in LDS
-
-    while (true) {
-        const bool own = (cur.j == i);
-        const bool has_next = nxt.j <= i;
-        const bool cube_ends = has_next && nxt.j != cur.j;
-        const int jsize = own ? qsize : cube_box(g, cur.j).size();
-        const int key0 = KEY_TILE * cur.t;
-        const bool active = ns > 0 && !(own && key0 > rank_hi);
+    // ---- the two compute phases of a tile for this wavefront
+    // S^T = K.Q^T and softmax of tile cc, K in buffer `buf`
+    auto qk_softmax = [&](int buf) __attribute__((always_inline)) {
+        const unsigned char *kt = kvbuf + buf * C::CHUNK;
+        const bool own = (cc.j == i);
+        const int key0 = KEY_TILE * cc.t;
+        const int nsl = (ns > 0 && !(own && key0 > rank_hi)) ? ns : 0;  // wave-uniform
         const bool need_mask = (key0 + KEY_TILE > jsize) || (own && key0 + KEY_TILE - 1 > rank_lo);
-        const int bv = bk == 2 ? 0 : bk + 1, bn = bv == 2 ? 0 : bv + 1;
-
-        // the next cube's slabs are worked out under this cube's last tile
-        int lr_n[NS], ns_n = 0, lo_n = 0, hi_n = 0;
-        if (SPARSE && cube_ends) slab_rows(nxt.j, lr_n, ns_n, lo_n, hi_n);
-
-        f32x4 sacc[NS][4];
-        bf16x8 pf[NS][2];
-        const int nsl = active ? ns : 0;  // wave-uniform
-        lds_barrier();  // K(cur) is in buffer bk; at a cube boundary every row's state is back in LDS
-        if (SPARSE && new_slabs) state_in();
-        {
-            const unsigned char *kt = kvbuf + bk * C::CHUNK;
-            if (SPARSE) {
-                // slab counts vary from cube to cube: one guarded block per slab
-                if (nsl >= 1) qk_tile<D, 0, 1, NS>(kt, n16, q4, qf, sacc);
-                if (NS >= 2 && nsl >= 2) qk_tile<D, 1, NS, NS>(kt, n16, q4, qf, sacc);
-            } else if (nsl) {
-                // fixed row set: all slabs, padding columns of a partial slab compute on the scratch row
-                qk_tile<D, 0, NS, NS>(kt, n16, q4, qf, sacc);
-            }
+        if (SPARSE && new_slabs) {
+            state_in();
+            new_slabs = false;
         }
-        // this cube's Q operands have had their last use: the next cube's arrive under the softmax and P.V
-        if (SPARSE && cube_ends) load_q(lr_n, ns_n, qf);
-        stash(gv, bv);  // V(cur)
-        if (has_next) fetch(gv, tile_ptr(Vt, nxt));
+        if (SPARSE && cc.t + 1 == cc.nt && cc.k + 1 < ncubes) {
+            // last tile of the cube: work out the next cube's slabs and start fetching the Q operands of the
+            // first one.  They land in registers of their own and are copied over at the end of this cube, so
+            // that the only wait for them sits there and not in front of every S^T.
+            slab_rows(cube_at(cc.k + 1), lr_n, ns_n, lo_n, hi_n);
+            if (ns_n > 0) load_q(lr_n[0], qf_n);
+        }
         if (SPARSE) {
-            if (nsl >= 1) softmax_tile<D, 0, 1, NS>(sacc, pf, oacc, m_run, l_run, lim, key0, need_mask, c2, q4);
-            if (NS >= 2 && nsl >= 2)
+            // slab counts vary from cube to cube: one guarded block per slab
+            if (nsl >= 1) {
+                qk_tile<D, 0, 1, NS>(kt, n16, q4, qf, sacc);
+                softmax_tile<D, 0, 1, NS>(sacc, pf, oacc, m_run, l_run, lim, key0, need_mask, c2, q4);
+            }
+            if (NS >= 2 && nsl >= 2) {
+                qk_tile<D, 1, NS, NS>(kt, n16, q4, qf, sacc);
                 softmax_tile<D, 1, NS, NS>(sacc, pf, oacc, m_run, l_run, lim, key0, need_mask, c2, q4);
+            }
         } else if (nsl) {
+            // fixed row set: all slabs, padding columns of a partial slab compute on the scratch row
+            qk_tile<D, 0, NS, NS>(kt, n16, q4, qf, sacc);
             softmax_tile<D, 0, NS, NS>(sacc, pf, oacc, m_run, l_run, lim, key0, need_mask, c2, q4);
         }
-        lds_barrier();  // V(cur) is in buffer bv
-        {
-            const unsigned char *vt = kvbuf + bv * C::CHUNK;
-            if (SPARSE) {
-                if (nsl >= 1) pv_tile<D, 0, 1, NS>(vt, n16, q4, pf, oacc);
-                if (NS >= 2 && nsl >= 2) pv_tile<D, 1, NS, NS>(vt, n16, q4, pf, oacc);
-            } else if (nsl) {
-                pv_tile<D, 0, NS, NS>(vt, n16, q4, pf, oacc);
-            }
+    };
+    // O^T += V^T.P^T of tile cc, V^T in buffer `buf`; then on to the next tile
+    auto pv_next = [&](int buf) __attribute__((always_inline)) {
+        const unsigned char *vt = kvbuf + buf * C::CHUNK;
+        const bool own = (cc.j == i);
+        const int key0 = KEY_TILE * cc.t;
+        const int nsl = (ns > 0 && !(own && key0 > rank_hi)) ? ns : 0;
+        if (SPARSE) {
+            if (nsl >= 1) pv_tile<D, 0, 1, NS>(vt, n16, q4, pf, oacc);
+            if (NS >= 2 && nsl >= 2) pv_tile<D, 1, NS, NS>(vt, n16, q4, pf, oacc);
+        } else if (nsl) {
+            pv_tile<D, 0, NS, NS>(vt, n16, q4, pf, oacc);
         }
-        new_slabs = false;
-        if (!has_next) break;
-        stash(gk, bn);  // K(nxt)
-        const TilePos nn = advance(nxt);
-        if (nn.j <= i) fetch(gk, tile_ptr(Kp, nn));
-
+        const bool cube_ends = cc.t + 1 == cc.nt && cc.k + 1 < ncubes;
+        advance(cc);
         if (cube_ends) {
             if (SPARSE) {
-                // slabs move between wavefronts from cube to cube: state back to LDS now, the new slabs'
-                // state out of LDS after the next barrier
+                // slabs move between the wavefronts of a half from cube to cube: state back to LDS now, the
+                // new slabs' state out of LDS after the next barrier
                 state_out();
                 ns = ns_n;
                 rank_lo = lo_n;
                 rank_hi = hi_n;
 #pragma unroll
                 for (int s = 0; s < NS; ++s) lr[s] = lr_n[s];
+                // a second slab is rare (own cube, unusually popular cube): its Q operands come late
+#pragma unroll
+                for (int s = 1; s < NS; ++s)
+                    if (s < ns) {
+                        load_q(lr[s], qf[s]);
+                        settle_q(qf[s]);
+                    }
+                if (ns > 0) {
+#pragma unroll
+                    for (int c = 0; c < KSTEPS; ++c) qf[0][c] = qf_n[c];
+                }
                 new_slabs = true;
             }
-            set_limits(nxt.j);
+            jsize = set_limits(cc.j);
         }
-        cur = nxt;
-        nxt = nn;
-        bk = bn;
-    }
+    };
 
-    // ---- normalise and write out
+    // ---- phases.  Chunk c of the stream K0 V0 K1 V1 ... lives in LDS buffer c % NBUF.  In phase p every
+    // wavefront starts the direct-to-LDS loads of its share of chunk p+2; the barrier that opens phase p+2 waits
+    // for them.  Half 0 computes on chunk p, half 1 on chunk p-1.  A chunk is read during two consecutive phases
+    // and overwritten two phases later.  The loads are issued in every phase (past the end of the stream they
+    // re-read the last tile) so that "all but the youngest loads" always means the same thing.  Both halves run
+    // 2*ntiles + 1 barriers.
+    auto run = [&](auto half_tag) __attribute__((always_inline)) {
+        constexpr int H = decltype(half_tag)::value;
+        for (int tau = 0; tau < ntiles; ++tau) {
+            const int b0 = (2 * tau) % C::NBUF;  // buffer of chunk 2*tau; the following chunks follow
+            phase_barrier<C::DMA>();             // phase 2*tau: chunks 2*tau and 2*tau-1 visible
+            if (tau + 1 < ntiles) advance(sc);
+            issue(Kp, sc, (b0 + 2) % C::NBUF);
+            if (H == 0) qk_softmax(b0);
+            else if (tau > 0) pv_next((b0 + C::NBUF - 1) % C::NBUF);
+            phase_barrier<C::DMA>();  // phase 2*tau+1
+            issue(Vt, sc, (b0 + 3) % C::NBUF);
+            if (H == 0) pv_next((b0 + 1) % C::NBUF);
+            else qk_softmax(b0);
+        }
+        phase_barrier<C::DMA>();  // phase 2*ntiles
+        if (H == 1) pv_next((2 * ntiles - 1) % C::NBUF);
+    };
+    if (half == 0) run(std::integral_constant<int, 0>{});
+    else run(std::integral_constant<int, 1>{});
+
+    // ---- normalise and write out (no direct-to-LDS load may outlive the workgroup's LDS allocation)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if (SPARSE) {
         state_out();
         __syncthreads();
@@ -545,14 +641,16 @@ static hipError_t launch_fwd(const Geom &g, const uint16_t *Q, const void *packe
 {
     using C = Fwd<D, SPARSE>;
     const uint16_t *Kp = reinterpret_cast<const uint16_t *>(packed);
-    const uint16_t *Vt = Kp + (size_t)g.Hkv * g.N * g.TPC * KEY_TILE * D;
+    const size_t half_elems = (size_t)g.Hkv * g.N * g.TPC * KEY_TILE * D;
+    const uint16_t *Vt = Kp + half_elems;
+    const int32_t *csize = reinterpret_cast<const int32_t *>(Vt + half_elems);
     const int nblk_max = (g.G * g.Cmax + C::MMAX - 1) / C::MMAX;
     const dim3 grid((unsigned)((size_t)((g.N * g.Hkv + 7) / 8) * nblk_max * 8));
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_fwd_kernel<D, SPARSE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::BYTES);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((attn_fwd_kernel<D, SPARSE>), grid, dim3(C::THREADS), C::BYTES, st, g, Q, Kp, Vt, sel_mask, O,
-                       lse);
+    hipLaunchKernelGGL((attn_fwd_kernel<D, SPARSE>), grid, dim3(C::THREADS), C::BYTES, st, g, Q, Kp, Vt, csize,
+                       sel_mask, O, lse);
     return hipGetLastError();
 }
 

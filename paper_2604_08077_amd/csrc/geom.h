@@ -21,6 +21,7 @@ struct Geom {
     int Cmax;           // tokens in an unclipped cube
     int TPC;            // key tiles per cube in the packed layout = ceil(Cmax / KEY_TILE)
     int words;          // u32 words per selection-mask row = ceil(N / 32)
+    int ragged;         // some cubes are clipped at the grid edge (otherwise every cube has Cmax tokens)
 };
 
 inline Geom make_geom(const adaspark_shape &s)
@@ -35,6 +36,7 @@ inline Geom make_geom(const adaspark_shape &s)
     g.Cmax = g.ct * g.ch * g.cw;
     g.TPC = (g.Cmax + KEY_TILE - 1) / KEY_TILE;
     g.words = (g.N + 31) / 32;
+    g.ragged = (g.T % g.ct != 0) || (g.H % g.ch != 0) || (g.W % g.cw != 0);
     return g;
 }
 

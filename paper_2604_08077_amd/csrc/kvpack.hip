@@ -2,7 +2,8 @@
 //
 // kv_pack_kernel gathers K and V from raster token order into a cube-major tiled copy in the workspace, one
 // 64-key tile per workgroup (layout and swizzle: kvtile.h).  Ranks beyond a (clipped) cube's size are
-// zero-filled; the attention kernel masks them.  HBM-bound: K and V are read once and written once.
+// zero-filled; the attention kernel masks them.  A table of the cubes' sizes follows the two copies.  HBM-bound:
+// K and V are read once and written once.
 #include "kvtile.h"
 
 namespace adaspark {
@@ -10,13 +11,14 @@ namespace adaspark {
 template <int D>
 __global__ __launch_bounds__(256) void kv_pack_kernel(Geom g, const uint16_t *__restrict__ K,
                                                       const uint16_t *__restrict__ V, uint16_t *__restrict__ Kp,
-                                                      uint16_t *__restrict__ Vt)
+                                                      uint16_t *__restrict__ Vt, int32_t *__restrict__ csize)
 {
     constexpr int CPR = D / 8;  // 16-byte chunks per key row
     __shared__ __attribute__((aligned(16))) uint16_t vs[KEY_TILE][D + 8];
     const int t = blockIdx.x, c = blockIdx.y, kv = blockIdx.z;
     const CubeBox box = cube_box(g, c);
     const int size = box.size();
+    if (t == 0 && kv == 0 && threadIdx.x == 0) csize[c] = size;  // table of (clipped) cube sizes for the readers
     const size_t tile_base = ((((size_t)kv * g.N + c) * g.TPC) + t) * (size_t)(KEY_TILE * D);
 
     for (int x = threadIdx.x; x < KEY_TILE * CPR; x += 256) {
@@ -46,16 +48,18 @@ __global__ __launch_bounds__(256) void kv_pack_kernel(Geom g, const uint16_t *__
 
 size_t attn_workspace_bytes(const Geom &g)
 {
-    // Kp and Vt: [Hkv][N][TPC][64][D] bf16 each
-    return 2 * (size_t)g.Hkv * g.N * g.TPC * KEY_TILE * g.D * sizeof(uint16_t);
+    // Kp and Vt: [Hkv][N][TPC][64][D] bf16 each, then the cube sizes: int32 [N]
+    return 2 * (size_t)g.Hkv * g.N * g.TPC * KEY_TILE * g.D * sizeof(uint16_t) + (((size_t)g.N * 4 + 15) / 16) * 16;
 }
 
 template <int D>
 static hipError_t launch_pack_d(const Geom &g, const uint16_t *K, const uint16_t *V, void *ws, hipStream_t st)
 {
     uint16_t *Kp = reinterpret_cast<uint16_t *>(ws);
-    uint16_t *Vt = Kp + (size_t)g.Hkv * g.N * g.TPC * KEY_TILE * D;
-    hipLaunchKernelGGL((kv_pack_kernel<D>), dim3(g.TPC, g.N, g.Hkv), dim3(256), 0, st, g, K, V, Kp, Vt);
+    const size_t half_elems = (size_t)g.Hkv * g.N * g.TPC * KEY_TILE * D;
+    uint16_t *Vt = Kp + half_elems;
+    int32_t *csize = reinterpret_cast<int32_t *>(Vt + half_elems);
+    hipLaunchKernelGGL((kv_pack_kernel<D>), dim3(g.TPC, g.N, g.Hkv), dim3(256), 0, st, g, K, V, Kp, Vt, csize);
     return hipGetLastError();
 }
 
