@@ -5,21 +5,21 @@
 // mask-based tile kernel would execute dense FLOPs.  Here a workgroup owns up to MMAX query rows of one
 // (query cube i, KV head) -- all query heads of the GQA group, token-major -- and keeps their online-softmax
 // state (fp32 O, m, l) in LDS (MI355X: 160 KB per CU).  It walks the key cubes j <= i that any of its rows
-// attends.  The rows are split into two halves, each served by four wavefronts (one per SIMD).  For each cube
-//   1. every wavefront ballots the selection bits of its half's rows and so knows the (sorted) list of rows
-//      that attend j (dense mode, own cube: all rows); no extra barrier is needed,
-//   2. the list is cut into 16-row slabs, dealt round-robin to the half's wavefronts,
+// attends.  For each cube
+//   1. every wavefront ballots the selection bits of all rows and so knows the (sorted) list of rows that
+//      attend j (dense mode, own cube: all rows); no extra barrier is needed,
+//   2. the list is cut into 16-row slabs, dealt round-robin to the eight wavefronts (two per SIMD: while one
+//      is in its softmax the other can feed the MFMA pipe),
 //   3. per slab the Q operands are gathered (prefetched under the previous cube's last tile), the rows' state
 //      moves from LDS into MFMA accumulators, flash attention runs over the cube's 64-key tiles with
 //      mfma_f32_16x16x32_bf16 (S^T = K.Q^T, O^T += V^T.P^T: a lane owns one query row and a quarter of the
 //      keys of a tile), and the state moves back.
-// Executed MFMA work is the selected (row, cube) pairs rounded up to 16 rows per half and cube.  In dense mode
-// the row set never changes and the state stays in registers.
+// Executed MFMA work is the selected (row, cube) pairs rounded up to 16 rows per workgroup and cube.  In dense
+// mode the row set never changes and the state stays in registers.
 //
-// K and V^T tiles come from the packed, pre-swizzled copy (kvtile.h) by direct-to-LDS loads.  The tile stream
-// K0 V0 K1 V1 ... rotates through four LDS buffers; a tile is requested two phases before it is needed.  The two
-// halves run one phase apart: on every SIMD one wavefront is in its S^T + softmax phase while the other runs its
-// P.V MFMAs.
+// K and V^T tiles come from the packed, pre-swizzled copy (kvtile.h) by direct-to-LDS loads into two LDS
+// stages: the loads of tile t+1 are started right after the barrier that opens tile t and waited for at the
+// barrier that closes it, so there is one barrier per 64-key tile.
 #include <type_traits>
 
 #include "kvtile.h"
@@ -33,13 +33,12 @@ constexpr int FWD_NS = 2;  // 16-row slabs a wavefront works on at a time
 template <int D, bool SPARSE>
 struct Fwd {
     static constexpr int WAVES = FWD_WAVES;
-    static constexpr int HWAVES = WAVES / 2;  // wavefronts per half
     static constexpr int THREADS = FWD_THREADS;
     static constexpr int NS = FWD_NS;
     static constexpr int MMAX = SPARSE ? 168 : 16 * NS * WAVES;  // rows per workgroup (sparse: what LDS can hold)
-    static constexpr int GROUPS = (MMAX / 2 + 63) / 64;          // 64-row ballot groups of a half
+    static constexpr int GROUPS = (MMAX + 63) / 64;              // 64-row ballot groups
     static constexpr int CHUNK = KEY_TILE * D * 2;               // bytes of a K tile (= bytes of a V^T tile)
-    static constexpr int NBUF = 4;                               // LDS buffers the tile stream rotates through
+    static constexpr int NBUF = 4;                               // LDS buffers: K and V^T of two tiles
     static constexpr int DMA = CHUNK / 1024 / WAVES;             // 1 KB direct-to-LDS loads per wavefront and tile
     static constexpr int OST = D + 4;  // floats per state row (padded: 16 rows start in 16 different bank groups)
     static constexpr int SMALL = (((MMAX + 1) * 4 + 15) / 16) * 16;
@@ -54,19 +53,16 @@ struct Fwd {
     static constexpr int OFF_L = OFF_M + SMALL;
     static constexpr int OFF_O = OFF_L + SMALL;
     static constexpr int BYTES = SPARSE ? OFF_O + (MMAX + 1) * OST * 4 : OFF_UMASK;
-    static_assert(MMAX <= 16 * NS * WAVES && MMAX % 2 == 0, "every attending row needs a slab");
-    static_assert(DMA >= 1 && DMA <= 2, "phase_barrier() leaves DMA loads in flight: keep the two in step");
+    static_assert(MMAX <= 16 * NS * WAVES, "every attending row needs a slab");
+    static_assert(DMA >= 1, "a tile is at least 1 KB per wavefront");
     static_assert(BYTES <= 160 * 1024, "LDS of one CU");
 };
 
-// Phase barrier.  Waits for this wavefront's LDS traffic and for all but its youngest N vector-memory operations
-// (the direct-to-LDS loads issued in the phase that is ending stay in flight; older ones have landed), then the
-// workgroup barrier.
-template <int N>
-__device__ __forceinline__ void phase_barrier()
+// Tile barrier.  Waits for everything this wavefront has in flight -- its LDS traffic and its direct-to-LDS loads
+// of the next tile, started a whole tile ago -- then the workgroup barrier.
+__device__ __forceinline__ void tile_barrier()
 {
-    if constexpr (N == 2) asm volatile("s_waitcnt vmcnt(2) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(1) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 // One wavefront copies 1 KB from global memory straight into LDS: lane l moves the 16 bytes at src (its own
@@ -216,7 +212,7 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(
 {
     using C = Fwd<D, SPARSE>;
     constexpr int NS = C::NS, MMAX = C::MMAX, OST = C::OST, THREADS = C::THREADS;
-    constexpr int HWAVES = C::HWAVES, GROUPS = C::GROUPS;
+    constexpr int WAVES = C::WAVES, GROUPS = C::GROUPS;
     constexpr int KSTEPS = D / 32;  // MFMA k-steps of S^T (32 head-dim elements each)
     constexpr int DT = D / 16;      // 16-wide tiles of O^T
     extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
@@ -232,7 +228,6 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n16 = lane & 15, q4 = lane >> 4;
-    const int half = wave / HWAVES, hw = wave % HWAVES;  // half-workgroup, wavefront inside it (one per SIMD)
     unsigned char *clist = smem + C::OFF_LIST + wave * 64 * GROUPS;  // this wavefront's list of attending rows
 
     // workgroup -> (query cube, KV head, row block).  The row blocks of one (cube, KV head) stream the same K/V
@@ -255,10 +250,6 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(
     const int Mrows = row1 - row0;
     const int max_rank = (row1 - 1) / g.G;
     const int own_tiles = min((qsize + KEY_TILE - 1) / KEY_TILE, max_rank / KEY_TILE + 1);
-    // rows [hbase, hbase + hrows) of the workgroup belong to this half
-    const int hsplit = (Mrows + 1) / 2;
-    const int hbase = half ? hsplit : 0;
-    const int hrows = half ? Mrows - hsplit : hsplit;
 
     for (int r = tid; r < Mrows; r += THREADS) {
         const int rho = row0 + r, rank = rho / g.G, hg = rho % g.G;
@@ -362,15 +353,15 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(
         }
     };
 
-    // ---- slabs of this wavefront for cube j.  The rows of the half that attend j, in row order, are cut into
-    // 16-row slabs; slab k goes to the half's wavefront k % HWAVES as its slot k / HWAVES.  lr[s]: workgroup row
-    // in column n16 of slot s (MMAX: padding column); ns: slots in use; lo/hi: smallest/largest rank among the
-    // wavefront's rows (own cube only).
-    int mrid[GROUPS];  // global row id behind (group, lane) of this half; -1: no such row
+    // ---- slabs of this wavefront for cube j.  The rows that attend j, in row order, are cut into 16-row slabs;
+    // slab k goes to wavefront k % WAVES as its slot k / WAVES.  lr[s]: workgroup row in column n16 of slot s
+    // (MMAX: padding column); ns: slots in use; lo/hi: smallest/largest rank among the wavefront's rows (own
+    // cube only).
+    int mrid[GROUPS];  // global row id behind (group, lane); -1: no such row
 #pragma unroll
     for (int gq = 0; gq < GROUPS; ++gq) {
         const int r = 64 * gq + lane;
-        mrid[gq] = r < hrows ? rowid[hbase + r] : -1;
+        mrid[gq] = r < Mrows ? rowid[r] : -1;
     }
     int cw = -1;  // mask word index cached in wbits
     uint32_t wbits[GROUPS];
@@ -379,7 +370,7 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(
     auto slab_rows = [&](int j, int (&lr)[NS], int &ns, int &lo, int &hi) __attribute__((always_inline)) {
         int total;
         const bool all = !SPARSE || j == i;
-        if (all) total = hrows;
+        if (all) total = Mrows;
         else {
             if ((j >> 5) != cw) {
                 cw = j >> 5;
@@ -387,7 +378,7 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(
                 for (int gq = 0; gq < GROUPS; ++gq)
                     wbits[gq] = mrid[gq] >= 0 ? sel_mask[(size_t)mrid[gq] * g.words + cw] : 0u;
             }
-            // every attending row writes its index (inside the half) at its position in the list: the number
+            // every attending row writes its index at its position in the list: the number
             // of attending rows below it.  The list is private to the wavefront: no barrier.
             total = 0;
 #pragma unroll
@@ -401,19 +392,19 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(
             }
         }
         const int nslab = (total + 15) >> 4;
-        ns = nslab > hw ? (nslab - hw + HWAVES - 1) / HWAVES : 0;
+        ns = nslab > wave ? (nslab - wave + WAVES - 1) / WAVES : 0;
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            const int idx = 16 * (hw + HWAVES * s) + n16;
+            const int idx = 16 * (wave + WAVES * s) + n16;
             int r = MMAX;
-            if (idx < total) r = hbase + (all ? idx : (int)clist[idx]);
+            if (idx < total) r = all ? idx : (int)clist[idx];
             lr[s] = r;
         }
         // rows are sorted by rank: the first column of slot 0 and the last used column of the last slot bound them
         lo = hi = 0;
         if (all && ns > 0) {
-            lo = rrank[hbase + 16 * hw];
-            hi = rrank[hbase + min(16 * (hw + HWAVES * (ns - 1)) + 15, total - 1)];
+            lo = rrank[16 * wave];
+            hi = rrank[min(16 * (wave + WAVES * (ns - 1)) + 15, total - 1)];
         }
     };
     // Q operands of one slab: lane (n16, q4) takes head-dim elements 32c + 8*q4 .. +7 of its column's row
@@ -433,9 +424,9 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(
     const float c2 = 1.44269504088896340736f / sqrtf((float)D);
 
     TilePos sc = first_tile();  // staging cursor: the tile whose K and V^T are being brought in
-    TilePos cc = sc;            // compute cursor of this wavefront
-    issue(Kp, sc, 0);           // chunk 0
-    issue(Vt, sc, 1);           // chunk 1
+    TilePos cc = sc;            // compute cursor
+    issue(Kp, sc, 0);           // tile 0 -> stage 0 (K in buffer 0, V^T in buffer 1)
+    issue(Vt, sc, 1);
 
     int lr[NS], ns, rank_lo, rank_hi;
     bf16x8 qf[NS][KSTEPS];
@@ -494,22 +485,48 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(
     f32x4 sacc[NS][4];
     bf16x8 pf[NS][2];
 
-    // ---- the two compute phases of a tile for this wavefront
-    // S^T = K.Q^T and softmax of tile cc, K in buffer `buf`
-    auto qk_softmax = [&](int buf) __attribute__((always_inline)) {
-        const unsigned char *kt = kvbuf + buf * C::CHUNK;
+    // ---- one 64-key tile per barrier.  Tile t sits in stage t % 2 (buffers 2*stage, 2*stage + 1).
+    for (int tau = 0; tau < ntiles; ++tau) {
+        tile_barrier();  // tile tau has landed; everybody is done with tile tau-1
+        const int st = tau & 1;
+        if (SPARSE && new_slabs) {
+            // cube boundary: the slabs (and with them rows) move between wavefronts.  Every wavefront wrote
+            // its state back before the barrier.
+            ns = ns_n;
+            rank_lo = lo_n;
+            rank_hi = hi_n;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) lr[s] = lr_n[s];
+            if (ns > 0) {
+#pragma unroll
+                for (int c = 0; c < KSTEPS; ++c) qf[0][c] = qf_n[c];
+            }
+            // a second slab is rare (own cube, unusually popular cube): its Q operands come late
+#pragma unroll
+            for (int s = 1; s < NS; ++s)
+                if (s < ns) {
+                    load_q(lr[s], qf[s]);
+                    settle_q(qf[s]);
+                }
+            state_in();
+            jsize = set_limits(cc.j);
+            new_slabs = false;
+        }
+        if (tau + 1 < ntiles) {
+            advance(sc);
+            issue(Kp, sc, 2 * (st ^ 1));
+            issue(Vt, sc, 2 * (st ^ 1) + 1);
+        }
+        const unsigned char *kt = kvbuf + (2 * st) * C::CHUNK, *vt = kt + C::CHUNK;
         const bool own = (cc.j == i);
         const int key0 = KEY_TILE * cc.t;
         const int nsl = (ns > 0 && !(own && key0 > rank_hi)) ? ns : 0;  // wave-uniform
         const bool need_mask = (key0 + KEY_TILE > jsize) || (own && key0 + KEY_TILE - 1 > rank_lo);
-        if (SPARSE && new_slabs) {
-            state_in();
-            new_slabs = false;
-        }
-        if (SPARSE && cc.t + 1 == cc.nt && cc.k + 1 < ncubes) {
+        const bool cube_ends = cc.t + 1 == cc.nt && cc.k + 1 < ncubes;
+        if (SPARSE && cube_ends) {
             // last tile of the cube: work out the next cube's slabs and start fetching the Q operands of the
-            // first one.  They land in registers of their own and are copied over at the end of this cube, so
-            // that the only wait for them sits there and not in front of every S^T.
+            // first one into registers of their own.  They are copied over after the next barrier, which has
+            // waited for them anyway.
             slab_rows(cube_at(cc.k + 1), lr_n, ns_n, lo_n, hi_n);
             if (ns_n > 0) load_q(lr_n[0], qf_n);
         }
@@ -518,88 +535,34 @@ __global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(
             if (nsl >= 1) {
                 qk_tile<D, 0, 1, NS>(kt, n16, q4, qf, sacc);
                 softmax_tile<D, 0, 1, NS>(sacc, pf, oacc, m_run, l_run, lim, key0, need_mask, c2, q4);
+                pv_tile<D, 0, 1, NS>(vt, n16, q4, pf, oacc);
             }
             if (NS >= 2 && nsl >= 2) {
                 qk_tile<D, 1, NS, NS>(kt, n16, q4, qf, sacc);
                 softmax_tile<D, 1, NS, NS>(sacc, pf, oacc, m_run, l_run, lim, key0, need_mask, c2, q4);
+                pv_tile<D, 1, NS, NS>(vt, n16, q4, pf, oacc);
             }
         } else if (nsl) {
             // fixed row set: all slabs, padding columns of a partial slab compute on the scratch row
             qk_tile<D, 0, NS, NS>(kt, n16, q4, qf, sacc);
             softmax_tile<D, 0, NS, NS>(sacc, pf, oacc, m_run, l_run, lim, key0, need_mask, c2, q4);
-        }
-    };
-    // O^T += V^T.P^T of tile cc, V^T in buffer `buf`; then on to the next tile
-    auto pv_next = [&](int buf) __attribute__((always_inline)) {
-        const unsigned char *vt = kvbuf + buf * C::CHUNK;
-        const bool own = (cc.j == i);
-        const int key0 = KEY_TILE * cc.t;
-        const int nsl = (ns > 0 && !(own && key0 > rank_hi)) ? ns : 0;
-        if (SPARSE) {
-            if (nsl >= 1) pv_tile<D, 0, 1, NS>(vt, n16, q4, pf, oacc);
-            if (NS >= 2 && nsl >= 2) pv_tile<D, 1, NS, NS>(vt, n16, q4, pf, oacc);
-        } else if (nsl) {
             pv_tile<D, 0, NS, NS>(vt, n16, q4, pf, oacc);
         }
-        const bool cube_ends = cc.t + 1 == cc.nt && cc.k + 1 < ncubes;
         advance(cc);
         if (cube_ends) {
             if (SPARSE) {
-                // slabs move between the wavefronts of a half from cube to cube: state back to LDS now, the
-                // new slabs' state out of LDS after the next barrier
                 state_out();
-                ns = ns_n;
-                rank_lo = lo_n;
-                rank_hi = hi_n;
-#pragma unroll
-                for (int s = 0; s < NS; ++s) lr[s] = lr_n[s];
-                // a second slab is rare (own cube, unusually popular cube): its Q operands come late
-#pragma unroll
-                for (int s = 1; s < NS; ++s)
-                    if (s < ns) {
-                        load_q(lr[s], qf[s]);
-                        settle_q(qf[s]);
-                    }
-                if (ns > 0) {
-#pragma unroll
-                    for (int c = 0; c < KSTEPS; ++c) qf[0][c] = qf_n[c];
-                }
                 new_slabs = true;
+            } else {
+                jsize = set_limits(cc.j);
             }
-            jsize = set_limits(cc.j);
         }
-    };
-
-    // ---- phases.  Chunk c of the stream K0 V0 K1 V1 ... lives in LDS buffer c % NBUF.  In phase p every
-    // wavefront starts the direct-to-LDS loads of its share of chunk p+2; the barrier that opens phase p+2 waits
-    // for them.  Half 0 computes on chunk p, half 1 on chunk p-1.  A chunk is read during two consecutive phases
-    // and overwritten two phases later.  The loads are issued in every phase (past the end of the stream they
-    // re-read the last tile) so that "all but the youngest loads" always means the same thing.  Both halves run
-    // 2*ntiles + 1 barriers.
-    auto run = [&](auto half_tag) __attribute__((always_inline)) {
-        constexpr int H = decltype(half_tag)::value;
-        for (int tau = 0; tau < ntiles; ++tau) {
-            const int b0 = (2 * tau) % C::NBUF;  // buffer of chunk 2*tau; the following chunks follow
-            phase_barrier<C::DMA>();             // phase 2*tau: chunks 2*tau and 2*tau-1 visible
-            if (tau + 1 < ntiles) advance(sc);
-            issue(Kp, sc, (b0 + 2) % C::NBUF);
-            if (H == 0) qk_softmax(b0);
-            else if (tau > 0) pv_next((b0 + C::NBUF - 1) % C::NBUF);
-            phase_barrier<C::DMA>();  // phase 2*tau+1
-            issue(Vt, sc, (b0 + 3) % C::NBUF);
-            if (H == 0) pv_next((b0 + 1) % C::NBUF);
-            else qk_softmax(b0);
-        }
-        phase_barrier<C::DMA>();  // phase 2*ntiles
-        if (H == 1) pv_next((2 * ntiles - 1) % C::NBUF);
-    };
-    if (half == 0) run(std::integral_constant<int, 0>{});
-    else run(std::integral_constant<int, 1>{});
+    }
 
     // ---- normalise and write out (no direct-to-LDS load may outlive the workgroup's LDS allocation)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if (SPARSE) {
-        state_out();
+        if (!new_slabs) state_out();
         __syncthreads();
         for (int x = tid; x < Mrows * (D / 8); x += THREADS) {
             const int r = x / (D / 8), c = x % (D / 8);
