@@ -120,6 +120,9 @@ def main():
     ap.add_argument("--top-p", type=float, default=0.9)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch one plain 1 GiB device copy after the timed region: the known-size "
+                         "reference the HBM counters of a rocprofv3 --pmc run are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -184,6 +187,13 @@ def main():
         torch.cuda.synchronize()
         dense_ms = timed(f_dense, max(1, min(args.steps, 3)))
 
+    if args.copy_probe:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     cube, rank, sizes = cube_tables(w)
     keys_total, pairs = attended_keys_total(w, mask, sizes, rank)
     eff_flops = 4.0 * w.D * keys_total
@@ -225,7 +235,7 @@ def main():
         "dense_tflops": None if dense_ms is None else dense_flops / (dense_ms * 1e-3) / 1e12,
         "speedup_vs_dense": None if dense_ms is None else (k_ms["kv_pack"] + dense_ms) / ms_per_step,
         "roofline": {
-            "kernel": "attn_kernel<128,sparse>" if w.D == 128 else "attn_kernel<64,sparse>",
+            "kernel": f"attn_fwd_kernel<{w.D}, true>",
             "bound": "mfma",
             "achieved": attn_tflops,
             "peak": PEAK_BF16_TFLOPS,

@@ -215,3 +215,61 @@ def test_c3_p_sweep_sampled(B, oracle):
 
 def test_c4_sampled(B, oracle):
     sampled_case(B, oracle, synth.WORKLOADS["C4"], (0.9,), 192, check_dense=False)
+
+
+@pytest.mark.parametrize("name", ["T_gqa128", "T_manycubes", "C1"])
+def test_select_ties_zero_queries(B, oracle, name):
+    """All-zero queries make every candidate cube equally likely: the whole Top-p decision is the tie rule
+    (lower cube index first, keep while the mass before an element is below p)."""
+    w = synth.TEST_WORKLOADS.get(name) or synth.WORKLOADS[name]
+    print(f"case {w.name} zero queries (ties)", flush=True)
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    _, K, _ = synth.generate(w)
+    Q = torch.zeros((w.S, w.Hq, w.D), dtype=torch.bfloat16)
+    kbar_ref = oracle.cube_pool(osh, K)
+    kbar = B.cube_pool(sh, K.cuda())
+    for p in (0.35, 0.6, 0.85):
+        p32 = float(np.float32(p))
+        ref_mask, ref_count, near = oracle.cube_select(osh, Q, kbar_ref, p32)
+        mask, count, _, _ = B.cube_select(sh, Q.cuda(), kbar, p32)
+        torch.cuda.synchronize()
+        same = check_selection(f"{w.name} ties p={p}", to_u32(mask), count.cpu().numpy(), ref_mask, ref_count, near)
+        # the kept cubes are a prefix 0..k-1 of the candidates
+        gm = to_u32(mask)
+        bits = np.unpackbits(gm.view(np.uint8), axis=1, bitorder="little").astype(np.int64)
+        k = bits.sum(1)
+        assert np.array_equal(bits.cumsum(1)[np.arange(len(k)), np.maximum(k, 1) - 1], np.where(k > 0, k, 0))
+        assert same[~near].all()
+
+
+def test_lse_matches_attended_logits(B, oracle):
+    """The optional log-sum-exp output: recomputed here in fp64 from the bf16 inputs over exactly the keys the
+    row attends (selected cubes + causal part of the own cube)."""
+    w = synth.TEST_WORKLOADS["T_ragged"]
+    print(f"case {w.name} lse", flush=True)
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    Q, K, V = synth.generate(w)
+    Qg, Kg, Vg = Q.cuda(), K.cuda(), V.cuda()
+    kbar = B.cube_pool(sh, Kg)
+    mask, _, _, _ = B.cube_select(sh, Qg, kbar, float(np.float32(0.9)))
+    _, lse = B.sparse_attn(sh, Qg, Kg, Vg, mask, return_lse=True)
+    _, lse_d = B.dense_attn(sh, Qg, Kg, Vg, return_lse=True)
+    torch.cuda.synchronize()
+    cube_of, rank_of, _, start = oracle.cube_map(osh)
+    pos = start[cube_of] + rank_of
+    gm = to_u32(mask)
+    N = B.num_cubes(sh)
+    bits = np.unpackbits(gm.view(np.uint8), axis=1, bitorder="little")[:, :N].astype(bool)
+    Qf, Kf = Q.double().numpy(), K.double().numpy()
+    G = w.Hq // w.Hkv
+    rows = synth.sample_rows(w, 96)
+    for r in rows:
+        n, a = divmod(int(r), w.Hq)
+        logits = Kf[:, a // G, :] @ Qf[n, a] / np.sqrt(w.D)
+        own = (cube_of == cube_of[n]) & (rank_of <= rank_of[n])
+        att = bits[r][cube_of] | own
+        ref = np.log(np.exp(logits[att] - logits[att].max()).sum()) + logits[att].max()
+        assert abs(lse[r].item() - ref) < 2e-3, (r, lse[r].item(), ref)
+        causal = pos <= pos[n]
+        ref_d = np.log(np.exp(logits[causal] - logits[causal].max()).sum()) + logits[causal].max()
+        assert abs(lse_d[r].item() - ref_d) < 2e-3, (r, lse_d[r].item(), ref_d)
