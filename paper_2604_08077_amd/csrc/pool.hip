@@ -29,14 +29,28 @@ __global__ __launch_bounds__(POOL_THREADS) void cube_pool_kernel(Geom g, const u
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[e] = 0.f;
         if (slot < slots) {
-            for (int r = slot; r < size; r += slots) {
-                const int n = token_of(g, box, r);
-                const uint4 v = *reinterpret_cast<const uint4 *>(K + (size_t)n * row_elems + (size_t)(chunk0 + col) * 8);
-                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+            // eight independent 16-byte loads in flight per thread: a cube is read by one workgroup, so the
+            // memory-level parallelism has to come from inside it
+            constexpr int UNROLL = 8;
+            for (int r0 = slot; r0 < size; r0 += slots * UNROLL) {
+                uint4 v[UNROLL];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    acc[2 * e] += __uint_as_float(w[e] << 16);
-                    acc[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u);
+                for (int u = 0; u < UNROLL; ++u) {
+                    const int r = r0 + u * slots;
+                    v[u] = make_uint4(0, 0, 0, 0);
+                    if (r < size) {
+                        const int n = token_of(g, box, r);
+                        v[u] = *reinterpret_cast<const uint4 *>(K + (size_t)n * row_elems + (size_t)(chunk0 + col) * 8);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        acc[2 * e] += __uint_as_float(w[e] << 16);
+                        acc[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u);
+                    }
                 }
             }
         }

@@ -221,6 +221,13 @@ __device__ __forceinline__ uint32_t selm_quad_or(uint32_t x)
     const auto b = __builtin_amdgcn_permlane32_swap(y, y, false, false);
     return b[0] | b[1];
 }
+__device__ __forceinline__ uint32_t selm_quad_umax(uint32_t x)
+{
+    const auto a = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+    const uint32_t y = max(a[0], a[1]);
+    const auto b = __builtin_amdgcn_permlane32_swap(y, y, false, false);
+    return max(b[0], b[1]);
+}
 __device__ __forceinline__ float selm_quad_sum(float x)
 {
     const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -379,6 +386,33 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
                         }
                 }
             if (selm_quad_sum(sum) >= target) tau = cand;
+            // tau is the value of one of the row's elements, the smallest kept one, and it lies in
+            // [tau, tau + 2^b).  Once that bucket holds a single distinct value for every row of the slab the
+            // remaining bits are known; looked at every fourth step once the exponent bits are settled.
+            if (b <= 22 && (b & 3) == 2) {
+                const uint32_t width = 1u << b;
+                uint32_t mn = 0xffffffffu, mxb = 0u;
+#pragma unroll
+                for (int k4 = 0; k4 < (MAXG + 3) / 4; ++k4)
+                    if (k4 < ng4) {
+#pragma unroll
+                        for (int cg = 4 * k4; cg < 4 * k4 + 4 && cg < MAXG; ++cg)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) {
+                                const uint32_t bits = __float_as_uint(acc[s][cg][v]);
+                                const bool inb = bits - tau < width;
+                                mn = inb ? min(mn, bits) : mn;
+                                mxb = inb ? max(mxb, bits) : mxb;
+                            }
+                    }
+                // min over the row's four lanes via max of the complement
+                mn = ~selm_quad_umax(~mn);
+                mxb = selm_quad_umax(mxb);
+                if (__all(mn == mxb)) {
+                    tau = mn;
+                    break;
+                }
+            }
         }
         const float tauf = __uint_as_float(tau);
         float sgt = 0.f;
