@@ -26,14 +26,16 @@
 
 namespace adaspark {
 
-constexpr int FWD_WAVES = 8;  // two wavefronts per SIMD
-constexpr int FWD_THREADS = 64 * FWD_WAVES;
-constexpr int FWD_NS = 2;  // 16-row slabs a wavefront works on at a time
+constexpr int FWD_MAX_THREADS = 512;  // largest workgroup of the two modes (register budget: 256 per lane)
+constexpr int FWD_NS = 2;             // 16-row slabs a wavefront works on at a time
 
 template <int D, bool SPARSE>
 struct Fwd {
-    static constexpr int WAVES = FWD_WAVES;
-    static constexpr int THREADS = FWD_THREADS;
+    // Sparse: one workgroup of eight wavefronts per CU (its LDS holds the rows' state).  Dense: workgroups of
+    // four wavefronts, two per CU: they are not tied to each other's barriers and drift apart, which lets one
+    // workgroup's softmax run under the other's MFMAs.
+    static constexpr int WAVES = SPARSE ? 8 : 4;
+    static constexpr int THREADS = 64 * WAVES;
     static constexpr int NS = FWD_NS;
     static constexpr int MMAX = SPARSE ? 168 : 16 * NS * WAVES;  // rows per workgroup (sparse: what LDS can hold)
     static constexpr int GROUPS = (MMAX + 63) / 64;              // 64-row ballot groups
@@ -205,7 +207,7 @@ struct TilePos {
 };
 
 template <int D, bool SPARSE>
-__global__ __launch_bounds__(FWD_THREADS) void attn_fwd_kernel(
+__global__ __launch_bounds__(FWD_MAX_THREADS) void attn_fwd_kernel(
     Geom g, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Kp, const uint16_t *__restrict__ Vt,
     const int32_t *__restrict__ csize, const uint32_t *__restrict__ sel_mask, uint16_t *__restrict__ O,
     float *__restrict__ lse)
