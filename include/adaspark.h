@@ -59,6 +59,18 @@ typedef enum {
     ADASPARK_CALL_DENSE_ATTN = 3
 } adaspark_call;
 
+/* Which kernel a sparse-attention call runs.  Both compute the same result (Eq. 3).
+ *   COMPACT  per key cube, the rows that selected it are gathered into dense MFMA tiles: executed work follows
+ *            the selection; the better choice when few cubes are selected.
+ *   MASKED   every row walks every preceding cube and its selection bits act as a mask: dense work, none of
+ *            the gathering cost; the better choice when most cubes are selected.
+ *   AUTO     a device-side estimate of the selected share picks one of the two (no host synchronisation). */
+typedef enum {
+    ADASPARK_SPARSE_AUTO = 0,
+    ADASPARK_SPARSE_COMPACT = 1,
+    ADASPARK_SPARSE_MASKED = 2
+} adaspark_sparse_kernel;
+
 /* Limits: head_dim in {64,128}; number of cubes <= ADASPARK_MAX_CUBES;
  * tokens*q_heads < 2^31; only causal != 0 (the paper's method) is implemented. */
 #define ADASPARK_MAX_CUBES 2048
@@ -130,14 +142,20 @@ int adaspark_dense_attn(const adaspark_shape *shape, const void *Q, const void *
  * Top-p sweep, sparse and dense side by side) can pack once:
  *   adaspark_kv_pack            fills `workspace` (same size as for the attention entries)
  *   adaspark_sparse_attn_packed / adaspark_dense_attn_packed
- *                               read a workspace filled by adaspark_kv_pack for the same shape;
- *                               `packed` is only read.
+ *                               read a workspace filled by adaspark_kv_pack for the same shape.  The K/V copy
+ *                               in it is only read; the sparse entries use its last 16 bytes as scratch, so
+ *                               two sparse calls on one workspace must not overlap in time.
+ *   adaspark_sparse_attn_packed_with
+ *                               the same with an explicit adaspark_sparse_kernel (the plain entry uses AUTO).
  * adaspark_sparse_attn(...) == adaspark_kv_pack(...) followed by adaspark_sparse_attn_packed(...).
  */
 int adaspark_kv_pack(const adaspark_shape *shape, const void *K, const void *V,
                      void *workspace, size_t workspace_bytes, void *stream);
-int adaspark_sparse_attn_packed(const adaspark_shape *shape, const void *Q, const void *packed, size_t packed_bytes,
+int adaspark_sparse_attn_packed(const adaspark_shape *shape, const void *Q, void *packed, size_t packed_bytes,
                                 const uint32_t *sel_mask, int causal, void *O, float *lse, void *stream);
+int adaspark_sparse_attn_packed_with(const adaspark_shape *shape, const void *Q, void *packed, size_t packed_bytes,
+                                     const uint32_t *sel_mask, int causal, int sparse_kernel, void *O, float *lse,
+                                     void *stream);
 int adaspark_dense_attn_packed(const adaspark_shape *shape, const void *Q, const void *packed, size_t packed_bytes,
                                int causal, void *O, float *lse, void *stream);
 

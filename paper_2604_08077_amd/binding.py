@@ -73,8 +73,11 @@ EXPORTS = (
     "adaspark_dense_attn",
     "adaspark_kv_pack",
     "adaspark_sparse_attn_packed",
+    "adaspark_sparse_attn_packed_with",
     "adaspark_dense_attn_packed",
 )
+
+SPARSE_AUTO, SPARSE_COMPACT, SPARSE_MASKED = 0, 1, 2
 
 
 def load():
@@ -99,6 +102,8 @@ def load():
         lib.adaspark_dense_attn.argtypes = [sp, vp, vp, vp, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
         lib.adaspark_kv_pack.argtypes = [sp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.adaspark_sparse_attn_packed.argtypes = [sp, vp, vp, ctypes.c_size_t, vp, ctypes.c_int, vp, vp, vp]
+        lib.adaspark_sparse_attn_packed_with.argtypes = [sp, vp, vp, ctypes.c_size_t, vp, ctypes.c_int, ctypes.c_int,
+                                                         vp, vp, vp]
         lib.adaspark_dense_attn_packed.argtypes = [sp, vp, vp, ctypes.c_size_t, ctypes.c_int, vp, vp, vp]
         for name in EXPORTS:
             if name != "adaspark_status_string":
@@ -235,7 +240,7 @@ def kv_pack(shape: Shape, K, V, workspace=None) -> torch.Tensor:
     return workspace
 
 
-def _attn_packed(fn_name, shape, Q, packed, sel_mask, causal, O, lse, want_lse):
+def _attn_packed(fn_name, shape, Q, packed, sel_mask, causal, O, lse, want_lse, kernel=None):
     R = shape.rows
     if O is None:
         O = torch.empty((shape.tokens, shape.q_heads, shape.head_dim), dtype=torch.bfloat16, device=Q.device)
@@ -245,18 +250,25 @@ def _attn_packed(fn_name, shape, Q, packed, sel_mask, causal, O, lse, want_lse):
         raise ValueError("packed must be a GPU tensor")
     cs = shape._c()
     args = [ctypes.byref(cs), _dev(Q, torch.bfloat16, R * shape.head_dim, "Q"), packed.data_ptr(), packed.numel()]
-    if fn_name == "adaspark_sparse_attn_packed":
+    if fn_name.startswith("adaspark_sparse_attn_packed"):
         words = (num_cubes(shape) + 31) // 32
         args.append(_dev(sel_mask, torch.int32, R * words, "sel_mask"))
-    args += [int(bool(causal)), _dev(O, torch.bfloat16, R * shape.head_dim, "O"),
+    args.append(int(bool(causal)))
+    if kernel is not None:
+        args.append(int(kernel))
+    args += [_dev(O, torch.bfloat16, R * shape.head_dim, "O"),
              None if lse is None else _dev(lse, torch.float32, R, "lse"), _stream()]
     _check(getattr(load(), fn_name)(*args), fn_name)
     return (O, lse) if want_lse else O
 
 
 def sparse_attn_packed(shape: Shape, Q, packed, sel_mask, causal: bool = True, O=None, lse=None,
-                       return_lse: bool = False):
-    return _attn_packed("adaspark_sparse_attn_packed", shape, Q, packed, sel_mask, causal, O, lse, return_lse)
+                       return_lse: bool = False, kernel: int | None = None):
+    """``kernel``: None/SPARSE_AUTO lets the library choose, SPARSE_COMPACT / SPARSE_MASKED force one."""
+    if kernel is None:
+        return _attn_packed("adaspark_sparse_attn_packed", shape, Q, packed, sel_mask, causal, O, lse, return_lse)
+    return _attn_packed("adaspark_sparse_attn_packed_with", shape, Q, packed, sel_mask, causal, O, lse, return_lse,
+                        kernel)
 
 
 def dense_attn_packed(shape: Shape, Q, packed, causal: bool = True, O=None, lse=None, return_lse: bool = False):

@@ -132,28 +132,41 @@ int adaspark_kv_pack(const adaspark_shape *shape, const void *K, const void *V, 
     return e == hipSuccess ? ADASPARK_OK : ADASPARK_EHIP;
 }
 
-static int attn_packed(const adaspark_shape *shape, const void *Q, const void *packed, size_t packed_bytes,
-                       const uint32_t *sel_mask, bool sparse, int causal, void *O, float *lse, void *stream)
+static int attn_packed(const adaspark_shape *shape, const void *Q, void *packed, size_t packed_bytes,
+                       const uint32_t *sel_mask, bool sparse, int sparse_kernel, int causal, void *O, float *lse,
+                       void *stream)
 {
     int rc = attn_check(shape, Q, sel_mask, sparse, causal, O, lse);
     if (rc != ADASPARK_OK) return rc;
+    if (sparse_kernel != ADASPARK_SPARSE_AUTO && sparse_kernel != ADASPARK_SPARSE_COMPACT &&
+        sparse_kernel != ADASPARK_SPARSE_MASKED)
+        return ADASPARK_EINVAL;
     const Geom g = make_geom(*shape);
     if ((rc = workspace_check(g, packed, packed_bytes)) != ADASPARK_OK) return rc;
-    const hipError_t e = launch_attn(g, static_cast<const uint16_t *>(Q), packed, sparse ? sel_mask : nullptr,
+    const hipError_t e = launch_attn(g, static_cast<const uint16_t *>(Q), packed, sparse ? sel_mask : nullptr, sparse_kernel,
                                      static_cast<uint16_t *>(O), lse, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? ADASPARK_OK : ADASPARK_EHIP;
 }
 
-int adaspark_sparse_attn_packed(const adaspark_shape *shape, const void *Q, const void *packed, size_t packed_bytes,
+int adaspark_sparse_attn_packed(const adaspark_shape *shape, const void *Q, void *packed, size_t packed_bytes,
                                 const uint32_t *sel_mask, int causal, void *O, float *lse, void *stream)
 {
-    return attn_packed(shape, Q, packed, packed_bytes, sel_mask, true, causal, O, lse, stream);
+    return attn_packed(shape, Q, packed, packed_bytes, sel_mask, true, ADASPARK_SPARSE_AUTO, causal, O, lse, stream);
+}
+
+int adaspark_sparse_attn_packed_with(const adaspark_shape *shape, const void *Q, void *packed, size_t packed_bytes,
+                                     const uint32_t *sel_mask, int causal, int sparse_kernel, void *O, float *lse,
+                                     void *stream)
+{
+    return attn_packed(shape, Q, packed, packed_bytes, sel_mask, true, sparse_kernel, causal, O, lse, stream);
 }
 
 int adaspark_dense_attn_packed(const adaspark_shape *shape, const void *Q, const void *packed, size_t packed_bytes,
                                int causal, void *O, float *lse, void *stream)
 {
-    return attn_packed(shape, Q, packed, packed_bytes, nullptr, false, causal, O, lse, stream);
+    // the dense kernel only reads the workspace
+    return attn_packed(shape, Q, const_cast<void *>(packed), packed_bytes, nullptr, false, ADASPARK_SPARSE_AUTO, causal, O,
+                       lse, stream);
 }
 
 static int attn_full(const adaspark_shape *shape, const void *Q, const void *K, const void *V,
@@ -166,7 +179,7 @@ static int attn_full(const adaspark_shape *shape, const void *Q, const void *K, 
     if ((rc = check_ptrs({K, V})) != ADASPARK_OK) return rc;
     if ((rc = workspace_check(make_geom(*shape), workspace, workspace_bytes)) != ADASPARK_OK) return rc;
     if ((rc = adaspark_kv_pack(shape, K, V, workspace, workspace_bytes, stream)) != ADASPARK_OK) return rc;
-    return attn_packed(shape, Q, workspace, workspace_bytes, sel_mask, sparse, causal, O, lse, stream);
+    return attn_packed(shape, Q, workspace, workspace_bytes, sel_mask, sparse, ADASPARK_SPARSE_AUTO, causal, O, lse, stream);
 }
 
 int adaspark_sparse_attn(const adaspark_shape *shape, const void *Q, const void *K, const void *V,

@@ -130,19 +130,24 @@ __device__ __forceinline__ void qk_tile(const unsigned char *kt, int n16, int q4
 }
 
 // fp32 online softmax of the tile's scores, base-2 exponentials; P rounded to bf16 in P.V operand order.
-template <int D, int S0, int S1, int NS>
+// With MASKED, a row whose rsel flag is off takes no part in the tile: its probabilities are 0 and its running
+// state stays as it is (the subtracted maximum is +inf, the rescale factor 1).
+template <int D, int S0, int S1, int NS, bool MASKED = false>
 __device__ __forceinline__ void softmax_tile(f32x4 (&sacc)[NS][4], bf16x8 (&pf)[NS][2], f32x4 (&oacc)[NS][D / 16],
                                              float (&m_run)[NS], float (&l_run)[NS], const int (&lim)[NS], int key0,
-                                             bool need_mask, float c2, int q4)
+                                             bool need_mask, float c2, int q4, const bool (&rsel)[NS])
 {
 #pragma unroll
     for (int s = S0; s < S1; ++s) {
         if (need_mask) {
+            // few tiles come here; the empty statement keeps the index arithmetic from being hoisted out to all
+            int kb = key0 + 8 * q4;
+            asm volatile("" : "+v"(kb));
 #pragma unroll
             for (int kg = 0; kg < 4; ++kg)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const int kr = key0 + 32 * (kg >> 1) + 8 * q4 + 4 * (kg & 1) + v;
+                    const int kr = kb + 32 * (kg >> 1) + 4 * (kg & 1) + v;
                     if (kr > lim[s]) sacc[s][kg][v] = -INFINITY;
                 }
         }
@@ -155,13 +160,15 @@ __device__ __forceinline__ void softmax_tile(f32x4 (&sacc)[NS][4], bf16x8 (&pf)[
         mx = vmax3(mx, sacc[s][3][1], sacc[s][3][2]);
         mx = vmax(mx, sacc[s][3][3]);
         mx = quad_max(mx);
-        const float m_new = vmax(m_run[s], mx * c2);
+        float m_new = vmax(m_run[s], mx * c2);
+        if (MASKED && !rsel[s]) m_new = m_run[s];
+        const float m_sub = (MASKED && !rsel[s]) ? INFINITY : m_new;
         const float alpha = __builtin_amdgcn_exp2f(m_run[s] - m_new);
 #pragma unroll
         for (int kg = 0; kg < 4; ++kg)
 #pragma unroll
             for (int v = 0; v < 4; ++v)
-                pf[s][kg >> 1][4 * (kg & 1) + v] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[s][kg][v], c2, -m_new));
+                pf[s][kg >> 1][4 * (kg & 1) + v] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[s][kg][v], c2, -m_sub));
         // the row sum is taken over the rounded probabilities, the very weights P.V uses, two per instruction
         float rs = 0.f;
         const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
@@ -206,12 +213,18 @@ struct TilePos {
     int nt;  // tiles of cube j this workgroup reads
 };
 
-template <int D, bool SPARSE>
+// SPARSE: rows are compacted per cube (state in LDS).  MASKED (with SPARSE off): the dense walk over fixed rows
+// with every row's selection bit applied as a mask -- dense FLOPs, but no state traffic and two workgroups per
+// CU; the better choice when most cubes are selected.  mode_flag (may be null): the kernel runs only if
+// *mode_flag == my_mode, so that both variants can be enqueued and a device-side density estimate picks one.
+template <int D, bool SPARSE, bool MASKED>
 __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_fwd_kernel(
     Geom g, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Kp, const uint16_t *__restrict__ Vt,
-    const int32_t *__restrict__ csize, const uint32_t *__restrict__ sel_mask, uint16_t *__restrict__ O,
-    float *__restrict__ lse)
+    const int32_t *__restrict__ csize, const uint32_t *__restrict__ sel_mask, const int *__restrict__ mode_flag,
+    int my_mode, uint16_t *__restrict__ O, float *__restrict__ lse)
 {
+    static_assert(!(SPARSE && MASKED), "masking is the dense walk's way of honouring the selection");
+    if (mode_flag != nullptr && *mode_flag != my_mode) return;
     using C = Fwd<D, SPARSE>;
     constexpr int NS = C::NS, MMAX = C::MMAX, OST = C::OST, THREADS = C::THREADS;
     constexpr int WAVES = C::WAVES, GROUPS = C::GROUPS;
@@ -408,6 +421,9 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_fwd_kernel(
             lo = rrank[16 * wave];
             hi = rrank[min(16 * (wave + WAVES * (ns - 1)) + 15, total - 1)];
         }
+        // the same in every lane: say so, and the tests on them become scalar branches
+        lo = __builtin_amdgcn_readfirstlane(lo);
+        hi = __builtin_amdgcn_readfirstlane(hi);
     };
     // Q operands of one slab: lane (n16, q4) takes head-dim elements 32c + 8*q4 .. +7 of its column's row
     auto load_q = [&](int row, bf16x8 (&q)[KSTEPS]) __attribute__((always_inline)) {
@@ -480,6 +496,28 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_fwd_kernel(
                 }
             }
     };
+    // MASKED: does this lane's row (per slab) attend cube j?  One mask word per row is cached in registers.
+    bool rsel[NS];
+    uint32_t mword[NS];
+    int mword_idx = -1;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) { rsel[s] = true; mword[s] = 0; }
+    auto set_rsel = [&](int j) __attribute__((always_inline)) {
+        if (!MASKED) return;
+        if (j == i) {
+#pragma unroll
+            for (int s = 0; s < NS; ++s) rsel[s] = true;
+            return;
+        }
+        if ((j >> 5) != mword_idx) {
+            mword_idx = j >> 5;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) mword[s] = sel_mask[(size_t)rowid[lr[s]] * g.words + mword_idx];
+        }
+#pragma unroll
+        for (int s = 0; s < NS; ++s) rsel[s] = (mword[s] >> (j & 31)) & 1u;
+    };
+    set_rsel(cc.j);
     int jsize = set_limits(cc.j);  // first cube: the state registers already hold the initial state
     bool new_slabs = false;        // the slabs changed at the last cube boundary: their state is still in LDS
     int lr_n[NS], ns_n = 0, lo_n = 0, hi_n = 0;
@@ -522,7 +560,13 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_fwd_kernel(
         const unsigned char *kt = kvbuf + (2 * st) * C::CHUNK, *vt = kt + C::CHUNK;
         const bool own = (cc.j == i);
         const int key0 = KEY_TILE * cc.t;
-        const int nsl = (ns > 0 && !(own && key0 > rank_hi)) ? ns : 0;  // wave-uniform
+        int nsl = (ns > 0 && !(own && key0 > rank_hi)) ? ns : 0;  // wave-uniform
+        if (MASKED) {
+            bool any = false;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) any = any || rsel[s];
+            if (!__any(any)) nsl = 0;  // none of the wavefront's rows attends this cube
+        }
         const bool need_mask = (key0 + KEY_TILE > jsize) || (own && key0 + KEY_TILE - 1 > rank_lo);
         const bool cube_ends = cc.t + 1 == cc.nt && cc.k + 1 < ncubes;
         if (SPARSE && cube_ends) {
@@ -536,18 +580,18 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_fwd_kernel(
             // slab counts vary from cube to cube: one guarded block per slab
             if (nsl >= 1) {
                 qk_tile<D, 0, 1, NS>(kt, n16, q4, qf, sacc);
-                softmax_tile<D, 0, 1, NS>(sacc, pf, oacc, m_run, l_run, lim, key0, need_mask, c2, q4);
+                softmax_tile<D, 0, 1, NS>(sacc, pf, oacc, m_run, l_run, lim, key0, need_mask, c2, q4, rsel);
                 pv_tile<D, 0, 1, NS>(vt, n16, q4, pf, oacc);
             }
             if (NS >= 2 && nsl >= 2) {
                 qk_tile<D, 1, NS, NS>(kt, n16, q4, qf, sacc);
-                softmax_tile<D, 1, NS, NS>(sacc, pf, oacc, m_run, l_run, lim, key0, need_mask, c2, q4);
+                softmax_tile<D, 1, NS, NS>(sacc, pf, oacc, m_run, l_run, lim, key0, need_mask, c2, q4, rsel);
                 pv_tile<D, 1, NS, NS>(vt, n16, q4, pf, oacc);
             }
-        } else if (nsl) {
+        } else if (nsl || !MASKED) {
             // fixed row set: all slabs, padding columns of a partial slab compute on the scratch row
             qk_tile<D, 0, NS, NS>(kt, n16, q4, qf, sacc);
-            softmax_tile<D, 0, NS, NS>(sacc, pf, oacc, m_run, l_run, lim, key0, need_mask, c2, q4);
+            softmax_tile<D, 0, NS, NS, MASKED>(sacc, pf, oacc, m_run, l_run, lim, key0, need_mask, c2, q4, rsel);
             pv_tile<D, 0, NS, NS>(vt, n16, q4, pf, oacc);
         }
         advance(cc);
@@ -557,6 +601,7 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_fwd_kernel(
                 new_slabs = true;
             } else {
                 jsize = set_limits(cc.j);
+                set_rsel(cc.j);
             }
         }
     }
@@ -600,9 +645,35 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_fwd_kernel(
     }
 }
 
-template <int D, bool SPARSE>
+// ---- choice between the compacting and the masked kernel: the share of candidate cubes the rows select, from a
+// sample of rows.  One workgroup; writes 1 (compact) or 2 (masked) to *flag.
+constexpr int DENSITY_THREADS = 1024;
+constexpr int DENSITY_MAX_ROWS = 16384;
+constexpr int MASKED_ABOVE_PERCENT = 35;  // measured crossover of the two kernels on MI355X
+
+__global__ __launch_bounds__(DENSITY_THREADS) void sel_density_kernel(Geom g, const uint32_t *__restrict__ sel_mask,
+                                                                      int *__restrict__ flag)
+{
+    __shared__ unsigned long long acc[2];
+    if (threadIdx.x == 0) acc[0] = acc[1] = 0ull;
+    __syncthreads();
+    const long long R = (long long)g.S * g.Hq;
+    const long long stride = max(1ll, R / DENSITY_MAX_ROWS);
+    unsigned long long sel = 0, cand = 0;
+    for (long long r = threadIdx.x * stride; r < R; r += DENSITY_THREADS * stride) {
+        cand += (unsigned long long)cube_of_token(g, (int)(r / g.Hq));
+        const uint32_t *mr = sel_mask + (size_t)r * g.words;
+        for (int w = 0; w < g.words; ++w) sel += __popc(mr[w]);
+    }
+    atomicAdd(&acc[0], sel);
+    atomicAdd(&acc[1], cand);
+    __syncthreads();
+    if (threadIdx.x == 0) *flag = (acc[0] * 100ull > acc[1] * (unsigned long long)MASKED_ABOVE_PERCENT) ? 2 : 1;
+}
+
+template <int D, bool SPARSE, bool MASKED>
 static hipError_t launch_fwd(const Geom &g, const uint16_t *Q, const void *packed, const uint32_t *sel_mask,
-                             uint16_t *O, float *lse, hipStream_t st)
+                             const int *mode_flag, int my_mode, uint16_t *O, float *lse, hipStream_t st)
 {
     using C = Fwd<D, SPARSE>;
     const uint16_t *Kp = reinterpret_cast<const uint16_t *>(packed);
@@ -611,23 +682,36 @@ static hipError_t launch_fwd(const Geom &g, const uint16_t *Q, const void *packe
     const int32_t *csize = reinterpret_cast<const int32_t *>(Vt + half_elems);
     const int nblk_max = (g.G * g.Cmax + C::MMAX - 1) / C::MMAX;
     const dim3 grid((unsigned)((size_t)((g.N * g.Hkv + 7) / 8) * nblk_max * 8));
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_fwd_kernel<D, SPARSE>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_fwd_kernel<D, SPARSE, MASKED>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::BYTES);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((attn_fwd_kernel<D, SPARSE>), grid, dim3(C::THREADS), C::BYTES, st, g, Q, Kp, Vt, csize,
-                       sel_mask, O, lse);
+    hipLaunchKernelGGL((attn_fwd_kernel<D, SPARSE, MASKED>), grid, dim3(C::THREADS), C::BYTES, st, g, Q, Kp, Vt, csize,
+                       sel_mask, mode_flag, my_mode, O, lse);
     return hipGetLastError();
 }
 
-hipError_t launch_attn(const Geom &g, const uint16_t *Q, const void *packed, const uint32_t *sel_mask, uint16_t *O,
-                       float *lse, hipStream_t st)
+template <int D>
+static hipError_t launch_attn_d(const Geom &g, const uint16_t *Q, void *packed, const uint32_t *sel_mask,
+                                int sparse_kernel, uint16_t *O, float *lse, hipStream_t st)
 {
-    if (sel_mask != nullptr) {
-        if (g.D == 64) return launch_fwd<64, true>(g, Q, packed, sel_mask, O, lse, st);
-        return launch_fwd<128, true>(g, Q, packed, sel_mask, O, lse, st);
-    }
-    if (g.D == 64) return launch_fwd<64, false>(g, Q, packed, nullptr, O, lse, st);
-    return launch_fwd<128, false>(g, Q, packed, nullptr, O, lse, st);
+    if (sel_mask == nullptr) return launch_fwd<D, false, false>(g, Q, packed, nullptr, nullptr, 0, O, lse, st);
+    if (sparse_kernel == ADASPARK_SPARSE_COMPACT)
+        return launch_fwd<D, true, false>(g, Q, packed, sel_mask, nullptr, 0, O, lse, st);
+    if (sparse_kernel == ADASPARK_SPARSE_MASKED)
+        return launch_fwd<D, false, true>(g, Q, packed, sel_mask, nullptr, 0, O, lse, st);
+    // automatic: estimate the density on the device, enqueue both kernels, the one not chosen returns at once
+    int *flag = reinterpret_cast<int *>(reinterpret_cast<char *>(packed) + attn_workspace_bytes(g) - 16);
+    hipLaunchKernelGGL(sel_density_kernel, dim3(1), dim3(DENSITY_THREADS), 0, st, g, sel_mask, flag);
+    hipError_t e = launch_fwd<D, true, false>(g, Q, packed, sel_mask, flag, 1, O, lse, st);
+    if (e != hipSuccess) return e;
+    return launch_fwd<D, false, true>(g, Q, packed, sel_mask, flag, 2, O, lse, st);
+}
+
+hipError_t launch_attn(const Geom &g, const uint16_t *Q, void *packed, const uint32_t *sel_mask, int sparse_kernel,
+                       uint16_t *O, float *lse, hipStream_t st)
+{
+    if (g.D == 64) return launch_attn_d<64>(g, Q, packed, sel_mask, sparse_kernel, O, lse, st);
+    return launch_attn_d<128>(g, Q, packed, sel_mask, sparse_kernel, O, lse, st);
 }
 
 }  // namespace adaspark

@@ -88,8 +88,9 @@ hipError_t launch_cube_select(const Geom &g, const uint16_t *Q, const float *kba
                               hipStream_t st);
 size_t attn_workspace_bytes(const Geom &g);
 hipError_t launch_kv_pack(const Geom &g, const uint16_t *K, const uint16_t *V, void *ws, hipStream_t st);
-// sel_mask == nullptr: dense (every preceding cube attended)
-hipError_t launch_attn(const Geom &g, const uint16_t *Q, const void *packed, const uint32_t *sel_mask, uint16_t *O,
-                       float *lse, hipStream_t st);
+// sel_mask == nullptr: dense (every preceding cube attended); otherwise sparse_kernel is an adaspark_sparse_kernel.
+// The automatic choice writes a flag into the last 16 bytes of the packed workspace.
+hipError_t launch_attn(const Geom &g, const uint16_t *Q, void *packed, const uint32_t *sel_mask, int sparse_kernel,
+                       uint16_t *O, float *lse, hipStream_t st);
 
 }  // namespace adaspark

@@ -48,8 +48,9 @@ __global__ __launch_bounds__(256) void kv_pack_kernel(Geom g, const uint16_t *__
 
 size_t attn_workspace_bytes(const Geom &g)
 {
-    // Kp and Vt: [Hkv][N][TPC][64][D] bf16 each, then the cube sizes: int32 [N]
-    return 2 * (size_t)g.Hkv * g.N * g.TPC * KEY_TILE * g.D * sizeof(uint16_t) + (((size_t)g.N * 4 + 15) / 16) * 16;
+    // Kp and Vt: [Hkv][N][TPC][64][D] bf16 each, then the cube sizes: int32 [N], then 16 bytes of scratch for the
+    // attention entries (kernel choice flag)
+    return 2 * (size_t)g.Hkv * g.N * g.TPC * KEY_TILE * g.D * sizeof(uint16_t) + (((size_t)g.N * 4 + 15) / 16) * 16 + 16;
 }
 
 template <int D>

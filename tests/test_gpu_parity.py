@@ -114,6 +114,14 @@ def test_full_path_small(B, oracle, w):
     torch.cuda.synchronize()
     check_outputs(f"{w.name} attn(oracle sel)", O.reshape(-1, w.D).float().cpu().numpy(), ref_out)
     assert torch.isfinite(lse).all()
+    # (1b) each of the two sparse kernels, forced: the library's own choice above is one of them
+    packed = B.kv_pack(sh, Kg, Vg)
+    for kern in (B.SPARSE_COMPACT, B.SPARSE_MASKED):
+        Ok, lsek = B.sparse_attn_packed(sh, Qg, packed, torch.from_numpy(ref_mask.view(np.int32)).cuda(),
+                                        return_lse=True, kernel=kern)
+        torch.cuda.synchronize()
+        check_outputs(f"{w.name} attn(oracle sel, kernel {kern})", Ok.reshape(-1, w.D).float().cpu().numpy(), ref_out)
+        assert torch.allclose(lsek, lse, atol=2e-3, rtol=0)
     # (2) whole GPU pipeline; rows whose set differs (all exempt) are excluded from the statistic
     mask, count, _, _ = B.cube_select(sh, Qg, kbar, p32)
     O2 = B.sparse_attn(sh, Qg, Kg, Vg, mask)
@@ -194,6 +202,11 @@ def sampled_case(B, oracle, w, p_list, n_rows, check_dense=True):
         ref_out, _ = oracle.sparse_attn(osh, Q, K, V, ref_mask, rows=rows)
         got = rows_of(O, rows, w)
         check_outputs(f"{w.name} p={p} pipeline(sampled)", got[same], ref_out[same])
+        # both sparse kernels, forced (the call above let the library choose)
+        for kern in (B.SPARSE_COMPACT, B.SPARSE_MASKED):
+            Ok = B.sparse_attn_packed(sh, Qg, ws_att, mask, kernel=kern)
+            torch.cuda.synchronize()
+            check_outputs(f"{w.name} p={p} kernel {kern}(sampled)", rows_of(Ok, rows, w)[same], ref_out[same])
     if check_dense:
         Od = B.dense_attn(sh, Qg, Kg, Vg, workspace=ws_att)
         torch.cuda.synchronize()
