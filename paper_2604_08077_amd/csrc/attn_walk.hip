@@ -1,0 +1,424 @@
+// Dense causal attention, and sparse attention (Eq. 3 + own-cube rule, Sec. 3.2) with the selection applied as a
+// mask: every row walks every preceding cube.  Also the entry that chooses between this kernel and the
+// compacting one (attn_compact.hip).
+//
+// Fixed-row walk with two wavefront sets in counter-phase (dense attention, and sparse attention with the
+// selection applied as a mask).
+//
+// On a SIMD an MFMA keeps the matrix pipe busy for ~16 cycles and leaves room for two or three vector
+// instructions; a wavefront alone cannot use that room, because its softmax needs the finished scores.  So a
+// workgroup holds eight wavefronts, two per SIMD, and the two of a SIMD are kept half a tile apart: while set X
+// (wavefronts 0-3) runs the softmax of tile t, set Y (4-7) runs P.V of tile t-1 and S = Q.K^T of tile t; then X
+// runs P.V(t) and S(t+1) while Y runs softmax(t).  Two workgroup barriers per tile hold the sets in that phase.
+//
+//   slot a(t):  X: softmax(t)          Y: P.V(t-1), S(t)
+//   slot b(t):  X: P.V(t), S(t+1)      Y: softmax(t)
+//
+// K and V^T tiles go through three LDS stages each (tile t in stage t % 3).  After the barrier that opens slot
+// b(t) nobody reads K(t) or V(t-1) any more, and the direct-to-LDS loads of K(t+3) and V(t+2) go into their
+// stages; they are waited for two barriers later (the loads started one tile ago may stay in flight).
+#include "attn_tile.h"
+
+namespace adaspark {
+
+template <int D>
+struct Walk {
+    static constexpr int WAVES = 8;
+    static constexpr int THREADS = 64 * WAVES;
+    static constexpr int NS = FWD_NS;
+    static constexpr int MMAX = 16 * NS * WAVES;  // 256 rows
+    static constexpr int NST = 3;  // LDS stages of K and of V^T
+    static constexpr int PF = 4;   // operand loads in flight ahead of the MFMAs
+    static constexpr int CHUNK = KEY_TILE * D * 2;
+    static constexpr int DMA = CHUNK / 1024 / WAVES;
+    static constexpr int SMALL = (((MMAX + 1) * 4 + 15) / 16) * 16;
+    static constexpr int OFF_K = 0;
+    static constexpr int OFF_V = OFF_K + NST * CHUNK;
+    static constexpr int OFF_ROWID = OFF_V + NST * CHUNK;
+    static constexpr int OFF_RANK = OFF_ROWID + SMALL;
+    static constexpr int OFF_MISC = OFF_RANK + SMALL;
+    static constexpr int BYTES = OFF_MISC + 16;
+    static_assert(DMA >= 1, "a tile is at least 1 KB per wavefront");
+    static_assert(BYTES <= 160 * 1024, "LDS of one CU");
+};
+
+
+// Barrier that opens a slot a: all direct-to-LDS loads but the newest KEEP of this wavefront have landed.  Nothing
+// waits for LDS reads here: the reads of a phase are consumed by its MFMAs before the wavefront gets here, and
+// the operand loads started ahead of the next phase touch stages nobody writes.
+template <int KEEP>
+__device__ __forceinline__ void dma_barrier()
+{
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(KEEP) : "memory");
+}
+// Barrier that opens a slot b: synchronisation only.
+__device__ __forceinline__ void bare_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+template <int D, bool MASKED>
+__global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
+    Geom g, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Kp, const uint16_t *__restrict__ Vt,
+    const int32_t *__restrict__ csize, const uint32_t *__restrict__ sel_mask, const int *__restrict__ mode_flag,
+    int my_mode, uint16_t *__restrict__ O, float *__restrict__ lse)
+{
+    if (mode_flag != nullptr && *mode_flag != my_mode) return;
+    using C = Walk<D>;
+    constexpr int NS = C::NS, MMAX = C::MMAX, THREADS = C::THREADS, WAVES = C::WAVES, NST = C::NST;
+    constexpr int KSTEPS = D / 32, DT = D / 16;
+    constexpr int PF = C::PF;
+    extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
+    int *rowid = reinterpret_cast<int *>(smem + C::OFF_ROWID);
+    int *rrank = reinterpret_cast<int *>(smem + C::OFF_RANK);
+    int *misc = reinterpret_cast<int *>(smem + C::OFF_MISC);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n16 = lane & 15, q4 = lane >> 4;
+    const bool set_y = __builtin_amdgcn_readfirstlane(wave >> 2) != 0;
+
+    // workgroup -> (query cube, KV head, row block): as in attn_fwd_kernel
+    const int nblk_max = (g.G * g.Cmax + MMAX - 1) / MMAX;
+    const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+    const int grp = (seq / nblk_max) * 8 + xcd;
+    const int blk = seq % nblk_max;
+    if (grp >= g.N * g.Hkv) return;
+    const int kv = grp % g.Hkv;
+    const int i = g.N - 1 - grp / g.Hkv;
+    const CubeBox qbox = cube_box(g, i);
+    const int qsize = qbox.size();
+    const int P = g.G * qsize;
+    const int nblk = (P + MMAX - 1) / MMAX;
+    if (blk >= nblk) return;
+    const int row0 = (int)((long long)blk * P / nblk), row1 = (int)((long long)(blk + 1) * P / nblk);
+    const int Mrows = row1 - row0;
+    const int max_rank = (row1 - 1) / g.G;
+    const int own_tiles = min((qsize + KEY_TILE - 1) / KEY_TILE, max_rank / KEY_TILE + 1);
+
+    for (int r = tid; r < Mrows; r += THREADS) {
+        const int rho = row0 + r, rank = rho / g.G, hg = rho % g.G;
+        const int rid = token_of(g, qbox, rank) * g.Hq + kv * g.G + hg;
+        rowid[r] = rid;
+        rrank[r] = rank;
+        if (r == 0) {  // scratch row behind the padding columns of a partial slab
+            rowid[MMAX] = rid;
+            rrank[MMAX] = 0;
+        }
+    }
+    if (tid == 0) misc[0] = 0;
+    __syncthreads();
+
+    // the tile stream: cubes 0..i in order, the own cube i last and only up to the largest rank of the block
+    const int ncubes = i + 1;
+    auto tiles_of = [&](int j) -> int {
+        if (j == i) return own_tiles;
+        return g.ragged ? (csize[j] + KEY_TILE - 1) / KEY_TILE : g.TPC;
+    };
+    {
+        int part = 0;
+        for (int k = tid; k < ncubes; k += THREADS) part += tiles_of(k);
+        for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
+        if (lane == 0) atomicAdd(&misc[0], part);
+        __syncthreads();
+    }
+    const int ntiles = __builtin_amdgcn_readfirstlane(misc[0]);
+
+    auto first_tile = [&]() -> TilePos {
+        TilePos p;
+        p.k = p.j = 0;
+        p.t = 0;
+        p.nt = tiles_of(0);
+        return p;
+    };
+    auto advance = [&](TilePos &p) __attribute__((always_inline)) {
+        if (p.t + 1 < p.nt) ++p.t;
+        else if (p.j + 1 < ncubes) {
+            p.k = ++p.j;
+            p.t = 0;
+            p.nt = tiles_of(p.j);
+        }  // the last tile stays where it is: nothing is issued or computed past the end
+    };
+    // The K and V^T tiles are fetched as two streams: a wave-uniform pointer to the current tile and a countdown
+    // to the end of its cube (cubes are padded to TPC tiles in memory; a ragged cube's padding tiles are skipped).
+    struct Stream {
+        const unsigned char *tile;
+        int j, t, nt;
+    };
+    auto stream_begin = [&](const uint16_t *base) -> Stream {
+        Stream q;
+        q.tile = reinterpret_cast<const unsigned char *>(base + (size_t)kv * g.N * g.TPC * (KEY_TILE * D));
+        q.j = 0;
+        q.t = 0;
+        q.nt = tiles_of(0);
+        return q;
+    };
+    auto stream_next = [&](Stream &q) __attribute__((always_inline)) {
+        if (q.t + 1 < q.nt) {
+            ++q.t;
+            q.tile += C::CHUNK;
+        } else {
+            q.tile += (size_t)(g.TPC - q.t) * C::CHUNK;
+            q.j = min(q.j + 1, i);  // past the end nothing is issued; the index only has to stay valid
+            q.t = 0;
+            q.nt = tiles_of(q.j);
+        }
+    };
+    const uint32_t lds_piece =
+        __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem + (uint32_t)(wave * C::DMA * 1024));
+    const uint32_t src_piece = (uint32_t)(wave * C::DMA * 1024 + lane * 16);
+    auto issue = [&](const Stream &q, int off_bytes) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < C::DMA; ++u)
+            dma_1k_s(lds_piece + (uint32_t)(off_bytes + u * 1024), q.tile, src_piece + (uint32_t)(u * 1024));
+    };
+    auto next_stage = [](int st) -> int { return st + 1 == NST ? 0 : st + 1; };
+
+    // rows of this wavefront: slab k of the block belongs to wavefront k % WAVES as its slot k / WAVES
+    int lr[NS];
+    int ns = 0;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        const int idx = 16 * (wave + WAVES * s) + n16;
+        lr[s] = idx < Mrows ? idx : MMAX;
+        if (16 * (wave + WAVES * s) < Mrows) ns = s + 1;
+    }
+    int rank_lo = 0;
+    if (ns > 0) rank_lo = rrank[16 * wave];
+    rank_lo = __builtin_amdgcn_readfirstlane(rank_lo);
+
+    // prologue: K(0..2), V(0..1)
+    Stream sk = stream_begin(Kp), sv = stream_begin(Vt);
+    int tk = 0, tv = 0;  // index of the tile sk / sv points at
+    for (; tk < NST && tk < ntiles; ++tk) {
+        issue(sk, C::OFF_K + tk * C::CHUNK);
+        stream_next(sk);
+    }
+    for (; tv < NST - 1 && tv < ntiles; ++tv) {
+        issue(sv, C::OFF_V + tv * C::CHUNK);
+        stream_next(sv);
+    }
+
+    bf16x8 qf[NS][KSTEPS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        const uint16_t *qrow = Q + (size_t)rowid[lr[s]] * D + 8 * q4;
+#pragma unroll
+        for (int c = 0; c < KSTEPS; ++c) qf[s][c] = *reinterpret_cast<const bf16x8 *>(qrow + 32 * c);
+    }
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+        for (int c = 0; c < KSTEPS; ++c) asm volatile("" : "+v"(qf[s][c]));
+
+    const float c2 = 1.44269504088896340736f / sqrtf((float)D);
+    int lim[NS];
+    float m_run[NS];
+    f32x4 l_run[NS];  // every element holds the row's running sum
+    f32x4 oacc[NS][DT];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        m_run[s] = -1e30f;
+        l_run[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int e = 0; e < DT; ++e) oacc[s][e] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    bool rsel[NS];
+    uint32_t mword[NS];
+    int mword_idx = -1;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) { rsel[s] = true; mword[s] = 0; }
+    int jsize = 0;
+    // per-cube constants of the softmax: key limits of every row, and (MASKED) whether the row attends the cube
+    auto enter_cube = [&](int j) __attribute__((always_inline)) {
+        const bool own = (j == i);
+        jsize = own ? qsize : (g.ragged ? csize[j] : g.Cmax);
+#pragma unroll
+        for (int s = 0; s < NS; ++s) lim[s] = own ? min(rrank[lr[s]], jsize - 1) : jsize - 1;
+        if (MASKED) {
+            if (own) {
+#pragma unroll
+                for (int s = 0; s < NS; ++s) rsel[s] = true;
+            } else {
+                if ((j >> 5) != mword_idx) {
+                    mword_idx = j >> 5;
+#pragma unroll
+                    for (int s = 0; s < NS; ++s) mword[s] = sel_mask[(size_t)rowid[lr[s]] * g.words + mword_idx];
+                }
+#pragma unroll
+                for (int s = 0; s < NS; ++s) rsel[s] = (mword[s] >> (j & 31)) & 1u;
+            }
+        }
+    };
+    TilePos cc = first_tile();  // the tile whose softmax comes next
+    enter_cube(cc.j);
+
+    f32x4 sacc[NS][4];
+    bf16x8 pf[NS][2];
+    auto softmax_step = [&]() __attribute__((always_inline)) {
+        const bool own = (cc.j == i);
+        const int key0 = KEY_TILE * cc.t;
+        const bool need_mask = (key0 + KEY_TILE > jsize) || (own && key0 + KEY_TILE - 1 > rank_lo);
+        softmax_tile<D, 0, NS, NS, MASKED>(sacc, pf, oacc, m_run, l_run, lim, key0, need_mask, c2, q4, rsel);
+        const int j0 = cc.j;
+        advance(cc);
+        if (cc.j != j0) enter_cube(cc.j);
+    };
+
+    tile_barrier();  // the prologue's tiles have landed
+    int st = 0;      // stage of tile T
+    bf16x8 ring[PF];
+    // Opens slot a(T).  The loads started after the barrier of slot b(T-1) may stay in flight; everything older
+    // has landed: K(T+1) and V(T), one slot before set X needs them, so X can start its operand loads early.
+    auto open_slot_a = [&](int T) __attribute__((always_inline)) {
+        if (T + NST - 1 < ntiles) dma_barrier<(NST - 2) * 2 * C::DMA>();
+        else dma_barrier<0>();
+    };
+    // Opens slot b(T) and refills the two stages that fell free (K(T)'s with K(T+3), V(T-1)'s with V(T+2)).
+    auto open_slot_b = [&]() __attribute__((always_inline)) {
+        bare_barrier();
+        const int st_prev = st == 0 ? NST - 1 : st - 1;
+        if (tk < ntiles) {
+            issue(sk, C::OFF_K + st * C::CHUNK);
+            stream_next(sk);
+            ++tk;
+        }
+        if (tv < ntiles) {
+            issue(sv, C::OFF_V + st_prev * C::CHUNK);
+            stream_next(sv);
+            ++tv;
+        }
+    };
+    // The first and the last tile are peeled off the loops: a loop body with a conditional MFMA phase would merge
+    // two versions of every accumulator at its end, at the price of a register copy each.
+    if (!set_y) {
+        phase_prefetch<D, PF, false, true>(nullptr, smem + C::OFF_K, n16, q4, ring);
+        mfma_phase<D, NS, PF, false, true>(nullptr, smem + C::OFF_K, n16, q4, ring, pf, oacc, l_run, qf, sacc);
+        for (int T = 0; T + 1 < ntiles; ++T) {
+            open_slot_a(T);
+            softmax_step();
+            const unsigned char *vt = smem + C::OFF_V + st * C::CHUNK;                 // V(T)
+            const unsigned char *kt = smem + C::OFF_K + next_stage(st) * C::CHUNK;     // K(T+1)
+            phase_prefetch<D, PF, true, true>(vt, kt, n16, q4, ring);
+            open_slot_b();
+            st = next_stage(st);
+            mfma_phase<D, NS, PF, true, true>(vt, kt, n16, q4, ring, pf, oacc, l_run, qf, sacc);
+        }
+        open_slot_a(ntiles - 1);
+        softmax_step();
+        const unsigned char *vt = smem + C::OFF_V + st * C::CHUNK;
+        phase_prefetch<D, PF, true, false>(vt, nullptr, n16, q4, ring);
+        open_slot_b();
+        mfma_phase<D, NS, PF, true, false>(vt, nullptr, n16, q4, ring, pf, oacc, l_run, qf, sacc);
+    } else {
+        phase_prefetch<D, PF, false, true>(nullptr, smem + C::OFF_K, n16, q4, ring);
+        open_slot_a(0);
+        mfma_phase<D, NS, PF, false, true>(nullptr, smem + C::OFF_K, n16, q4, ring, pf, oacc, l_run, qf, sacc);
+        open_slot_b();
+        softmax_step();
+        for (int T = 1; T < ntiles; ++T) {
+            const unsigned char *vt = smem + C::OFF_V + st * C::CHUNK;  // V(T-1): landed two barriers ago
+            st = next_stage(st);
+            const unsigned char *kt = smem + C::OFF_K + st * C::CHUNK;  // K(T): likewise
+            phase_prefetch<D, PF, true, true>(vt, kt, n16, q4, ring);
+            open_slot_a(T);
+            mfma_phase<D, NS, PF, true, true>(vt, kt, n16, q4, ring, pf, oacc, l_run, qf, sacc);
+            open_slot_b();
+            softmax_step();
+        }
+        const unsigned char *vt = smem + C::OFF_V + st * C::CHUNK;
+        phase_prefetch<D, PF, true, false>(vt, nullptr, n16, q4, ring);
+        mfma_phase<D, NS, PF, true, false>(vt, nullptr, n16, q4, ring, pf, oacc, l_run, qf, sacc);
+    }
+
+    // ---- normalise and write out (no direct-to-LDS load may outlive the workgroup's LDS allocation)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        if (lr[s] == MMAX) continue;
+        const int rid = rowid[lr[s]];
+        const float inv = 1.0f / l_run[s][0];
+        uint16_t *orow = O + (size_t)rid * D + 4 * q4;
+#pragma unroll
+        for (int e = 0; e < DT; ++e) {
+            const uint32_t w0 = (uint32_t)float_to_bf16_bits(oacc[s][e][0] * inv) |
+                                ((uint32_t)float_to_bf16_bits(oacc[s][e][1] * inv) << 16);
+            const uint32_t w1 = (uint32_t)float_to_bf16_bits(oacc[s][e][2] * inv) |
+                                ((uint32_t)float_to_bf16_bits(oacc[s][e][3] * inv) << 16);
+            *reinterpret_cast<uint2 *>(orow + 16 * e) = make_uint2(w0, w1);
+        }
+        if (lse != nullptr && q4 == 0) lse[rid] = (m_run[s] + log2f(l_run[s][0])) * 0.69314718055994530942f;
+    }
+}
+
+// ---- choice between the compacting and the masked kernel: the share of candidate cubes the rows select, from a
+// sample of rows.  One workgroup; writes 1 (compact) or 2 (masked) to *flag.
+constexpr int DENSITY_THREADS = 1024;
+constexpr int DENSITY_MAX_ROWS = 16384;
+// Measured on MI355X with rows that select independently of each other: the compacting kernel wins only below
+// about 1.5 % selected cubes.
+constexpr int MASKED_ABOVE_PERMILLE = 15;
+
+__global__ __launch_bounds__(DENSITY_THREADS) void sel_density_kernel(Geom g, const uint32_t *__restrict__ sel_mask,
+                                                                      int *__restrict__ flag)
+{
+    __shared__ unsigned long long acc[2];
+    if (threadIdx.x == 0) acc[0] = acc[1] = 0ull;
+    __syncthreads();
+    const long long R = (long long)g.S * g.Hq;
+    const long long stride = max(1ll, R / DENSITY_MAX_ROWS);
+    unsigned long long sel = 0, cand = 0;
+    for (long long r = threadIdx.x * stride; r < R; r += DENSITY_THREADS * stride) {
+        cand += (unsigned long long)cube_of_token(g, (int)(r / g.Hq));
+        const uint32_t *mr = sel_mask + (size_t)r * g.words;
+        for (int w = 0; w < g.words; ++w) sel += __popc(mr[w]);
+    }
+    atomicAdd(&acc[0], sel);
+    atomicAdd(&acc[1], cand);
+    __syncthreads();
+    if (threadIdx.x == 0)
+        *flag = (acc[0] * 1000ull > acc[1] * (unsigned long long)MASKED_ABOVE_PERMILLE) ? 2 : 1;
+}
+
+template <int D, bool MASKED>
+static hipError_t launch_walk(const Geom &g, const uint16_t *Q, const void *packed, const uint32_t *sel_mask,
+                              const int *mode_flag, int my_mode, uint16_t *O, float *lse, hipStream_t st)
+{
+    using C = Walk<D>;
+    const uint16_t *Kp = reinterpret_cast<const uint16_t *>(packed);
+    const size_t half_elems = (size_t)g.Hkv * g.N * g.TPC * KEY_TILE * D;
+    const uint16_t *Vt = Kp + half_elems;
+    const int32_t *csize = reinterpret_cast<const int32_t *>(Vt + half_elems);
+    const int nblk_max = (g.G * g.Cmax + C::MMAX - 1) / C::MMAX;
+    const dim3 grid((unsigned)((size_t)((g.N * g.Hkv + 7) / 8) * nblk_max * 8));
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_walk_kernel<D, MASKED>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::BYTES);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((attn_walk_kernel<D, MASKED>), grid, dim3(C::THREADS), C::BYTES, st, g, Q, Kp, Vt, csize,
+                       sel_mask, mode_flag, my_mode, O, lse);
+    return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_attn_d(const Geom &g, const uint16_t *Q, void *packed, const uint32_t *sel_mask,
+                                int sparse_kernel, uint16_t *O, float *lse, hipStream_t st)
+{
+    if (sel_mask == nullptr) return launch_walk<D, false>(g, Q, packed, nullptr, nullptr, 0, O, lse, st);
+    if (sparse_kernel == ADASPARK_SPARSE_COMPACT)
+        return launch_attn_compact(g, Q, packed, sel_mask, nullptr, 0, O, lse, st);
+    if (sparse_kernel == ADASPARK_SPARSE_MASKED)
+        return launch_walk<D, true>(g, Q, packed, sel_mask, nullptr, 0, O, lse, st);
+    // automatic: estimate the density on the device, enqueue both kernels, the one not chosen returns at once
+    int *flag = reinterpret_cast<int *>(reinterpret_cast<char *>(packed) + attn_workspace_bytes(g) - 16);
+    hipLaunchKernelGGL(sel_density_kernel, dim3(1), dim3(DENSITY_THREADS), 0, st, g, sel_mask, flag);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = launch_attn_compact(g, Q, packed, sel_mask, flag, 1, O, lse, st);
+    if (e != hipSuccess) return e;
+    return launch_walk<D, true>(g, Q, packed, sel_mask, flag, 2, O, lse, st);
+}
+
+hipError_t launch_attn(const Geom &g, const uint16_t *Q, void *packed, const uint32_t *sel_mask, int sparse_kernel,
+                       uint16_t *O, float *lse, hipStream_t st)
+{
+    if (g.D == 64) return launch_attn_d<64>(g, Q, packed, sel_mask, sparse_kernel, O, lse, st);
+    return launch_attn_d<128>(g, Q, packed, sel_mask, sparse_kernel, O, lse, st);
+}
+
+}  // namespace adaspark

@@ -92,5 +92,9 @@ hipError_t launch_kv_pack(const Geom &g, const uint16_t *K, const uint16_t *V, v
 // The automatic choice writes a flag into the last 16 bytes of the packed workspace.
 hipError_t launch_attn(const Geom &g, const uint16_t *Q, void *packed, const uint32_t *sel_mask, int sparse_kernel,
                        uint16_t *O, float *lse, hipStream_t st);
+// The compacting sparse kernel alone (attn_compact.hip).  mode_flag (device, may be null): run only if
+// *mode_flag == my_mode.
+hipError_t launch_attn_compact(const Geom &g, const uint16_t *Q, const void *packed, const uint32_t *sel_mask,
+                               const int *mode_flag, int my_mode, uint16_t *O, float *lse, hipStream_t st);
 
 }  // namespace adaspark
