@@ -2,21 +2,24 @@
 // mask: every row walks every preceding cube.  Also the entry that chooses between this kernel and the
 // compacting one (attn_compact.hip).
 //
-// Fixed-row walk with two wavefront sets in counter-phase (dense attention, and sparse attention with the
-// selection applied as a mask).
+// Fixed-row walk with two wavefront sets in counter-phase.
 //
-// On a SIMD an MFMA keeps the matrix pipe busy for ~16 cycles and leaves room for two or three vector
-// instructions; a wavefront alone cannot use that room, because its softmax needs the finished scores.  So a
-// workgroup holds eight wavefronts, two per SIMD, and the two of a SIMD are kept half a tile apart: while set X
-// (wavefronts 0-3) runs the softmax of tile t, set Y (4-7) runs P.V of tile t-1 and S = Q.K^T of tile t; then X
-// runs P.V(t) and S(t+1) while Y runs softmax(t).  Two workgroup barriers per tile hold the sets in that phase.
+// On a SIMD an MFMA keeps the matrix pipe busy for ~16 cycles, and vector instructions of another wavefront can
+// issue underneath it; a wavefront alone cannot use that room, because its softmax needs its finished scores.  So
+// a workgroup holds eight wavefronts, two per SIMD, and the two of a SIMD take the two halves of a tile's work in
+// opposite order.  Per tile t every wavefront runs one MFMA phase -- P.V of tile t-1, then S = Q.K^T of tile t --
+// and one softmax; set X (wavefronts 0-3) runs the MFMA phase first and the softmax of tile t after it, set Y (4-7)
+// first runs the softmax of tile t-1 (one tile late) and then the MFMA phase:
 //
-//   slot a(t):  X: softmax(t)          Y: P.V(t-1), S(t)
-//   slot b(t):  X: P.V(t), S(t+1)      Y: softmax(t)
+//   slot t:   X: [P.V(t-1), S(t)]  softmax(t)
+//             Y: softmax(t-1)      [P.V(t-1), S(t)]
 //
-// K and V^T tiles go through three LDS stages each (tile t in stage t % 3).  After the barrier that opens slot
-// b(t) nobody reads K(t) or V(t-1) any more, and the direct-to-LDS loads of K(t+3) and V(t+2) go into their
-// stages; they are waited for two barriers later (the loads started one tile ago may stay in flight).
+// so that one wavefront's softmax runs under the other's MFMAs, with one workgroup barrier per tile.
+//
+// K and V^T tiles go through three LDS stages each (tile t in stage t % 3).  Slot t reads K(t) and V(t-1); after
+// the barrier that opens it nobody reads K(t-1) or V(t-2) any more, and the direct-to-LDS loads of K(t+2) and
+// V(t+1) go into their stages; they are waited for two barriers later (the loads started one tile ago may stay in
+// flight).
 #include "attn_tile.h"
 
 namespace adaspark {
@@ -26,7 +29,7 @@ struct Walk {
     static constexpr int WAVES = 8;
     static constexpr int THREADS = 64 * WAVES;
     static constexpr int NS = FWD_NS;
-    static constexpr int MMAX = 16 * NS * WAVES;  // 256 rows
+    static constexpr int MMAX = 16 * NS * WAVES;  // 256 rows per workgroup
     static constexpr int NST = 3;  // LDS stages of K and of V^T
     static constexpr int PF = 4;   // operand loads in flight ahead of the MFMAs
     static constexpr int CHUNK = KEY_TILE * D * 2;
@@ -43,16 +46,13 @@ struct Walk {
 };
 
 
-// Barrier that opens a slot a: all direct-to-LDS loads but the newest KEEP of this wavefront have landed.  Nothing
-// waits for LDS reads here: the reads of a phase are consumed by its MFMAs before the wavefront gets here, and
-// the operand loads started ahead of the next phase touch stages nobody writes.
+// Barrier that opens a slot: all direct-to-LDS loads but the newest KEEP of this wavefront have landed.  Nothing
+// waits for LDS reads here: the operand reads of a slot are consumed by its MFMAs before the wavefront gets here.
 template <int KEEP>
 __device__ __forceinline__ void dma_barrier()
 {
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(KEEP) : "memory");
 }
-// Barrier that opens a slot b: synchronisation only.
-__device__ __forceinline__ void bare_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
 template <int D, bool MASKED>
 __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
@@ -183,14 +183,14 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
     if (ns > 0) rank_lo = rrank[16 * wave];
     rank_lo = __builtin_amdgcn_readfirstlane(rank_lo);
 
-    // prologue: K(0..2), V(0..1)
+    // prologue: K(0), K(1), V(0)
     Stream sk = stream_begin(Kp), sv = stream_begin(Vt);
     int tk = 0, tv = 0;  // index of the tile sk / sv points at
-    for (; tk < NST && tk < ntiles; ++tk) {
+    for (; tk < 2 && tk < ntiles; ++tk) {
         issue(sk, C::OFF_K + tk * C::CHUNK);
         stream_next(sk);
     }
-    for (; tv < NST - 1 && tv < ntiles; ++tv) {
+    for (; tv < 1 && tv < ntiles; ++tv) {
         issue(sv, C::OFF_V + tv * C::CHUNK);
         stream_next(sv);
     }
@@ -261,70 +261,60 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
         if (cc.j != j0) enter_cube(cc.j);
     };
 
-    tile_barrier();  // the prologue's tiles have landed
-    int st = 0;      // stage of tile T
+    static_assert(NST == 3, "the stage arithmetic below is for three stages");
+    int kst = 0;  // stage of K(t); V(t-1) sits in stage (kst + 2) % 3
     bf16x8 ring[PF];
-    // Opens slot a(T).  The loads started after the barrier of slot b(T-1) may stay in flight; everything older
-    // has landed: K(T+1) and V(T), one slot before set X needs them, so X can start its operand loads early.
-    auto open_slot_a = [&](int T) __attribute__((always_inline)) {
-        if (T + NST - 1 < ntiles) dma_barrier<(NST - 2) * 2 * C::DMA>();
+    // Opens slot t.  The loads started after the previous barrier, K(t+1) and V(t), may stay in flight; everything
+    // older has landed: K(t) and V(t-1).  Then K(t+2) and V(t+1) are started into the stages that fell free.
+    auto open_slot = [&](int t) __attribute__((always_inline)) {
+        if (t > 0 && t + 1 < ntiles) dma_barrier<2 * C::DMA>();
         else dma_barrier<0>();
-    };
-    // Opens slot b(T) and refills the two stages that fell free (K(T)'s with K(T+3), V(T-1)'s with V(T+2)).
-    auto open_slot_b = [&]() __attribute__((always_inline)) {
-        bare_barrier();
-        const int st_prev = st == 0 ? NST - 1 : st - 1;
+        const int st_v = kst == 0 ? 2 : kst - 1;  // (kst + 2) % 3: stage of V(t-1), and of K(t+2)
+        const int st_n = kst == 2 ? 0 : kst + 1;  // (kst + 1) % 3: stage of V(t+1)
         if (tk < ntiles) {
-            issue(sk, C::OFF_K + st * C::CHUNK);
+            issue(sk, C::OFF_K + st_v * C::CHUNK);
             stream_next(sk);
             ++tk;
         }
         if (tv < ntiles) {
-            issue(sv, C::OFF_V + st_prev * C::CHUNK);
+            issue(sv, C::OFF_V + st_n * C::CHUNK);
             stream_next(sv);
             ++tv;
         }
     };
-    // The first and the last tile are peeled off the loops: a loop body with a conditional MFMA phase would merge
+    auto k_tile = [&]() -> const unsigned char * { return smem + C::OFF_K + kst * C::CHUNK; };
+    auto v_tile = [&]() -> const unsigned char * { return smem + C::OFF_V + (kst == 0 ? 2 : kst - 1) * C::CHUNK; };
+    // The first and the last slot are peeled off the loops: a loop body with a conditional MFMA phase would merge
     // two versions of every accumulator at its end, at the price of a register copy each.
+    open_slot(0);
+    phase_prefetch<D, PF, false, true>(nullptr, k_tile(), n16, q4, ring);
+    mfma_phase<D, NS, PF, false, true>(nullptr, k_tile(), n16, q4, ring, pf, oacc, l_run, qf, sacc);
     if (!set_y) {
-        phase_prefetch<D, PF, false, true>(nullptr, smem + C::OFF_K, n16, q4, ring);
-        mfma_phase<D, NS, PF, false, true>(nullptr, smem + C::OFF_K, n16, q4, ring, pf, oacc, l_run, qf, sacc);
-        for (int T = 0; T + 1 < ntiles; ++T) {
-            open_slot_a(T);
-            softmax_step();
-            const unsigned char *vt = smem + C::OFF_V + st * C::CHUNK;                 // V(T)
-            const unsigned char *kt = smem + C::OFF_K + next_stage(st) * C::CHUNK;     // K(T+1)
-            phase_prefetch<D, PF, true, true>(vt, kt, n16, q4, ring);
-            open_slot_b();
-            st = next_stage(st);
-            mfma_phase<D, NS, PF, true, true>(vt, kt, n16, q4, ring, pf, oacc, l_run, qf, sacc);
-        }
-        open_slot_a(ntiles - 1);
         softmax_step();
-        const unsigned char *vt = smem + C::OFF_V + st * C::CHUNK;
-        phase_prefetch<D, PF, true, false>(vt, nullptr, n16, q4, ring);
-        open_slot_b();
-        mfma_phase<D, NS, PF, true, false>(vt, nullptr, n16, q4, ring, pf, oacc, l_run, qf, sacc);
+        for (int t = 1; t < ntiles; ++t) {
+            kst = next_stage(kst);
+            open_slot(t);
+            phase_prefetch<D, PF, true, true>(v_tile(), k_tile(), n16, q4, ring);
+            mfma_phase<D, NS, PF, true, true>(v_tile(), k_tile(), n16, q4, ring, pf, oacc, l_run, qf, sacc);
+            softmax_step();
+        }
+        kst = next_stage(kst);
+        open_slot(ntiles);
+        phase_prefetch<D, PF, true, false>(v_tile(), nullptr, n16, q4, ring);
+        mfma_phase<D, NS, PF, true, false>(v_tile(), nullptr, n16, q4, ring, pf, oacc, l_run, qf, sacc);
     } else {
-        phase_prefetch<D, PF, false, true>(nullptr, smem + C::OFF_K, n16, q4, ring);
-        open_slot_a(0);
-        mfma_phase<D, NS, PF, false, true>(nullptr, smem + C::OFF_K, n16, q4, ring, pf, oacc, l_run, qf, sacc);
-        open_slot_b();
-        softmax_step();
-        for (int T = 1; T < ntiles; ++T) {
-            const unsigned char *vt = smem + C::OFF_V + st * C::CHUNK;  // V(T-1): landed two barriers ago
-            st = next_stage(st);
-            const unsigned char *kt = smem + C::OFF_K + st * C::CHUNK;  // K(T): likewise
-            phase_prefetch<D, PF, true, true>(vt, kt, n16, q4, ring);
-            open_slot_a(T);
-            mfma_phase<D, NS, PF, true, true>(vt, kt, n16, q4, ring, pf, oacc, l_run, qf, sacc);
-            open_slot_b();
-            softmax_step();
+        for (int t = 1; t < ntiles; ++t) {
+            kst = next_stage(kst);
+            open_slot(t);
+            softmax_step();  // of tile t-1
+            phase_prefetch<D, PF, true, true>(v_tile(), k_tile(), n16, q4, ring);
+            mfma_phase<D, NS, PF, true, true>(v_tile(), k_tile(), n16, q4, ring, pf, oacc, l_run, qf, sacc);
         }
-        const unsigned char *vt = smem + C::OFF_V + st * C::CHUNK;
-        phase_prefetch<D, PF, true, false>(vt, nullptr, n16, q4, ring);
-        mfma_phase<D, NS, PF, true, false>(vt, nullptr, n16, q4, ring, pf, oacc, l_run, qf, sacc);
+        kst = next_stage(kst);
+        open_slot(ntiles);
+        softmax_step();
+        phase_prefetch<D, PF, true, false>(v_tile(), nullptr, n16, q4, ring);
+        mfma_phase<D, NS, PF, true, false>(v_tile(), nullptr, n16, q4, ring, pf, oacc, l_run, qf, sacc);
     }
 
     // ---- normalise and write out (no direct-to-LDS load may outlive the workgroup's LDS allocation)
