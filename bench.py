@@ -39,10 +39,7 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM traffic of one sparse-attention launch (bytes), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # scaled by a copy kernel of known size; keyed by (workload, top_p).  See profiles/.
-MEASURED_TRAFFIC_BYTES = {
-    # profiles/adas_attn_path_C3_p0.9_hbm_traffic.md: 6912.9 MB read + 469.8 MB written
-    ("C3", 0.9): 7.3827e9,
-}
+MEASURED_TRAFFIC_BYTES = {("C3", 0.9): 5.2155e9}
 
 
 def cube_tables(w):
