@@ -1,173 +1,25 @@
-// Relevance scoring + Top-p cube selection (Eqs. 1-2), and the compact
-// cube-index list built from the selection bitmask.
-//
-// One wavefront per query row (token, query head).  Lane l owns the candidate
-// cubes l, l+64, l+128, ...; the row's logits never leave registers.
-//   1. logits: q . kbar_j as an fp32 FMA chain over head_dim.  The mean keys are
-//      read from a transposed copy [kv_head][d][cube] so the 64 lanes read 64
-//      consecutive cubes (coalesced); q[d] is broadcast from the lane that
-//      holds it with a scalar lane read.
-//   2. softmax numerators e_j = exp2(logit_j*log2(e)/sqrt(D) - max) and their sum Z.
-//   3. Top-p without sorting: the kept set is {e_j > tau} plus, in index order,
-//      as many cubes with e_j == tau as are needed, where tau is the largest
-//      value with mass{e_j >= tau} >= p*Z.  tau is found bit by bit on the fp32
-//      pattern (positive floats order like unsigned integers), one wavefront
-//      sum per bit.  This equals "sort descending, ties by lower index, keep
-//      while the mass before an element is < p".
-//   4. the kept flags of each 64-cube chunk are one wave ballot = two mask words.
-#include "geom.h"
-
-namespace adaspark {
-
-constexpr int SELECT_THREADS = 256;
-constexpr int SELECT_ROWS_PER_BLOCK = SELECT_THREADS / 64;
-
-__device__ inline float wave_sum(float x)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
-    return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(x)));
-}
-
-__device__ inline float wave_max(float x)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off, 64));
-    return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(x)));
-}
-
-// kbar [N][Hkv][D] -> kbarT [Hkv][D][Npad], zero in the padding columns.
-__global__ void kbar_transpose_kernel(Geom g, int Npad, const float *__restrict__ kbar, float *__restrict__ kbarT)
-{
-    const size_t total = (size_t)g.Hkv * g.D * Npad;
-    for (size_t x = blockIdx.x * (size_t)blockDim.x + threadIdx.x; x < total; x += (size_t)gridDim.x * blockDim.x) {
-        const int j = (int)(x % Npad);
-        const int d = (int)((x / Npad) % g.D);
-        const int kv = (int)(x / ((size_t)Npad * g.D));
-        kbarT[x] = j < g.N ? kbar[((size_t)j * g.Hkv + kv) * g.D + d] : 0.f;
-    }
-}
-
-template <int D, int MAXK>
-__global__ __launch_bounds__(SELECT_THREADS) void cube_select_kernel(Geom g, int Npad, const uint16_t *__restrict__ Q,
-                                                                     const float *__restrict__ kbarT, float top_p,
-                                                                     uint32_t *__restrict__ sel_mask,
-                                                                     int32_t *__restrict__ sel_count)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const long long R = (long long)g.S * g.Hq;
-    const long long row = (long long)blockIdx.x * SELECT_ROWS_PER_BLOCK + wave;
-    if (row >= R) return;  // whole wavefront leaves together; no barriers below
-    const int n = (int)(row / g.Hq), a = (int)(row % g.Hq), kv = a / g.G;
-    const int i = cube_of_token(g, n);  // candidates are cubes 0..i-1
-    uint32_t *mrow = sel_mask + (size_t)row * g.words;
-
-    if (i == 0 || top_p <= 0.f || top_p >= 1.f) {
-        const int keep = (i > 0 && top_p >= 1.f) ? i : 0;  // p>=1: every preceding cube
-        for (int w = lane; w < g.words; w += 64) {
-            const int lo = 32 * w;
-            uint32_t bits = 0;
-            if (keep >= lo + 32) bits = 0xffffffffu;
-            else if (keep > lo) bits = (1u << (keep - lo)) - 1u;
-            mrow[w] = bits;
-        }
-        if (lane == 0) sel_count[row] = keep;
-        return;
-    }
-
-    // query row: lane l holds q[l] (and q[l+64] for D = 128)
-    const uint16_t *qrow = Q + (size_t)row * D;
-    const float q0 = bf16_bits_to_float(qrow[lane]);
-    const float q1 = (D > 64) ? bf16_bits_to_float(qrow[64 + lane]) : 0.f;
-
-    const int nch = (i + 63) >> 6;  // 64-cube chunks that hold candidates (wave-uniform)
-    const float scale = 1.44269504088896340736f / sqrtf((float)D);
-    float e[MAXK];
-    float mx = -INFINITY;
-#pragma unroll
-    for (int k = 0; k < MAXK; ++k) {
-        e[k] = -INFINITY;
-        if (k < nch) {
-            const float *col = kbarT + (size_t)kv * D * Npad + 64 * k + lane;
-            float acc = 0.f;
-#pragma unroll 16
-            for (int d = 0; d < 64; ++d)
-                acc = fmaf(__int_as_float(__builtin_amdgcn_readlane(__float_as_int(q0), d)), col[(size_t)d * Npad], acc);
-            if (D > 64) {
-#pragma unroll 16
-                for (int d = 0; d < 64; ++d)
-                    acc = fmaf(__int_as_float(__builtin_amdgcn_readlane(__float_as_int(q1), d)),
-                               col[(size_t)(64 + d) * Npad], acc);
-            }
-            if (64 * k + lane < i) {
-                e[k] = acc * scale;
-                mx = fmaxf(mx, e[k]);
-            }
-        }
-    }
-    mx = wave_max(mx);
-    float part = 0.f;
-#pragma unroll
-    for (int k = 0; k < MAXK; ++k) {
-        e[k] = (e[k] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(e[k] - mx);
-        part += e[k];
-    }
-    const float Z = wave_sum(part);
-    const float target = top_p * Z;
-
-    // largest tau (as a bit pattern) with mass{e >= tau} >= target
-    uint32_t tau = 0;
-    for (int b = 30; b >= 0; --b) {
-        const uint32_t cand = tau | (1u << b);
-        float s = 0.f;
-#pragma unroll
-        for (int k = 0; k < MAXK; ++k) s += (__float_as_uint(e[k]) >= cand) ? e[k] : 0.f;
-        if (wave_sum(s) >= target) tau = cand;
-    }
-    const float tauf = __uint_as_float(tau);
-    float sgt = 0.f;
-    int n_eq = 0;
-#pragma unroll
-    for (int k = 0; k < MAXK; ++k) {
-        sgt += (__float_as_uint(e[k]) > tau) ? e[k] : 0.f;
-        n_eq += __popcll(__ballot(__float_as_uint(e[k]) == tau && tau != 0));
-    }
-    const float mass_gt = wave_sum(sgt);
-
-    int kept = 0, ties_before = 0;
-    const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-#pragma unroll
-    for (int k = 0; k < MAXK; ++k) {
-        const uint32_t bits = __float_as_uint(e[k]);
-        const bool is_eq = (bits == tau) && tau != 0;
-        const unsigned long long eqb = __ballot(is_eq);
-        bool keep = bits > tau;
-        if (is_eq) {
-            // ties are taken in cube-index order while the mass before them is below the target
-            const int t = ties_before + __popcll(eqb & lt_mask);
-            keep = (t == 0) || (mass_gt + (float)t * tauf < target);
-        }
-        ties_before += __popcll(eqb);
-        const unsigned long long kb = __ballot(keep);
-        kept += __popcll(kb);
-        if (lane == 0) {
-            if (2 * k < g.words) mrow[2 * k] = (uint32_t)kb;
-            if (2 * k + 1 < g.words) mrow[2 * k + 1] = (uint32_t)(kb >> 32);
-        }
-    }
-    (void)n_eq;
-    if (lane == 0) sel_count[row] = kept;
-}
-
-// ---- MFMA path for grids of up to 256 cubes ---------------------------------------------------------------
+// Relevance scoring + Top-p cube selection (Eqs. 1-2), and the compact cube-index list built from the selection
+// bitmask.
 //
 // The logits of 16 query rows against 16 cubes are one 16x16 tile of K-bar.Q^T.  The fp32 mean keys are split
 // into three bf16 terms (hi + mid + lo reproduces the fp32 value to 2^-25), so three bf16 MFMAs accumulate the
 // fp32-accurate dot product; Q is bf16 already.  A wavefront holds the logits of its 16-row slabs in MFMA
-// accumulators: lane (n16, q4) owns row n16 and cubes 16*cg + 4*q4 + v.  Softmax and the Top-p threshold search
-// then run per lane over its 4*MAXG values, and a row's four lanes combine with two lane-swap steps: no
-// wavefront-wide reductions, no sort.  All rows of a workgroup belong to one query cube, so they share the
-// number of candidate cubes.
+// accumulators: lane (n16, q4) owns row n16 and cubes 16*cg + 4*q4 + v.  Then, per row:
+//   1. softmax numerators e_j = exp2(logit_j*log2(e)/sqrt(D) - max) and their sum Z,
+//   2. Top-p without sorting: the kept set is {e_j > tau} plus, in cube order, as many cubes with e_j == tau as
+//      are needed, where tau is the largest value with mass{e_j >= tau} >= p*Z.  tau is found bit by bit on the
+//      fp32 pattern (positive floats order like unsigned integers).  This equals "sort descending, ties by lower
+//      index, keep while the mass before an element is < p",
+//   3. the kept flags become mask words.
+// A lane works on its own 4*MAXG values and a row's four lanes combine with two lane-swap steps: no
+// wavefront-wide reductions, no sort.  All rows of a workgroup belong to one query cube, so they share the number
+// of candidate cubes.  Query cubes with up to 256 candidates are handled by cube_select_mfma_kernel (a wavefront
+// holds all candidates of its rows), later ones by cube_select_wide_kernel (four or eight wavefronts share the
+// rows and split the candidates).
+#include "geom.h"
+
+namespace adaspark {
+
 constexpr int SELM_THREADS = 256;
 constexpr int SELM_SLABS = 2;                                      // 16-row slabs per wavefront
 constexpr int SELM_ROWS = (SELM_THREADS / 64) * SELM_SLABS * 16;  // rows per workgroup
@@ -245,7 +97,7 @@ __device__ __forceinline__ float selm_quad_max(float x)
 
 template <int D, int MAXG>
 __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
-    Geom g, int NG, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ ksplit, float top_p,
+    Geom g, int NG, int i_end, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ ksplit, float top_p,
     uint32_t *__restrict__ sel_mask, int32_t *__restrict__ sel_count)
 {
     constexpr int KS = D / 32;
@@ -260,7 +112,7 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
     const int nblk_max = (g.G * g.Cmax + SELM_ROWS - 1) / SELM_ROWS;
     const int blk = blockIdx.x % nblk_max;
     const int kv = (blockIdx.x / nblk_max) % g.Hkv;
-    const int i = g.N - 1 - blockIdx.x / (nblk_max * g.Hkv);
+    const int i = i_end - 1 - blockIdx.x / (nblk_max * g.Hkv);  // this launch covers query cubes [.., i_end)
     const CubeBox qbox = cube_box(g, i);
     const int P = g.G * qbox.size();  // rows of this (cube, KV head): rho = rank * G + head-in-group
     if (blk * SELM_ROWS >= P) return;
@@ -486,7 +338,355 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
             kept += __popc(word);
             if (w < g.words && rowg[s] >= 0 && q4 == (w & 3)) sel_mask[(size_t)rowg[s] * g.words + w] = word;
         }
+        // words beyond this kernel's cube groups (grids with more cubes): no candidates there for these rows
+        if (rowg[s] >= 0)
+            for (int w = (MAXG + 1) / 2 + q4; w < g.words; w += 4) sel_mask[(size_t)rowg[s] * g.words + w] = 0u;
         if (rowg[s] >= 0 && q4 == 0) sel_count[rowg[s]] = kept;
+    }
+}
+
+// ---- More than 256 candidate cubes -----------------------------------------------------------------------
+//
+// The candidates of a row no longer fit one lane quad's registers, so the SPLIT wavefronts of a workgroup share the
+// same 32 query rows and each owns a block of 16 cube groups (256 cubes): wavefront p holds the logits of cubes
+// 256p .. 256p+255.  Everything per row that spans the blocks -- maximum, sum, the mass above a threshold
+// candidate, the tie counts -- is combined through a small LDS exchange, one workgroup barrier per combination;
+// every wavefront adds the parts in the same order, so all of them take the same decisions.  The mean-key operands
+// go straight from global memory (L2) into registers, one cube group ahead.
+constexpr int SELW_MAXG = 16;
+constexpr int SELW_SLABS = 2;
+constexpr int SELW_ROWS = 16 * SELW_SLABS;
+
+template <int D, int SPLIT>
+__global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
+    Geom g, int NG, int i_end, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ ksplit, float top_p,
+    uint32_t *__restrict__ sel_mask, int32_t *__restrict__ sel_count)
+{
+    constexpr int KS = D / 32, MAXG = SELW_MAXG, SLABS = SELW_SLABS;
+    constexpr int OPS = KS * 3;  // A operands (16 bytes per lane each) of one cube group
+    constexpr int XK = 2;        // values per row and wavefront in one exchange
+    __shared__ __attribute__((aligned(16))) uint32_t xch[2][SLABS][16][SPLIT * XK];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int part = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n16 = lane & 15, q4 = lane >> 4;
+    const int nblk_max = (g.G * g.Cmax + SELW_ROWS - 1) / SELW_ROWS;
+    const int blk = blockIdx.x % nblk_max;
+    const int kv = (blockIdx.x / nblk_max) % g.Hkv;
+    const int i = i_end - 1 - blockIdx.x / (nblk_max * g.Hkv);  // this launch covers query cubes [.., i_end)
+    const CubeBox qbox = cube_box(g, i);
+    const int P = g.G * qbox.size();
+    if (blk * SELW_ROWS >= P) return;  // the whole workgroup
+
+    int rowg[SLABS], rowq[SLABS];
+#pragma unroll
+    for (int s = 0; s < SLABS; ++s) {
+        const int rho = blk * SELW_ROWS + s * 16 + n16;
+        const int rc = min(rho, P - 1);
+        const int rid = token_of(g, qbox, rc / g.G) * g.Hq + kv * g.G + rc % g.G;
+        rowg[s] = rho < P ? rid : -1;
+        rowq[s] = rid;
+    }
+
+    if (i == 0 || top_p <= 0.f || top_p >= 1.f) {  // the whole workgroup; wavefront 0 writes
+        if (part != 0) return;
+        const int keep = (i > 0 && top_p >= 1.f) ? i : 0;
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) {
+            if (rowg[s] < 0) continue;
+            for (int w = q4; w < g.words; w += 4) {
+                const int lo = 32 * w;
+                uint32_t bits = 0;
+                if (keep >= lo + 32) bits = 0xffffffffu;
+                else if (keep > lo) bits = (1u << (keep - lo)) - 1u;
+                sel_mask[(size_t)rowg[s] * g.words + w] = bits;
+            }
+            if (q4 == 0) sel_count[rowg[s]] = keep;
+        }
+        return;
+    }
+
+    sel_bf16x8 qf[SLABS][KS];
+#pragma unroll
+    for (int s = 0; s < SLABS; ++s)
+#pragma unroll
+        for (int c = 0; c < KS; ++c)
+            qf[s][c] = *reinterpret_cast<const sel_bf16x8 *>(Q + (size_t)rowq[s] * D + 32 * c + 8 * q4);
+
+    // ---- logits of this wavefront's cube block: acc[s][lg][v] = q(row n16 of slab s) . kbar(cube 16(g0+lg)+4q4+v)
+    const int ng = (i + 15) >> 4;  // cube groups that hold candidates
+    const int g0 = part * MAXG;
+    const int nlg = min(max(ng - g0, 0), MAXG);  // of them, in this wavefront's block
+    sel_f32x4 acc[SLABS][MAXG];
+#pragma unroll
+    for (int s = 0; s < SLABS; ++s)
+#pragma unroll
+        for (int lg = 0; lg < MAXG; ++lg) acc[s][lg] = sel_f32x4{0.f, 0.f, 0.f, 0.f};
+    const sel_bf16x8 *src =
+        reinterpret_cast<const sel_bf16x8 *>(ksplit) + ((size_t)kv * NG + min(g0, NG - 1)) * (OPS * 64) + lane;
+    // operands run half a cube group ahead of the MFMAs: two register buffers of OPS/2 operands each
+    constexpr int HALF = OPS / 2, KSH = KS / 2;  // a half covers k-steps [KSH*h, KSH*h + KSH), three terms each
+    static_assert(KS % 2 == 0, "a cube group's operands are fetched in two halves");
+    sel_bf16x8 buf0[HALF], buf1[HALF];
+    if (nlg > 0) {
+#pragma unroll
+        for (int o = 0; o < HALF; ++o) buf0[o] = src[o * 64];
+    }
+#pragma unroll
+    for (int lg = 0; lg < MAXG; ++lg) {
+        if (lg < nlg) {  // uniform for the wavefront
+#pragma unroll
+            for (int o = 0; o < HALF; ++o) buf1[o] = src[((size_t)lg * OPS + HALF + o) * 64];
+#pragma unroll
+            for (int o = 0; o < HALF; ++o)
+#pragma unroll
+                for (int s = 0; s < SLABS; ++s)
+                    acc[s][lg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(buf0[o], qf[s][o / 3], acc[s][lg], 0, 0, 0);
+            if (lg + 1 < nlg) {
+#pragma unroll
+                for (int o = 0; o < HALF; ++o) buf0[o] = src[((size_t)(lg + 1) * OPS + o) * 64];
+            }
+#pragma unroll
+            for (int o = 0; o < HALF; ++o)
+#pragma unroll
+                for (int s = 0; s < SLABS; ++s)
+                    acc[s][lg] =
+                        __builtin_amdgcn_mfma_f32_16x16x32_bf16(buf1[o], qf[s][KSH + o / 3], acc[s][lg], 0, 0, 0);
+        }
+    }
+
+    // ---- exchange: every wavefront contributes XK values per row; afterwards each lane holds those of its row
+    // from all wavefronts.  Two buffers in turn: a wavefront that runs ahead writes the other one.
+    int xbuf = 0;
+    auto exchange = [&](const uint32_t (&v)[XK][SLABS], uint32_t (&all)[SPLIT][XK][SLABS]) __attribute__((always_inline)) {
+        if (q4 == 0) {
+#pragma unroll
+            for (int s = 0; s < SLABS; ++s)
+#pragma unroll
+                for (int k = 0; k < XK; ++k) xch[xbuf][s][n16][part * XK + k] = v[k][s];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s)
+#pragma unroll
+            for (int p = 0; p < SPLIT; ++p)
+#pragma unroll
+                for (int k = 0; k < XK; ++k) all[p][k][s] = xch[xbuf][s][n16][p * XK + k];
+        xbuf ^= 1;
+    };
+    uint32_t xv[XK][SLABS], xa[SPLIT][XK][SLABS];
+
+    // ---- softmax numerators e = exp2(logit*log2(e)/sqrt(D) - max), 0 for non-candidates; kept in acc
+    const float scale = 1.44269504088896340736f / sqrtf((float)D);
+#pragma unroll
+    for (int s = 0; s < SLABS; ++s) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int lg = 0; lg < MAXG; ++lg)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const bool valid = 16 * (g0 + lg) + 4 * q4 + v < i;
+                const float x = valid ? acc[s][lg][v] * scale : -INFINITY;
+                acc[s][lg][v] = x;
+                mx = fmaxf(mx, x);
+            }
+        xv[0][s] = __float_as_uint(selm_quad_max(mx));
+        xv[1][s] = 0;
+    }
+    exchange(xv, xa);
+    float target[SLABS];
+#pragma unroll
+    for (int s = 0; s < SLABS; ++s) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int p = 0; p < SPLIT; ++p) mx = fmaxf(mx, __uint_as_float(xa[p][0][s]));
+        float sum = 0.f;
+#pragma unroll
+        for (int lg = 0; lg < MAXG; ++lg)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float x = acc[s][lg][v];
+                const float e = (x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(x - mx);
+                acc[s][lg][v] = e;
+                sum += e;
+            }
+        xv[0][s] = __float_as_uint(selm_quad_sum(sum));
+    }
+    exchange(xv, xa);
+#pragma unroll
+    for (int s = 0; s < SLABS; ++s) {
+        float z = 0.f;
+#pragma unroll
+        for (int p = 0; p < SPLIT; ++p) z += __uint_as_float(xa[p][0][s]);
+        target[s] = top_p * z;
+    }
+
+    // ---- largest tau (as a bit pattern) with mass{e >= tau} >= target, bit by bit, both slabs in step
+    uint32_t tau[SLABS];
+#pragma unroll
+    for (int s = 0; s < SLABS; ++s) tau[s] = 0;
+    for (int b = 30; b >= 0; --b) {
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) {
+            const uint32_t cand = tau[s] | (1u << b);
+            float sum = 0.f;
+#pragma unroll
+            for (int lg = 0; lg < MAXG; ++lg)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float e = acc[s][lg][v];
+                    sum += (__float_as_uint(e) >= cand) ? e : 0.f;
+                }
+            xv[0][s] = __float_as_uint(selm_quad_sum(sum));
+        }
+        exchange(xv, xa);
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) {
+            float mass = 0.f;
+#pragma unroll
+            for (int p = 0; p < SPLIT; ++p) mass += __uint_as_float(xa[p][0][s]);
+            if (mass >= target[s]) tau[s] |= 1u << b;
+        }
+        // tau is the value of one of the row's elements and lies in [tau, tau + 2^b): once that bucket holds a
+        // single distinct value for every row, the remaining bits are known
+        if (b <= 22 && (b & 3) == 2) {
+            const uint32_t width = 1u << b;
+#pragma unroll
+            for (int s = 0; s < SLABS; ++s) {
+                uint32_t mn = 0xffffffffu, mxb = 0u;
+#pragma unroll
+                for (int lg = 0; lg < MAXG; ++lg)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const uint32_t bits = __float_as_uint(acc[s][lg][v]);
+                        const bool inb = bits - tau[s] < width;
+                        mn = inb ? min(mn, bits) : mn;
+                        mxb = inb ? max(mxb, bits) : mxb;
+                    }
+                xv[0][s] = selm_quad_umax(~mn);  // min via max of the complement
+                xv[1][s] = selm_quad_umax(mxb);
+            }
+            exchange(xv, xa);
+            bool single = true;
+            uint32_t only[SLABS];
+#pragma unroll
+            for (int s = 0; s < SLABS; ++s) {
+                uint32_t nmn = 0u, mxb = 0u;
+#pragma unroll
+                for (int p = 0; p < SPLIT; ++p) {
+                    nmn = max(nmn, xa[p][0][s]);
+                    mxb = max(mxb, xa[p][1][s]);
+                }
+                only[s] = ~nmn;
+                single = single && (only[s] == mxb);
+            }
+            if (__all(single)) {  // the same in every wavefront: they hold the same rows
+#pragma unroll
+                for (int s = 0; s < SLABS; ++s) tau[s] = only[s];
+                break;
+            }
+        }
+    }
+
+    // ---- mass above tau and the number of elements equal to it: in the whole row, and in the blocks before this
+    // wavefront's (ties are kept in cube order)
+#pragma unroll
+    for (int s = 0; s < SLABS; ++s) {
+        float sgt = 0.f;
+        int neq = 0;
+#pragma unroll
+        for (int lg = 0; lg < MAXG; ++lg)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const uint32_t bits = __float_as_uint(acc[s][lg][v]);
+                sgt += bits > tau[s] ? acc[s][lg][v] : 0.f;
+                neq += (bits == tau[s] && tau[s] != 0) ? 1 : 0;
+            }
+        xv[0][s] = __float_as_uint(selm_quad_sum(sgt));
+        xv[1][s] = (uint32_t)selm_quad_sum((float)neq);  // small counts: exact in fp32
+    }
+    exchange(xv, xa);
+    uint32_t kept_part[SLABS];
+#pragma unroll
+    for (int s = 0; s < SLABS; ++s) {
+        float mass_gt = 0.f;
+        int neq_row = 0, neq_before = 0;
+#pragma unroll
+        for (int p = 0; p < SPLIT; ++p) {
+            mass_gt += __uint_as_float(xa[p][0][s]);
+            neq_row += (int)xa[p][1][s];
+            neq_before += p < part ? (int)xa[p][1][s] : 0;
+        }
+        const float tauf = __uint_as_float(tau[s]);
+        uint32_t nib[MAXG];  // bit v of nib[lg]: cube 16(g0+lg) + 4q4 + v is kept
+        if (__any(neq_row > 1)) {
+            int running = neq_before;  // tied elements of this row in earlier cube groups
+#pragma unroll
+            for (int lg = 0; lg < MAXG; ++lg) {
+                int own = 0;
+                bool eq[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    eq[v] = __float_as_uint(acc[s][lg][v]) == tau[s] && tau[s] != 0;
+                    own += eq[v] ? 1 : 0;
+                }
+                const auto a = __builtin_amdgcn_permlane16_swap((uint32_t)own, (uint32_t)own, false, false);
+                const uint32_t pair = a[0] + a[1];
+                const auto b2 = __builtin_amdgcn_permlane32_swap(pair, pair, false, false);
+                const int before = (q4 & 1 ? (int)a[0] : 0) + (q4 & 2 ? (int)b2[0] : 0);
+                int t = running + before;
+                uint32_t bitsk = 0;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const uint32_t bits = __float_as_uint(acc[s][lg][v]);
+                    bool keep = bits > tau[s];
+                    if (eq[v]) {
+                        keep = (t == 0) || (mass_gt + (float)t * tauf < target[s]);
+                        ++t;
+                    }
+                    bitsk |= keep ? (1u << v) : 0u;
+                }
+                nib[lg] = bitsk;
+                running += (int)(b2[0] + b2[1]);
+            }
+        } else {
+#pragma unroll
+            for (int lg = 0; lg < MAXG; ++lg) {
+                uint32_t bitsk = 0;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const uint32_t bits = __float_as_uint(acc[s][lg][v]);
+                    bitsk |= (bits > tau[s] || (bits == tau[s] && tau[s] != 0)) ? (1u << v) : 0u;
+                }
+                nib[lg] = bitsk;
+            }
+        }
+        // mask words of this wavefront's block: word 8*part + w covers its cube groups 2w, 2w+1
+        int kept = 0;
+#pragma unroll
+        for (int w = 0; w < MAXG / 2; ++w) {
+            uint32_t word = (nib[2 * w] << (4 * q4)) | (nib[2 * w + 1] << (16 + 4 * q4));
+            word = selm_quad_or(word);
+            kept += __popc(word);
+            const int wg = (MAXG / 2) * part + w;
+            if (wg < g.words && rowg[s] >= 0 && q4 == (w & 3)) sel_mask[(size_t)rowg[s] * g.words + wg] = word;
+        }
+        kept_part[s] = (uint32_t)kept;
+    }
+#pragma unroll
+    for (int s = 0; s < SLABS; ++s) {
+        xv[0][s] = kept_part[s];
+        xv[1][s] = 0;
+    }
+    exchange(xv, xa);
+    if (part == 0 && q4 == 0) {
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) {
+            int kept = 0;
+#pragma unroll
+            for (int p = 0; p < SPLIT; ++p) kept += (int)xa[p][0][s];
+            if (rowg[s] >= 0) sel_count[rowg[s]] = kept;
+        }
     }
 }
 
@@ -580,8 +780,6 @@ __global__ void csr_fill_kernel(Geom g, long long R, const uint32_t *__restrict_
     }
 }
 
-static int select_npad(const Geom &g) { return (g.N + 63) / 64 * 64; }
-static bool select_use_mfma(const Geom &g) { return g.N <= SELM_MAX_CUBES; }
 static int select_groups(const Geom &g) { return (g.N + 15) / 16; }
 static size_t select_ksplit_bytes(const Geom &g)
 {
@@ -591,68 +789,52 @@ static long long scan_tiles(const Geom &g) { return ((long long)g.S * g.Hq + SCA
 
 size_t select_workspace_bytes(const Geom &g)
 {
-    // the transposed fp32 mean keys (general path) or their bf16 split (MFMA path), then the scan's tile sums
-    const size_t kbarT = (size_t)g.Hkv * g.D * select_npad(g) * sizeof(float);
-    const size_t first = select_use_mfma(g) ? select_ksplit_bytes(g) : ((kbarT + 255) / 256) * 256;
+    // the bf16 split of the mean keys, then the scan's tile sums
     const size_t tiles = (size_t)scan_tiles(g) * sizeof(long long);
-    return first + ((tiles + 255) / 256) * 256;
+    return select_ksplit_bytes(g) + ((tiles + 255) / 256) * 256;
 }
 
 template <int D>
-static void launch_select_d(const Geom &g, int Npad, const uint16_t *Q, const float *kbarT, float top_p,
+static void launch_select_d(const Geom &g, int NG, const uint16_t *Q, const uint16_t *ksplit, float top_p,
                             uint32_t *sel_mask, int32_t *sel_count, hipStream_t st)
 {
-    const long long R = (long long)g.S * g.Hq;
-    const dim3 grid((unsigned)((R + SELECT_ROWS_PER_BLOCK - 1) / SELECT_ROWS_PER_BLOCK)), block(SELECT_THREADS);
-#define ADASPARK_SELECT_CASE(MAXK)                                                                          \
-    hipLaunchKernelGGL((cube_select_kernel<D, MAXK>), grid, block, 0, st, g, Npad, Q, kbarT, top_p, sel_mask, \
-                       sel_count)
-    if (g.N <= 64) ADASPARK_SELECT_CASE(1);
-    else if (g.N <= 128) ADASPARK_SELECT_CASE(2);
-    else if (g.N <= 256) ADASPARK_SELECT_CASE(4);
-    else if (g.N <= 512) ADASPARK_SELECT_CASE(8);
-    else if (g.N <= 1024) ADASPARK_SELECT_CASE(16);
-    else ADASPARK_SELECT_CASE(32);
-#undef ADASPARK_SELECT_CASE
+    // query cubes below SELM_MAX_CUBES have at most that many candidates: one wavefront holds a row's logits
+    const int i_narrow = g.N < SELM_MAX_CUBES ? g.N : SELM_MAX_CUBES;
+    {
+        const int nblk_max = (g.G * g.Cmax + SELM_ROWS - 1) / SELM_ROWS;
+        const dim3 grid((unsigned)((size_t)i_narrow * g.Hkv * nblk_max)), block(SELM_THREADS);
+        if (i_narrow <= 64)
+            hipLaunchKernelGGL((cube_select_mfma_kernel<D, 4>), grid, block, 0, st, g, NG, i_narrow, Q, ksplit, top_p,
+                               sel_mask, sel_count);
+        else
+            hipLaunchKernelGGL((cube_select_mfma_kernel<D, 16>), grid, block, 0, st, g, NG, i_narrow, Q, ksplit, top_p,
+                               sel_mask, sel_count);
+    }
+    if (g.N > i_narrow) {  // the later query cubes: a row's candidates are spread over 4 or 8 wavefronts
+        const int nblk_max = (g.G * g.Cmax + SELW_ROWS - 1) / SELW_ROWS;
+        const dim3 grid((unsigned)((size_t)(g.N - i_narrow) * g.Hkv * nblk_max));
+        if (g.N <= 4 * 16 * SELW_MAXG)
+            hipLaunchKernelGGL((cube_select_wide_kernel<D, 4>), grid, dim3(256), 0, st, g, NG, g.N, Q, ksplit, top_p,
+                               sel_mask, sel_count);
+        else
+            hipLaunchKernelGGL((cube_select_wide_kernel<D, 8>), grid, dim3(512), 0, st, g, NG, g.N, Q, ksplit, top_p,
+                               sel_mask, sel_count);
+    }
 }
 
 hipError_t launch_cube_select(const Geom &g, const uint16_t *Q, const float *kbar, float top_p, uint32_t *sel_mask,
                               int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx, int64_t capacity, void *ws,
                               hipStream_t st)
 {
-    const int Npad = select_npad(g);
+    static_assert(ADASPARK_MAX_CUBES <= 8 * 16 * SELW_MAXG, "eight wavefronts hold the candidates of a row");
     const long long R = (long long)g.S * g.Hq;
-    const size_t kbarT_bytes = (((size_t)g.Hkv * g.D * Npad * sizeof(float)) + 255) / 256 * 256;
-    const size_t first_bytes = select_use_mfma(g) ? select_ksplit_bytes(g) : kbarT_bytes;
-    long long *tile_sum = reinterpret_cast<long long *>(reinterpret_cast<char *>(ws) + first_bytes);
-
-    if (select_use_mfma(g)) {
-        uint16_t *ksplit = reinterpret_cast<uint16_t *>(ws);
-        const int NG = select_groups(g);
-        const size_t total = (size_t)g.Hkv * NG * (g.D / 32) * 64;
-        hipLaunchKernelGGL(kbar_split_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, g, NG, kbar,
-                           ksplit);
-        const int nblk_max = (g.G * g.Cmax + SELM_ROWS - 1) / SELM_ROWS;
-        const dim3 grid((unsigned)((size_t)g.N * g.Hkv * nblk_max)), block(SELM_THREADS);
-#define ADASPARK_SELM_CASE(DD, MAXG)                                                                          \
-    hipLaunchKernelGGL((cube_select_mfma_kernel<DD, MAXG>), grid, block, 0, st, g, NG, Q, ksplit, top_p, sel_mask, \
-                       sel_count)
-        if (g.D == 64) {
-            if (NG <= 4) ADASPARK_SELM_CASE(64, 4);
-            else ADASPARK_SELM_CASE(64, 16);
-        } else {
-            if (NG <= 4) ADASPARK_SELM_CASE(128, 4);
-            else ADASPARK_SELM_CASE(128, 16);
-        }
-#undef ADASPARK_SELM_CASE
-    } else {
-        float *kbarT = reinterpret_cast<float *>(ws);
-        const size_t total = (size_t)g.Hkv * g.D * Npad;
-        hipLaunchKernelGGL(kbar_transpose_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, g, Npad,
-                           kbar, kbarT);
-        if (g.D == 64) launch_select_d<64>(g, Npad, Q, kbarT, top_p, sel_mask, sel_count, st);
-        else launch_select_d<128>(g, Npad, Q, kbarT, top_p, sel_mask, sel_count, st);
-    }
+    long long *tile_sum = reinterpret_cast<long long *>(reinterpret_cast<char *>(ws) + select_ksplit_bytes(g));
+    uint16_t *ksplit = reinterpret_cast<uint16_t *>(ws);
+    const int NG = select_groups(g);
+    const size_t total = (size_t)g.Hkv * NG * (g.D / 32) * 64;
+    hipLaunchKernelGGL(kbar_split_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, g, NG, kbar, ksplit);
+    if (g.D == 64) launch_select_d<64>(g, NG, Q, ksplit, top_p, sel_mask, sel_count, st);
+    else launch_select_d<128>(g, NG, Q, ksplit, top_p, sel_mask, sel_count, st);
 
     if (row_ptr != nullptr) {
         const int tiles = (int)scan_tiles(g);

@@ -74,6 +74,9 @@ TEST_WORKLOADS = {
     "T_mha64": _wl("T_mha64", 13, (6, 8, 8), (2, 4, 4), 3, 3, 64, 0.7, 0.5),
     "T_gqa128": _wl("T_gqa128", 14, (12, 16, 16), (4, 8, 8), 14, 2, 128, 0.9, 1.0),
     "T_manycubes": _wl("T_manycubes", 15, (40, 4, 4), (1, 2, 2), 4, 2, 64, 0.6, 1.0),
+    # more than 256 and more than 1024 cubes: a row's candidate cubes are spread over several wavefronts
+    "T_cubes280": _wl("T_cubes280", 16, (70, 4, 4), (1, 2, 2), 4, 2, 64, 0.7, 1.0),
+    "T_cubes1100": _wl("T_cubes1100", 17, (275, 4, 4), (1, 2, 2), 2, 1, 128, 0.8, 0.5),
 }
 
 

@@ -88,6 +88,13 @@ def test_bad_pointers_and_arguments_are_rejected_before_launch(lib):
     assert lib.adaspark_sparse_attn(ctypes.byref(cs), ok_ptr, ok_ptr, ok_ptr, None, 1, ok_ptr, None, ok_ptr, 1 << 30, None) == -1
     assert lib.adaspark_dense_attn(ctypes.byref(cs), ok_ptr, ok_ptr, ok_ptr, 1, ok_ptr, None, None, 0, None) == -3
     assert lib.adaspark_dense_attn(None, ok_ptr, ok_ptr, ok_ptr, 1, ok_ptr, None, ok_ptr, 1 << 30, None) == -1
+    # packed sparse entry with an explicit kernel: unknown choice, workspace too small, missing selection
+    pw = lambda kernel, nbytes, mask: lib.adaspark_sparse_attn_packed_with(
+        ctypes.byref(cs), ok_ptr, ok_ptr, nbytes, mask, 1, kernel, ok_ptr, None, None)
+    assert pw(7, 1 << 30, ok_ptr) == -1
+    assert pw(-1, 1 << 30, ok_ptr) == -1
+    assert pw(binding.SPARSE_COMPACT, 8, ok_ptr) == -3
+    assert pw(binding.SPARSE_MASKED, 1 << 30, None) == -1
 
 
 def test_binding_refuses_cpu_tensors(lib):

@@ -67,7 +67,8 @@ def rows_of(O, rows, w):
     return O.reshape(w.S * w.Hq, w.D)[torch.as_tensor(rows, device=O.device)].float().cpu().numpy()
 
 
-SMALL = [synth.TEST_WORKLOADS[k] for k in ("T_tiny", "T_ragged", "T_mha64", "T_gqa128", "T_manycubes")] + [
+SMALL = [synth.TEST_WORKLOADS[k] for k in ("T_tiny", "T_ragged", "T_mha64", "T_gqa128", "T_manycubes", "T_cubes280",
+                                           "T_cubes1100")] + [
     synth.WORKLOADS["C1"]]
 
 
@@ -230,7 +231,7 @@ def test_c4_sampled(B, oracle):
     sampled_case(B, oracle, synth.WORKLOADS["C4"], (0.9,), 192, check_dense=False)
 
 
-@pytest.mark.parametrize("name", ["T_gqa128", "T_manycubes", "C1"])
+@pytest.mark.parametrize("name", ["T_gqa128", "T_manycubes", "T_cubes280", "T_cubes1100", "C1"])
 def test_select_ties_zero_queries(B, oracle, name):
     """All-zero queries make every candidate cube equally likely: the whole Top-p decision is the tie rule
     (lower cube index first, keep while the mass before an element is below p)."""
