@@ -101,10 +101,6 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
     uint32_t *__restrict__ sel_mask, int32_t *__restrict__ sel_count)
 {
     constexpr int KS = D / 32;
-    constexpr int GB = KS * 3 * 1024;            // bytes of one cube group's operands
-    constexpr int PIECES = GB / 16;              // 16-byte pieces of a group
-    constexpr int PPT = (PIECES + SELM_THREADS - 1) / SELM_THREADS;
-    __shared__ __attribute__((aligned(16))) unsigned char abuf[GB];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n16 = lane & 15, q4 = lane >> 4;
@@ -159,36 +155,34 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
     for (int s = 0; s < SELM_SLABS; ++s)
 #pragma unroll
         for (int cg = 0; cg < MAXG; ++cg) acc[s][cg] = sel_f32x4{0.f, 0.f, 0.f, 0.f};
-    const sel_u32x4 *src = reinterpret_cast<const sel_u32x4 *>(ksplit + (size_t)kv * NG * (GB / 2));
-    sel_u32x4 pre[PPT];
+    // The mean-key operands go from global memory (they stay in L2: a few MB per call) straight into registers,
+    // half a cube group ahead of the MFMAs that use them: no staging through LDS, no barriers.
+    constexpr int OPS = KS * 3, HALF = OPS / 2, KSH = KS / 2;
+    static_assert(KS % 2 == 0, "a cube group's operands are fetched in two halves");
+    const sel_bf16x8 *src = reinterpret_cast<const sel_bf16x8 *>(ksplit) + (size_t)kv * NG * (OPS * 64) + lane;
+    sel_bf16x8 buf0[HALF], buf1[HALF];
 #pragma unroll
-    for (int u = 0; u < PPT; ++u)
-        if (tid + SELM_THREADS * u < PIECES) pre[u] = src[tid + SELM_THREADS * u];
+    for (int o = 0; o < HALF; ++o) buf0[o] = src[o * 64];  // ng >= 1 here
 #pragma unroll
     for (int cg = 0; cg < MAXG; ++cg) {
         if (cg < ng) {  // uniform for the workgroup
-            __syncthreads();  // the previous group's operands have been consumed
 #pragma unroll
-            for (int u = 0; u < PPT; ++u)
-                if (tid + SELM_THREADS * u < PIECES)
-                    reinterpret_cast<sel_u32x4 *>(abuf)[tid + SELM_THREADS * u] = pre[u];
+            for (int o = 0; o < HALF; ++o) buf1[o] = src[((size_t)cg * OPS + HALF + o) * 64];
+#pragma unroll
+            for (int o = 0; o < HALF; ++o)
+#pragma unroll
+                for (int s = 0; s < SELM_SLABS; ++s)
+                    acc[s][cg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(buf0[o], qf[s][o / 3], acc[s][cg], 0, 0, 0);
             if (cg + 1 < ng) {
 #pragma unroll
-                for (int u = 0; u < PPT; ++u)
-                    if (tid + SELM_THREADS * u < PIECES)
-                        pre[u] = src[(size_t)(cg + 1) * PIECES + tid + SELM_THREADS * u];
+                for (int o = 0; o < HALF; ++o) buf0[o] = src[((size_t)(cg + 1) * OPS + o) * 64];
             }
-            __syncthreads();
 #pragma unroll
-            for (int c = 0; c < KS; ++c)
+            for (int o = 0; o < HALF; ++o)
 #pragma unroll
-                for (int term = 0; term < 3; ++term) {
-                    const sel_bf16x8 af =
-                        *reinterpret_cast<const sel_bf16x8 *>(abuf + ((c * 3 + term) * 64 + lane) * 16);
-#pragma unroll
-                    for (int s = 0; s < SELM_SLABS; ++s)
-                        acc[s][cg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, qf[s][c], acc[s][cg], 0, 0, 0);
-                }
+                for (int s = 0; s < SELM_SLABS; ++s)
+                    acc[s][cg] =
+                        __builtin_amdgcn_mfma_f32_16x16x32_bf16(buf1[o], qf[s][KSH + o / 3], acc[s][cg], 0, 0, 0);
         }
     }
 
