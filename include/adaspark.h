@@ -110,6 +110,19 @@ int adaspark_cube_select(const adaspark_shape *shape, const void *Q, const float
                          int64_t capacity, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Fixed Top-K cube selection, the comparison baseline of the paper's ablation
+ * "Effect of Top-P Adaptive Selection" (Sec. 4) and of its table of selection
+ * strategies: row r keeps the top_k preceding cubes of highest relevance (Eq. 1),
+ * ties by lower cube index; all of them if it has no more than top_k.  Same
+ * outputs, workspace and conventions as adaspark_cube_select; the result feeds
+ * adaspark_sparse_attn unchanged.  top_k = 0 keeps nothing (local attention
+ * only); top_k < 0 is ADASPARK_EINVAL.
+ */
+int adaspark_cube_select_topk(const adaspark_shape *shape, const void *Q, const float *kbar, int32_t top_k, int causal,
+                              uint32_t *sel_mask, int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx,
+                              int64_t capacity, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Sparse attention (Eq. 3 plus the own-cube rule of Sec. 3.2): row r attends
  * all tokens of the cubes set in its sel_mask row and the tokens of its own
  * cube with rank <= its own rank; softmax(q.K_att^T/sqrt(head_dim)).V_att with

@@ -11,7 +11,9 @@ from .adaspark_oracle import (  # noqa: F401
     cube_pool,
     relevance,
     top_p,
+    top_k,
     cube_select,
+    cube_select_topk,
     sparse_attn,
     dense_attn,
     num_threads,

@@ -28,6 +28,8 @@
  *     index; element k is kept iff the mass ranked strictly before it is < p,
  *     i.e. the minimal prefix whose mass reaches p; p >= 1 keeps every
  *     preceding cube, p = 0 keeps none;
+ *   - fixed Top-K (the ablation baseline): the k highest-ranked preceding cubes
+ *     in the same order, all of them if there are no more than k;
  *   - selection is per (token, query head); with grouped-query attention query
  *     head a reads K, V and the mean keys of KV head a / (Hq / Hkv);
  *   - both the relevance score and the attention logits are scaled by
@@ -233,6 +235,76 @@ void oracle_cube_select(const oracle_shape *s, const uint16_t *Q, const double *
             }
         }
         free(q); free(logits); free(probs); free(cum); free(keep); free(order);
+    }
+    free(cube_of); free(rank_of); free(size_of); free(start);
+}
+
+/* ---------------------------------------------------------------------------
+ * Fixed Top-K rule on one distribution (the baseline of the ablation "Effect of
+ * Top-P Adaptive Selection", Sec. 4): rank by probability descending, ties by
+ * ascending cube index, keep the first min(k, n).  Returns the number kept.
+ * order_out (optional, n ints): candidate indices in ranked order.
+ * ------------------------------------------------------------------------- */
+int oracle_top_k(const double *probs, int n, int k, uint8_t *keep, int32_t *order_out)
+{
+    if (n <= 0) return 0;
+    ranked *r = malloc(sizeof(ranked) * n);
+    for (int j = 0; j < n; ++j) { r[j].p = probs[j]; r[j].j = j; keep[j] = 0; }
+    qsort(r, n, sizeof(ranked), ranked_cmp);
+    int kept = 0;
+    for (int t = 0; t < n; ++t) {
+        if (t < k) { keep[r[t].j] = 1; ++kept; }
+        if (order_out) order_out[t] = r[t].j;
+    }
+    free(r);
+    return kept;
+}
+
+/* ---------------------------------------------------------------------------
+ * Top-K cube selection for a list of query rows: as oracle_cube_select with the
+ * Top-K rule in place of Top-p.  The ranking uses the logits of Eq. 1 (softmax
+ * is monotone, so this is the ranking by probability, free of underflow).
+ * near_cut (optional): 1 iff the logit gap between the last kept and the first
+ * dropped cube is < eps.
+ * ------------------------------------------------------------------------- */
+void oracle_cube_select_topk(const oracle_shape *s, const uint16_t *Q, const double *kbar, int k,
+                             const int64_t *rows, int64_t nrows,
+                             uint32_t *sel_mask, int32_t *sel_count, uint8_t *near_cut, double eps)
+{
+    const int S = s->T * s->H * s->W, N = oracle_num_cubes(s);
+    const int Hq = s->Hq, Hkv = s->Hkv, D = s->D, G = Hq / Hkv;
+    const int words = ceil_div(N, 32);
+    int32_t *cube_of = malloc(sizeof(int32_t) * S), *rank_of = malloc(sizeof(int32_t) * S);
+    int32_t *size_of = malloc(sizeof(int32_t) * N);
+    int64_t *start = malloc(sizeof(int64_t) * (N + 1));
+    oracle_cube_map(s, cube_of, rank_of, size_of, start);
+
+    #pragma omp parallel
+    {
+        double *q = malloc(sizeof(double) * D);
+        double *logits = malloc(sizeof(double) * N), *probs = malloc(sizeof(double) * N);
+        uint8_t *keep = malloc(N);
+        int32_t *order = malloc(sizeof(int32_t) * N);
+        #pragma omp for schedule(dynamic, 64)
+        for (int64_t x = 0; x < nrows; ++x) {
+            const int64_t r = rows ? rows[x] : x;
+            const int n = (int)(r / Hq), a = (int)(r % Hq), g = a / G;
+            const int i = cube_of[n];                 /* candidates are cubes 0..i-1 */
+            uint32_t *mrow = sel_mask + (size_t)x * words;
+            for (int w = 0; w < words; ++w) mrow[w] = 0;
+            sel_count[x] = 0;
+            if (near_cut) near_cut[x] = 0;
+            if (i == 0) continue;
+            for (int d = 0; d < D; ++d) q[d] = bf16_widen(Q[((size_t)n * Hq + a) * D + d]);
+            oracle_relevance(q, kbar + (size_t)g * D, (int64_t)Hkv * D, i, D, logits, probs);
+            /* rank the logits: the same order as the probabilities, and exact where exp() would underflow */
+            const int kept = oracle_top_k(logits, i, k, keep, order);
+            for (int j = 0; j < i; ++j) if (keep[j]) mrow[j >> 5] |= (uint32_t)1 << (j & 31);
+            sel_count[x] = kept;
+            if (near_cut && kept > 0 && kept < i && logits[order[kept - 1]] - logits[order[kept]] < eps)
+                near_cut[x] = 1;
+        }
+        free(q); free(logits); free(probs); free(keep); free(order);
     }
     free(cube_of); free(rank_of); free(size_of); free(start);
 }

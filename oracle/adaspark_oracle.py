@@ -63,6 +63,7 @@ def _load():
         _lib = ctypes.CDLL(build())
         _lib.oracle_num_cubes.restype = ctypes.c_int
         _lib.oracle_top_p.restype = ctypes.c_int
+        _lib.oracle_top_k.restype = ctypes.c_int
     return _lib
 
 
@@ -170,6 +171,37 @@ def cube_select(shape: Shape, Q, kbar: np.ndarray, p: float, rows=None, eps: flo
     lib.oracle_cube_select(ctypes.byref(cs), _p(q, ctypes.c_uint16), _p(kb, ctypes.c_double), ctypes.c_double(p),
                            _p(r, ctypes.c_int64), ctypes.c_int64(nrows), _p(mask, ctypes.c_uint32),
                            _p(count, ctypes.c_int32), _p(near, ctypes.c_uint8), ctypes.c_double(eps))
+    return mask, count, near.astype(bool)
+
+
+def top_k(probs: np.ndarray, k: int):
+    """Fixed Top-K rule on one distribution -> (keep[n] bool, order[n])."""
+    lib = _load()
+    pr = np.ascontiguousarray(probs, np.float64)
+    n = pr.size
+    keep = np.zeros(n, np.uint8)
+    order = np.zeros(n, np.int32)
+    lib.oracle_top_k(_p(pr, ctypes.c_double), ctypes.c_int(n), ctypes.c_int(k), _p(keep, ctypes.c_uint8),
+                     _p(order, ctypes.c_int32))
+    return keep.astype(bool), order
+
+
+def cube_select_topk(shape: Shape, Q, kbar: np.ndarray, k: int, rows=None, eps: float = 1e-5):
+    """Top-K selection for the given rows (all if None); outputs as cube_select."""
+    lib, cs, N = _load(), shape._c(), num_cubes(shape)
+    q = _u16(Q)
+    assert q.size == shape.S * shape.Hq * shape.D
+    kb = np.ascontiguousarray(kbar, np.float64)
+    assert kb.shape == (N, shape.Hkv, shape.D)
+    r = _rows(rows)
+    nrows = shape.S * shape.Hq if r is None else r.size
+    words = (N + 31) // 32
+    mask = np.zeros((nrows, words), np.uint32)
+    count = np.zeros(nrows, np.int32)
+    near = np.zeros(nrows, np.uint8)
+    lib.oracle_cube_select_topk(ctypes.byref(cs), _p(q, ctypes.c_uint16), _p(kb, ctypes.c_double), ctypes.c_int(int(k)),
+                                _p(r, ctypes.c_int64), ctypes.c_int64(nrows), _p(mask, ctypes.c_uint32),
+                                _p(count, ctypes.c_int32), _p(near, ctypes.c_uint8), ctypes.c_double(eps))
     return mask, count, near.astype(bool)
 
 

@@ -69,6 +69,7 @@ EXPORTS = (
     "adaspark_status_string",
     "adaspark_cube_pool",
     "adaspark_cube_select",
+    "adaspark_cube_select_topk",
     "adaspark_sparse_attn",
     "adaspark_dense_attn",
     "adaspark_kv_pack",
@@ -98,6 +99,8 @@ def load():
         lib.adaspark_cube_pool.argtypes = [sp, vp, vp, vp]
         lib.adaspark_cube_select.argtypes = [sp, vp, vp, ctypes.c_float, ctypes.c_int, vp, vp, vp, vp,
                                              ctypes.c_int64, vp, ctypes.c_size_t, vp]
+        lib.adaspark_cube_select_topk.argtypes = [sp, vp, vp, ctypes.c_int32, ctypes.c_int, vp, vp, vp, vp,
+                                                  ctypes.c_int64, vp, ctypes.c_size_t, vp]
         lib.adaspark_sparse_attn.argtypes = [sp, vp, vp, vp, vp, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
         lib.adaspark_dense_attn.argtypes = [sp, vp, vp, vp, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
         lib.adaspark_kv_pack.argtypes = [sp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -166,6 +169,18 @@ def cube_pool(shape: Shape, K: torch.Tensor, kbar: torch.Tensor | None = None) -
 def cube_select(shape: Shape, Q: torch.Tensor, kbar: torch.Tensor, top_p: float, causal: bool = True,
                 sel_mask=None, sel_count=None, csr_capacity: int | None = None, workspace=None):
     """Eqs. 1-2: -> (sel_mask int32-viewed-u32 [R, words], sel_count int32 [R], row_ptr|None, cube_idx|None)."""
+    return _cube_select("adaspark_cube_select", ctypes.c_float(top_p), shape, Q, kbar, causal, sel_mask, sel_count,
+                        csr_capacity, workspace)
+
+
+def cube_select_topk(shape: Shape, Q: torch.Tensor, kbar: torch.Tensor, top_k: int, causal: bool = True,
+                     sel_mask=None, sel_count=None, csr_capacity: int | None = None, workspace=None):
+    """Fixed Top-K selection (the paper's ablation baseline); outputs as cube_select."""
+    return _cube_select("adaspark_cube_select_topk", ctypes.c_int32(int(top_k)), shape, Q, kbar, causal, sel_mask,
+                        sel_count, csr_capacity, workspace)
+
+
+def _cube_select(fn_name, rule_arg, shape, Q, kbar, causal, sel_mask, sel_count, csr_capacity, workspace):
     N = num_cubes(shape)
     words = (N + 31) // 32
     R = shape.rows
@@ -185,12 +200,12 @@ def cube_select(shape: Shape, Q: torch.Tensor, kbar: torch.Tensor, top_p: float,
     if workspace is None:
         workspace = alloc_workspace(shape, CALL_CUBE_SELECT, dev)
     cs = shape._c()
-    _check(load().adaspark_cube_select(
+    _check(getattr(load(), fn_name)(
         ctypes.byref(cs), _dev(Q, torch.bfloat16, R * shape.head_dim, "Q"),
         _dev(kbar, torch.float32, N * shape.kv_heads * shape.head_dim, "kbar"),
-        ctypes.c_float(top_p), int(bool(causal)),
+        rule_arg, int(bool(causal)),
         _dev(sel_mask, torch.int32, R * words, "sel_mask"), _dev(sel_count, torch.int32, R, "sel_count"),
-        rp, ci, cap, workspace.data_ptr(), workspace.numel(), _stream()), "adaspark_cube_select")
+        rp, ci, cap, workspace.data_ptr(), workspace.numel(), _stream()), fn_name)
     return sel_mask, sel_count, row_ptr, cube_idx
 
 

@@ -81,23 +81,42 @@ int adaspark_cube_pool(const adaspark_shape *shape, const void *K, float *kbar, 
     return e == hipSuccess ? ADASPARK_OK : ADASPARK_EHIP;
 }
 
-int adaspark_cube_select(const adaspark_shape *shape, const void *Q, const float *kbar, float top_p, int causal,
-                         uint32_t *sel_mask, int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx,
-                         int64_t capacity, void *workspace, size_t workspace_bytes, void *stream)
+// top_k < 0: Top-p with threshold top_p; otherwise fixed Top-K
+static int cube_select(const adaspark_shape *shape, const void *Q, const float *kbar, float top_p, int top_k, int causal,
+                       uint32_t *sel_mask, int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx, int64_t capacity,
+                       void *workspace, size_t workspace_bytes, void *stream)
 {
     int rc = check_shape(shape);
     if (rc != ADASPARK_OK) return rc;
     if ((rc = check_ptrs({Q, kbar, sel_mask, sel_count})) != ADASPARK_OK) return rc;
-    if (!(top_p >= 0.f && top_p <= 1.f)) return ADASPARK_EINVAL;  // also rejects NaN
     if ((row_ptr == nullptr) != (cube_idx == nullptr)) return ADASPARK_EINVAL;
     if (row_ptr != nullptr && (!aligned16(row_ptr) || !aligned16(cube_idx) || capacity < 0)) return ADASPARK_EINVAL;
     if (!causal) return ADASPARK_EUNSUPPORTED;
     const Geom g = make_geom(*shape);
     if (workspace == nullptr || !aligned16(workspace) || workspace_bytes < select_workspace_bytes(g))
         return ADASPARK_EWORKSPACE;
-    const hipError_t e = launch_cube_select(g, static_cast<const uint16_t *>(Q), kbar, top_p, sel_mask, sel_count,
-                                            row_ptr, cube_idx, capacity, workspace, static_cast<hipStream_t>(stream));
+    const hipError_t e =
+        launch_cube_select(g, static_cast<const uint16_t *>(Q), kbar, top_p, top_k, sel_mask, sel_count, row_ptr,
+                           cube_idx, capacity, workspace, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? ADASPARK_OK : ADASPARK_EHIP;
+}
+
+int adaspark_cube_select(const adaspark_shape *shape, const void *Q, const float *kbar, float top_p, int causal,
+                         uint32_t *sel_mask, int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx,
+                         int64_t capacity, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!(top_p >= 0.f && top_p <= 1.f)) return ADASPARK_EINVAL;  // also rejects NaN
+    return cube_select(shape, Q, kbar, top_p, -1, causal, sel_mask, sel_count, row_ptr, cube_idx, capacity, workspace,
+                       workspace_bytes, stream);
+}
+
+int adaspark_cube_select_topk(const adaspark_shape *shape, const void *Q, const float *kbar, int32_t top_k, int causal,
+                              uint32_t *sel_mask, int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx,
+                              int64_t capacity, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (top_k < 0) return ADASPARK_EINVAL;
+    return cube_select(shape, Q, kbar, 0.f, top_k, causal, sel_mask, sel_count, row_ptr, cube_idx, capacity, workspace,
+                       workspace_bytes, stream);
 }
 
 static int attn_check(const adaspark_shape *shape, const void *Q, const uint32_t *sel_mask, bool sparse, int causal,

@@ -83,9 +83,10 @@ __device__ inline uint16_t float_to_bf16_bits(float f)
 // Kernel launchers (defined one per .hip file).  All return hipError_t from the launch.
 hipError_t launch_cube_pool(const Geom &g, const uint16_t *K, float *kbar, hipStream_t st);
 size_t select_workspace_bytes(const Geom &g);
-hipError_t launch_cube_select(const Geom &g, const uint16_t *Q, const float *kbar, float top_p, uint32_t *sel_mask,
-                              int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx, int64_t capacity, void *ws,
-                              hipStream_t st);
+// top_k < 0: Top-p selection with threshold top_p; top_k >= 0: fixed Top-K selection (top_p ignored).
+hipError_t launch_cube_select(const Geom &g, const uint16_t *Q, const float *kbar, float top_p, int top_k,
+                              uint32_t *sel_mask, int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx,
+                              int64_t capacity, void *ws, hipStream_t st);
 size_t attn_workspace_bytes(const Geom &g);
 hipError_t launch_kv_pack(const Geom &g, const uint16_t *K, const uint16_t *V, void *ws, hipStream_t st);
 // sel_mask == nullptr: dense (every preceding cube attended); otherwise sparse_kernel is an adaspark_sparse_kernel.

@@ -65,6 +65,13 @@ __global__ void kbar_split_kernel(Geom g, int NG, const float *__restrict__ kbar
     }
 }
 
+// Order-preserving map of a float onto unsigned integers (larger float <=> larger key); never 0 for a number.
+__device__ __forceinline__ uint32_t sel_order_key(float x)
+{
+    const uint32_t b = __float_as_uint(x);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
 // OR / sum / max over the four lanes {n, n+16, n+32, n+48} that share a query row
 __device__ __forceinline__ uint32_t selm_quad_or(uint32_t x)
 {
@@ -95,10 +102,13 @@ __device__ __forceinline__ float selm_quad_max(float x)
     return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 
-template <int D, int MAXG>
+// TOPK: fixed Top-K selection (the ablation baseline of "Effect of Top-P Adaptive Selection") instead of Top-p: the
+// top_k most relevant preceding cubes, ties by lower index.  The values ranked are then the logits themselves
+// (as order-preserving integer keys: no softmax, nothing can underflow) and the "mass" is a count.
+template <int D, int MAXG, bool TOPK>
 __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
     Geom g, int NG, int i_end, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ ksplit, float top_p,
-    uint32_t *__restrict__ sel_mask, int32_t *__restrict__ sel_count)
+    int top_k, uint32_t *__restrict__ sel_mask, int32_t *__restrict__ sel_count)
 {
     constexpr int KS = D / 32;
 
@@ -124,8 +134,9 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
         rowq[s] = rid;
     }
 
-    if (i == 0 || top_p <= 0.f || top_p >= 1.f) {
-        const int keep = (i > 0 && top_p >= 1.f) ? i : 0;  // p>=1: every preceding cube
+    if (i == 0 || (TOPK ? (top_k <= 0 || top_k >= i) : (top_p <= 0.f || top_p >= 1.f))) {
+        // p >= 1 (or k >= number of candidates): every preceding cube; p = 0 (k = 0): none
+        const int keep = (i > 0 && (TOPK ? top_k >= i : top_p >= 1.f)) ? i : 0;
 #pragma unroll
         for (int s = 0; s < SELM_SLABS; ++s) {
             if (rowg[s] < 0) continue;
@@ -202,22 +213,35 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
                 mx = fmaxf(mx, x);
             }
         mx = selm_quad_max(mx);
-        float part = 0.f;
+        float target;
+        if (TOPK) {
+            // rank the logits themselves: acc holds their order keys (0 for non-candidates)
 #pragma unroll
-        for (int cg = 0; cg < MAXG; ++cg)
+            for (int cg = 0; cg < MAXG; ++cg)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float x = acc[s][cg][v];
-                const float e = (x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(x - mx);
-                acc[s][cg][v] = e;
-                part += e;
-            }
-        const float target = top_p * selm_quad_sum(part);
+                for (int v = 0; v < 4; ++v) {
+                    const float x = acc[s][cg][v];
+                    acc[s][cg][v] = __uint_as_float((x == -INFINITY) ? 0u : sel_order_key(x));
+                }
+            target = (float)top_k;
+        } else {
+            float part = 0.f;
+#pragma unroll
+            for (int cg = 0; cg < MAXG; ++cg)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float x = acc[s][cg][v];
+                    const float e = (x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(x - mx);
+                    acc[s][cg][v] = e;
+                    part += e;
+                }
+            target = top_p * selm_quad_sum(part);
+        }
 
         // ---- largest tau (as a bit pattern) with mass{e >= tau} >= target: positive floats order like
         // unsigned integers, so tau is found bit by bit; every row (four lanes) runs its own search
         uint32_t tau = 0;
-        for (int b = 30; b >= 0; --b) {
+        for (int b = TOPK ? 31 : 30; b >= 0; --b) {
             const uint32_t cand = tau | (1u << b);
             float sum = 0.f;
 #pragma unroll
@@ -228,7 +252,7 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
 #pragma unroll
                         for (int v = 0; v < 4; ++v) {
                             const float e = acc[s][cg][v];
-                            sum += (__float_as_uint(e) >= cand) ? e : 0.f;
+                            sum += (__float_as_uint(e) >= cand) ? (TOPK ? 1.f : e) : 0.f;
                         }
                 }
             if (selm_quad_sum(sum) >= target) tau = cand;
@@ -260,7 +284,7 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
                 }
             }
         }
-        const float tauf = __uint_as_float(tau);
+        const float tauf = TOPK ? 1.f : __uint_as_float(tau);  // weight of an element equal to tau
         float sgt = 0.f;
         int neq = 0;
 #pragma unroll
@@ -268,7 +292,7 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const uint32_t bits = __float_as_uint(acc[s][cg][v]);
-                sgt += bits > tau ? acc[s][cg][v] : 0.f;
+                sgt += bits > tau ? (TOPK ? 1.f : acc[s][cg][v]) : 0.f;
                 neq += (bits == tau && tau != 0) ? 1 : 0;
             }
         const float mass_gt = selm_quad_sum(sgt);
@@ -351,10 +375,10 @@ constexpr int SELW_MAXG = 16;
 constexpr int SELW_SLABS = 2;
 constexpr int SELW_ROWS = 16 * SELW_SLABS;
 
-template <int D, int SPLIT>
+template <int D, int SPLIT, bool TOPK>
 __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
     Geom g, int NG, int i_end, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ ksplit, float top_p,
-    uint32_t *__restrict__ sel_mask, int32_t *__restrict__ sel_count)
+    int top_k, uint32_t *__restrict__ sel_mask, int32_t *__restrict__ sel_count)
 {
     constexpr int KS = D / 32, MAXG = SELW_MAXG, SLABS = SELW_SLABS;
     constexpr int OPS = KS * 3;  // A operands (16 bytes per lane each) of one cube group
@@ -382,9 +406,10 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
         rowq[s] = rid;
     }
 
-    if (i == 0 || top_p <= 0.f || top_p >= 1.f) {  // the whole workgroup; wavefront 0 writes
+    if (i == 0 || (TOPK ? (top_k <= 0 || top_k >= i) : (top_p <= 0.f || top_p >= 1.f))) {
+        // the whole workgroup; wavefront 0 writes
         if (part != 0) return;
-        const int keep = (i > 0 && top_p >= 1.f) ? i : 0;
+        const int keep = (i > 0 && (TOPK ? top_k >= i : top_p >= 1.f)) ? i : 0;
 #pragma unroll
         for (int s = 0; s < SLABS; ++s) {
             if (rowg[s] < 0) continue;
@@ -500,9 +525,13 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const float x = acc[s][lg][v];
-                const float e = (x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(x - mx);
-                acc[s][lg][v] = e;
-                sum += e;
+                if (TOPK) {  // rank the logits themselves: their order keys, 0 for non-candidates
+                    acc[s][lg][v] = __uint_as_float((x == -INFINITY) ? 0u : sel_order_key(x));
+                } else {
+                    const float e = (x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(x - mx);
+                    acc[s][lg][v] = e;
+                    sum += e;
+                }
             }
         xv[0][s] = __float_as_uint(selm_quad_sum(sum));
     }
@@ -512,14 +541,14 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
         float z = 0.f;
 #pragma unroll
         for (int p = 0; p < SPLIT; ++p) z += __uint_as_float(xa[p][0][s]);
-        target[s] = top_p * z;
+        target[s] = TOPK ? (float)top_k : top_p * z;
     }
 
     // ---- largest tau (as a bit pattern) with mass{e >= tau} >= target, bit by bit, both slabs in step
     uint32_t tau[SLABS];
 #pragma unroll
     for (int s = 0; s < SLABS; ++s) tau[s] = 0;
-    for (int b = 30; b >= 0; --b) {
+    for (int b = TOPK ? 31 : 30; b >= 0; --b) {
 #pragma unroll
         for (int s = 0; s < SLABS; ++s) {
             const uint32_t cand = tau[s] | (1u << b);
@@ -529,7 +558,7 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const float e = acc[s][lg][v];
-                    sum += (__float_as_uint(e) >= cand) ? e : 0.f;
+                    sum += (__float_as_uint(e) >= cand) ? (TOPK ? 1.f : e) : 0.f;
                 }
             xv[0][s] = __float_as_uint(selm_quad_sum(sum));
         }
@@ -593,7 +622,7 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const uint32_t bits = __float_as_uint(acc[s][lg][v]);
-                sgt += bits > tau[s] ? acc[s][lg][v] : 0.f;
+                sgt += bits > tau[s] ? (TOPK ? 1.f : acc[s][lg][v]) : 0.f;
                 neq += (bits == tau[s] && tau[s] != 0) ? 1 : 0;
             }
         xv[0][s] = __float_as_uint(selm_quad_sum(sgt));
@@ -611,7 +640,7 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
             neq_row += (int)xa[p][1][s];
             neq_before += p < part ? (int)xa[p][1][s] : 0;
         }
-        const float tauf = __uint_as_float(tau[s]);
+        const float tauf = TOPK ? 1.f : __uint_as_float(tau[s]);  // weight of an element equal to tau
         uint32_t nib[MAXG];  // bit v of nib[lg]: cube 16(g0+lg) + 4q4 + v is kept
         if (__any(neq_row > 1)) {
             int running = neq_before;  // tied elements of this row in earlier cube groups
@@ -788,8 +817,8 @@ size_t select_workspace_bytes(const Geom &g)
     return select_ksplit_bytes(g) + ((tiles + 255) / 256) * 256;
 }
 
-template <int D>
-static void launch_select_d(const Geom &g, int NG, const uint16_t *Q, const uint16_t *ksplit, float top_p,
+template <int D, bool TOPK>
+static void launch_select_d(const Geom &g, int NG, const uint16_t *Q, const uint16_t *ksplit, float top_p, int top_k,
                             uint32_t *sel_mask, int32_t *sel_count, hipStream_t st)
 {
     // query cubes below SELM_MAX_CUBES have at most that many candidates: one wavefront holds a row's logits
@@ -798,27 +827,28 @@ static void launch_select_d(const Geom &g, int NG, const uint16_t *Q, const uint
         const int nblk_max = (g.G * g.Cmax + SELM_ROWS - 1) / SELM_ROWS;
         const dim3 grid((unsigned)((size_t)i_narrow * g.Hkv * nblk_max)), block(SELM_THREADS);
         if (i_narrow <= 64)
-            hipLaunchKernelGGL((cube_select_mfma_kernel<D, 4>), grid, block, 0, st, g, NG, i_narrow, Q, ksplit, top_p,
-                               sel_mask, sel_count);
+            hipLaunchKernelGGL((cube_select_mfma_kernel<D, 4, TOPK>), grid, block, 0, st, g, NG, i_narrow, Q, ksplit,
+                               top_p, top_k, sel_mask, sel_count);
         else
-            hipLaunchKernelGGL((cube_select_mfma_kernel<D, 16>), grid, block, 0, st, g, NG, i_narrow, Q, ksplit, top_p,
-                               sel_mask, sel_count);
+            hipLaunchKernelGGL((cube_select_mfma_kernel<D, 16, TOPK>), grid, block, 0, st, g, NG, i_narrow, Q, ksplit,
+                               top_p, top_k, sel_mask, sel_count);
     }
     if (g.N > i_narrow) {  // the later query cubes: a row's candidates are spread over 4 or 8 wavefronts
         const int nblk_max = (g.G * g.Cmax + SELW_ROWS - 1) / SELW_ROWS;
         const dim3 grid((unsigned)((size_t)(g.N - i_narrow) * g.Hkv * nblk_max));
         if (g.N <= 4 * 16 * SELW_MAXG)
-            hipLaunchKernelGGL((cube_select_wide_kernel<D, 4>), grid, dim3(256), 0, st, g, NG, g.N, Q, ksplit, top_p,
-                               sel_mask, sel_count);
+            hipLaunchKernelGGL((cube_select_wide_kernel<D, 4, TOPK>), grid, dim3(256), 0, st, g, NG, g.N, Q, ksplit,
+                               top_p, top_k, sel_mask, sel_count);
         else
-            hipLaunchKernelGGL((cube_select_wide_kernel<D, 8>), grid, dim3(512), 0, st, g, NG, g.N, Q, ksplit, top_p,
-                               sel_mask, sel_count);
+            hipLaunchKernelGGL((cube_select_wide_kernel<D, 8, TOPK>), grid, dim3(512), 0, st, g, NG, g.N, Q, ksplit,
+                               top_p, top_k, sel_mask, sel_count);
     }
 }
 
-hipError_t launch_cube_select(const Geom &g, const uint16_t *Q, const float *kbar, float top_p, uint32_t *sel_mask,
-                              int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx, int64_t capacity, void *ws,
-                              hipStream_t st)
+// top_k < 0: Top-p selection with threshold top_p; top_k >= 0: fixed Top-K selection (top_p ignored).
+hipError_t launch_cube_select(const Geom &g, const uint16_t *Q, const float *kbar, float top_p, int top_k,
+                              uint32_t *sel_mask, int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx,
+                              int64_t capacity, void *ws, hipStream_t st)
 {
     static_assert(ADASPARK_MAX_CUBES <= 8 * 16 * SELW_MAXG, "eight wavefronts hold the candidates of a row");
     const long long R = (long long)g.S * g.Hq;
@@ -827,8 +857,13 @@ hipError_t launch_cube_select(const Geom &g, const uint16_t *Q, const float *kba
     const int NG = select_groups(g);
     const size_t total = (size_t)g.Hkv * NG * (g.D / 32) * 64;
     hipLaunchKernelGGL(kbar_split_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, g, NG, kbar, ksplit);
-    if (g.D == 64) launch_select_d<64>(g, NG, Q, ksplit, top_p, sel_mask, sel_count, st);
-    else launch_select_d<128>(g, NG, Q, ksplit, top_p, sel_mask, sel_count, st);
+    if (top_k >= 0) {
+        if (g.D == 64) launch_select_d<64, true>(g, NG, Q, ksplit, top_p, top_k, sel_mask, sel_count, st);
+        else launch_select_d<128, true>(g, NG, Q, ksplit, top_p, top_k, sel_mask, sel_count, st);
+    } else {
+        if (g.D == 64) launch_select_d<64, false>(g, NG, Q, ksplit, top_p, top_k, sel_mask, sel_count, st);
+        else launch_select_d<128, false>(g, NG, Q, ksplit, top_p, top_k, sel_mask, sel_count, st);
+    }
 
     if (row_ptr != nullptr) {
         const int tiles = (int)scan_tiles(g);

@@ -256,6 +256,58 @@ def test_select_ties_zero_queries(B, oracle, name):
         assert same[~near].all()
 
 
+@pytest.mark.parametrize("name", ["T_ragged", "T_gqa128", "T_manycubes", "T_cubes280", "T_cubes1100", "C1"])
+def test_topk_selection_small(B, oracle, name):
+    """Fixed Top-K selection (the ablation baseline): every row, several k, incl. 0 and more than there are cubes;
+    the sparse attention fed that selection."""
+    w = synth.TEST_WORKLOADS.get(name) or synth.WORKLOADS[name]
+    print(f"case {w.name} top-k", flush=True)
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    Q, K, V = synth.generate(w)
+    Qg, Kg, Vg = Q.cuda(), K.cuda(), V.cuda()
+    N = B.num_cubes(sh)
+    kbar_ref = oracle.cube_pool(osh, K)
+    kbar = B.cube_pool(sh, Kg)
+    for k in (0, 1, 5, 17, N // 2, N + 1):
+        ref_mask, ref_count, near = oracle.cube_select_topk(osh, Q, kbar_ref, k)
+        mask, count, row_ptr, cube_idx = B.cube_select_topk(sh, Qg, kbar, k, csr_capacity=int(ref_count.sum()) + 64)
+        torch.cuda.synchronize()
+        gm, gc = to_u32(mask), count.cpu().numpy()
+        assert np.array_equal(gc, ref_count)                      # the count is exact whatever the ties
+        same = check_selection(f"{w.name} k={k}", gm, gc, ref_mask, ref_count, near)
+        if k in (0, N + 1):
+            assert same.all()
+        rp = row_ptr.cpu().numpy()
+        assert rp[0] == 0 and np.array_equal(np.diff(rp), gc)
+    k = 5
+    ref_mask, _, _ = oracle.cube_select_topk(osh, Q, kbar_ref, k)
+    mask, _, _, _ = B.cube_select_topk(sh, Qg, kbar, k)
+    O = B.sparse_attn(sh, Qg, Kg, Vg, mask)
+    torch.cuda.synchronize()
+    ref_out, _ = oracle.sparse_attn(osh, Q, K, V, ref_mask)
+    same = (to_u32(mask) == ref_mask).all(axis=1)
+    check_outputs(f"{w.name} top-{k} pipeline", O.reshape(-1, w.D).float().cpu().numpy()[same], ref_out[same])
+
+
+def test_topk_c3_sampled(B, oracle):
+    """Top-K at the 65,536-token workload, sampled rows; k calibrated to the mean Top-p(0.9) count."""
+    w = synth.WORKLOADS["C3"]
+    print(f"case {w.name} top-k sampled", flush=True)
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    Q, K, V = synth.generate(w)
+    Qg, Kg = Q.cuda(), K.cuda()
+    rows = synth.sample_rows(w, 384)
+    kbar_ref = oracle.cube_pool(osh, K)
+    kbar = B.cube_pool(sh, Kg)
+    for k in (8, 79):
+        mask, count, _, _ = B.cube_select_topk(sh, Qg, kbar, k)
+        torch.cuda.synchronize()
+        ridx = torch.as_tensor(rows, device="cuda")
+        ref_mask, ref_count, near = oracle.cube_select_topk(osh, Q, kbar_ref, k, rows=rows)
+        assert np.array_equal(count[ridx].cpu().numpy(), ref_count)
+        check_selection(f"{w.name} k={k}", to_u32(mask[ridx]), count[ridx].cpu().numpy(), ref_mask, ref_count, near)
+
+
 def test_lse_matches_attended_logits(B, oracle):
     """The optional log-sum-exp output: recomputed here in fp64 from the bf16 inputs over exactly the keys the
     row attends (selected cubes + causal part of the own cube)."""

@@ -256,6 +256,91 @@ def test_select_heads_differ_and_p_limits(oracle):
     assert np.array_equal(ms, m[rows]) and np.array_equal(cs, c[rows])
 
 
+# --------------------------------------------------------------------------- fixed Top-K (ablation baseline)
+def brute_top_k(probs, k):
+    """Set definition: the subset of min(k, n) elements of largest total mass; among subsets of equal mass the
+    lexicographically smallest index set (ties go to the lower cube index)."""
+    n = len(probs)
+    m = min(k, n)
+    best = None
+    for sub in itertools.combinations(range(n), m):
+        key = (-sum(probs[j] for j in sub), sub)      # dyadic masses: exact sums
+        if best is None or key < best:
+            best = key
+    return set(best[1])
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 8, 10])
+def test_top_k_equals_subset_enumeration_and_stable_argsort(oracle, n):
+    rng = np.random.default_rng(300 + n)
+    for trial in range(10):
+        probs = dyadic_distribution(rng, n) if n > 1 else np.array([1.0])
+        if trial % 3 == 0 and n > 3:               # plant a three-way tie straddling typical cuts
+            probs[1] = probs[2] = probs[3] = (probs[1] + probs[2] + probs[3]) / 3 if n > 3 else probs[1]
+        for k in (0, 1, 2, n // 2, n - 1, n, n + 3):
+            if k < 0:
+                continue
+            keep, order = oracle.top_k(probs, k)
+            got = set(np.nonzero(keep)[0].tolist())
+            assert len(got) == min(k, n)
+            # library routine: a stable sort of the negated values ranks ties by ascending index
+            ref_order = np.argsort(-probs, kind="stable")
+            assert order.tolist() == ref_order.tolist()
+            assert got == set(ref_order[:k].tolist())
+            if n <= 8 and abs(probs.sum() - 1.0) < 1e-15 and trial % 3 != 0:
+                assert got == brute_top_k(probs.tolist(), k)
+
+
+def test_top_k_ties_prefer_low_index_and_nesting(oracle):
+    probs = np.array([0.125, 0.25, 0.25, 0.125, 0.25])
+    assert oracle.top_k(probs, 2)[0].tolist() == [False, True, True, False, False]
+    assert oracle.top_k(probs, 3)[0].tolist() == [False, True, True, False, True]
+    assert oracle.top_k(probs, 4)[0].tolist() == [True, True, True, False, True]
+    prev = np.zeros(5, bool)
+    for k in range(0, 7):
+        keep, _ = oracle.top_k(probs, k)
+        assert not (prev & ~keep).any() and keep.sum() == min(k, 5)
+        prev = keep
+
+
+@pytest.mark.parametrize("w", [synth.TEST_WORKLOADS[k] for k in ("T_ragged", "T_gqa128", "T_manycubes")],
+                         ids=lambda w: w.name)
+def test_select_topk_invariants(oracle, w):
+    sh = shape_of(oracle, w)
+    N = oracle.num_cubes(sh)
+    Q, K, _ = synth.generate(w)
+    kbar = oracle.cube_pool(sh, K)
+    bc, _, _ = brute_cube_table(w)
+    Qd = widen(Q)
+    G = w.Hq // w.Hkv
+    cubes_of_row = np.repeat(bc, w.Hq)
+    prev = None
+    for k in (0, 1, 3, 7, N):
+        mask, count, _ = oracle.cube_select_topk(sh, Q, kbar, k)
+        sel = unpack(mask, N)
+        assert np.array_equal(sel.sum(1), count)
+        assert np.array_equal(count, np.minimum(k, cubes_of_row))     # exactly min(k, #preceding cubes)
+        if prev is not None:
+            assert not (prev & ~sel).any()                            # nesting in k
+        prev = sel
+        rng = np.random.default_rng(9)
+        for r in rng.choice(w.S * w.Hq, size=60, replace=False):
+            n, a = divmod(int(r), w.Hq)
+            i = bc[n]
+            assert not sel[r, i:].any()
+            if i == 0 or k == 0:
+                continue
+            logits = kbar[:i, a // G] @ Qd[n, a] / math.sqrt(w.D)
+            s = sel[r, :i]
+            if (~s).any():
+                assert logits[s].min() >= logits[~s].max()            # nothing dropped outranks a kept cube
+            assert set(np.nonzero(s)[0].tolist()) == set(np.argsort(-logits, kind="stable")[:k].tolist())
+    # k >= number of cubes is the p = 1 selection: every preceding cube
+    m_all, _, _ = oracle.cube_select_topk(sh, Q, kbar, N)
+    m_p1, _, _ = oracle.cube_select(sh, Q, kbar, 1.0)
+    assert np.array_equal(m_all, m_p1)
+
+
 # --------------------------------------------------------------------------- attention (Eq. 3)
 def torch_dense_reference(w, Q, K, V, pos):
     """scaled_dot_product_attention (CPU, fp64, is_causal) on cube-major ordered,
