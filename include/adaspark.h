@@ -23,6 +23,16 @@
  *     raster order.  "Preceding" / causal order everywhere in this library is
  *     cube-major: all tokens of cube j < i precede all tokens of cube i, and
  *     inside a cube lower rank precedes higher rank.
+ *   - Text tokens (end of Sec. 3.2: cube-wise attention to the preceding visual
+ *     tokens, token-wise attention among text tokens): the sequence is the video
+ *     tokens followed by `text_tokens` text tokens, indices T*H*W .. tokens-1.
+ *     They are cut into runs of cube_t*cube_h*cube_w tokens, numbered as cubes
+ *     after the video cubes ("text cubes"; the last may be shorter).  A text
+ *     query scores and selects among ALL video cubes (Eqs. 1-2), attends the
+ *     selected ones cube-wise, and attends every earlier text token and itself:
+ *     its selection always contains the text cubes before its own, and its own
+ *     text cube is attended causally like any own cube.  Text cubes are never
+ *     candidates of the selection rule; video queries are unaffected.
  *   - Query row id r = n*q_heads + a.
  *   - Return value: ADASPARK_OK (0) or a negative adaspark_status.  Arguments
  *     are validated before anything is enqueued; on a validation error nothing
@@ -39,9 +49,11 @@ extern "C" {
 #endif
 
 typedef struct {
-    int32_t frames, height, width;       /* token grid T, H, W; tokens = T*H*W                 */
+    int32_t frames, height, width;       /* video token grid T, H, W                            */
     int32_t cube_t, cube_h, cube_w;      /* cube shape along frames, height, width (Sec. 3.1)  */
     int32_t q_heads, kv_heads, head_dim; /* q_heads % kv_heads == 0; head_dim in {64, 128}     */
+    int32_t text_tokens;                 /* text tokens that follow the video tokens (0: none); */
+                                         /* tokens = T*H*W + text_tokens                        */
 } adaspark_shape;
 
 typedef enum {
@@ -97,7 +109,8 @@ int adaspark_cube_pool(const adaspark_shape *shape, const void *K, float *kbar, 
  *   kbar      in   fp32 [cubes][kv_heads][head_dim]
  *   sel_mask  out  u32  [tokens*q_heads][ceil(cubes/32)]; bit (j%32) of word j/32 set
  *                  iff cube j is selected.  The own cube's bit is never set.
- *   sel_count out  i32  [tokens*q_heads] number of selected cubes
+ *   sel_count out  i32  [tokens*q_heads] number of selected cubes (for a text row: including the
+ *                  text cubes before its own, which are always set)
  *   row_ptr   out  i64  [tokens*q_heads + 1] exclusive prefix sum of sel_count, or NULL
  *   cube_idx  out  i32  [capacity] selected cube ids, ascending inside each row,
  *                  row r at [row_ptr[r], row_ptr[r+1]); entries at positions

@@ -20,7 +20,7 @@ _lib = None
 
 
 class _CShape(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int) for n in ("T", "H", "W", "ct", "ch", "cw", "Hq", "Hkv", "D")]
+    _fields_ = [(n, ctypes.c_int) for n in ("T", "H", "W", "ct", "ch", "cw", "Hq", "Hkv", "D", "text")]
 
 
 @dataclass(frozen=True)
@@ -36,13 +36,14 @@ class Shape:
     Hq: int
     Hkv: int
     D: int
+    text: int = 0  # text tokens that follow the video tokens
 
     @property
     def S(self) -> int:
-        return self.T * self.H * self.W
+        return self.T * self.H * self.W + self.text
 
     def _c(self) -> _CShape:
-        return _CShape(self.T, self.H, self.W, self.ct, self.ch, self.cw, self.Hq, self.Hkv, self.D)
+        return _CShape(self.T, self.H, self.W, self.ct, self.ch, self.cw, self.Hq, self.Hkv, self.D, self.text)
 
 
 def build(force: bool = False) -> str:

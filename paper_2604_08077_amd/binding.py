@@ -20,7 +20,7 @@ CALL_CUBE_POOL, CALL_CUBE_SELECT, CALL_SPARSE_ATTN, CALL_DENSE_ATTN = 0, 1, 2, 3
 
 class _CShape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
-        "frames", "height", "width", "cube_t", "cube_h", "cube_w", "q_heads", "kv_heads", "head_dim")]
+        "frames", "height", "width", "cube_t", "cube_h", "cube_w", "q_heads", "kv_heads", "head_dim", "text_tokens")]
 
 
 @dataclass(frozen=True)
@@ -36,10 +36,11 @@ class Shape:
     q_heads: int
     kv_heads: int
     head_dim: int
+    text_tokens: int = 0  # text tokens that follow the video tokens
 
     @property
     def tokens(self) -> int:
-        return self.frames * self.height * self.width
+        return self.frames * self.height * self.width + self.text_tokens
 
     @property
     def rows(self) -> int:
@@ -47,12 +48,12 @@ class Shape:
 
     def _c(self) -> _CShape:
         return _CShape(self.frames, self.height, self.width, self.cube_t, self.cube_h, self.cube_w,
-                       self.q_heads, self.kv_heads, self.head_dim)
+                       self.q_heads, self.kv_heads, self.head_dim, self.text_tokens)
 
     @staticmethod
     def of(w) -> "Shape":
         """From a ``synth.Workload``."""
-        return Shape(w.T, w.H, w.W, w.ct, w.ch, w.cw, w.Hq, w.Hkv, w.D)
+        return Shape(w.T, w.H, w.W, w.ct, w.ch, w.cw, w.Hq, w.Hkv, w.D, w.text)
 
 
 class AdasparkError(RuntimeError):

@@ -12,16 +12,18 @@ namespace adaspark {
 constexpr int KEY_TILE = 64;  // keys per staged K/V tile; cubes are padded to a multiple of it in the packed KV layout
 
 struct Geom {
-    int T, H, W;        // token grid
+    int T, H, W;        // video token grid
     int ct, ch, cw;     // cube shape
     int Hq, Hkv, D, G;  // heads, head_dim, group size Hq/Hkv
-    int nTb, nHb, nWb;  // cubes along each axis
-    int N;              // cubes
-    int S;              // tokens
+    int nTb, nHb, nWb;  // video cubes along each axis
+    int Nv, Sv;         // video cubes, video tokens
+    int St;             // text tokens (they follow the video tokens), cut into text cubes of up to Cmax tokens
+    int N;              // cubes: video cubes, then text cubes
+    int S;              // tokens: video tokens, then text tokens
     int Cmax;           // tokens in an unclipped cube
     int TPC;            // key tiles per cube in the packed layout = ceil(Cmax / KEY_TILE)
     int words;          // u32 words per selection-mask row = ceil(N / 32)
-    int ragged;         // some cubes are clipped at the grid edge (otherwise every cube has Cmax tokens)
+    int ragged;         // some cubes are smaller than Cmax (clipped at the grid edge, or the last text cube)
 };
 
 inline Geom make_geom(const adaspark_shape &s)
@@ -31,16 +33,20 @@ inline Geom make_geom(const adaspark_shape &s)
     g.ct = s.cube_t; g.ch = s.cube_h; g.cw = s.cube_w;
     g.Hq = s.q_heads; g.Hkv = s.kv_heads; g.D = s.head_dim; g.G = s.q_heads / s.kv_heads;
     g.nTb = (g.T + g.ct - 1) / g.ct; g.nHb = (g.H + g.ch - 1) / g.ch; g.nWb = (g.W + g.cw - 1) / g.cw;
-    g.N = g.nTb * g.nHb * g.nWb;
-    g.S = g.T * g.H * g.W;
+    g.Nv = g.nTb * g.nHb * g.nWb;
+    g.Sv = g.T * g.H * g.W;
+    g.St = s.text_tokens;
     g.Cmax = g.ct * g.ch * g.cw;
+    g.N = g.Nv + (g.St + g.Cmax - 1) / g.Cmax;
+    g.S = g.Sv + g.St;
     g.TPC = (g.Cmax + KEY_TILE - 1) / KEY_TILE;
     g.words = (g.N + 31) / 32;
-    g.ragged = (g.T % g.ct != 0) || (g.H % g.ch != 0) || (g.W % g.cw != 0);
+    g.ragged = (g.T % g.ct != 0) || (g.H % g.ch != 0) || (g.W % g.cw != 0) || (g.St % g.Cmax != 0);
     return g;
 }
 
-// Clipped extents and origin of cube c.
+// Clipped extents and origin of cube c.  A text cube is a run of consecutive tokens: t0 < 0, w0 = its first
+// token, ew = its length.
 struct CubeBox {
     int t0, h0, w0;  // origin in the token grid
     int et, eh, ew;  // extents after clipping at the grid edge
@@ -50,22 +56,30 @@ struct CubeBox {
 __host__ __device__ inline CubeBox cube_box(const Geom &g, int c)
 {
     CubeBox b;
+    if (c >= g.Nv) {
+        const int first = (c - g.Nv) * g.Cmax;
+        b.t0 = -1; b.h0 = 0; b.w0 = g.Sv + first;
+        b.et = 1; b.eh = 1; b.ew = min(g.Cmax, g.St - first);
+        return b;
+    }
     const int wb = c % g.nWb, hb = (c / g.nWb) % g.nHb, tb = c / (g.nWb * g.nHb);
     b.t0 = tb * g.ct; b.h0 = hb * g.ch; b.w0 = wb * g.cw;
     b.et = min(g.ct, g.T - b.t0); b.eh = min(g.ch, g.H - b.h0); b.ew = min(g.cw, g.W - b.w0);
     return b;
 }
 
-// Raster token index of the token with rank `rank` in the cube described by b.
+// Token index of the token with rank `rank` in the cube described by b.
 __host__ __device__ inline int token_of(const Geom &g, const CubeBox &b, int rank)
 {
+    if (b.t0 < 0) return b.w0 + rank;
     const int lw = rank % b.ew, lh = (rank / b.ew) % b.eh, lt = rank / (b.ew * b.eh);
     return ((b.t0 + lt) * g.H + (b.h0 + lh)) * g.W + (b.w0 + lw);
 }
 
-// Cube of raster token n (rank not needed by the callers of this one).
+// Cube of token n (rank not needed by the callers of this one).
 __host__ __device__ inline int cube_of_token(const Geom &g, int n)
 {
+    if (n >= g.Sv) return g.Nv + (n - g.Sv) / g.Cmax;
     const int w = n % g.W, h = (n / g.W) % g.H, t = n / (g.W * g.H);
     return ((t / g.ct) * g.nHb + (h / g.ch)) * g.nWb + (w / g.cw);
 }

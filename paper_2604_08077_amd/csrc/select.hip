@@ -72,6 +72,15 @@ __device__ __forceinline__ uint32_t sel_order_key(float x)
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
+// Bits of mask word w (cubes 32w .. 32w+31) that fall into the cube range [lo, hi).
+__device__ __forceinline__ uint32_t sel_range_bits(int w, int lo, int hi)
+{
+    const int a = max(lo - 32 * w, 0), b = min(hi - 32 * w, 32);
+    if (b <= a) return 0u;
+    const uint32_t upto_b = b >= 32 ? 0xffffffffu : ((1u << b) - 1u);
+    return upto_b & ~((1u << a) - 1u);
+}
+
 // OR / sum / max over the four lanes {n, n+16, n+32, n+48} that share a query row
 __device__ __forceinline__ uint32_t selm_quad_or(uint32_t x)
 {
@@ -122,6 +131,9 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
     const CubeBox qbox = cube_box(g, i);
     const int P = g.G * qbox.size();  // rows of this (cube, KV head): rho = rank * G + head-in-group
     if (blk * SELM_ROWS >= P) return;
+    // Candidates are the video cubes before the own cube.  A text query (own cube i >= Nv) scores every video cube
+    // and always attends the text cubes before its own: those bits are set whatever the rule selects.
+    const int ncand = min(i, g.Nv);
 
     int rowg[SELM_SLABS];  // global row id of this lane's column, -1: past the end
     int rowq[SELM_SLABS];  // row whose Q is loaded (a valid one also for padding columns)
@@ -134,20 +146,15 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
         rowq[s] = rid;
     }
 
-    if (i == 0 || (TOPK ? (top_k <= 0 || top_k >= i) : (top_p <= 0.f || top_p >= 1.f))) {
-        // p >= 1 (or k >= number of candidates): every preceding cube; p = 0 (k = 0): none
-        const int keep = (i > 0 && (TOPK ? top_k >= i : top_p >= 1.f)) ? i : 0;
+    if (ncand == 0 || (TOPK ? (top_k <= 0 || top_k >= ncand) : (top_p <= 0.f || top_p >= 1.f))) {
+        // p >= 1 (or k >= number of candidates): every candidate; p = 0 (k = 0): none
+        const int keep = (TOPK ? top_k >= ncand : top_p >= 1.f) ? ncand : 0;
 #pragma unroll
         for (int s = 0; s < SELM_SLABS; ++s) {
             if (rowg[s] < 0) continue;
-            for (int w = q4; w < g.words; w += 4) {
-                const int lo = 32 * w;
-                uint32_t bits = 0;
-                if (keep >= lo + 32) bits = 0xffffffffu;
-                else if (keep > lo) bits = (1u << (keep - lo)) - 1u;
-                sel_mask[(size_t)rowg[s] * g.words + w] = bits;
-            }
-            if (q4 == 0) sel_count[rowg[s]] = keep;
+            for (int w = q4; w < g.words; w += 4)
+                sel_mask[(size_t)rowg[s] * g.words + w] = sel_range_bits(w, 0, keep) | sel_range_bits(w, g.Nv, i);
+            if (q4 == 0) sel_count[rowg[s]] = keep + (i - ncand);
         }
         return;
     }
@@ -160,7 +167,7 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
             qf[s][c] = *reinterpret_cast<const sel_bf16x8 *>(Q + (size_t)rowq[s] * D + 32 * c + 8 * q4);
 
     // ---- logits: acc[s][cg][v] = q(row n16 of slab s) . kbar(cube 16cg + 4q4 + v)
-    const int ng = (i + 15) >> 4;  // cube groups that hold candidates (the same for every row here)
+    const int ng = (ncand + 15) >> 4;  // cube groups that hold candidates (the same for every row here)
     sel_f32x4 acc[SELM_SLABS][MAXG];
 #pragma unroll
     for (int s = 0; s < SELM_SLABS; ++s)
@@ -207,7 +214,7 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
         for (int cg = 0; cg < MAXG; ++cg)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const bool valid = 16 * cg + 4 * q4 + v < i;
+                const bool valid = 16 * cg + 4 * q4 + v < ncand;
                 const float x = valid ? acc[s][cg][v] * scale : -INFINITY;
                 acc[s][cg][v] = x;
                 mx = fmaxf(mx, x);
@@ -354,12 +361,14 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
             if (2 * w + 1 < MAXG) word |= nib[2 * w + 1] << (16 + 4 * q4);
             word = selm_quad_or(word);
             kept += __popc(word);
-            if (w < g.words && rowg[s] >= 0 && q4 == (w & 3)) sel_mask[(size_t)rowg[s] * g.words + w] = word;
+            if (w < g.words && rowg[s] >= 0 && q4 == (w & 3))
+                sel_mask[(size_t)rowg[s] * g.words + w] = word | sel_range_bits(w, g.Nv, i);
         }
         // words beyond this kernel's cube groups (grids with more cubes): no candidates there for these rows
         if (rowg[s] >= 0)
-            for (int w = (MAXG + 1) / 2 + q4; w < g.words; w += 4) sel_mask[(size_t)rowg[s] * g.words + w] = 0u;
-        if (rowg[s] >= 0 && q4 == 0) sel_count[rowg[s]] = kept;
+            for (int w = (MAXG + 1) / 2 + q4; w < g.words; w += 4)
+                sel_mask[(size_t)rowg[s] * g.words + w] = sel_range_bits(w, g.Nv, i);
+        if (rowg[s] >= 0 && q4 == 0) sel_count[rowg[s]] = kept + (i - ncand);
     }
 }
 
@@ -395,6 +404,7 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
     const CubeBox qbox = cube_box(g, i);
     const int P = g.G * qbox.size();
     if (blk * SELW_ROWS >= P) return;  // the whole workgroup
+    const int ncand = min(i, g.Nv);    // candidates: video cubes before the own cube; text cubes before it are forced
 
     int rowg[SLABS], rowq[SLABS];
 #pragma unroll
@@ -406,21 +416,16 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
         rowq[s] = rid;
     }
 
-    if (i == 0 || (TOPK ? (top_k <= 0 || top_k >= i) : (top_p <= 0.f || top_p >= 1.f))) {
+    if (ncand == 0 || (TOPK ? (top_k <= 0 || top_k >= ncand) : (top_p <= 0.f || top_p >= 1.f))) {
         // the whole workgroup; wavefront 0 writes
         if (part != 0) return;
-        const int keep = (i > 0 && (TOPK ? top_k >= i : top_p >= 1.f)) ? i : 0;
+        const int keep = (TOPK ? top_k >= ncand : top_p >= 1.f) ? ncand : 0;
 #pragma unroll
         for (int s = 0; s < SLABS; ++s) {
             if (rowg[s] < 0) continue;
-            for (int w = q4; w < g.words; w += 4) {
-                const int lo = 32 * w;
-                uint32_t bits = 0;
-                if (keep >= lo + 32) bits = 0xffffffffu;
-                else if (keep > lo) bits = (1u << (keep - lo)) - 1u;
-                sel_mask[(size_t)rowg[s] * g.words + w] = bits;
-            }
-            if (q4 == 0) sel_count[rowg[s]] = keep;
+            for (int w = q4; w < g.words; w += 4)
+                sel_mask[(size_t)rowg[s] * g.words + w] = sel_range_bits(w, 0, keep) | sel_range_bits(w, g.Nv, i);
+            if (q4 == 0) sel_count[rowg[s]] = keep + (i - ncand);
         }
         return;
     }
@@ -433,7 +438,7 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
             qf[s][c] = *reinterpret_cast<const sel_bf16x8 *>(Q + (size_t)rowq[s] * D + 32 * c + 8 * q4);
 
     // ---- logits of this wavefront's cube block: acc[s][lg][v] = q(row n16 of slab s) . kbar(cube 16(g0+lg)+4q4+v)
-    const int ng = (i + 15) >> 4;  // cube groups that hold candidates
+    const int ng = (ncand + 15) >> 4;  // cube groups that hold candidates
     const int g0 = part * MAXG;
     const int nlg = min(max(ng - g0, 0), MAXG);  // of them, in this wavefront's block
     sel_f32x4 acc[SLABS][MAXG];
@@ -504,7 +509,7 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
         for (int lg = 0; lg < MAXG; ++lg)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const bool valid = 16 * (g0 + lg) + 4 * q4 + v < i;
+                const bool valid = 16 * (g0 + lg) + 4 * q4 + v < ncand;
                 const float x = valid ? acc[s][lg][v] * scale : -INFINITY;
                 acc[s][lg][v] = x;
                 mx = fmaxf(mx, x);
@@ -692,7 +697,8 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
             word = selm_quad_or(word);
             kept += __popc(word);
             const int wg = (MAXG / 2) * part + w;
-            if (wg < g.words && rowg[s] >= 0 && q4 == (w & 3)) sel_mask[(size_t)rowg[s] * g.words + wg] = word;
+            if (wg < g.words && rowg[s] >= 0 && q4 == (w & 3))
+                sel_mask[(size_t)rowg[s] * g.words + wg] = word | sel_range_bits(wg, g.Nv, i);
         }
         kept_part[s] = (uint32_t)kept;
     }
@@ -708,7 +714,7 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
             int kept = 0;
 #pragma unroll
             for (int p = 0; p < SPLIT; ++p) kept += (int)xa[p][0][s];
-            if (rowg[s] >= 0) sel_count[rowg[s]] = kept;
+            if (rowg[s] >= 0) sel_count[rowg[s]] = kept + (i - ncand);
         }
     }
 }

@@ -35,9 +35,15 @@ class Workload:
     top_p: Tuple[float, ...]
     # scale of the per-cube key mean, one entry per KV head
     k_mean_scale: Tuple[float, ...]
+    # text tokens appended after the video tokens (no per-cube key mean: plain noise keys)
+    text: int = 0
 
     @property
     def S(self) -> int:
+        return self.T * self.H * self.W + self.text
+
+    @property
+    def S_video(self) -> int:
         return self.T * self.H * self.W
 
     @property
@@ -49,12 +55,12 @@ class Workload:
         return (self.ct, self.ch, self.cw)
 
 
-def _wl(name, cid, grid, cube, hq, hkv, d, top_p, scale):
+def _wl(name, cid, grid, cube, hq, hkv, d, top_p, scale, text=0):
     if not isinstance(scale, tuple):
         scale = (float(scale),) * hkv
     if not isinstance(top_p, tuple):
         top_p = (float(top_p),)
-    return Workload(name, cid, *grid, *cube, hq, hkv, d, top_p, scale)
+    return Workload(name, cid, *grid, *cube, hq, hkv, d, top_p, scale, text)
 
 
 # The five benchmark configurations (token grid, cube, heads, head_dim, Top-p).
@@ -77,6 +83,15 @@ TEST_WORKLOADS = {
     # more than 256 and more than 1024 cubes: a row's candidate cubes are spread over several wavefronts
     "T_cubes280": _wl("T_cubes280", 16, (70, 4, 4), (1, 2, 2), 4, 2, 64, 0.7, 1.0),
     "T_cubes1100": _wl("T_cubes1100", 17, (275, 4, 4), (1, 2, 2), 2, 1, 128, 0.8, 0.5),
+    # video followed by text tokens: 100 = three full text cubes of 32 and one of 4; 37 = a single short text cube
+    "T_text64": _wl("T_text64", 18, (6, 8, 8), (2, 4, 4), 4, 2, 64, 0.8, 1.0, text=100),
+    "T_text128": _wl("T_text128", 19, (5, 10, 12), (4, 4, 8), 6, 2, 128, 0.9, (0.0, 2.0), text=37),
+}
+
+# Mid-sized cases, checked on sampled rows only.
+SAMPLED_WORKLOADS = {
+    # a 16,384-token video with a 1,000-token prompt after it: 64 video cubes, 4 text cubes
+    "M_text16k": _wl("M_text16k", 20, (64, 16, 16), (4, 8, 8), 28, 4, 128, 0.9, 1.0, text=1000),
 }
 
 
@@ -90,10 +105,11 @@ def generate(w: Workload):
     """-> (Q [S,Hq,D], K [S,Hkv,D], V [S,Hkv,D]) CPU bf16 tensors.
 
     Q, V ~ N(0,1).  K = N(0,1) + scale[g] * mu, mu ~ N(0, I) drawn once per
-    (cube, KV head) and shared by all tokens of that cube.
+    (cube, KV head) and shared by all tokens of that cube.  Text tokens (the last
+    ``w.text`` rows) have plain N(0,1) keys.
     """
     seed = BASE_SEED + 1000 * w.config_id
-    S = w.S
+    S, Sv = w.S, w.S_video
     Q = _randn((S, w.Hq, w.D), seed + 0).to(torch.bfloat16)
     V = _randn((S, w.Hkv, w.D), seed + 2).to(torch.bfloat16)
     K = _randn((S, w.Hkv, w.D), seed + 1)
@@ -102,8 +118,8 @@ def generate(w: Workload):
         mu = _randn((nt, nh, nw, w.Hkv, w.D), seed + 3)
         mu = mu * torch.tensor(w.k_mean_scale, dtype=torch.float32).view(1, 1, 1, w.Hkv, 1)
         field = mu.repeat_interleave(w.ct, 0).repeat_interleave(w.ch, 1).repeat_interleave(w.cw, 2)
-        field = field[: w.T, : w.H, : w.W].reshape(S, w.Hkv, w.D)
-        K = K + field
+        field = field[: w.T, : w.H, : w.W].reshape(Sv, w.Hkv, w.D)
+        K[:Sv] = K[:Sv] + field
     return Q, K.to(torch.bfloat16), V
 
 
@@ -111,7 +127,8 @@ def sample_rows(w: Workload, n: int, seed: int = 7):
     """A seeded sample of query row ids (row = token * Hq + head), sorted.
 
     Always contains the first and last token's rows so that both ends of the
-    sequence are covered; the rest is uniform without replacement.
+    sequence are covered; the rest is uniform without replacement.  With text
+    tokens, an eighth as many rows again are drawn from the text rows alone.
     """
     R = w.S * w.Hq
     g = torch.Generator(device="cpu")
@@ -119,5 +136,10 @@ def sample_rows(w: Workload, n: int, seed: int = 7):
     n = min(n, R)
     picks = torch.randperm(R, generator=g)[:n]
     fixed = torch.tensor([0, w.Hq - 1, R - w.Hq, R - 1], dtype=torch.int64)
-    rows = torch.unique(torch.cat([picks, fixed]))
+    parts = [picks, fixed]
+    if w.text:
+        first = w.S_video * w.Hq
+        parts.append(first + torch.randperm(R - first, generator=g)[: max(8, n // 8)])
+        parts.append(torch.tensor([first, first + w.Hq - 1], dtype=torch.int64))
+    rows = torch.unique(torch.cat(parts))
     return rows.numpy()

@@ -31,7 +31,7 @@ def B():
 
 
 def oshape(o, w):
-    return o.Shape(w.T, w.H, w.W, w.ct, w.ch, w.cw, w.Hq, w.Hkv, w.D)
+    return o.Shape(w.T, w.H, w.W, w.ct, w.ch, w.cw, w.Hq, w.Hkv, w.D, w.text)
 
 
 def to_u32(t):
@@ -68,7 +68,7 @@ def rows_of(O, rows, w):
 
 
 SMALL = [synth.TEST_WORKLOADS[k] for k in ("T_tiny", "T_ragged", "T_mha64", "T_gqa128", "T_manycubes", "T_cubes280",
-                                           "T_cubes1100")] + [
+                                           "T_cubes1100", "T_text64", "T_text128")] + [
     synth.WORKLOADS["C1"]]
 
 
@@ -137,11 +137,13 @@ def test_full_path_small(B, oracle, w):
     torch.cuda.synchronize()
     check_outputs(f"{w.name} dense", Od.reshape(-1, w.D).float().cpu().numpy(), dense_ref)
     check_outputs(f"{w.name} sparse p=1", O1.reshape(-1, w.D).float().cpu().numpy(), dense_ref)
-    # (4) p = 0: own cube only
+    # (4) p = 0: own cube only (a text row: and the text cubes before its own)
     m0, c0, _, _ = B.cube_select(sh, Qg, kbar, 0.0)
     O0 = B.sparse_attn(sh, Qg, Kg, Vg, m0)
     torch.cuda.synchronize()
-    ref0, _ = oracle.sparse_attn(osh, Q, K, V, np.zeros_like(ref_mask))
+    ref_m0, _, _ = oracle.cube_select(osh, Q, kbar_ref, 0.0)
+    assert w.text or not ref_m0.any()
+    ref0, _ = oracle.sparse_attn(osh, Q, K, V, ref_m0)
     check_outputs(f"{w.name} sparse p=0", O0.reshape(-1, w.D).float().cpu().numpy(), ref0)
 
 
@@ -219,6 +221,29 @@ def test_c2_sampled(B, oracle):
     sampled_case(B, oracle, synth.WORKLOADS["C2"], (0.9,), 768)
 
 
+def test_video_then_text_sampled(B, oracle):
+    """A 16,384-token video followed by a 1,000-token prompt (end of Sec. 3.2): sampled video and text rows."""
+    w = synth.SAMPLED_WORKLOADS["M_text16k"]
+    sampled_case(B, oracle, w, (0.5, 0.9), 512)
+    # text rows: every earlier text cube is set whatever p, and counted
+    sh = B.Shape.of(w)
+    Q, K, _ = synth.generate(w)
+    kbar = B.cube_pool(sh, K.cuda())
+    mask, count, _, _ = B.cube_select(sh, Q.cuda(), kbar, 0.0)
+    torch.cuda.synchronize()
+    n_video = 64
+    cmax = w.ct * w.ch * w.cw
+    gm = to_u32(mask).reshape(w.S, w.Hq, -1)
+    bits = np.unpackbits(gm.view(np.uint8), axis=2, bitorder="little")
+    cnt = count.cpu().numpy().reshape(w.S, w.Hq)
+    assert not bits[: w.S_video].any() and not cnt[: w.S_video].any()
+    for n in range(w.S_video, w.S, 97):
+        earlier = (n - w.S_video) // cmax
+        assert not bits[n, :, :n_video].any()
+        assert bits[n, :, n_video:n_video + earlier].all() and not bits[n, :, n_video + earlier:].any()
+        assert (cnt[n] == earlier).all()
+
+
 def test_c5_entropy_stress_sampled(B, oracle):
     sampled_case(B, oracle, synth.WORKLOADS["C5"], (0.9,), 512)
 
@@ -231,7 +256,7 @@ def test_c4_sampled(B, oracle):
     sampled_case(B, oracle, synth.WORKLOADS["C4"], (0.9,), 192, check_dense=False)
 
 
-@pytest.mark.parametrize("name", ["T_gqa128", "T_manycubes", "T_cubes280", "T_cubes1100", "C1"])
+@pytest.mark.parametrize("name", ["T_gqa128", "T_manycubes", "T_cubes280", "T_cubes1100", "T_text64", "C1"])
 def test_select_ties_zero_queries(B, oracle, name):
     """All-zero queries make every candidate cube equally likely: the whole Top-p decision is the tie rule
     (lower cube index first, keep while the mass before an element is below p)."""
@@ -248,15 +273,17 @@ def test_select_ties_zero_queries(B, oracle, name):
         mask, count, _, _ = B.cube_select(sh, Q.cuda(), kbar, p32)
         torch.cuda.synchronize()
         same = check_selection(f"{w.name} ties p={p}", to_u32(mask), count.cpu().numpy(), ref_mask, ref_count, near)
-        # the kept cubes are a prefix 0..k-1 of the candidates
+        # the kept cubes are a prefix 0..k-1 of the candidates (the video cubes: text cubes are never candidates)
         gm = to_u32(mask)
-        bits = np.unpackbits(gm.view(np.uint8), axis=1, bitorder="little").astype(np.int64)
+        n_video = -(-w.T // w.ct) * -(-w.H // w.ch) * -(-w.W // w.cw)
+        bits = np.unpackbits(gm.view(np.uint8), axis=1, bitorder="little").astype(np.int64)[:, :n_video]
         k = bits.sum(1)
         assert np.array_equal(bits.cumsum(1)[np.arange(len(k)), np.maximum(k, 1) - 1], np.where(k > 0, k, 0))
         assert same[~near].all()
 
 
-@pytest.mark.parametrize("name", ["T_ragged", "T_gqa128", "T_manycubes", "T_cubes280", "T_cubes1100", "C1"])
+@pytest.mark.parametrize("name", ["T_ragged", "T_gqa128", "T_manycubes", "T_cubes280", "T_cubes1100", "T_text128",
+                                  "C1"])
 def test_topk_selection_small(B, oracle, name):
     """Fixed Top-K selection (the ablation baseline): every row, several k, incl. 0 and more than there are cubes;
     the sparse attention fed that selection."""

@@ -20,7 +20,7 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 
 def shape_of(o, w):
-    return o.Shape(w.T, w.H, w.W, w.ct, w.ch, w.cw, w.Hq, w.Hkv, w.D)
+    return o.Shape(w.T, w.H, w.W, w.ct, w.ch, w.cw, w.Hq, w.Hkv, w.D, w.text)
 
 
 def widen(x):
@@ -48,7 +48,26 @@ def brute_cube_table(w):
                             r += 1
                 sizes.append(r)
                 c += 1
+    # text tokens follow the video tokens; runs of one full cube's length, numbered after the video cubes
+    full = ct * ch * cw
+    text_cube, text_rank = [], []
+    left = w.text
+    while left > 0:
+        take = min(full, left)
+        text_cube += [c] * take
+        text_rank += list(range(take))
+        sizes.append(take)
+        c += 1
+        left -= take
+    cube_of = np.concatenate([cube_of, np.array(text_cube, np.int64)])
+    rank_of = np.concatenate([rank_of, np.array(text_rank, np.int64)])
     return cube_of, rank_of, np.array(sizes)
+
+
+def video_cubes(w):
+    T, H, W = w.grid
+    ct, ch, cw = w.cube
+    return -(-T // ct) * -(-H // ch) * -(-W // cw)
 
 
 ALL_SMALL = list(synth.TEST_WORKLOADS.values())
@@ -215,12 +234,18 @@ def test_select_invariants_and_independent_recomputation(oracle, w):
             assert not (prev & ~sel).any()
         prev = sel
         rng = np.random.default_rng(5)
-        for r in rng.choice(w.S * w.Hq, size=60, replace=False):
+        nv = video_cubes(w)
+        picks = rng.choice(w.S * w.Hq, size=60, replace=False).tolist()
+        picks += list(range(w.S * w.Hq - min(w.text, 3) * w.Hq, w.S * w.Hq))   # the last text rows, if any
+        for r in picks:
             n, a = divmod(int(r), w.Hq)
-            i = bc[n]
-            assert not sel[r, i:].any()           # own and later cubes never selected
+            own = bc[n]
+            assert not sel[r, own:].any()         # own and later cubes never selected
+            i = min(own, nv)                      # candidates: the video cubes before the own cube
+            assert sel[r, nv:own].all()           # a text row always attends the text cubes before its own
+            assert count[r] == sel[r, :i].sum() + max(own - nv, 0)
             if i == 0:
-                assert count[r] == 0
+                assert sel[r, :nv].sum() == 0
                 continue
             probs = sp_softmax(kbar[:i, a // G] @ Qd[n, a] / math.sqrt(w.D))
             s = sel[r, :i]
@@ -396,6 +421,49 @@ def test_p_zero_is_block_diagonal_causal_and_first_cube_ignores_p(oracle, w):
     first = np.repeat(bc == 0, w.Hq)
     assert np.array_equal(outp[first], out0[first])
     assert N > 1 and not np.allclose(outp[~first], out0[~first])
+
+
+@pytest.mark.parametrize("name", ["T_text64", "T_text128"])
+def test_text_rows_attend_selected_video_cubes_and_all_earlier_text(oracle, name):
+    """End of Sec. 3.2 for text queries, recomputed in numpy from an explicit token list: the video tokens of
+    the cubes the nucleus rule keeps among ALL video cubes, every earlier text token and the token itself;
+    video rows of the same inputs give what they give without the text."""
+    w = synth.TEST_WORKLOADS[name]
+    sh = shape_of(oracle, w)
+    N, nv, Sv = oracle.num_cubes(sh), video_cubes(w), w.S_video
+    Q, K, V = synth.generate(w)
+    Qd, Kd, Vd = widen(Q), widen(K), widen(V)
+    kbar = oracle.cube_pool(sh, K)
+    bc, _, _ = brute_cube_table(w)
+    G = w.Hq // w.Hkv
+    p = w.top_p[0]
+    rows = np.arange(Sv * w.Hq, w.S * w.Hq, 5)
+    mask, count, _ = oracle.cube_select(sh, Q, kbar, p, rows=rows)
+    out, nk = oracle.sparse_attn(sh, Q, K, V, mask, rows=rows)
+    sel = unpack(mask, N)
+    for x, r in enumerate(rows):
+        n, a = divmod(int(r), w.Hq)
+        kvh = a // G
+        probs = sp_softmax(kbar[:nv, kvh] @ Qd[n, a] / math.sqrt(w.D))
+        keep, _, _ = oracle.top_p(probs, p)       # the nucleus rule itself is pinned by enumeration above
+        assert np.array_equal(sel[x, :nv], keep)
+        toks = np.concatenate([np.nonzero(keep[bc[:Sv]])[0], np.arange(Sv, n + 1)])
+        assert nk[x] == toks.size
+        ref = sp_softmax(Kd[toks, kvh] @ Qd[n, a] / math.sqrt(w.D)) @ Vd[toks, kvh]
+        assert np.abs(out[x] - ref).max() < 1e-10
+    # video rows do not see the text: same selection and output as for the video alone
+    wv = synth.Workload(**{**w.__dict__, "text": 0})
+    shv = shape_of(oracle, wv)
+    vrows = np.arange(0, Sv * w.Hq, 37)
+    kbar_v = oracle.cube_pool(shv, K[:Sv])
+    assert np.array_equal(kbar_v, kbar[:nv])
+    m1, c1, _ = oracle.cube_select(sh, Q, kbar, p, rows=vrows)
+    m2, c2, _ = oracle.cube_select(shv, Q[:Sv], kbar_v, p, rows=vrows)
+    assert np.array_equal(unpack(m1, N)[:, :nv], unpack(m2, nv)) and not unpack(m1, N)[:, nv:].any()
+    assert np.array_equal(c1, c2)
+    o1, _ = oracle.sparse_attn(sh, Q, K, V, m1, rows=vrows)
+    o2, _ = oracle.sparse_attn(shv, Q[:Sv], K[:Sv], V[:Sv], m2, rows=vrows)
+    assert np.array_equal(o1, o2)
 
 
 def test_attention_special_inputs(oracle):
