@@ -85,7 +85,7 @@ def cpu_baseline(w, p, Q, K, V, budget_rows_sel=262144, budget_rows_attn=24576):
     """The fp64 oracle on a bounded row sample of the same workload, extrapolated to tokens/s."""
     import oracle
 
-    osh = oracle.Shape(w.T, w.H, w.W, w.ct, w.ch, w.cw, w.Hq, w.Hkv, w.D, w.text)
+    osh = oracle.Shape(w.T, w.H, w.W, w.ct, w.ch, w.cw, w.Hq, w.Hkv, w.D, w.text, w.lead)
     R = w.S * w.Hq
     t0 = time.perf_counter()
     kbar = oracle.cube_pool(osh, K)

@@ -24,15 +24,18 @@
  *     cube-major: all tokens of cube j < i precede all tokens of cube i, and
  *     inside a cube lower rank precedes higher rank.
  *   - Text tokens (end of Sec. 3.2: cube-wise attention to the preceding visual
- *     tokens, token-wise attention among text tokens): the sequence is the video
- *     tokens followed by `text_tokens` text tokens, indices T*H*W .. tokens-1.
- *     They are cut into runs of cube_t*cube_h*cube_w tokens, numbered as cubes
- *     after the video cubes ("text cubes"; the last may be shorter).  A text
- *     query scores and selects among ALL video cubes (Eqs. 1-2), attends the
- *     selected ones cube-wise, and attends every earlier text token and itself:
- *     its selection always contains the text cubes before its own, and its own
- *     text cube is attended causally like any own cube.  Text cubes are never
- *     candidates of the selection rule; video queries are unaffected.
+ *     tokens, token-wise attention to text tokens): the sequence is
+ *     `prefix_tokens` text tokens, then the T*H*W video tokens (token index
+ *     prefix_tokens + raster index), then `text_tokens` text tokens.  Each text
+ *     span is cut into runs of cube_t*cube_h*cube_w tokens ("text cubes"; the
+ *     last of a span may be shorter) and cubes are numbered in sequence order:
+ *     the prefix's text cubes, the video cubes, the trailing text cubes.  The
+ *     candidates of the selection rule (Eqs. 1-2) are, for every query, the
+ *     VIDEO cubes before its own cube: a query in the trailing text scores all
+ *     video cubes, a query in the prefix none.  Text is attended token-wise:
+ *     a row's selection always contains every text cube before its own, and an
+ *     own text cube is attended causally like any own cube.  Text cubes are
+ *     never candidates; a video query with no prefix is unaffected.
  *   - Query row id r = n*q_heads + a.
  *   - Return value: ADASPARK_OK (0) or a negative adaspark_status.  Arguments
  *     are validated before anything is enqueued; on a validation error nothing
@@ -52,8 +55,9 @@ typedef struct {
     int32_t frames, height, width;       /* video token grid T, H, W                            */
     int32_t cube_t, cube_h, cube_w;      /* cube shape along frames, height, width (Sec. 3.1)  */
     int32_t q_heads, kv_heads, head_dim; /* q_heads % kv_heads == 0; head_dim in {64, 128}     */
-    int32_t text_tokens;                 /* text tokens that follow the video tokens (0: none); */
-                                         /* tokens = T*H*W + text_tokens                        */
+    int32_t text_tokens;                 /* text tokens that follow the video tokens (0: none)  */
+    int32_t prefix_tokens;               /* text tokens that precede the video tokens (0: none); */
+                                         /* tokens = prefix_tokens + T*H*W + text_tokens         */
 } adaspark_shape;
 
 typedef enum {
@@ -83,7 +87,7 @@ typedef enum {
     ADASPARK_SPARSE_MASKED = 2
 } adaspark_sparse_kernel;
 
-/* Limits: head_dim in {64,128}; number of cubes <= ADASPARK_MAX_CUBES;
+/* Limits: head_dim in {64,128}; number of cubes (text cubes included) <= ADASPARK_MAX_CUBES;
  * tokens*q_heads < 2^31; only causal != 0 (the paper's method) is implemented. */
 #define ADASPARK_MAX_CUBES 2048
 

@@ -30,11 +30,14 @@
  *     preceding cube, p = 0 keeps none;
  *   - fixed Top-K (the ablation baseline): the k highest-ranked preceding cubes
  *     in the same order, all of them if there are no more than k;
- *   - text tokens (end of Sec. 3.2) follow the video tokens; they are cut into
- *     runs of one full cube's length, numbered as cubes after the video cubes;
- *     a text query selects among all video cubes and always attends the text
- *     cubes before its own plus the causal part of its own: cube-wise
- *     attention to the video, token-wise attention among text;
+ *   - text tokens (end of Sec. 3.2) come before the video (`lead`) and after it
+ *     (`text`): the sequence is leading text, video in raster order, trailing
+ *     text.  Each text span is cut into runs of one full cube's length, numbered
+ *     as cubes in sequence order (leading text cubes, video cubes, trailing text
+ *     cubes).  Every query selects among the video cubes before its own cube (a
+ *     trailing-text query: all video cubes) and always attends the text cubes
+ *     before its own plus the causal part of its own: cube-wise attention to
+ *     the video, token-wise attention to text;
  *   - selection is per (token, query head); with grouped-query attention query
  *     head a reads K, V and the mean keys of KV head a / (Hq / Hkv);
  *   - both the relevance score and the attention logits are scaled by
@@ -51,10 +54,11 @@ typedef struct {
     int ct, ch, cw;   /* cube shape along frames, height, width       */
     int Hq, Hkv, D;   /* query heads, KV heads, head dimension        */
     int text;         /* text tokens that follow the video tokens     */
+    int lead;         /* text tokens that precede the video tokens    */
 } oracle_shape;
 
 static int video_tokens(const oracle_shape *s) { return s->T * s->H * s->W; }
-static int all_tokens(const oracle_shape *s) { return s->T * s->H * s->W + s->text; }
+static int all_tokens(const oracle_shape *s) { return s->lead + s->T * s->H * s->W + s->text; }
 static int cube_tokens(const oracle_shape *s) { return s->ct * s->ch * s->cw; }
 
 static double bf16_widen(uint16_t b)
@@ -72,15 +76,17 @@ int oracle_num_video_cubes(const oracle_shape *s)
     return ceil_div(s->T, s->ct) * ceil_div(s->H, s->ch) * ceil_div(s->W, s->cw);
 }
 
-/* video cubes, then the text tokens in runs of one full cube's length ("text cubes") */
+/* leading text in runs of one full cube's length ("text cubes"), video cubes, trailing text cubes */
+int oracle_num_lead_cubes(const oracle_shape *s) { return ceil_div(s->lead, cube_tokens(s)); }
 int oracle_num_cubes(const oracle_shape *s)
 {
-    return oracle_num_video_cubes(s) + ceil_div(s->text, cube_tokens(s));
+    return oracle_num_lead_cubes(s) + oracle_num_video_cubes(s) + ceil_div(s->text, cube_tokens(s));
 }
 
 /* ---------------------------------------------------------------------------
- * Video cube partition (Sec. 3.1; Alg. 1 "Reshape K,V into Cubes"), followed by
- * the text cubes.  For every token n (video tokens in raster order, then text) writes the cube it falls in and its rank
+ * Video cube partition (Sec. 3.1; Alg. 1 "Reshape K,V into Cubes"), between the
+ * leading and the trailing text cubes.  For every token n (leading text, video
+ * tokens in raster order, trailing text) writes the cube it falls in and its rank
  * inside that cube; for every cube its size; start[c] = sum of sizes of cubes
  * before c (start has N+1 entries).  Cube-major position of a token is
  * start[cube] + rank.
@@ -89,12 +95,18 @@ void oracle_cube_map(const oracle_shape *s, int32_t *cube_of, int32_t *rank_of,
                      int32_t *size_of, int64_t *start)
 {
     const int nHb = ceil_div(s->H, s->ch), nWb = ceil_div(s->W, s->cw);
-    const int N = oracle_num_cubes(s), Nv = oracle_num_video_cubes(s);
+    const int N = oracle_num_cubes(s), Nv = oracle_num_video_cubes(s), Np = oracle_num_lead_cubes(s);
     for (int c = 0; c < N; ++c) size_of[c] = 0;
-    /* text tokens (end of Sec. 3.2): they follow the video tokens; run k of cube_tokens consecutive text tokens
-     * is cube Nv + k, rank = position in the run */
+    /* text tokens (end of Sec. 3.2): run k of cube_tokens consecutive tokens of the leading text is cube k, of
+     * the trailing text cube Np + Nv + k; rank = position in the run */
+    for (int x = 0; x < s->lead; ++x) {
+        const int c = x / cube_tokens(s);
+        cube_of[x] = c;
+        rank_of[x] = x % cube_tokens(s);
+        size_of[c] += 1;
+    }
     for (int x = 0; x < s->text; ++x) {
-        const int n = video_tokens(s) + x, c = Nv + x / cube_tokens(s);
+        const int n = s->lead + video_tokens(s) + x, c = Np + Nv + x / cube_tokens(s);
         cube_of[n] = c;
         rank_of[n] = x % cube_tokens(s);
         size_of[c] += 1;
@@ -102,9 +114,9 @@ void oracle_cube_map(const oracle_shape *s, int32_t *cube_of, int32_t *rank_of,
     for (int t = 0; t < s->T; ++t)
         for (int h = 0; h < s->H; ++h)
             for (int w = 0; w < s->W; ++w) {
-                const int n = (t * s->H + h) * s->W + w;
+                const int n = s->lead + (t * s->H + h) * s->W + w;
                 const int tb = t / s->ct, hb = h / s->ch, wb = w / s->cw;
-                const int c = (tb * nHb + hb) * nWb + wb;
+                const int c = Np + (tb * nHb + hb) * nWb + wb;
                 /* clipped extents of this cube along height and width */
                 int eh = s->H - hb * s->ch; if (eh > s->ch) eh = s->ch;
                 int ew = s->W - wb * s->cw; if (ew > s->cw) ew = s->cw;
@@ -219,6 +231,7 @@ void oracle_cube_select(const oracle_shape *s, const uint16_t *Q, const double *
                         uint32_t *sel_mask, int32_t *sel_count, uint8_t *near_cut, double eps)
 {
     const int S = all_tokens(s), N = oracle_num_cubes(s), Nv = oracle_num_video_cubes(s);
+    const int Np = oracle_num_lead_cubes(s);
     const int Hq = s->Hq, Hkv = s->Hkv, D = s->D, G = Hq / Hkv;
     const int words = ceil_div(N, 32);
     int32_t *cube_of = malloc(sizeof(int32_t) * S), *rank_of = malloc(sizeof(int32_t) * S);
@@ -238,19 +251,23 @@ void oracle_cube_select(const oracle_shape *s, const uint16_t *Q, const double *
             const int64_t r = rows ? rows[x] : x;
             const int n = (int)(r / Hq), a = (int)(r % Hq), g = a / G;
             const int own = cube_of[n];
-            /* candidates are the video cubes before the own cube: 0..i-1.  A text query (own >= Nv) scores all
-             * video cubes and always attends the text cubes before its own (token-wise attention among text) */
-            const int i = own < Nv ? own : Nv;
+            /* candidates are the video cubes before the own cube: cubes Np .. Np+i-1 (a query in the trailing
+             * text scores all video cubes, one in the leading text none).  The text cubes before the own cube
+             * are always attended (token-wise attention to text) */
+            const int first_trailing = Np + Nv;
+            const int cand_end = own < first_trailing ? own : first_trailing;
+            const int i = cand_end > Np ? cand_end - Np : 0;
             uint32_t *mrow = sel_mask + (size_t)x * words;
             for (int w = 0; w < words; ++w) mrow[w] = 0;
             sel_count[x] = 0;
             if (near_cut) near_cut[x] = 0;
-            for (int j = Nv; j < own; ++j) { mrow[j >> 5] |= (uint32_t)1 << (j & 31); sel_count[x] += 1; }
+            for (int j = 0; j < own; ++j)
+                if (j < Np || j >= first_trailing) { mrow[j >> 5] |= (uint32_t)1 << (j & 31); sel_count[x] += 1; }
             if (i == 0) continue;
             for (int d = 0; d < D; ++d) q[d] = bf16_widen(Q[((size_t)n * Hq + a) * D + d]);
-            oracle_relevance(q, kbar + (size_t)g * D, (int64_t)Hkv * D, i, D, logits, probs);
+            oracle_relevance(q, kbar + ((size_t)Np * Hkv + g) * D, (int64_t)Hkv * D, i, D, logits, probs);
             const int kept = oracle_top_p(probs, i, p, keep, order, cum);
-            for (int j = 0; j < i; ++j) if (keep[j]) mrow[j >> 5] |= (uint32_t)1 << (j & 31);
+            for (int j = 0; j < i; ++j) if (keep[j]) mrow[(Np + j) >> 5] |= (uint32_t)1 << ((Np + j) & 31);
             sel_count[x] += kept;
             if (near_cut && p < 1.0 && p > 0.0) {
                 int flag = 0;
@@ -300,6 +317,7 @@ void oracle_cube_select_topk(const oracle_shape *s, const uint16_t *Q, const dou
                              uint32_t *sel_mask, int32_t *sel_count, uint8_t *near_cut, double eps)
 {
     const int S = all_tokens(s), N = oracle_num_cubes(s), Nv = oracle_num_video_cubes(s);
+    const int Np = oracle_num_lead_cubes(s);
     const int Hq = s->Hq, Hkv = s->Hkv, D = s->D, G = Hq / Hkv;
     const int words = ceil_div(N, 32);
     int32_t *cube_of = malloc(sizeof(int32_t) * S), *rank_of = malloc(sizeof(int32_t) * S);
@@ -318,20 +336,24 @@ void oracle_cube_select_topk(const oracle_shape *s, const uint16_t *Q, const dou
             const int64_t r = rows ? rows[x] : x;
             const int n = (int)(r / Hq), a = (int)(r % Hq), g = a / G;
             const int own = cube_of[n];
-            /* candidates are the video cubes before the own cube: 0..i-1.  A text query (own >= Nv) scores all
-             * video cubes and always attends the text cubes before its own (token-wise attention among text) */
-            const int i = own < Nv ? own : Nv;
+            /* candidates are the video cubes before the own cube: cubes Np .. Np+i-1 (a query in the trailing
+             * text scores all video cubes, one in the leading text none).  The text cubes before the own cube
+             * are always attended (token-wise attention to text) */
+            const int first_trailing = Np + Nv;
+            const int cand_end = own < first_trailing ? own : first_trailing;
+            const int i = cand_end > Np ? cand_end - Np : 0;
             uint32_t *mrow = sel_mask + (size_t)x * words;
             for (int w = 0; w < words; ++w) mrow[w] = 0;
             sel_count[x] = 0;
             if (near_cut) near_cut[x] = 0;
-            for (int j = Nv; j < own; ++j) { mrow[j >> 5] |= (uint32_t)1 << (j & 31); sel_count[x] += 1; }
+            for (int j = 0; j < own; ++j)
+                if (j < Np || j >= first_trailing) { mrow[j >> 5] |= (uint32_t)1 << (j & 31); sel_count[x] += 1; }
             if (i == 0) continue;
             for (int d = 0; d < D; ++d) q[d] = bf16_widen(Q[((size_t)n * Hq + a) * D + d]);
-            oracle_relevance(q, kbar + (size_t)g * D, (int64_t)Hkv * D, i, D, logits, probs);
+            oracle_relevance(q, kbar + ((size_t)Np * Hkv + g) * D, (int64_t)Hkv * D, i, D, logits, probs);
             /* rank the logits: the same order as the probabilities, and exact where exp() would underflow */
             const int kept = oracle_top_k(logits, i, k, keep, order);
-            for (int j = 0; j < i; ++j) if (keep[j]) mrow[j >> 5] |= (uint32_t)1 << (j & 31);
+            for (int j = 0; j < i; ++j) if (keep[j]) mrow[(Np + j) >> 5] |= (uint32_t)1 << ((Np + j) & 31);
             sel_count[x] += kept;
             if (near_cut && kept > 0 && kept < i && logits[order[kept - 1]] - logits[order[kept]] < eps)
                 near_cut[x] = 1;

@@ -20,7 +20,7 @@ _lib = None
 
 
 class _CShape(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int) for n in ("T", "H", "W", "ct", "ch", "cw", "Hq", "Hkv", "D", "text")]
+    _fields_ = [(n, ctypes.c_int) for n in ("T", "H", "W", "ct", "ch", "cw", "Hq", "Hkv", "D", "text", "lead")]
 
 
 @dataclass(frozen=True)
@@ -37,13 +37,15 @@ class Shape:
     Hkv: int
     D: int
     text: int = 0  # text tokens that follow the video tokens
+    lead: int = 0  # text tokens that precede the video tokens
 
     @property
     def S(self) -> int:
-        return self.T * self.H * self.W + self.text
+        return self.lead + self.T * self.H * self.W + self.text
 
     def _c(self) -> _CShape:
-        return _CShape(self.T, self.H, self.W, self.ct, self.ch, self.cw, self.Hq, self.Hkv, self.D, self.text)
+        return _CShape(self.T, self.H, self.W, self.ct, self.ch, self.cw, self.Hq, self.Hkv, self.D, self.text,
+                       self.lead)
 
 
 def build(force: bool = False) -> str:

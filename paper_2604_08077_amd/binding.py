@@ -20,7 +20,8 @@ CALL_CUBE_POOL, CALL_CUBE_SELECT, CALL_SPARSE_ATTN, CALL_DENSE_ATTN = 0, 1, 2, 3
 
 class _CShape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
-        "frames", "height", "width", "cube_t", "cube_h", "cube_w", "q_heads", "kv_heads", "head_dim", "text_tokens")]
+        "frames", "height", "width", "cube_t", "cube_h", "cube_w", "q_heads", "kv_heads", "head_dim", "text_tokens",
+        "prefix_tokens")]
 
 
 @dataclass(frozen=True)
@@ -36,11 +37,12 @@ class Shape:
     q_heads: int
     kv_heads: int
     head_dim: int
-    text_tokens: int = 0  # text tokens that follow the video tokens
+    text_tokens: int = 0    # text tokens that follow the video tokens
+    prefix_tokens: int = 0  # text tokens that precede the video tokens
 
     @property
     def tokens(self) -> int:
-        return self.frames * self.height * self.width + self.text_tokens
+        return self.prefix_tokens + self.frames * self.height * self.width + self.text_tokens
 
     @property
     def rows(self) -> int:
@@ -48,12 +50,12 @@ class Shape:
 
     def _c(self) -> _CShape:
         return _CShape(self.frames, self.height, self.width, self.cube_t, self.cube_h, self.cube_w,
-                       self.q_heads, self.kv_heads, self.head_dim, self.text_tokens)
+                       self.q_heads, self.kv_heads, self.head_dim, self.text_tokens, self.prefix_tokens)
 
     @staticmethod
     def of(w) -> "Shape":
         """From a ``synth.Workload``."""
-        return Shape(w.T, w.H, w.W, w.ct, w.ch, w.cw, w.Hq, w.Hkv, w.D, w.text)
+        return Shape(w.T, w.H, w.W, w.ct, w.ch, w.cw, w.Hq, w.Hkv, w.D, w.text, w.lead)
 
 
 class AdasparkError(RuntimeError):

@@ -14,15 +14,16 @@ int check_shape(const adaspark_shape *s)
     if (s->cube_t <= 0 || s->cube_h <= 0 || s->cube_w <= 0) return ADASPARK_EINVAL;
     if (s->q_heads <= 0 || s->kv_heads <= 0 || s->head_dim <= 0) return ADASPARK_EINVAL;
     if (s->q_heads % s->kv_heads != 0) return ADASPARK_EINVAL;
-    if (s->text_tokens < 0) return ADASPARK_EINVAL;
-    const long long tokens = (long long)s->frames * s->height * s->width + s->text_tokens;
+    if (s->text_tokens < 0 || s->prefix_tokens < 0) return ADASPARK_EINVAL;
+    const long long tokens = (long long)s->frames * s->height * s->width + s->text_tokens + s->prefix_tokens;
     if (tokens * s->q_heads >= (1ll << 31)) return ADASPARK_EUNSUPPORTED;
     if (s->head_dim != 64 && s->head_dim != 128) return ADASPARK_EUNSUPPORTED;
     const long long cube = (long long)s->cube_t * s->cube_h * s->cube_w;
     if (cube >= (1ll << 24)) return ADASPARK_EUNSUPPORTED;
     const long long nt = (s->frames + (long long)s->cube_t - 1) / s->cube_t, nh = (s->height + (long long)s->cube_h - 1) / s->cube_h,
                     nw = (s->width + (long long)s->cube_w - 1) / s->cube_w;
-    if (nt * nh * nw + (s->text_tokens + cube - 1) / cube > ADASPARK_MAX_CUBES) return ADASPARK_EUNSUPPORTED;
+    if (nt * nh * nw + (s->text_tokens + cube - 1) / cube + (s->prefix_tokens + cube - 1) / cube > ADASPARK_MAX_CUBES)
+        return ADASPARK_EUNSUPPORTED;
     return ADASPARK_OK;
 }
 

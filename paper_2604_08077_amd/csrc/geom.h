@@ -17,9 +17,10 @@ struct Geom {
     int Hq, Hkv, D, G;  // heads, head_dim, group size Hq/Hkv
     int nTb, nHb, nWb;  // video cubes along each axis
     int Nv, Sv;         // video cubes, video tokens
-    int St;             // text tokens (they follow the video tokens), cut into text cubes of up to Cmax tokens
-    int N;              // cubes: video cubes, then text cubes
-    int S;              // tokens: video tokens, then text tokens
+    int Sp, Np;         // text tokens before the video, cut into Np text cubes of up to Cmax tokens
+    int St;             // text tokens after the video, cut into text cubes the same way
+    int N;              // cubes: leading text cubes, video cubes, trailing text cubes
+    int S;              // tokens: leading text, video (raster order), trailing text
     int Cmax;           // tokens in an unclipped cube
     int TPC;            // key tiles per cube in the packed layout = ceil(Cmax / KEY_TILE)
     int words;          // u32 words per selection-mask row = ceil(N / 32)
@@ -35,18 +36,21 @@ inline Geom make_geom(const adaspark_shape &s)
     g.nTb = (g.T + g.ct - 1) / g.ct; g.nHb = (g.H + g.ch - 1) / g.ch; g.nWb = (g.W + g.cw - 1) / g.cw;
     g.Nv = g.nTb * g.nHb * g.nWb;
     g.Sv = g.T * g.H * g.W;
+    g.Sp = s.prefix_tokens;
     g.St = s.text_tokens;
     g.Cmax = g.ct * g.ch * g.cw;
-    g.N = g.Nv + (g.St + g.Cmax - 1) / g.Cmax;
-    g.S = g.Sv + g.St;
+    g.Np = (g.Sp + g.Cmax - 1) / g.Cmax;
+    g.N = g.Np + g.Nv + (g.St + g.Cmax - 1) / g.Cmax;
+    g.S = g.Sp + g.Sv + g.St;
     g.TPC = (g.Cmax + KEY_TILE - 1) / KEY_TILE;
     g.words = (g.N + 31) / 32;
-    g.ragged = (g.T % g.ct != 0) || (g.H % g.ch != 0) || (g.W % g.cw != 0) || (g.St % g.Cmax != 0);
+    g.ragged = (g.T % g.ct != 0) || (g.H % g.ch != 0) || (g.W % g.cw != 0) || (g.St % g.Cmax != 0) ||
+               (g.Sp % g.Cmax != 0);
     return g;
 }
 
 // Clipped extents and origin of cube c.  A text cube is a run of consecutive tokens: t0 < 0, w0 = its first
-// token, ew = its length.
+// token, ew = its length.  Video cubes are numbered from Np; their box is in video-grid coordinates.
 struct CubeBox {
     int t0, h0, w0;  // origin in the token grid
     int et, eh, ew;  // extents after clipping at the grid edge
@@ -56,9 +60,16 @@ struct CubeBox {
 __host__ __device__ inline CubeBox cube_box(const Geom &g, int c)
 {
     CubeBox b;
+    if (c < g.Np) {
+        const int first = c * g.Cmax;
+        b.t0 = -1; b.h0 = 0; b.w0 = first;
+        b.et = 1; b.eh = 1; b.ew = min(g.Cmax, g.Sp - first);
+        return b;
+    }
+    c -= g.Np;
     if (c >= g.Nv) {
         const int first = (c - g.Nv) * g.Cmax;
-        b.t0 = -1; b.h0 = 0; b.w0 = g.Sv + first;
+        b.t0 = -1; b.h0 = 0; b.w0 = g.Sp + g.Sv + first;
         b.et = 1; b.eh = 1; b.ew = min(g.Cmax, g.St - first);
         return b;
     }
@@ -73,15 +84,17 @@ __host__ __device__ inline int token_of(const Geom &g, const CubeBox &b, int ran
 {
     if (b.t0 < 0) return b.w0 + rank;
     const int lw = rank % b.ew, lh = (rank / b.ew) % b.eh, lt = rank / (b.ew * b.eh);
-    return ((b.t0 + lt) * g.H + (b.h0 + lh)) * g.W + (b.w0 + lw);
+    return g.Sp + ((b.t0 + lt) * g.H + (b.h0 + lh)) * g.W + (b.w0 + lw);
 }
 
 // Cube of token n (rank not needed by the callers of this one).
 __host__ __device__ inline int cube_of_token(const Geom &g, int n)
 {
-    if (n >= g.Sv) return g.Nv + (n - g.Sv) / g.Cmax;
+    if (n < g.Sp) return n / g.Cmax;
+    n -= g.Sp;
+    if (n >= g.Sv) return g.Np + g.Nv + (n - g.Sv) / g.Cmax;
     const int w = n % g.W, h = (n / g.W) % g.H, t = n / (g.W * g.H);
-    return ((t / g.ct) * g.nHb + (h / g.ch)) * g.nWb + (w / g.cw);
+    return g.Np + ((t / g.ct) * g.nHb + (h / g.ch)) * g.nWb + (w / g.cw);
 }
 
 // bf16 <-> fp32 bit helpers.

@@ -81,6 +81,13 @@ __device__ __forceinline__ uint32_t sel_range_bits(int w, int lo, int hi)
     return upto_b & ~((1u << a) - 1u);
 }
 
+// Bits of word w that a row of cube i always has: the text cubes before its own (leading ones are cubes
+// [0, Np), trailing ones follow the video cubes), which are attended whatever the rule selects.
+__device__ __forceinline__ uint32_t sel_forced_bits(const Geom &g, int w, int i)
+{
+    return sel_range_bits(w, 0, min(i, g.Np)) | sel_range_bits(w, g.Np + g.Nv, i);
+}
+
 // OR / sum / max over the four lanes {n, n+16, n+32, n+48} that share a query row
 __device__ __forceinline__ uint32_t selm_quad_or(uint32_t x)
 {
@@ -131,9 +138,12 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
     const CubeBox qbox = cube_box(g, i);
     const int P = g.G * qbox.size();  // rows of this (cube, KV head): rho = rank * G + head-in-group
     if (blk * SELM_ROWS >= P) return;
-    // Candidates are the video cubes before the own cube.  A text query (own cube i >= Nv) scores every video cube
-    // and always attends the text cubes before its own: those bits are set whatever the rule selects.
-    const int ncand = min(i, g.Nv);
+    // Candidates are the video cubes before the own cube: cubes [Np, cend).  A query after the video scores every
+    // video cube; the text cubes before a row's own are always attended: those bits are set whatever the rule
+    // selects.
+    const int cend = min(i, g.Np + g.Nv);
+    const int ncand = max(cend - g.Np, 0);
+    const int nforced = i - ncand;
 
     int rowg[SELM_SLABS];  // global row id of this lane's column, -1: past the end
     int rowq[SELM_SLABS];  // row whose Q is loaded (a valid one also for padding columns)
@@ -153,8 +163,8 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
         for (int s = 0; s < SELM_SLABS; ++s) {
             if (rowg[s] < 0) continue;
             for (int w = q4; w < g.words; w += 4)
-                sel_mask[(size_t)rowg[s] * g.words + w] = sel_range_bits(w, 0, keep) | sel_range_bits(w, g.Nv, i);
-            if (q4 == 0) sel_count[rowg[s]] = keep + (i - ncand);
+                sel_mask[(size_t)rowg[s] * g.words + w] = sel_range_bits(w, g.Np, g.Np + keep) | sel_forced_bits(g, w, i);
+            if (q4 == 0) sel_count[rowg[s]] = keep + nforced;
         }
         return;
     }
@@ -167,7 +177,7 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
             qf[s][c] = *reinterpret_cast<const sel_bf16x8 *>(Q + (size_t)rowq[s] * D + 32 * c + 8 * q4);
 
     // ---- logits: acc[s][cg][v] = q(row n16 of slab s) . kbar(cube 16cg + 4q4 + v)
-    const int ng = (ncand + 15) >> 4;  // cube groups that hold candidates (the same for every row here)
+    const int ng = (cend + 15) >> 4;  // cube groups up to the last candidate (the same for every row here)
     sel_f32x4 acc[SELM_SLABS][MAXG];
 #pragma unroll
     for (int s = 0; s < SELM_SLABS; ++s)
@@ -214,7 +224,8 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
         for (int cg = 0; cg < MAXG; ++cg)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const bool valid = 16 * cg + 4 * q4 + v < ncand;
+                const int cube = 16 * cg + 4 * q4 + v;
+                const bool valid = cube >= g.Np && cube < cend;
                 const float x = valid ? acc[s][cg][v] * scale : -INFINITY;
                 acc[s][cg][v] = x;
                 mx = fmaxf(mx, x);
@@ -362,13 +373,13 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
             word = selm_quad_or(word);
             kept += __popc(word);
             if (w < g.words && rowg[s] >= 0 && q4 == (w & 3))
-                sel_mask[(size_t)rowg[s] * g.words + w] = word | sel_range_bits(w, g.Nv, i);
+                sel_mask[(size_t)rowg[s] * g.words + w] = word | sel_forced_bits(g, w, i);
         }
         // words beyond this kernel's cube groups (grids with more cubes): no candidates there for these rows
         if (rowg[s] >= 0)
             for (int w = (MAXG + 1) / 2 + q4; w < g.words; w += 4)
-                sel_mask[(size_t)rowg[s] * g.words + w] = sel_range_bits(w, g.Nv, i);
-        if (rowg[s] >= 0 && q4 == 0) sel_count[rowg[s]] = kept + (i - ncand);
+                sel_mask[(size_t)rowg[s] * g.words + w] = sel_forced_bits(g, w, i);
+        if (rowg[s] >= 0 && q4 == 0) sel_count[rowg[s]] = kept + nforced;
     }
 }
 
@@ -404,7 +415,10 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
     const CubeBox qbox = cube_box(g, i);
     const int P = g.G * qbox.size();
     if (blk * SELW_ROWS >= P) return;  // the whole workgroup
-    const int ncand = min(i, g.Nv);    // candidates: video cubes before the own cube; text cubes before it are forced
+    // candidates: the video cubes before the own cube, [Np, cend); text cubes before it are forced
+    const int cend = min(i, g.Np + g.Nv);
+    const int ncand = max(cend - g.Np, 0);
+    const int nforced = i - ncand;
 
     int rowg[SLABS], rowq[SLABS];
 #pragma unroll
@@ -424,8 +438,8 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
         for (int s = 0; s < SLABS; ++s) {
             if (rowg[s] < 0) continue;
             for (int w = q4; w < g.words; w += 4)
-                sel_mask[(size_t)rowg[s] * g.words + w] = sel_range_bits(w, 0, keep) | sel_range_bits(w, g.Nv, i);
-            if (q4 == 0) sel_count[rowg[s]] = keep + (i - ncand);
+                sel_mask[(size_t)rowg[s] * g.words + w] = sel_range_bits(w, g.Np, g.Np + keep) | sel_forced_bits(g, w, i);
+            if (q4 == 0) sel_count[rowg[s]] = keep + nforced;
         }
         return;
     }
@@ -438,7 +452,7 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
             qf[s][c] = *reinterpret_cast<const sel_bf16x8 *>(Q + (size_t)rowq[s] * D + 32 * c + 8 * q4);
 
     // ---- logits of this wavefront's cube block: acc[s][lg][v] = q(row n16 of slab s) . kbar(cube 16(g0+lg)+4q4+v)
-    const int ng = (ncand + 15) >> 4;  // cube groups that hold candidates
+    const int ng = (cend + 15) >> 4;  // cube groups up to the last candidate
     const int g0 = part * MAXG;
     const int nlg = min(max(ng - g0, 0), MAXG);  // of them, in this wavefront's block
     sel_f32x4 acc[SLABS][MAXG];
@@ -509,7 +523,8 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
         for (int lg = 0; lg < MAXG; ++lg)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const bool valid = 16 * (g0 + lg) + 4 * q4 + v < ncand;
+                const int cube = 16 * (g0 + lg) + 4 * q4 + v;
+                const bool valid = cube >= g.Np && cube < cend;
                 const float x = valid ? acc[s][lg][v] * scale : -INFINITY;
                 acc[s][lg][v] = x;
                 mx = fmaxf(mx, x);
@@ -698,7 +713,7 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
             kept += __popc(word);
             const int wg = (MAXG / 2) * part + w;
             if (wg < g.words && rowg[s] >= 0 && q4 == (w & 3))
-                sel_mask[(size_t)rowg[s] * g.words + wg] = word | sel_range_bits(wg, g.Nv, i);
+                sel_mask[(size_t)rowg[s] * g.words + wg] = word | sel_forced_bits(g, wg, i);
         }
         kept_part[s] = (uint32_t)kept;
     }
@@ -714,7 +729,7 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
             int kept = 0;
 #pragma unroll
             for (int p = 0; p < SPLIT; ++p) kept += (int)xa[p][0][s];
-            if (rowg[s] >= 0) sel_count[rowg[s]] = kept + (i - ncand);
+            if (rowg[s] >= 0) sel_count[rowg[s]] = kept + nforced;
         }
     }
 }

@@ -37,10 +37,12 @@ class Workload:
     k_mean_scale: Tuple[float, ...]
     # text tokens appended after the video tokens (no per-cube key mean: plain noise keys)
     text: int = 0
+    # text tokens placed before the video tokens (the same)
+    lead: int = 0
 
     @property
     def S(self) -> int:
-        return self.T * self.H * self.W + self.text
+        return self.lead + self.T * self.H * self.W + self.text
 
     @property
     def S_video(self) -> int:
@@ -55,12 +57,12 @@ class Workload:
         return (self.ct, self.ch, self.cw)
 
 
-def _wl(name, cid, grid, cube, hq, hkv, d, top_p, scale, text=0):
+def _wl(name, cid, grid, cube, hq, hkv, d, top_p, scale, text=0, lead=0):
     if not isinstance(scale, tuple):
         scale = (float(scale),) * hkv
     if not isinstance(top_p, tuple):
         top_p = (float(top_p),)
-    return Workload(name, cid, *grid, *cube, hq, hkv, d, top_p, scale, text)
+    return Workload(name, cid, *grid, *cube, hq, hkv, d, top_p, scale, text, lead)
 
 
 # The five benchmark configurations (token grid, cube, heads, head_dim, Top-p).
@@ -86,12 +88,18 @@ TEST_WORKLOADS = {
     # video followed by text tokens: 100 = three full text cubes of 32 and one of 4; 37 = a single short text cube
     "T_text64": _wl("T_text64", 18, (6, 8, 8), (2, 4, 4), 4, 2, 64, 0.8, 1.0, text=100),
     "T_text128": _wl("T_text128", 19, (5, 10, 12), (4, 4, 8), 6, 2, 128, 0.9, (0.0, 2.0), text=37),
+    # text on both sides of the video: 70 leading tokens (two full text cubes and one of 6), 45 trailing
+    "T_lead64": _wl("T_lead64", 21, (6, 8, 8), (2, 4, 4), 4, 2, 64, 0.8, 1.0, text=45, lead=70),
+    # a short leading prompt only (a single text cube of 50), ragged video grid, D 128
+    "T_lead128": _wl("T_lead128", 22, (5, 10, 12), (4, 4, 8), 6, 2, 128, 0.9, (0.0, 2.0), lead=50),
 }
 
 # Mid-sized cases, checked on sampled rows only.
 SAMPLED_WORKLOADS = {
     # a 16,384-token video with a 1,000-token prompt after it: 64 video cubes, 4 text cubes
     "M_text16k": _wl("M_text16k", 20, (64, 16, 16), (4, 8, 8), 28, 4, 128, 0.9, 1.0, text=1000),
+    # a 300-token system prompt, an 8,192-token video, a 500-token question
+    "M_lead8k": _wl("M_lead8k", 23, (32, 16, 16), (4, 8, 8), 28, 4, 128, 0.9, 1.0, text=500, lead=300),
 }
 
 
@@ -105,8 +113,8 @@ def generate(w: Workload):
     """-> (Q [S,Hq,D], K [S,Hkv,D], V [S,Hkv,D]) CPU bf16 tensors.
 
     Q, V ~ N(0,1).  K = N(0,1) + scale[g] * mu, mu ~ N(0, I) drawn once per
-    (cube, KV head) and shared by all tokens of that cube.  Text tokens (the last
-    ``w.text`` rows) have plain N(0,1) keys.
+    (cube, KV head) and shared by all tokens of that cube.  Text tokens (the first
+    ``w.lead`` and the last ``w.text`` rows) have plain N(0,1) keys.
     """
     seed = BASE_SEED + 1000 * w.config_id
     S, Sv = w.S, w.S_video
@@ -119,7 +127,7 @@ def generate(w: Workload):
         mu = mu * torch.tensor(w.k_mean_scale, dtype=torch.float32).view(1, 1, 1, w.Hkv, 1)
         field = mu.repeat_interleave(w.ct, 0).repeat_interleave(w.ch, 1).repeat_interleave(w.cw, 2)
         field = field[: w.T, : w.H, : w.W].reshape(Sv, w.Hkv, w.D)
-        K[:Sv] = K[:Sv] + field
+        K[w.lead : w.lead + Sv] = K[w.lead : w.lead + Sv] + field
     return Q, K.to(torch.bfloat16), V
 
 
@@ -138,8 +146,12 @@ def sample_rows(w: Workload, n: int, seed: int = 7):
     fixed = torch.tensor([0, w.Hq - 1, R - w.Hq, R - 1], dtype=torch.int64)
     parts = [picks, fixed]
     if w.text:
-        first = w.S_video * w.Hq
+        first = (w.lead + w.S_video) * w.Hq
         parts.append(first + torch.randperm(R - first, generator=g)[: max(8, n // 8)])
         parts.append(torch.tensor([first, first + w.Hq - 1], dtype=torch.int64))
+    if w.lead:
+        end = w.lead * w.Hq
+        parts.append(torch.randperm(end, generator=g)[: max(8, n // 8)])
+        parts.append(torch.tensor([end - 1, end, end + w.Hq - 1], dtype=torch.int64))
     rows = torch.unique(torch.cat(parts))
     return rows.numpy()

@@ -60,7 +60,7 @@ def _raw_shape(**kw):
 @pytest.mark.parametrize("kw,code", [
     (dict(frames=0), -1), (dict(cube_w=0), -1), (dict(q_heads=3), -1), (dict(kv_heads=0), -1),
     (dict(head_dim=96), -2), (dict(frames=4096, height=64, width=64, cube_t=1, cube_h=1, cube_w=1), -2),
-    (dict(text_tokens=-1), -1), (dict(text_tokens=32 * 2048), -2),
+    (dict(text_tokens=-1), -1), (dict(prefix_tokens=-1), -1), (dict(prefix_tokens=32 * 2048), -2), (dict(text_tokens=32 * 2048), -2),
 ])
 def test_bad_shapes_are_rejected(lib, kw, code):
     with pytest.raises(binding.AdasparkError) as e:

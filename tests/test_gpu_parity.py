@@ -31,7 +31,7 @@ def B():
 
 
 def oshape(o, w):
-    return o.Shape(w.T, w.H, w.W, w.ct, w.ch, w.cw, w.Hq, w.Hkv, w.D, w.text)
+    return o.Shape(w.T, w.H, w.W, w.ct, w.ch, w.cw, w.Hq, w.Hkv, w.D, w.text, w.lead)
 
 
 def to_u32(t):
@@ -68,7 +68,8 @@ def rows_of(O, rows, w):
 
 
 SMALL = [synth.TEST_WORKLOADS[k] for k in ("T_tiny", "T_ragged", "T_mha64", "T_gqa128", "T_manycubes", "T_cubes280",
-                                           "T_cubes1100", "T_text64", "T_text128")] + [
+                                           "T_cubes1100", "T_text64", "T_text128", "T_lead64",
+                                           "T_lead128")] + [
     synth.WORKLOADS["C1"]]
 
 
@@ -142,7 +143,7 @@ def test_full_path_small(B, oracle, w):
     O0 = B.sparse_attn(sh, Qg, Kg, Vg, m0)
     torch.cuda.synchronize()
     ref_m0, _, _ = oracle.cube_select(osh, Q, kbar_ref, 0.0)
-    assert w.text or not ref_m0.any()
+    assert w.text or w.lead or not ref_m0.any()
     ref0, _ = oracle.sparse_attn(osh, Q, K, V, ref_m0)
     check_outputs(f"{w.name} sparse p=0", O0.reshape(-1, w.D).float().cpu().numpy(), ref0)
 
@@ -244,6 +245,11 @@ def test_video_then_text_sampled(B, oracle):
         assert (cnt[n] == earlier).all()
 
 
+def test_text_video_text_sampled(B, oracle):
+    """A 300-token prompt, an 8,192-token video and a 500-token question: sampled rows of all three spans."""
+    sampled_case(B, oracle, synth.SAMPLED_WORKLOADS["M_lead8k"], (0.5, 0.9), 512)
+
+
 def test_c5_entropy_stress_sampled(B, oracle):
     sampled_case(B, oracle, synth.WORKLOADS["C5"], (0.9,), 512)
 
@@ -256,7 +262,8 @@ def test_c4_sampled(B, oracle):
     sampled_case(B, oracle, synth.WORKLOADS["C4"], (0.9,), 192, check_dense=False)
 
 
-@pytest.mark.parametrize("name", ["T_gqa128", "T_manycubes", "T_cubes280", "T_cubes1100", "T_text64", "C1"])
+@pytest.mark.parametrize("name", ["T_gqa128", "T_manycubes", "T_cubes280", "T_cubes1100", "T_text64", "T_lead64",
+                                  "C1"])
 def test_select_ties_zero_queries(B, oracle, name):
     """All-zero queries make every candidate cube equally likely: the whole Top-p decision is the tie rule
     (lower cube index first, keep while the mass before an element is below p)."""
@@ -276,14 +283,15 @@ def test_select_ties_zero_queries(B, oracle, name):
         # the kept cubes are a prefix 0..k-1 of the candidates (the video cubes: text cubes are never candidates)
         gm = to_u32(mask)
         n_video = -(-w.T // w.ct) * -(-w.H // w.ch) * -(-w.W // w.cw)
-        bits = np.unpackbits(gm.view(np.uint8), axis=1, bitorder="little").astype(np.int64)[:, :n_video]
+        n_lead = -(-w.lead // (w.ct * w.ch * w.cw))
+        bits = np.unpackbits(gm.view(np.uint8), axis=1, bitorder="little").astype(np.int64)[:, n_lead:n_lead + n_video]
         k = bits.sum(1)
         assert np.array_equal(bits.cumsum(1)[np.arange(len(k)), np.maximum(k, 1) - 1], np.where(k > 0, k, 0))
         assert same[~near].all()
 
 
 @pytest.mark.parametrize("name", ["T_ragged", "T_gqa128", "T_manycubes", "T_cubes280", "T_cubes1100", "T_text128",
-                                  "C1"])
+                                  "T_lead64", "C1"])
 def test_topk_selection_small(B, oracle, name):
     """Fixed Top-K selection (the ablation baseline): every row, several k, incl. 0 and more than there are cubes;
     the sparse attention fed that selection."""

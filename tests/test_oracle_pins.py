@@ -20,7 +20,7 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 
 def shape_of(o, w):
-    return o.Shape(w.T, w.H, w.W, w.ct, w.ch, w.cw, w.Hq, w.Hkv, w.D, w.text)
+    return o.Shape(w.T, w.H, w.W, w.ct, w.ch, w.cw, w.Hq, w.Hkv, w.D, w.text, w.lead)
 
 
 def widen(x):
@@ -28,14 +28,30 @@ def widen(x):
 
 
 def brute_cube_table(w):
-    """Independent cube map: walk cubes in (tb,hb,wb) order and inside each cube
-    in local (t,h,w) order, handing out ranks as tokens are met."""
+    """Independent cube map: leading text in runs of one full cube's length, then the video cubes walked in
+    (tb,hb,wb) order and inside each cube in local (t,h,w) order, handing out ranks as tokens are met, then the
+    trailing text in runs."""
     T, H, W = w.grid
     ct, ch, cw = w.cube
-    cube_of = -np.ones(T * H * W, np.int64)
-    rank_of = -np.ones(T * H * W, np.int64)
+    full = ct * ch * cw
+    S = w.lead + T * H * W + w.text
+    cube_of = -np.ones(S, np.int64)
+    rank_of = -np.ones(S, np.int64)
     sizes = []
     c = 0
+
+    def text_span(first, count):
+        nonlocal c
+        done = 0
+        while done < count:
+            take = min(full, count - done)
+            cube_of[first + done: first + done + take] = c
+            rank_of[first + done: first + done + take] = np.arange(take)
+            sizes.append(take)
+            c += 1
+            done += take
+
+    text_span(0, w.lead)
     for t0 in range(0, T, ct):
         for h0 in range(0, H, ch):
             for w0 in range(0, W, cw):
@@ -43,24 +59,13 @@ def brute_cube_table(w):
                 for t in range(t0, min(t0 + ct, T)):
                     for h in range(h0, min(h0 + ch, H)):
                         for x in range(w0, min(w0 + cw, W)):
-                            n = (t * H + h) * W + x
+                            n = w.lead + (t * H + h) * W + x
                             cube_of[n], rank_of[n] = c, r
                             r += 1
                 sizes.append(r)
                 c += 1
-    # text tokens follow the video tokens; runs of one full cube's length, numbered after the video cubes
-    full = ct * ch * cw
-    text_cube, text_rank = [], []
-    left = w.text
-    while left > 0:
-        take = min(full, left)
-        text_cube += [c] * take
-        text_rank += list(range(take))
-        sizes.append(take)
-        c += 1
-        left -= take
-    cube_of = np.concatenate([cube_of, np.array(text_cube, np.int64)])
-    rank_of = np.concatenate([rank_of, np.array(text_rank, np.int64)])
+    text_span(w.lead + T * H * W, w.text)
+    assert (cube_of >= 0).all()
     return cube_of, rank_of, np.array(sizes)
 
 
@@ -68,6 +73,10 @@ def video_cubes(w):
     T, H, W = w.grid
     ct, ch, cw = w.cube
     return -(-T // ct) * -(-H // ch) * -(-W // cw)
+
+
+def lead_cubes(w):
+    return -(-w.lead // (w.ct * w.ch * w.cw))
 
 
 ALL_SMALL = list(synth.TEST_WORKLOADS.values())
@@ -234,21 +243,23 @@ def test_select_invariants_and_independent_recomputation(oracle, w):
             assert not (prev & ~sel).any()
         prev = sel
         rng = np.random.default_rng(5)
-        nv = video_cubes(w)
+        nv, npre = video_cubes(w), lead_cubes(w)
         picks = rng.choice(w.S * w.Hq, size=60, replace=False).tolist()
         picks += list(range(w.S * w.Hq - min(w.text, 3) * w.Hq, w.S * w.Hq))   # the last text rows, if any
+        picks += list(range(0, min(w.lead, 3) * w.Hq))                         # the first text rows, if any
         for r in picks:
             n, a = divmod(int(r), w.Hq)
             own = bc[n]
             assert not sel[r, own:].any()         # own and later cubes never selected
-            i = min(own, nv)                      # candidates: the video cubes before the own cube
-            assert sel[r, nv:own].all()           # a text row always attends the text cubes before its own
-            assert count[r] == sel[r, :i].sum() + max(own - nv, 0)
+            lo, hi = npre, max(npre, min(own, npre + nv))   # candidates: the video cubes before the own cube
+            i = hi - lo
+            # text cubes before the own cube are always attended
+            assert sel[r, :min(own, npre)].all() and sel[r, npre + nv:own].all()
+            assert count[r] == sel[r, lo:hi].sum() + min(own, npre) + max(own - npre - nv, 0)
             if i == 0:
-                assert sel[r, :nv].sum() == 0
                 continue
-            probs = sp_softmax(kbar[:i, a // G] @ Qd[n, a] / math.sqrt(w.D))
-            s = sel[r, :i]
+            probs = sp_softmax(kbar[lo:hi, a // G] @ Qd[n, a] / math.sqrt(w.D))
+            s = sel[r, lo:hi]
             mass = probs[s].sum()
             assert mass >= p - 1e-12
             assert mass - probs[s].min() < p + 1e-12         # minimal prefix
@@ -423,47 +434,58 @@ def test_p_zero_is_block_diagonal_causal_and_first_cube_ignores_p(oracle, w):
     assert N > 1 and not np.allclose(outp[~first], out0[~first])
 
 
-@pytest.mark.parametrize("name", ["T_text64", "T_text128"])
-def test_text_rows_attend_selected_video_cubes_and_all_earlier_text(oracle, name):
-    """End of Sec. 3.2 for text queries, recomputed in numpy from an explicit token list: the video tokens of
-    the cubes the nucleus rule keeps among ALL video cubes, every earlier text token and the token itself;
-    video rows of the same inputs give what they give without the text."""
+@pytest.mark.parametrize("name", ["T_text64", "T_text128", "T_lead64", "T_lead128"])
+def test_rows_of_text_and_video_recomputed_from_explicit_token_lists(oracle, name):
+    """End of Sec. 3.2, recomputed in numpy from an explicit token list for rows of all three spans: every
+    earlier text token (leading and trailing), the video tokens of the cubes the nucleus rule keeps among the
+    video cubes before the own cube (a trailing-text query: among ALL video cubes), and the causal part of the
+    own cube.  Without leading text, video rows give what they give with the trailing text cut off."""
     w = synth.TEST_WORKLOADS[name]
     sh = shape_of(oracle, w)
-    N, nv, Sv = oracle.num_cubes(sh), video_cubes(w), w.S_video
+    N, nv, npre, Sv = oracle.num_cubes(sh), video_cubes(w), lead_cubes(w), w.S_video
     Q, K, V = synth.generate(w)
     Qd, Kd, Vd = widen(Q), widen(K), widen(V)
     kbar = oracle.cube_pool(sh, K)
-    bc, _, _ = brute_cube_table(w)
+    bc, br, _ = brute_cube_table(w)
     G = w.Hq // w.Hkv
     p = w.top_p[0]
-    rows = np.arange(Sv * w.Hq, w.S * w.Hq, 5)
+    is_text = np.ones(w.S, bool)
+    is_text[w.lead: w.lead + Sv] = False
+    rows = np.unique(np.concatenate([np.arange(0, w.lead * w.Hq, 3), np.arange(w.lead * w.Hq, w.S * w.Hq, 41),
+                                     np.arange((w.lead + Sv) * w.Hq, w.S * w.Hq, 5)])).astype(np.int64)
     mask, count, _ = oracle.cube_select(sh, Q, kbar, p, rows=rows)
     out, nk = oracle.sparse_attn(sh, Q, K, V, mask, rows=rows)
     sel = unpack(mask, N)
     for x, r in enumerate(rows):
         n, a = divmod(int(r), w.Hq)
         kvh = a // G
-        probs = sp_softmax(kbar[:nv, kvh] @ Qd[n, a] / math.sqrt(w.D))
-        keep, _, _ = oracle.top_p(probs, p)       # the nucleus rule itself is pinned by enumeration above
-        assert np.array_equal(sel[x, :nv], keep)
-        toks = np.concatenate([np.nonzero(keep[bc[:Sv]])[0], np.arange(Sv, n + 1)])
+        own = bc[n]
+        ncand = max(min(own, npre + nv) - npre, 0)
+        keep_cube = np.zeros(N, bool)
+        if ncand:
+            probs = sp_softmax(kbar[npre:npre + ncand, kvh] @ Qd[n, a] / math.sqrt(w.D))
+            keep, _, _ = oracle.top_p(probs, p)       # the nucleus rule itself is pinned by enumeration above
+            keep_cube[npre:npre + ncand] = keep
+        assert np.array_equal(sel[x, npre:npre + nv], keep_cube[npre:npre + nv])
+        attended = (keep_cube[bc] & ~is_text) | (is_text & (bc < own)) | ((bc == own) & (br <= br[n]))
+        toks = np.nonzero(attended)[0]
         assert nk[x] == toks.size
         ref = sp_softmax(Kd[toks, kvh] @ Qd[n, a] / math.sqrt(w.D)) @ Vd[toks, kvh]
         assert np.abs(out[x] - ref).max() < 1e-10
-    # video rows do not see the text: same selection and output as for the video alone
-    wv = synth.Workload(**{**w.__dict__, "text": 0})
-    shv = shape_of(oracle, wv)
-    vrows = np.arange(0, Sv * w.Hq, 37)
-    kbar_v = oracle.cube_pool(shv, K[:Sv])
-    assert np.array_equal(kbar_v, kbar[:nv])
-    m1, c1, _ = oracle.cube_select(sh, Q, kbar, p, rows=vrows)
-    m2, c2, _ = oracle.cube_select(shv, Q[:Sv], kbar_v, p, rows=vrows)
-    assert np.array_equal(unpack(m1, N)[:, :nv], unpack(m2, nv)) and not unpack(m1, N)[:, nv:].any()
-    assert np.array_equal(c1, c2)
-    o1, _ = oracle.sparse_attn(sh, Q, K, V, m1, rows=vrows)
-    o2, _ = oracle.sparse_attn(shv, Q[:Sv], K[:Sv], V[:Sv], m2, rows=vrows)
-    assert np.array_equal(o1, o2)
+    if w.lead == 0:
+        # video rows do not see text that follows them: same selection and output as for the video alone
+        wv = synth.Workload(**{**w.__dict__, "text": 0})
+        shv = shape_of(oracle, wv)
+        vrows = np.arange(0, Sv * w.Hq, 37)
+        kbar_v = oracle.cube_pool(shv, K[:Sv])
+        assert np.array_equal(kbar_v, kbar[:nv])
+        m1, c1, _ = oracle.cube_select(sh, Q, kbar, p, rows=vrows)
+        m2, c2, _ = oracle.cube_select(shv, Q[:Sv], kbar_v, p, rows=vrows)
+        assert np.array_equal(unpack(m1, N)[:, :nv], unpack(m2, nv)) and not unpack(m1, N)[:, nv:].any()
+        assert np.array_equal(c1, c2)
+        o1, _ = oracle.sparse_attn(sh, Q, K, V, m1, rows=vrows)
+        o2, _ = oracle.sparse_attn(shv, Q[:Sv], K[:Sv], V[:Sv], m2, rows=vrows)
+        assert np.array_equal(o1, o2)
 
 
 def test_attention_special_inputs(oracle):
