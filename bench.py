@@ -146,7 +146,18 @@ def main():
     count = torch.empty((R,), dtype=torch.int32, device="cuda")
     O = torch.empty((w.S, w.Hq, w.D), dtype=torch.bfloat16, device="cuda")
     ws_sel = B.alloc_workspace(sh, B.CALL_CUBE_SELECT)
-    ws_att = B.alloc_workspace(sh, B.CALL_SPARSE_ATTN)
+    # Attention workspace: the packed K/V copy plus, where HBM allows, scratch for the key-stationary kernel up to
+    # the selected share below which the library prefers it (attn_walk.hip: 35 % of the candidate cubes).
+    cube, rank, sizes = cube_tables(w)
+    preceding = int(cube.astype(np.int64).sum()) * w.Hq
+    pairs_capacity = int(0.36 * preceding)
+    free_bytes, _ = torch.cuda.mem_get_info()
+    try:
+        if B.pairs_workspace_bytes(sh, pairs_capacity) > 0.4 * free_bytes:
+            pairs_capacity = None
+    except B.AdasparkError:
+        pairs_capacity = None  # geometry outside what that kernel covers
+    ws_att = B.alloc_workspace(sh, B.CALL_SPARSE_ATTN, pairs_capacity=pairs_capacity)
 
     def f_pool():
         B.cube_pool(sh, Kg, kbar)
@@ -163,7 +174,7 @@ def main():
     def f_dense():
         B.dense_attn_packed(sh, Qg, ws_att, O=O)
 
-    # the sparse entry picks one of two kernels from the share of selected cubes (on the device); for the roofline
+    # the sparse entry picks one of its kernels from the share of selected cubes (on the device); for the roofline
     # line the same kernel is launched alone, so that the HIP events bracket exactly one kernel
     def f_attn_kernel(kernel):
         B.sparse_attn_packed(sh, Qg, ws_att, mask, O=O, kernel=kernel)
@@ -199,15 +210,20 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    cube, rank, sizes = cube_tables(w)
     keys_total, pairs = attended_keys_total(w, mask, sizes, rank)
     eff_flops = 4.0 * w.D * keys_total
     dense_keys = int((np.cumsum(np.concatenate([[0], sizes[:-1]]))[cube] + rank + 1).sum()) * w.Hq
     dense_flops = 4.0 * w.D * dense_keys
-    preceding = int(cube.astype(np.int64).sum()) * w.Hq
     share = pairs / max(1, preceding)
-    masked_walk = share * 1000.0 > 15.0  # the library's own rule (attn_walk.hip)
-    attn_kernel_ms = timed(lambda: f_attn_kernel(B.SPARSE_MASKED if masked_walk else B.SPARSE_COMPACT), args.steps)
+    # the library's own rule (attn_walk.hip, attn_pairs.hip), restated to name the kernel that ran
+    if pairs_capacity is not None and share * 1000.0 < 350.0 and pairs <= pairs_capacity:
+        chosen, chosen_name = B.SPARSE_PAIRS, f"attn_pairs_kernel<{w.D}> + pairs_merge_kernel<{w.D}>"
+    elif share * 1000.0 > 15.0:
+        chosen, chosen_name = B.SPARSE_MASKED, f"attn_walk_kernel<{w.D}, true>"
+    else:
+        chosen, chosen_name = B.SPARSE_COMPACT, f"attn_compact_kernel<{w.D}>"
+    masked_walk = chosen == B.SPARSE_MASKED
+    attn_kernel_ms = timed(lambda: f_attn_kernel(chosen), args.steps)
     attn_tflops = eff_flops / (attn_kernel_ms * 1e-3) / 1e12
     executed_flops = dense_flops if masked_walk else None  # the masked walk computes every preceding cube
 
@@ -244,7 +260,7 @@ def main():
         "dense_tflops": None if dense_ms is None else dense_flops / (dense_ms * 1e-3) / 1e12,
         "speedup_vs_dense": None if dense_ms is None else (k_ms["kv_pack"] + dense_ms) / ms_per_step,
         "roofline": {
-            "kernel": f"attn_walk_kernel<{w.D}, true>" if masked_walk else f"attn_compact_kernel<{w.D}>",
+            "kernel": chosen_name,
             "kernel_ms": attn_kernel_ms,
             "bound": "mfma",
             "achieved": attn_tflops,

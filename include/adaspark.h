@@ -75,16 +75,24 @@ typedef enum {
     ADASPARK_CALL_DENSE_ATTN = 3
 } adaspark_call;
 
-/* Which kernel a sparse-attention call runs.  Both compute the same result (Eq. 3).
- *   COMPACT  per key cube, the rows that selected it are gathered into dense MFMA tiles: executed work follows
- *            the selection; the better choice when few cubes are selected.
+/* Which kernel a sparse-attention call runs.  All compute the same result (Eq. 3).
+ *   COMPACT  row blocks walk the key cubes; per cube the rows that selected it are gathered into dense MFMA
+ *            tiles.  Pays only when very few cubes are selected.
  *   MASKED   every row walks every preceding cube and its selection bits act as a mask: dense work, none of
  *            the gathering cost; the better choice when most cubes are selected.
- *   AUTO     a device-side estimate of the selected share picks one of the two (no host synchronisation). */
+ *   PAIRS    key-stationary: a workgroup keeps one key cube on chip and runs the rows that selected it; every
+ *            (row, selected cube) pair leaves a partial result of (head_dim + 2) * 4 bytes in scratch memory and
+ *            a second kernel merges them per row.  Work follows the selection; the better choice when less than
+ *            about a third of the cubes is selected.  Needs extra workspace (adaspark_pairs_workspace_bytes) and
+ *            cubes of at most 256 tokens.  If the selection turns out to hold more pairs than the scratch
+ *            memory was sized for, the call runs MASKED instead (decided on the device).
+ *   AUTO     the choice is made on the device from the selected share (no host synchronisation); PAIRS is
+ *            among the candidates iff the workspace is large enough for it. */
 typedef enum {
     ADASPARK_SPARSE_AUTO = 0,
     ADASPARK_SPARSE_COMPACT = 1,
-    ADASPARK_SPARSE_MASKED = 2
+    ADASPARK_SPARSE_MASKED = 2,
+    ADASPARK_SPARSE_PAIRS = 3
 } adaspark_sparse_kernel;
 
 /* Limits: head_dim in {64,128}; number of cubes (text cubes included) <= ADASPARK_MAX_CUBES;
@@ -95,6 +103,11 @@ typedef enum {
 int adaspark_num_cubes(const adaspark_shape *shape, int32_t *n_cubes);
 int adaspark_workspace_bytes(const adaspark_shape *shape, int which_call /* adaspark_call */, size_t *bytes);
 const char *adaspark_status_string(int status);
+/* Workspace size for the sparse attention entries that also lets the key-stationary kernel (ADASPARK_SPARSE_PAIRS)
+ * run for selections of up to max_selected selected (row, cube) pairs in total (the sum of sel_count):
+ * adaspark_workspace_bytes(ADASPARK_CALL_SPARSE_ATTN) plus tables of 12 bytes per row plus (head_dim + 2) * 4 bytes
+ * per pair and per row.  The sparse entries use whatever lies beyond the minimum size this way. */
+int adaspark_pairs_workspace_bytes(const adaspark_shape *shape, int64_t max_selected, size_t *bytes);
 
 /*
  * Cube mean keys (Eq. 1: k-bar_j = Mean(k in K_j)), per KV head.
@@ -148,7 +161,8 @@ int adaspark_cube_select_topk(const adaspark_shape *shape, const void *Q, const 
  *   sel_mask  in   as written by adaspark_cube_select
  *   O         out  bf16 [tokens][q_heads][head_dim]
  *   lse       out  fp32 [tokens*q_heads] natural-log sum-exp of the scaled logits, or NULL
- *   workspace      adaspark_workspace_bytes(ADASPARK_CALL_SPARSE_ATTN)
+ *   workspace      adaspark_workspace_bytes(ADASPARK_CALL_SPARSE_ATTN), or more: with
+ *                  adaspark_pairs_workspace_bytes(...) the key-stationary kernel becomes a candidate
  */
 int adaspark_sparse_attn(const adaspark_shape *shape, const void *Q, const void *K, const void *V,
                          const uint32_t *sel_mask, int causal, void *O, float *lse,
@@ -173,8 +187,9 @@ int adaspark_dense_attn(const adaspark_shape *shape, const void *Q, const void *
  *   adaspark_kv_pack            fills `workspace` (same size as for the attention entries)
  *   adaspark_sparse_attn_packed / adaspark_dense_attn_packed
  *                               read a workspace filled by adaspark_kv_pack for the same shape.  The K/V copy
- *                               in it is only read; the sparse entries use its last 16 bytes as scratch, so
- *                               two sparse calls on one workspace must not overlap in time.
+ *                               in it is only read; the sparse entries use the last 16 bytes of the minimum size
+ *                               and everything beyond it as scratch, so two sparse calls on one workspace must
+ *                               not overlap in time.
  *   adaspark_sparse_attn_packed_with
  *                               the same with an explicit adaspark_sparse_kernel (the plain entry uses AUTO).
  * adaspark_sparse_attn(...) == adaspark_kv_pack(...) followed by adaspark_sparse_attn_packed(...).

@@ -70,6 +70,7 @@ EXPORTS = (
     "adaspark_num_cubes",
     "adaspark_workspace_bytes",
     "adaspark_status_string",
+    "adaspark_pairs_workspace_bytes",
     "adaspark_cube_pool",
     "adaspark_cube_select",
     "adaspark_cube_select_topk",
@@ -81,7 +82,7 @@ EXPORTS = (
     "adaspark_dense_attn_packed",
 )
 
-SPARSE_AUTO, SPARSE_COMPACT, SPARSE_MASKED = 0, 1, 2
+SPARSE_AUTO, SPARSE_COMPACT, SPARSE_MASKED, SPARSE_PAIRS = 0, 1, 2, 3
 
 
 def load():
@@ -99,6 +100,7 @@ def load():
         lib.adaspark_workspace_bytes.argtypes = [sp, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
         lib.adaspark_status_string.argtypes = [ctypes.c_int]
         lib.adaspark_status_string.restype = ctypes.c_char_p
+        lib.adaspark_pairs_workspace_bytes.argtypes = [sp, ctypes.c_int64, ctypes.POINTER(ctypes.c_size_t)]
         lib.adaspark_cube_pool.argtypes = [sp, vp, vp, vp]
         lib.adaspark_cube_select.argtypes = [sp, vp, vp, ctypes.c_float, ctypes.c_int, vp, vp, vp, vp,
                                              ctypes.c_int64, vp, ctypes.c_size_t, vp]
@@ -153,8 +155,22 @@ def workspace_bytes(shape: Shape, which_call: int) -> int:
     return b.value
 
 
-def alloc_workspace(shape: Shape, which_call: int, device="cuda") -> torch.Tensor:
-    return torch.empty(max(workspace_bytes(shape, which_call), 16), dtype=torch.uint8, device=device)
+def pairs_workspace_bytes(shape: Shape, max_selected: int) -> int:
+    """Attention workspace size that lets the key-stationary kernel run for up to ``max_selected`` selected
+    (row, cube) pairs in total."""
+    b = ctypes.c_size_t(0)
+    cs = shape._c()
+    _check(load().adaspark_pairs_workspace_bytes(ctypes.byref(cs), int(max_selected), ctypes.byref(b)),
+           "adaspark_pairs_workspace_bytes")
+    return b.value
+
+
+def alloc_workspace(shape: Shape, which_call: int, device="cuda", pairs_capacity: int | None = None) -> torch.Tensor:
+    """``pairs_capacity``: size an attention workspace for that many selected (row, cube) pairs as well."""
+    n = workspace_bytes(shape, which_call)
+    if pairs_capacity is not None:
+        n = max(n, pairs_workspace_bytes(shape, pairs_capacity))
+    return torch.empty(max(n, 16), dtype=torch.uint8, device=device)
 
 
 def cube_pool(shape: Shape, K: torch.Tensor, kbar: torch.Tensor | None = None) -> torch.Tensor:
@@ -282,7 +298,8 @@ def _attn_packed(fn_name, shape, Q, packed, sel_mask, causal, O, lse, want_lse, 
 
 def sparse_attn_packed(shape: Shape, Q, packed, sel_mask, causal: bool = True, O=None, lse=None,
                        return_lse: bool = False, kernel: int | None = None):
-    """``kernel``: None/SPARSE_AUTO lets the library choose, SPARSE_COMPACT / SPARSE_MASKED force one."""
+    """``kernel``: None/SPARSE_AUTO lets the library choose, SPARSE_COMPACT / SPARSE_MASKED / SPARSE_PAIRS force
+    one (SPARSE_PAIRS needs a workspace from ``alloc_workspace(..., pairs_capacity=...)``)."""
     if kernel is None:
         return _attn_packed("adaspark_sparse_attn_packed", shape, Q, packed, sel_mask, causal, O, lse, return_lse)
     return _attn_packed("adaspark_sparse_attn_packed_with", shape, Q, packed, sel_mask, causal, O, lse, return_lse,

@@ -62,6 +62,18 @@ int adaspark_workspace_bytes(const adaspark_shape *shape, int which_call, size_t
     }
 }
 
+int adaspark_pairs_workspace_bytes(const adaspark_shape *shape, int64_t max_selected, size_t *bytes)
+{
+    const int rc = check_shape(shape);
+    if (rc != ADASPARK_OK) return rc;
+    if (bytes == nullptr || max_selected < 0) return ADASPARK_EINVAL;
+    const Geom g = make_geom(*shape);
+    if (!pairs_supported(g)) return ADASPARK_EUNSUPPORTED;
+    // the scratch part starts at the next 256-byte boundary after the minimum workspace
+    *bytes = attn_workspace_bytes(g) + 256 + pairs_scratch_bytes(g, (long long)max_selected);
+    return ADASPARK_OK;
+}
+
 const char *adaspark_status_string(int status)
 {
     switch (status) {
@@ -161,12 +173,26 @@ static int attn_packed(const adaspark_shape *shape, const void *Q, void *packed,
     int rc = attn_check(shape, Q, sel_mask, sparse, causal, O, lse);
     if (rc != ADASPARK_OK) return rc;
     if (sparse_kernel != ADASPARK_SPARSE_AUTO && sparse_kernel != ADASPARK_SPARSE_COMPACT &&
-        sparse_kernel != ADASPARK_SPARSE_MASKED)
+        sparse_kernel != ADASPARK_SPARSE_MASKED && sparse_kernel != ADASPARK_SPARSE_PAIRS)
         return ADASPARK_EINVAL;
     const Geom g = make_geom(*shape);
     if ((rc = workspace_check(g, packed, packed_bytes)) != ADASPARK_OK) return rc;
+    // whatever lies beyond the minimum workspace, from the next 256-byte boundary on, is scratch memory
+    const uintptr_t begin = reinterpret_cast<uintptr_t>(packed);
+    const uintptr_t sbegin = (begin + attn_workspace_bytes(g) + 255) & ~static_cast<uintptr_t>(255);
+    void *scratch = nullptr;
+    size_t scratch_bytes = 0;
+    if (sparse && begin + packed_bytes > sbegin) {
+        scratch = reinterpret_cast<void *>(sbegin);
+        scratch_bytes = begin + packed_bytes - sbegin;
+    }
+    if (sparse && sparse_kernel == ADASPARK_SPARSE_PAIRS) {
+        if (!pairs_supported(g)) return ADASPARK_EUNSUPPORTED;
+        if (scratch_bytes < pairs_scratch_bytes(g, 0)) return ADASPARK_EWORKSPACE;
+    }
     const hipError_t e = launch_attn(g, static_cast<const uint16_t *>(Q), packed, sparse ? sel_mask : nullptr, sparse_kernel,
-                                     static_cast<uint16_t *>(O), lse, static_cast<hipStream_t>(stream));
+                                     scratch, scratch_bytes, static_cast<uint16_t *>(O), lse,
+                                     static_cast<hipStream_t>(stream));
     return e == hipSuccess ? ADASPARK_OK : ADASPARK_EHIP;
 }
 

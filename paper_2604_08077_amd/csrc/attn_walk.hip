@@ -338,7 +338,7 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
 }
 
 // ---- choice between the compacting and the masked kernel: the share of candidate cubes the rows select, from a
-// sample of rows.  One workgroup; writes 1 (compact) or 2 (masked) to *flag.
+// sample of rows.  One workgroup; writes 1 (compact) or 2 (masked) to flag[0] and the estimated share to flag[1].
 constexpr int DENSITY_THREADS = 1024;
 constexpr int DENSITY_MAX_ROWS = 2048;  // two sampled rows per thread: an estimate is all that is needed
 // Measured on MI355X with rows that select independently of each other: the compacting kernel wins only below
@@ -362,8 +362,10 @@ __global__ __launch_bounds__(DENSITY_THREADS) void sel_density_kernel(Geom g, co
     atomicAdd(&acc[0], sel);
     atomicAdd(&acc[1], cand);
     __syncthreads();
-    if (threadIdx.x == 0)
-        *flag = (acc[0] * 1000ull > acc[1] * (unsigned long long)MASKED_ABOVE_PERMILLE) ? 2 : 1;
+    if (threadIdx.x == 0) {
+        flag[0] = (acc[0] * 1000ull > acc[1] * (unsigned long long)MASKED_ABOVE_PERMILLE) ? 2 : 1;
+        flag[1] = (int)(acc[0] * 1000ull / (acc[1] > 0ull ? acc[1] : 1ull));  // the estimate, in permille
+    }
 }
 
 template <int D, bool MASKED>
@@ -385,30 +387,43 @@ static hipError_t launch_walk(const Geom &g, const uint16_t *Q, const void *pack
     return hipGetLastError();
 }
 
+// Measured on MI355X (65,536 tokens, 28/4 heads, head_dim 128, rows selecting independently): the key-stationary
+// kernel is the faster one below this share of selected candidate cubes.
+constexpr int PAIRS_BELOW_PERMILLE = 350;
+
 template <int D>
 static hipError_t launch_attn_d(const Geom &g, const uint16_t *Q, void *packed, const uint32_t *sel_mask,
-                                int sparse_kernel, uint16_t *O, float *lse, hipStream_t st)
+                                int sparse_kernel, void *scratch, size_t scratch_bytes, uint16_t *O, float *lse,
+                                hipStream_t st)
 {
     if (sel_mask == nullptr) return launch_walk<D, false>(g, Q, packed, nullptr, nullptr, 0, O, lse, st);
     if (sparse_kernel == ADASPARK_SPARSE_COMPACT)
         return launch_attn_compact(g, Q, packed, sel_mask, nullptr, 0, O, lse, st);
     if (sparse_kernel == ADASPARK_SPARSE_MASKED)
         return launch_walk<D, true>(g, Q, packed, sel_mask, nullptr, 0, O, lse, st);
-    // automatic: estimate the density on the device, enqueue both kernels, the one not chosen returns at once
+    // automatic (or the key-stationary kernel asked for): the choice is made on the device, every candidate kernel
+    // is enqueued, and those not chosen return at once
+    // First the selected share from a sample of rows: that decides between the two row-stationary kernels, and
+    // whether the exact count for the key-stationary one is worth taking at all.
     int *flag = reinterpret_cast<int *>(reinterpret_cast<char *>(packed) + attn_workspace_bytes(g) - 16);
     hipLaunchKernelGGL(sel_density_kernel, dim3(1), dim3(DENSITY_THREADS), 0, st, g, sel_mask, flag);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    const bool counted =
+        launch_attn_pairs(g, Q, packed, sel_mask, scratch, scratch_bytes, sparse_kernel == ADASPARK_SPARSE_PAIRS,
+                          PAIRS_BELOW_PERMILLE, flag, O, lse, st, &e);
+    if (e != hipSuccess) return e;
+    if (!counted && sparse_kernel == ADASPARK_SPARSE_PAIRS) return hipErrorInvalidValue;  // the entry point checks this
     e = launch_attn_compact(g, Q, packed, sel_mask, flag, 1, O, lse, st);
     if (e != hipSuccess) return e;
     return launch_walk<D, true>(g, Q, packed, sel_mask, flag, 2, O, lse, st);
 }
 
 hipError_t launch_attn(const Geom &g, const uint16_t *Q, void *packed, const uint32_t *sel_mask, int sparse_kernel,
-                       uint16_t *O, float *lse, hipStream_t st)
+                       void *scratch, size_t scratch_bytes, uint16_t *O, float *lse, hipStream_t st)
 {
-    if (g.D == 64) return launch_attn_d<64>(g, Q, packed, sel_mask, sparse_kernel, O, lse, st);
-    return launch_attn_d<128>(g, Q, packed, sel_mask, sparse_kernel, O, lse, st);
+    if (g.D == 64) return launch_attn_d<64>(g, Q, packed, sel_mask, sparse_kernel, scratch, scratch_bytes, O, lse, st);
+    return launch_attn_d<128>(g, Q, packed, sel_mask, sparse_kernel, scratch, scratch_bytes, O, lse, st);
 }
 
 }  // namespace adaspark

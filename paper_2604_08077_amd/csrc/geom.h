@@ -114,12 +114,27 @@ size_t select_workspace_bytes(const Geom &g);
 hipError_t launch_cube_select(const Geom &g, const uint16_t *Q, const float *kbar, float top_p, int top_k,
                               uint32_t *sel_mask, int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx,
                               int64_t capacity, void *ws, hipStream_t st);
+// out[0..n] = exclusive prefix sums of count[0..n-1]; tile_sum: scan_tile_sum_bytes(n) bytes of scratch (select.hip)
+size_t scan_tile_sum_bytes(long long n);
+void launch_exclusive_scan(const int32_t *count, long long n, long long *tile_sum, int64_t *out, hipStream_t st);
 size_t attn_workspace_bytes(const Geom &g);
 hipError_t launch_kv_pack(const Geom &g, const uint16_t *K, const uint16_t *V, void *ws, hipStream_t st);
 // sel_mask == nullptr: dense (every preceding cube attended); otherwise sparse_kernel is an adaspark_sparse_kernel.
-// The automatic choice writes a flag into the last 16 bytes of the packed workspace.
+// The automatic choice writes a flag into the last 16 bytes of the packed workspace.  scratch (256-byte aligned, may
+// be null): memory for the key-stationary kernel's records.
 hipError_t launch_attn(const Geom &g, const uint16_t *Q, void *packed, const uint32_t *sel_mask, int sparse_kernel,
-                       uint16_t *O, float *lse, hipStream_t st);
+                       void *scratch, size_t scratch_bytes, uint16_t *O, float *lse, hipStream_t st);
+// The key-stationary sparse kernel (attn_pairs.hip).  pairs_scratch_bytes: scratch for max_selected selected (row,
+// cube) pairs.  On entry flag[0] holds the choice between the row-stationary kernels (1 compact, 2 masked walk) and
+// flag[1] an estimate of the selected share in permille.  launch_attn_pairs enqueues kernels that -- unless the
+// estimate is well above pairs_below_permille and force is 0 -- count the pairs exactly, set flag[0] = 3 if the
+// records fit and (force or the share is below pairs_below_permille), and then run this path (only if flag[0] ==
+// 3).  false: scratch too small even for the tables or geometry not covered, nothing enqueued.
+bool pairs_supported(const Geom &g);
+size_t pairs_scratch_bytes(const Geom &g, long long max_selected);
+bool launch_attn_pairs(const Geom &g, const uint16_t *Q, const void *packed, const uint32_t *sel_mask, void *scratch,
+                       size_t scratch_bytes, int force, int pairs_below_permille, int *flag, uint16_t *O, float *lse,
+                       hipStream_t st, hipError_t *err);
 // The compacting sparse kernel alone (attn_compact.hip).  mode_flag (device, may be null): run only if
 // *mode_flag == my_mode.
 hipError_t launch_attn_compact(const Geom &g, const uint16_t *Q, const void *packed, const uint32_t *sel_mask,

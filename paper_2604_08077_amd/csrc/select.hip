@@ -866,6 +866,17 @@ static void launch_select_d(const Geom &g, int NG, const uint16_t *Q, const uint
     }
 }
 
+size_t scan_tile_sum_bytes(long long n) { return (size_t)((n + SCAN_TILE - 1) / SCAN_TILE) * sizeof(long long); }
+
+// out[0..n] = exclusive prefix sums of count[0..n-1] (out[n] = total); tile_sum: scan_tile_sum_bytes(n) of scratch.
+void launch_exclusive_scan(const int32_t *count, long long n, long long *tile_sum, int64_t *out, hipStream_t st)
+{
+    const int tiles = (int)((n + SCAN_TILE - 1) / SCAN_TILE);
+    hipLaunchKernelGGL(scan_tile_sums_kernel, dim3(tiles), dim3(SCAN_THREADS), 0, st, count, n, tile_sum);
+    hipLaunchKernelGGL(scan_tile_offsets_kernel, dim3(1), dim3(SCAN_THREADS), 0, st, tile_sum, tiles);
+    hipLaunchKernelGGL(scan_write_kernel, dim3(tiles), dim3(SCAN_THREADS), 0, st, count, n, tile_sum, out);
+}
+
 // top_k < 0: Top-p selection with threshold top_p; top_k >= 0: fixed Top-K selection (top_p ignored).
 hipError_t launch_cube_select(const Geom &g, const uint16_t *Q, const float *kbar, float top_p, int top_k,
                               uint32_t *sel_mask, int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx,
@@ -887,10 +898,7 @@ hipError_t launch_cube_select(const Geom &g, const uint16_t *Q, const float *kba
     }
 
     if (row_ptr != nullptr) {
-        const int tiles = (int)scan_tiles(g);
-        hipLaunchKernelGGL(scan_tile_sums_kernel, dim3(tiles), dim3(SCAN_THREADS), 0, st, sel_count, R, tile_sum);
-        hipLaunchKernelGGL(scan_tile_offsets_kernel, dim3(1), dim3(SCAN_THREADS), 0, st, tile_sum, tiles);
-        hipLaunchKernelGGL(scan_write_kernel, dim3(tiles), dim3(SCAN_THREADS), 0, st, sel_count, R, tile_sum, row_ptr);
+        launch_exclusive_scan(sel_count, R, tile_sum, row_ptr, st);
         hipLaunchKernelGGL(csr_fill_kernel, dim3((unsigned)((R + 255) / 256)), dim3(256), 0, st, g, R, sel_mask, row_ptr,
                            cube_idx, (long long)capacity);
     }

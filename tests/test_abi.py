@@ -96,6 +96,17 @@ def test_bad_pointers_and_arguments_are_rejected_before_launch(lib):
     assert pw(-1, 1 << 30, ok_ptr) == -1
     assert pw(binding.SPARSE_COMPACT, 8, ok_ptr) == -3
     assert pw(binding.SPARSE_MASKED, 1 << 30, None) == -1
+    # the key-stationary kernel needs scratch memory beyond the minimum workspace
+    need = ctypes.c_size_t(0)
+    assert lib.adaspark_workspace_bytes(ctypes.byref(cs), binding.CALL_SPARSE_ATTN, ctypes.byref(need)) == 0
+    assert pw(binding.SPARSE_PAIRS, need.value, ok_ptr) == -3
+    big = ctypes.c_size_t(0)
+    assert lib.adaspark_pairs_workspace_bytes(ctypes.byref(cs), 1000, ctypes.byref(big)) == 0
+    assert big.value > need.value + 1000 * (cs.head_dim + 2) * 4
+    assert lib.adaspark_pairs_workspace_bytes(ctypes.byref(cs), -1, ctypes.byref(big)) == -1
+    assert lib.adaspark_pairs_workspace_bytes(ctypes.byref(cs), 1, None) == -1
+    huge = binding.Shape(4, 32, 32, 4, 32, 32, 4, 4, 64)._c()      # a cube of 4096 tokens does not fit on chip
+    assert lib.adaspark_pairs_workspace_bytes(ctypes.byref(huge), 1, ctypes.byref(big)) == -2
 
 
 def test_binding_refuses_cpu_tensors(lib):

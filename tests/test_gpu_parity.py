@@ -63,6 +63,9 @@ def check_outputs(name, gpu_out, ref_out):
     assert err.max() <= MAX_ABS and err.mean() <= MEAN_ABS
 
 
+PAIRS_TEST_BYTES = 48e9  # largest workspace the tests allocate for the key-stationary kernel
+
+
 def rows_of(O, rows, w):
     return O.reshape(w.S * w.Hq, w.D)[torch.as_tensor(rows, device=O.device)].float().cpu().numpy()
 
@@ -116,9 +119,9 @@ def test_full_path_small(B, oracle, w):
     torch.cuda.synchronize()
     check_outputs(f"{w.name} attn(oracle sel)", O.reshape(-1, w.D).float().cpu().numpy(), ref_out)
     assert torch.isfinite(lse).all()
-    # (1b) each of the two sparse kernels, forced: the library's own choice above is one of them
-    packed = B.kv_pack(sh, Kg, Vg)
-    for kern in (B.SPARSE_COMPACT, B.SPARSE_MASKED):
+    # (1b) each of the sparse kernels, forced: the library's own choice above is one of them
+    packed = B.kv_pack(sh, Kg, Vg, workspace=B.alloc_workspace(sh, B.CALL_SPARSE_ATTN, pairs_capacity=int(ref_count.sum())))
+    for kern in (B.SPARSE_COMPACT, B.SPARSE_MASKED, B.SPARSE_PAIRS):
         Ok, lsek = B.sparse_attn_packed(sh, Qg, packed, torch.from_numpy(ref_mask.view(np.int32)).cuda(),
                                         return_lse=True, kernel=kern)
         torch.cuda.synchronize()
@@ -206,16 +209,46 @@ def sampled_case(B, oracle, w, p_list, n_rows, check_dense=True):
         ref_out, _ = oracle.sparse_attn(osh, Q, K, V, ref_mask, rows=rows)
         got = rows_of(O, rows, w)
         check_outputs(f"{w.name} p={p} pipeline(sampled)", got[same], ref_out[same])
-        # both sparse kernels, forced (the call above let the library choose)
+        # the sparse kernels, forced (the call above let the library choose)
         for kern in (B.SPARSE_COMPACT, B.SPARSE_MASKED):
             Ok = B.sparse_attn_packed(sh, Qg, ws_att, mask, kernel=kern)
             torch.cuda.synchronize()
             check_outputs(f"{w.name} p={p} kernel {kern}(sampled)", rows_of(Ok, rows, w)[same], ref_out[same])
+        # the key-stationary kernel, where its records fit into a moderate scratch buffer; and the library's own
+        # choice when that buffer is there
+        n_sel = int(count.sum().item())
+        if B.pairs_workspace_bytes(sh, n_sel) <= PAIRS_TEST_BYTES:
+            ws_pairs = B.kv_pack(sh, Kg, Vg, workspace=B.alloc_workspace(sh, B.CALL_SPARSE_ATTN, pairs_capacity=n_sel))
+            for kern in (B.SPARSE_PAIRS, B.SPARSE_AUTO):
+                Ok = B.sparse_attn_packed(sh, Qg, ws_pairs, mask, kernel=kern)
+                torch.cuda.synchronize()
+                check_outputs(f"{w.name} p={p} kernel {kern}, large workspace (sampled)", rows_of(Ok, rows, w)[same],
+                              ref_out[same])
+            del ws_pairs
     if check_dense:
         Od = B.dense_attn(sh, Qg, Kg, Vg, workspace=ws_att)
         torch.cuda.synchronize()
         drows = rows[:: max(1, len(rows) // 96)]
         check_outputs(f"{w.name} dense(sampled)", rows_of(Od, drows, w), oracle.dense_attn(osh, Q, K, V, rows=drows))
+
+
+def test_pairs_kernel_falls_back_when_records_do_not_fit(B, oracle):
+    """A scratch buffer sized for fewer pairs than the selection holds: the call must still give the right answer
+    (it runs the masked walk instead, decided on the device)."""
+    w = synth.TEST_WORKLOADS["T_gqa128"]
+    print(f"case {w.name} pairs fallback", flush=True)
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    Q, K, V = synth.generate(w)
+    Qg, Kg, Vg = Q.cuda(), K.cuda(), V.cuda()
+    kbar_ref = oracle.cube_pool(osh, K)
+    ref_mask, ref_count, _ = oracle.cube_select(osh, Q, kbar_ref, 0.9)
+    ref_out, _ = oracle.sparse_attn(osh, Q, K, V, ref_mask)
+    maskg = torch.from_numpy(ref_mask.view(np.int32)).cuda()
+    for cap in (0, int(ref_count.sum()) // 2, int(ref_count.sum()) - 1, int(ref_count.sum())):
+        ws = B.kv_pack(sh, Kg, Vg, workspace=B.alloc_workspace(sh, B.CALL_SPARSE_ATTN, pairs_capacity=cap))
+        O = B.sparse_attn_packed(sh, Qg, ws, maskg, kernel=B.SPARSE_PAIRS)
+        torch.cuda.synchronize()
+        check_outputs(f"{w.name} pairs, scratch for {cap} pairs", O.reshape(-1, w.D).float().cpu().numpy(), ref_out)
 
 
 def test_c2_sampled(B, oracle):
