@@ -147,10 +147,10 @@ def main():
     O = torch.empty((w.S, w.Hq, w.D), dtype=torch.bfloat16, device="cuda")
     ws_sel = B.alloc_workspace(sh, B.CALL_CUBE_SELECT)
     # Attention workspace: the packed K/V copy plus, where HBM allows, scratch for the key-stationary kernel up to
-    # the selected share below which the library prefers it (attn_walk.hip: 35 % of the candidate cubes).
+    # the selected share below which the library prefers it (attn_walk.hip: 40 % of the candidate cubes).
     cube, rank, sizes = cube_tables(w)
     preceding = int(cube.astype(np.int64).sum()) * w.Hq
-    pairs_capacity = int(0.36 * preceding)
+    pairs_capacity = int(0.41 * preceding)
     free_bytes, _ = torch.cuda.mem_get_info()
     try:
         if B.pairs_workspace_bytes(sh, pairs_capacity) > 0.4 * free_bytes:
@@ -216,7 +216,7 @@ def main():
     dense_flops = 4.0 * w.D * dense_keys
     share = pairs / max(1, preceding)
     # the library's own rule (attn_walk.hip, attn_pairs.hip), restated to name the kernel that ran
-    if pairs_capacity is not None and share * 1000.0 < 350.0 and pairs <= pairs_capacity:
+    if pairs_capacity is not None and share * 1000.0 < 400.0 and pairs <= pairs_capacity:
         chosen, chosen_name = B.SPARSE_PAIRS, f"attn_pairs_kernel<{w.D}> + pairs_merge_kernel<{w.D}>"
     elif share * 1000.0 > 15.0:
         chosen, chosen_name = B.SPARSE_MASKED, f"attn_walk_kernel<{w.D}, true>"

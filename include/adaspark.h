@@ -81,9 +81,9 @@ typedef enum {
  *   MASKED   every row walks every preceding cube and its selection bits act as a mask: dense work, none of
  *            the gathering cost; the better choice when most cubes are selected.
  *   PAIRS    key-stationary: a workgroup keeps one key cube on chip and runs the rows that selected it; every
- *            (row, selected cube) pair leaves a partial result of (head_dim + 2) * 4 bytes in scratch memory and
- *            a second kernel merges them per row.  Work follows the selection; the better choice when less than
- *            about a third of the cubes is selected.  Needs extra workspace (adaspark_pairs_workspace_bytes) and
+ *            (row, selected cube) pair leaves a partial result of 2 * head_dim + 16 bytes in scratch memory (an
+ *            fp16 vector scaled by its fp32 maximum) and a second kernel merges them per row.  Work follows the selection; the better choice when less than
+ *            about 40 % of the cubes are selected.  Needs extra workspace (adaspark_pairs_workspace_bytes) and
  *            cubes of at most 256 tokens.  If the selection turns out to hold more pairs than the scratch
  *            memory was sized for, the call runs MASKED instead (decided on the device).
  *   AUTO     the choice is made on the device from the selected share (no host synchronisation); PAIRS is
@@ -105,7 +105,7 @@ int adaspark_workspace_bytes(const adaspark_shape *shape, int which_call /* adas
 const char *adaspark_status_string(int status);
 /* Workspace size for the sparse attention entries that also lets the key-stationary kernel (ADASPARK_SPARSE_PAIRS)
  * run for selections of up to max_selected selected (row, cube) pairs in total (the sum of sel_count):
- * adaspark_workspace_bytes(ADASPARK_CALL_SPARSE_ATTN) plus tables of 12 bytes per row plus (head_dim + 2) * 4 bytes
+ * adaspark_workspace_bytes(ADASPARK_CALL_SPARSE_ATTN) plus tables of 12 bytes per row plus 2 * head_dim + 24 bytes
  * per pair and per row.  The sparse entries use whatever lies beyond the minimum size this way. */
 int adaspark_pairs_workspace_bytes(const adaspark_shape *shape, int64_t max_selected, size_t *bytes);
 

@@ -7,12 +7,14 @@
 // cube.  A workgroup keeps ONE key cube's K and V^T tiles in LDS and its wavefronts run a chunk of that list
 // through the tiles, 32 rows at a time, with no workgroup barrier after the load.  What a row gets from one cube
 // is a partial result -- unnormalised O, running maximum m, sum l -- written to a record in caller-provided
-// scratch memory.  The causal part of every row's own cube is one more record, written by a second launch of the
+// scratch memory.  A record holds m, l and s = max |O| in fp32 and O / s in fp16: the merged output is a weighted
+// mean of the records' O / l, so a record's rounding error enters it with at most 2^-11 of that record's largest
+// element, an eighth of the rounding of the bf16 output itself, at half the memory traffic of fp32 records.  The causal part of every row's own cube is one more record, written by a second launch of the
 // same kernel over the rows of each cube.  A last kernel merges each row's records (they are contiguous: a row's
 // records are numbered in cube order after an exclusive scan of the per-row counts, the own cube last) into the
 // output.
 //
-// Cost: MFMA work in proportion to the selected pairs, plus (D + 2) * 4 bytes written and read per pair and 8
+// Cost: MFMA work in proportion to the selected pairs, plus 2 * D + 16 bytes written and read per pair and 8
 // bytes of work list.  The entry (attn_walk.hip: launch_attn) decides on the device, from the exact pair count,
 // whether this path or one of the row-stationary kernels runs.
 #include <algorithm>
@@ -54,8 +56,9 @@ bool pairs_supported(const Geom &g) { return g.TPC <= PAIRS_MAX_TPC && g.Hkv * g
 //   seg_cursor u32 [Hkv * N]
 //   seg_chunk  u32 [Hkv * N + 1]  exclusive scan of the lists' chunk counts (a chunk: PAIRS_CHUNK entries)
 //   entries    u32 [cap][2]   the work lists: (row id, record index), list (kv, j) at seg_start[kv * N + j]
-//   ml         f32 [cap][2]   running maximum (base-2, scaled) and sum of every record
-//   rec        f32 [cap][D]   unnormalised partial outputs
+//   ml         f32 [cap][4]   of every record: running maximum m (base-2, scaled), sum l, s = max |O|, unused
+//   rec        f16 [cap][D]   O / s, unnormalised partial outputs scaled to [-1, 1]; element (e, q4, v) of the
+//                             MFMA output layout (head-dim 16 e + 4 q4 + v) sits at ((e / 2) * 4 + q4) * 8 + (e % 2) * 4 + v
 struct PairsScratch {
     int32_t *cnt;
     int64_t *pair_ptr;
@@ -63,7 +66,7 @@ struct PairsScratch {
     uint32_t *seg_count, *seg_start, *seg_cursor, *seg_chunk;
     uint32_t *entries;
     float *ml;
-    float *rec;
+    uint16_t *rec;
     long long cap;  // records that fit; <= 0: not even the tables do
 };
 
@@ -77,7 +80,7 @@ static size_t pairs_table_bytes(const Geom &g)
 
 static size_t pairs_record_bytes(const Geom &g, size_t records)
 {
-    return up256(records * 8) + up256(records * 8) + up256(records * (size_t)g.D * 4);
+    return up256(records * 8) + up256(records * 16) + up256(records * (size_t)g.D * 2);
 }
 
 size_t pairs_scratch_bytes(const Geom &g, long long max_selected)
@@ -111,14 +114,14 @@ static PairsScratch pairs_layout(const Geom &g, void *base, size_t bytes)
     s.seg_chunk = reinterpret_cast<uint32_t *>(p);
     p += up256((segs + 1) * 4);
     const size_t left = bytes - tables;
-    size_t cap = left / (16 + (size_t)g.D * 4);
+    size_t cap = left / (24 + (size_t)g.D * 2);
     while (cap > 0 && pairs_record_bytes(g, cap) > left) --cap;  // every array starts on a 256-byte boundary
     if (cap > 0xfffffff0ull) cap = 0xfffffff0ull;                // record indices are 32-bit
     s.entries = reinterpret_cast<uint32_t *>(p);
     p += up256(cap * 8);
     s.ml = reinterpret_cast<float *>(p);
-    p += up256(cap * 8);
-    s.rec = reinterpret_cast<float *>(p);
+    p += up256(cap * 16);
+    s.rec = reinterpret_cast<uint16_t *>(p);
     s.cap = (long long)cap;
     return s;
 }
@@ -275,7 +278,7 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_pairs_kernel(
     Geom g, int own_chunks, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Kp,
     const uint16_t *__restrict__ Vt, const int32_t *__restrict__ csize, const int64_t *__restrict__ pair_ptr, const uint32_t *__restrict__ seg_count,
     const uint32_t *__restrict__ seg_start, const uint32_t *__restrict__ seg_chunk,
-    const uint32_t *__restrict__ entries, const int *__restrict__ mode_flag, float *__restrict__ rec,
+    const uint32_t *__restrict__ entries, const int *__restrict__ mode_flag, uint16_t *__restrict__ rec,
     float *__restrict__ ml)
 {
     if (*mode_flag != 3) return;
@@ -430,17 +433,33 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_pairs_kernel(
         for (int s = 0; s < NS; ++s) slot[s] = ids.slot[s];
         ids_of(refill, ids);
         q_of(ids, qf);
-        // The records: unnormalised O^T (a lane holds 4 consecutive head-dim elements per block of 16), m, l.
-        // Straight-line code, so that the stores are counted exactly and the wait for the operands loaded above
-        // does not become a wait for them: a padding row repeats the step's last row and writes the same record
-        // with the same values again, and the four lanes of a row all write its (m, l).
+        // The records: m, l, s = max |O| and O / s in fp16 (round toward zero).  A lane holds 4 consecutive head-dim
+        // elements per block of 16; two blocks make one 16-byte store.  Straight-line code, so that the stores are
+        // counted exactly and the wait for the operands loaded above does not become a wait for them: a padding
+        // row repeats the step's last row and writes the same record with the same values again, and the four
+        // lanes of a row all write its scalars.
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            float *orec = rec + (size_t)slot[s] * D + 4 * q4;
+            float amax = 0.f;
 #pragma unroll
-            for (int e = 0; e < DT; ++e)  // written once, read once by the merge kernel: streaming stores
-                __builtin_nontemporal_store(oacc[s][e], reinterpret_cast<f32x4 *>(orec + 16 * e));
-            *reinterpret_cast<float2 *>(ml + (size_t)slot[s] * 2) = make_float2(m_run[s], l_run[s][0]);
+            for (int e = 0; e < DT; ++e)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) amax = vmax(amax, fabsf(oacc[s][e][v]));
+            amax = vmax(quad_max(amax), 1e-30f);
+            const float inv = 1.0f / amax;
+            uint16_t *orec = rec + (size_t)slot[s] * D + 8 * q4;
+#pragma unroll
+            for (int e = 0; e < DT; e += 2) {
+                typedef __fp16 h2 __attribute__((ext_vector_type(2)));
+                union { h2 h[4]; u32x4 u; } pk;
+                pk.h[0] = __builtin_amdgcn_cvt_pkrtz(oacc[s][e][0] * inv, oacc[s][e][1] * inv);
+                pk.h[1] = __builtin_amdgcn_cvt_pkrtz(oacc[s][e][2] * inv, oacc[s][e][3] * inv);
+                pk.h[2] = __builtin_amdgcn_cvt_pkrtz(oacc[s][e + 1][0] * inv, oacc[s][e + 1][1] * inv);
+                pk.h[3] = __builtin_amdgcn_cvt_pkrtz(oacc[s][e + 1][2] * inv, oacc[s][e + 1][3] * inv);
+                // written once, read once by the merge kernel: streaming stores
+                __builtin_nontemporal_store(pk.u, reinterpret_cast<u32x4 *>(orec + 16 * e));
+            }
+            *reinterpret_cast<f32x4 *>(ml + (size_t)slot[s] * 4) = f32x4{m_run[s], l_run[s][0], amax, 0.f};
         }
     };
 
@@ -465,49 +484,60 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_pairs_kernel(
     }
 }
 
-// One wavefront per row: O = sum_k 2^(m_k - M) O_k / sum_k 2^(m_k - M) l_k over the row's records.
+// D / 4 lanes per row: O = sum_k 2^(m_k - M) s_k h_k / sum_k 2^(m_k - M) l_k over the row's records (h = O / s in
+// fp16), in one pass with a running maximum.  A lane owns four adjacent head-dim elements: the four fp16 values at
+// byte 8 * lane of a record.
 template <int D>
 __global__ __launch_bounds__(256) void pairs_merge_kernel(long long R, const int64_t *__restrict__ pair_ptr,
-                                                          const float *__restrict__ rec, const float *__restrict__ ml,
+                                                          const uint16_t *__restrict__ rec, const float *__restrict__ ml,
                                                           const int *__restrict__ mode_flag, uint16_t *__restrict__ O,
                                                           float *__restrict__ lse)
 {
     if (*mode_flag != 3) return;
-    constexpr int E = D / 64;  // head-dim elements per lane
-    const int lane = threadIdx.x & 63;
-    const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    constexpr int LPR = D / 4;  // lanes per row
+    typedef __fp16 h4 __attribute__((ext_vector_type(4)));
+    const int l = threadIdx.x % LPR;
+    const long long row = (long long)blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
     if (row >= R) return;
     const long long p0 = pair_ptr[row];
     const int n = (int)(pair_ptr[row + 1] - p0);
-    float M = -INFINITY;
-    for (int k = lane; k < n; k += 64) M = fmaxf(M, ml[(size_t)(p0 + k) * 2]);
-    for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
-    float L = 0.f, acc[E];
+    const float *mlr = ml + (size_t)p0 * 4;
+    const uint16_t *recr = rec + (size_t)p0 * D + 4 * l;
+    float M = -INFINITY, L = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    constexpr int U = 8;  // records in flight per lane
+    for (int k0 = 0; k0 < n; k0 += U) {
+        f32x4 x[U];
+        h4 h[U];
 #pragma unroll
-    for (int e = 0; e < E; ++e) acc[e] = 0.f;
-#pragma unroll 4
-    for (int k = 0; k < n; ++k) {
-        const float2 x = *reinterpret_cast<const float2 *>(ml + (size_t)(p0 + k) * 2);
-        const float w = __builtin_amdgcn_exp2f(x.x - M);
-        L = fmaf(w, x.y, L);
-        const float *o = rec + (size_t)(p0 + k) * D + E * lane;
-        if (E == 2) {
-            const float2 v = *reinterpret_cast<const float2 *>(o);
-            acc[0] = fmaf(w, v.x, acc[0]);
-            acc[E - 1] = fmaf(w, v.y, acc[E - 1]);
-        } else {
-            acc[0] = fmaf(w, o[0], acc[0]);
+        for (int u = 0; u < U; ++u) {
+            const int k = min(k0 + u, n - 1);  // past the end: the last record again, with weight 0 below
+            x[u] = *reinterpret_cast<const f32x4 *>(mlr + (size_t)k * 4);  // m, l, s
+            h[u] = *reinterpret_cast<const h4 *>(recr + (size_t)k * D);
+        }
+        float mx = M;
+#pragma unroll
+        for (int u = 0; u < U; ++u) mx = fmaxf(mx, x[u][0]);
+        const float scale = __builtin_amdgcn_exp2f(M - mx);  // 0 on the first trip (M = -inf)
+        M = mx;
+        L *= scale;
+        acc *= scale;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float w = (k0 + u < n) ? __builtin_amdgcn_exp2f(x[u][0] - M) : 0.f;
+            L = fmaf(w, x[u][1], L);
+            const float ws = w * x[u][2];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[v] = fmaf(ws, (float)h[u][v], acc[v]);
         }
     }
     const float inv = 1.0f / L;
-    uint16_t *orow = O + (size_t)row * D + E * lane;
-    if (E == 2) {
-        *reinterpret_cast<uint32_t *>(orow) = (uint32_t)float_to_bf16_bits(acc[0] * inv) |
-                                              ((uint32_t)float_to_bf16_bits(acc[E - 1] * inv) << 16);
-    } else {
-        orow[0] = float_to_bf16_bits(acc[0] * inv);
-    }
-    if (lse != nullptr && lane == 0) lse[row] = (M + log2f(L)) * 0.69314718055994530942f;
+    // position 4 l of a record is element (e, q4, v = 0) with e = 2 * (l / 8) + l % 2, q4 = (l % 8) / 2
+    const int d = 16 * (2 * (l / 8) + l % 2) + 4 * ((l % 8) / 2);
+    const uint32_t w0 = (uint32_t)float_to_bf16_bits(acc[0] * inv) | ((uint32_t)float_to_bf16_bits(acc[1] * inv) << 16);
+    const uint32_t w1 = (uint32_t)float_to_bf16_bits(acc[2] * inv) | ((uint32_t)float_to_bf16_bits(acc[3] * inv) << 16);
+    *reinterpret_cast<uint2 *>(O + (size_t)row * D + d) = make_uint2(w0, w1);
+    if (lse != nullptr && l == 0) lse[row] = (M + log2f(L)) * 0.69314718055994530942f;
 }
 
 // Number of candidate (row, cube) pairs: every row of cube i has i preceding cubes.
@@ -544,8 +574,9 @@ static hipError_t launch_pairs_d(const Geom &g, const uint16_t *Q, const void *p
                        csize, sc.pair_ptr, sc.seg_count, sc.seg_start, sc.seg_chunk, sc.entries, flag, sc.rec, sc.ml);
     hipLaunchKernelGGL((attn_pairs_kernel<D, true>), dim3((unsigned)(segs * own_chunks)), dim3(C::THREADS), C::BYTES, st, g,
                        own_chunks, Q, Kp, Vt, csize, sc.pair_ptr, sc.seg_count, sc.seg_start, sc.seg_chunk, sc.entries, flag, sc.rec, sc.ml);
-    hipLaunchKernelGGL((pairs_merge_kernel<D>), dim3((unsigned)((R + 3) / 4)), dim3(256), 0, st, R, sc.pair_ptr, sc.rec,
-                       sc.ml, flag, O, lse);
+    const int rows_per_block = 256 / (D / 4);
+    hipLaunchKernelGGL((pairs_merge_kernel<D>), dim3((unsigned)((R + rows_per_block - 1) / rows_per_block)), dim3(256), 0,
+                       st, R, sc.pair_ptr, sc.rec, sc.ml, flag, O, lse);
     return hipGetLastError();
 }
 

@@ -388,8 +388,8 @@ static hipError_t launch_walk(const Geom &g, const uint16_t *Q, const void *pack
 }
 
 // Measured on MI355X (65,536 tokens, 28/4 heads, head_dim 128, rows selecting independently): the key-stationary
-// kernel is the faster one below this share of selected candidate cubes.
-constexpr int PAIRS_BELOW_PERMILLE = 350;
+// kernel is the faster one below this share of selected candidate cubes (break-even at 44 %).
+constexpr int PAIRS_BELOW_PERMILLE = 400;
 
 template <int D>
 static hipError_t launch_attn_d(const Geom &g, const uint16_t *Q, void *packed, const uint32_t *sel_mask,
