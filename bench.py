@@ -215,13 +215,23 @@ def main():
     dense_keys = int((np.cumsum(np.concatenate([[0], sizes[:-1]]))[cube] + rank + 1).sum()) * w.Hq
     dense_flops = 4.0 * w.D * dense_keys
     share = pairs / max(1, preceding)
-    # the library's own rule (attn_walk.hip, attn_pairs.hip), restated to name the kernel that ran
-    if pairs_capacity is not None and share * 1000.0 < 400.0 and pairs <= pairs_capacity:
-        chosen, chosen_name = B.SPARSE_PAIRS, f"attn_pairs_kernel<{w.D}> + pairs_merge_kernel<{w.D}>"
-    elif share * 1000.0 > 15.0:
-        chosen, chosen_name = B.SPARSE_MASKED, f"attn_walk_kernel<{w.D}, true>"
-    else:
-        chosen, chosen_name = B.SPARSE_COMPACT, f"attn_compact_kernel<{w.D}>"
+    # the library's own rule (attn_walk.hip, attn_pairs.hip), restated to name the kernel(s) that ran: per KV head
+    # the key-stationary kernel below 40 % selected cubes (if its records fit), else one of the row-stationary ones
+    G = w.Hq // w.Hkv
+    sel_per_kv = count.view(w.S, w.Hkv, G).sum(dim=(0, 2), dtype=torch.int64).cpu().numpy()
+    pairs_heads = [kv for kv in range(w.Hkv) if pairs_capacity is not None
+                   and int(sel_per_kv[kv]) * 1000 < (preceding // w.Hkv) * 400]
+    if pairs_heads and int(sum(sel_per_kv[kv] for kv in pairs_heads)) > pairs_capacity:
+        pairs_heads = []
+    row_kernel, row_name = ((B.SPARSE_MASKED, f"attn_walk_kernel<{w.D}, true>") if share * 1000.0 > 15.0
+                            else (B.SPARSE_COMPACT, f"attn_compact_kernel<{w.D}>"))
+    pairs_name = f"attn_pairs_kernel<{w.D}> + pairs_merge_kernel<{w.D}>"
+    if len(pairs_heads) == w.Hkv:
+        chosen, chosen_name = B.SPARSE_PAIRS, pairs_name
+    elif not pairs_heads:
+        chosen, chosen_name = row_kernel, row_name
+    else:  # heads differ: the entry's own mix, timed as a whole
+        chosen, chosen_name = B.SPARSE_AUTO, f"{pairs_name} (KV heads {pairs_heads}), {row_name} (the others)"
     masked_walk = chosen == B.SPARSE_MASKED
     attn_kernel_ms = timed(lambda: f_attn_kernel(chosen), args.steps)
     attn_tflops = eff_flops / (attn_kernel_ms * 1e-3) / 1e12

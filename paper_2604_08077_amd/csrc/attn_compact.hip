@@ -49,15 +49,16 @@ struct Compact {
     static_assert(BYTES <= 160 * 1024, "LDS of one CU");
 };
 
-// mode_flag (may be null): the kernel runs only if *mode_flag == my_mode, so that this kernel and the masked walk
-// can both be enqueued and a device-side density estimate picks one.
+// flags (may be null): the kernel-choice flags (geom.h).  A workgroup runs only if flags[FLAG_MODE] == my_mode and
+// (kv_modes) its KV head has not been handed to the key-stationary kernel, so that all sparse kernels can be
+// enqueued and the choice is made on the device.
 template <int D>
 __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_compact_kernel(
     Geom g, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Kp, const uint16_t *__restrict__ Vt,
     const int32_t *__restrict__ csize, const uint32_t *__restrict__ sel_mask, const int *__restrict__ mode_flag,
-    int my_mode, uint16_t *__restrict__ O, float *__restrict__ lse)
+    int my_mode, int kv_modes, uint16_t *__restrict__ O, float *__restrict__ lse)
 {
-    if (mode_flag != nullptr && *mode_flag != my_mode) return;
+    if (mode_flag != nullptr && mode_flag[FLAG_MODE] != my_mode) return;
     using C = Compact<D>;
     constexpr int NS = C::NS, MMAX = C::MMAX, OST = C::OST, THREADS = C::THREADS;
     constexpr int WAVES = C::WAVES, GROUPS = C::GROUPS;
@@ -87,7 +88,10 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_compact_kernel(
     const int grp = (seq / nblk_max) * 8 + xcd;
     const int blk = seq % nblk_max;
     if (grp >= g.N * g.Hkv) return;
-    const int kv = grp % g.Hkv;
+    // (the head is rotated with the cube, so that a KV head is not tied to one XCD: when some heads are handed to
+    // the key-stationary kernel, the others still spread over all of them)
+    const int kv = (grp % g.Hkv + grp / g.Hkv) % g.Hkv;
+    if (kv_modes && mode_flag[FLAG_KV + kv] == 3) return;
     const int i = g.N - 1 - grp / g.Hkv;
     const CubeBox qbox = cube_box(g, i);
     const int qsize = qbox.size();
@@ -424,7 +428,7 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_compact_kernel(
 
 template <int D>
 static hipError_t launch_compact_d(const Geom &g, const uint16_t *Q, const void *packed, const uint32_t *sel_mask,
-                                   const int *mode_flag, int my_mode, uint16_t *O, float *lse, hipStream_t st)
+                                   const int *mode_flag, int my_mode, int kv_modes, uint16_t *O, float *lse, hipStream_t st)
 {
     using C = Compact<D>;
     const uint16_t *Kp = reinterpret_cast<const uint16_t *>(packed);
@@ -437,15 +441,15 @@ static hipError_t launch_compact_d(const Geom &g, const uint16_t *Q, const void 
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::BYTES);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((attn_compact_kernel<D>), grid, dim3(C::THREADS), C::BYTES, st, g, Q, Kp, Vt, csize, sel_mask,
-                       mode_flag, my_mode, O, lse);
+                       mode_flag, my_mode, kv_modes, O, lse);
     return hipGetLastError();
 }
 
 hipError_t launch_attn_compact(const Geom &g, const uint16_t *Q, const void *packed, const uint32_t *sel_mask,
-                               const int *mode_flag, int my_mode, uint16_t *O, float *lse, hipStream_t st)
+                               const int *mode_flag, int my_mode, int kv_modes, uint16_t *O, float *lse, hipStream_t st)
 {
-    if (g.D == 64) return launch_compact_d<64>(g, Q, packed, sel_mask, mode_flag, my_mode, O, lse, st);
-    return launch_compact_d<128>(g, Q, packed, sel_mask, mode_flag, my_mode, O, lse, st);
+    if (g.D == 64) return launch_compact_d<64>(g, Q, packed, sel_mask, mode_flag, my_mode, kv_modes, O, lse, st);
+    return launch_compact_d<128>(g, Q, packed, sel_mask, mode_flag, my_mode, kv_modes, O, lse, st);
 }
 
 }  // namespace adaspark

@@ -15,8 +15,9 @@
 // output.
 //
 // Cost: MFMA work in proportion to the selected pairs, plus 2 * D + 16 bytes written and read per pair and 8
-// bytes of work list.  The entry (attn_walk.hip: launch_attn) decides on the device, from the exact pair count,
-// whether this path or one of the row-stationary kernels runs.
+// bytes of work list.  The entry (attn_walk.hip: launch_attn) decides on the device, from the exact pair count and
+// per KV head (heads can differ widely in how much they select), whether this path or a row-stationary kernel
+// takes the head's rows.
 #include <algorithm>
 
 #include "attn_tile.h"
@@ -45,10 +46,16 @@ struct Pairs {
     static_assert(PAIRS_CHUNK % (2 * WAVES * ROWS) == 0, "an even number of steps per wavefront");
 };
 
-bool pairs_supported(const Geom &g) { return g.TPC <= PAIRS_MAX_TPC && g.Hkv * g.N <= PAIRS_MAX_SEGMENTS; }
+bool pairs_supported(const Geom &g)
+{
+    return g.TPC <= PAIRS_MAX_TPC && g.Hkv * g.N <= PAIRS_MAX_SEGMENTS && g.Hkv <= PAIRS_MAX_KV_HEADS;
+}
 
 // Scratch memory of the pair path, carved from `bytes` bytes at `base` (256-byte aligned):
-//   cnt        i32 [R]        records per row = selected cubes + 1 (the own cube)
+//   flags      i32 [4 + Hkv]  the kernel-choice flags (geom.h)
+//   kv_sel     u64 [Hkv]      selected (row, cube) pairs per KV head
+//   cnt        i32 [R]        records per row = selected cubes + 1 (the own cube); 0 for rows of heads left to a
+//                             row-stationary kernel
 //   pair_ptr   i64 [R + 1]    exclusive scan of cnt: a row's records, in cube order, the own cube last
 //   tile_sum                  scratch of that scan
 //   seg_count  u32 [Hkv * N]  rows that selected cube j, per KV head
@@ -60,6 +67,8 @@ bool pairs_supported(const Geom &g) { return g.TPC <= PAIRS_MAX_TPC && g.Hkv * g
 //   rec        f16 [cap][D]   O / s, unnormalised partial outputs scaled to [-1, 1]; element (e, q4, v) of the
 //                             MFMA output layout (head-dim 16 e + 4 q4 + v) sits at ((e / 2) * 4 + q4) * 8 + (e % 2) * 4 + v
 struct PairsScratch {
+    int *flags;
+    unsigned long long *kv_sel;
     int32_t *cnt;
     int64_t *pair_ptr;
     long long *tile_sum;
@@ -75,7 +84,8 @@ static size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 static size_t pairs_table_bytes(const Geom &g)
 {
     const size_t R = (size_t)g.S * g.Hq, segs = (size_t)g.Hkv * g.N;
-    return up256(R * 4) + up256((R + 1) * 8) + up256(scan_tile_sum_bytes((long long)R)) + 4 * up256((segs + 1) * 4);
+    return FLAG_BLOCK_BYTES + 512 + up256(R * 4) + up256((R + 1) * 8) + up256(scan_tile_sum_bytes((long long)R)) +
+           4 * up256((segs + 1) * 4);
 }
 
 static size_t pairs_record_bytes(const Geom &g, size_t records)
@@ -98,7 +108,13 @@ static PairsScratch pairs_layout(const Geom &g, void *base, size_t bytes)
         s.cap = 0;
         return s;
     }
+    static_assert((FLAG_KV + PAIRS_MAX_KV_HEADS) * 4 <= FLAG_BLOCK_BYTES && PAIRS_MAX_KV_HEADS * 8 <= 512,
+                  "flag block, head totals");
     char *p = reinterpret_cast<char *>(base);
+    s.flags = reinterpret_cast<int *>(p);
+    p += FLAG_BLOCK_BYTES;
+    s.kv_sel = reinterpret_cast<unsigned long long *>(p);  // right behind the flag block (geom.h)
+    p += 512;
     s.cnt = reinterpret_cast<int32_t *>(p);
     p += up256(R * 4);
     s.pair_ptr = reinterpret_cast<int64_t *>(p);
@@ -139,25 +155,66 @@ __device__ __forceinline__ uint32_t valid_bits(uint32_t word, int w, int i)
 // this path will not be chosen anyway: well above the threshold, and not forced.
 __device__ __forceinline__ bool pairs_gate_closed(const int *flag, int force, int pairs_below_permille)
 {
-    return !force && flag[1] > pairs_below_permille + pairs_below_permille / 4;
+    return !force && flag[FLAG_ESTIMATE] > pairs_below_permille + pairs_below_permille / 4;
 }
 
-__global__ void pair_count_kernel(Geom g, long long R, const uint32_t *__restrict__ sel_mask, int32_t *__restrict__ cnt,
-                                  uint32_t *__restrict__ seg_count, uint32_t *__restrict__ seg_cursor, int segs,
-                                  const int *__restrict__ flag, int force, int pairs_below_permille)
+__global__ __launch_bounds__(256) void pair_count_kernel(Geom g, long long R, const uint32_t *__restrict__ sel_mask,
+                                                         int32_t *__restrict__ cnt, uint32_t *__restrict__ seg_count,
+                                                         uint32_t *__restrict__ seg_cursor, int segs,
+                                                         unsigned long long *__restrict__ kv_sel,
+                                                         const int *__restrict__ flag, int force, int pairs_below_permille)
 {
     if (pairs_gate_closed(flag, force, pairs_below_permille)) return;
+    __shared__ unsigned int part[PAIRS_MAX_KV_HEADS];
+    if (threadIdx.x < PAIRS_MAX_KV_HEADS) part[threadIdx.x] = 0u;
+    __syncthreads();
     const long long r = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (r < segs) {  // cleared here for the passes that follow
         seg_count[r] = 0u;
         seg_cursor[r] = 0u;
     }
-    if (r >= R) return;
-    const uint32_t *mr = sel_mask + (size_t)r * g.words;
-    const int i = cube_of_token(g, (int)(r / g.Hq));
-    int c = 1;  // the own cube
-    for (int w = 0; 32 * w < i; ++w) c += __popc(valid_bits(mr[w], w, i));
-    cnt[r] = c;
+    if (r < R) {
+        const uint32_t *mr = sel_mask + (size_t)r * g.words;
+        const int i = cube_of_token(g, (int)(r / g.Hq));
+        int c = 0;
+        for (int w = 0; 32 * w < i; ++w) c += __popc(valid_bits(mr[w], w, i));
+        cnt[r] = c + 1;  // and the own cube
+        atomicAdd(&part[(int)(r % g.Hq) / g.G], (unsigned int)c);
+    }
+    __syncthreads();
+    if (threadIdx.x < g.Hkv && part[threadIdx.x]) atomicAdd(&kv_sel[threadIdx.x], (unsigned long long)part[threadIdx.x]);
+}
+
+// Per KV head: the key-stationary kernel takes the head's rows (flags[FLAG_KV + kv] = 3) if its share of selected
+// candidate cubes is below the threshold (or force); if the records of the heads so chosen do not fit, none is
+// taken.  Then cnt is cleared for the rows of the other heads (run as a second kernel: pair_keep_kernel).
+__global__ __launch_bounds__(PAIRS_MAX_KV_HEADS) void pairs_mode_kernel(Geom g, long long cap,
+                                                                        unsigned long long candidates_per_head,
+                                                                        const unsigned long long *__restrict__ kv_sel,
+                                                                        int force, int pairs_below_permille,
+                                                                        int *__restrict__ flags)
+{
+    if (pairs_gate_closed(flags, force, pairs_below_permille)) return;
+    __shared__ unsigned long long need[PAIRS_MAX_KV_HEADS];
+    const int kv = threadIdx.x;
+    bool take = false;
+    if (kv < g.Hkv) {
+        take = force || kv_sel[kv] * 1000ull < candidates_per_head * (unsigned long long)pairs_below_permille;
+        need[kv] = take ? kv_sel[kv] + (unsigned long long)g.S * g.G : 0ull;
+    }
+    __syncthreads();
+    unsigned long long total = 0;
+    for (int k = 0; k < g.Hkv; ++k) total += need[k];
+    const bool fits = total <= (unsigned long long)cap;
+    if (kv < g.Hkv) flags[FLAG_KV + kv] = (take && fits) ? 3 : 0;
+    if (kv == 0) flags[FLAG_ACTIVE] = (fits && total > 0ull) ? 1 : 0;
+}
+
+__global__ void pair_keep_kernel(Geom g, long long R, const int *__restrict__ flags, int32_t *__restrict__ cnt)
+{
+    if (!flags[FLAG_ACTIVE]) return;
+    const long long r = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r < R && flags[FLAG_KV + (int)(r % g.Hq) / g.G] != 3) cnt[r] = 0;
 }
 
 // Transposition of the selection, two passes over the set bits of PAIRS_HIST_ROWS rows per workgroup.
@@ -167,10 +224,9 @@ __global__ void pair_count_kernel(Geom g, long long R, const uint32_t *__restric
 template <bool FILL>
 __global__ __launch_bounds__(PAIRS_HIST_ROWS) void pair_transpose_kernel(
     Geom g, long long R, const uint32_t *__restrict__ sel_mask, const int64_t *__restrict__ pair_ptr,
-    const int *__restrict__ mode_flag, int force, int pairs_below_permille, uint32_t *__restrict__ seg_count,
-    const uint32_t *__restrict__ seg_start, uint32_t *__restrict__ seg_cursor, uint32_t *__restrict__ entries)
+    const int *__restrict__ mode_flag, uint32_t *__restrict__ seg_count, const uint32_t *__restrict__ seg_start, uint32_t *__restrict__ seg_cursor, uint32_t *__restrict__ entries)
 {
-    if (FILL ? *mode_flag != 3 : pairs_gate_closed(mode_flag, force, pairs_below_permille)) return;
+    if (!mode_flag[FLAG_ACTIVE]) return;
     extern __shared__ uint32_t hist[];  // [segs] counts, then (FILL) [segs] positions handed out
     const int segs = g.Hkv * g.N;
     uint32_t *taken = hist + segs;
@@ -179,9 +235,12 @@ __global__ __launch_bounds__(PAIRS_HIST_ROWS) void pair_transpose_kernel(
     const long long r = (long long)blockIdx.x * PAIRS_HIST_ROWS + threadIdx.x;
     int i = 0, kvN = 0;
     const uint32_t *mr = nullptr;
+    bool mine = false;  // rows of heads left to a row-stationary kernel take no part
     if (r < R) {
-        i = cube_of_token(g, (int)(r / g.Hq));
-        kvN = (int)((r % g.Hq) / g.G) * g.N;
+        const int kv = (int)((r % g.Hq) / g.G);
+        mine = mode_flag[FLAG_KV + kv] == 3;
+        i = mine ? cube_of_token(g, (int)(r / g.Hq)) : 0;
+        kvN = kv * g.N;
         mr = sel_mask + (size_t)r * g.words;
         for (int w = 0; 32 * w < i; ++w) {
             uint32_t bits = valid_bits(mr[w], w, i);
@@ -202,7 +261,7 @@ __global__ __launch_bounds__(PAIRS_HIST_ROWS) void pair_transpose_kernel(
     for (int x = threadIdx.x; x < segs; x += PAIRS_HIST_ROWS)
         if (hist[x]) hist[x] = seg_start[x] + atomicAdd(&seg_cursor[x], hist[x]);
     __syncthreads();
-    if (r < R) {
+    if (r < R && mine) {
         uint32_t slot = (uint32_t)pair_ptr[r];  // records of a row are numbered in cube order
         for (int w = 0; 32 * w < i; ++w) {
             uint32_t bits = valid_bits(mr[w], w, i);
@@ -218,18 +277,14 @@ __global__ __launch_bounds__(PAIRS_HIST_ROWS) void pair_transpose_kernel(
     }
 }
 
-// One workgroup: seg_start = exclusive scan of seg_count, seg_chunk = exclusive scan of the lists' chunk counts, and
-// the choice of the sparse kernel: flag[0] = 3 (this path) if its records fit and (unless forced) few enough
-// candidate cubes are selected; otherwise flag[0] keeps the choice between the row-stationary kernels.
+// One workgroup: seg_start = exclusive scan of seg_count, seg_chunk = exclusive scan of the lists' chunk counts.
 constexpr int PLAN_THREADS = 1024;
-__global__ __launch_bounds__(PLAN_THREADS) void pairs_plan_kernel(const int64_t *__restrict__ pair_ptr, long long R,
-                                                                  long long cap, unsigned long long candidates,
-                                                                  int force, int pairs_below_permille, int segs,
-                                                                  const uint32_t *__restrict__ seg_count,
+__global__ __launch_bounds__(PLAN_THREADS) void pairs_plan_kernel(int segs, const uint32_t *__restrict__ seg_count,
                                                                   uint32_t *__restrict__ seg_start,
-                                                                  uint32_t *__restrict__ seg_chunk, int *__restrict__ flag)
+                                                                  uint32_t *__restrict__ seg_chunk,
+                                                                  const int *__restrict__ flags)
 {
-    if (pairs_gate_closed(flag, force, pairs_below_permille)) return;
+    if (!flags[FLAG_ACTIVE]) return;
     __shared__ uint32_t part[PLAN_THREADS], cpart[PLAN_THREADS];
     const int t = threadIdx.x;
     const int per = (segs + PLAN_THREADS - 1) / PLAN_THREADS;
@@ -261,12 +316,6 @@ __global__ __launch_bounds__(PLAN_THREADS) void pairs_plan_kernel(const int64_t 
         seg_start[segs] = part[t];
         seg_chunk[segs] = cpart[t];
     }
-    if (t == 0) {
-        const long long total = pair_ptr[R];
-        const unsigned long long sel = (unsigned long long)(total - R);
-        if (total <= cap && (force || sel * 1000ull < candidates * (unsigned long long)pairs_below_permille))
-            flag[0] = 3;
-    }
 }
 
 // OWN = false: workgroup b runs chunk b of all lists' chunks: entries [c * PAIRS_CHUNK, ...) of the work list (kv, j)
@@ -281,7 +330,7 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_pairs_kernel(
     const uint32_t *__restrict__ entries, const int *__restrict__ mode_flag, uint16_t *__restrict__ rec,
     float *__restrict__ ml)
 {
-    if (*mode_flag != 3) return;
+    if (!mode_flag[FLAG_ACTIVE]) return;
     using C = Pairs<D>;
     constexpr int NS = C::NS, WAVES = C::WAVES, PF = C::PF;
     constexpr int KSTEPS = D / 32, DT = D / 16;
@@ -308,6 +357,7 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_pairs_kernel(
         c = (int)(b - seg_chunk[seg]);
     }
     const int j = seg % g.N, kv = seg / g.N;
+    if (OWN && mode_flag[FLAG_KV + kv] != 3) return;  // (the lists of such a head are empty)
     const int jsize = __builtin_amdgcn_readfirstlane(g.ragged ? csize[j] : g.Cmax);
     const CubeBox jbox = cube_box(g, j);  // (OWN) the rows
     // this workgroup's rows: positions [first, first + nrows) of the work list, or all rows of cube j
@@ -490,15 +540,15 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_pairs_kernel(
 template <int D>
 __global__ __launch_bounds__(256) void pairs_merge_kernel(long long R, const int64_t *__restrict__ pair_ptr,
                                                           const uint16_t *__restrict__ rec, const float *__restrict__ ml,
-                                                          const int *__restrict__ mode_flag, uint16_t *__restrict__ O,
-                                                          float *__restrict__ lse)
+                                                          const int *__restrict__ mode_flag, int Hq, int G,
+                                                          uint16_t *__restrict__ O, float *__restrict__ lse)
 {
-    if (*mode_flag != 3) return;
+    if (!mode_flag[FLAG_ACTIVE]) return;
     constexpr int LPR = D / 4;  // lanes per row
     typedef __fp16 h4 __attribute__((ext_vector_type(4)));
     const int l = threadIdx.x % LPR;
     const long long row = (long long)blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
-    if (row >= R) return;
+    if (row >= R || mode_flag[FLAG_KV + (int)(row % Hq) / G] != 3) return;  // another kernel writes that row
     const long long p0 = pair_ptr[row];
     const int n = (int)(pair_ptr[row + 1] - p0);
     const float *mlr = ml + (size_t)p0 * 4;
@@ -576,41 +626,47 @@ static hipError_t launch_pairs_d(const Geom &g, const uint16_t *Q, const void *p
                        own_chunks, Q, Kp, Vt, csize, sc.pair_ptr, sc.seg_count, sc.seg_start, sc.seg_chunk, sc.entries, flag, sc.rec, sc.ml);
     const int rows_per_block = 256 / (D / 4);
     hipLaunchKernelGGL((pairs_merge_kernel<D>), dim3((unsigned)((R + rows_per_block - 1) / rows_per_block)), dim3(256), 0,
-                       st, R, sc.pair_ptr, sc.rec, sc.ml, flag, O, lse);
+                       st, R, sc.pair_ptr, sc.rec, sc.ml, flag, g.Hq, g.G, O, lse);
     return hipGetLastError();
 }
 
-// Counts and numbers the records, may set flag[0] = 3, and enqueues this path's kernels (the heavy ones return at
-// once unless flag[0] == 3).  false: the scratch memory does not even hold the tables, or the geometry is not
-// covered: nothing was enqueued.
-bool launch_attn_pairs(const Geom &g, const uint16_t *Q, const void *packed, const uint32_t *sel_mask, void *scratch,
-                       size_t scratch_bytes, int force, int pairs_below_permille, int *flag, uint16_t *O, float *lse,
-                       hipStream_t st, hipError_t *err)
+int *pairs_flags(const Geom &g, void *scratch, size_t scratch_bytes)
 {
-    *err = hipSuccess;
-    if (!pairs_supported(g)) return false;
+    if (!pairs_supported(g)) return nullptr;
     const PairsScratch sc = pairs_layout(g, scratch, scratch_bytes);
-    if (sc.cap <= 0) return false;
+    return sc.cap > 0 ? sc.flags : nullptr;
+}
+
+// Counts the pairs per KV head, hands heads to this path (flags), numbers their records, and enqueues this path's
+// kernels (they return at once for heads, or altogether, when nothing was handed over).
+hipError_t launch_attn_pairs(const Geom &g, const uint16_t *Q, const void *packed, const uint32_t *sel_mask, void *scratch,
+                             size_t scratch_bytes, int force, int pairs_below_permille, uint16_t *O, float *lse,
+                             hipStream_t st)
+{
+    const PairsScratch sc = pairs_layout(g, scratch, scratch_bytes);
+    if (!pairs_supported(g) || sc.cap <= 0) return hipErrorInvalidValue;
+    int *flag = sc.flags;
     const long long R = (long long)g.S * g.Hq;
     const int segs = g.Hkv * g.N;
     const long long count_threads = R > segs ? R : segs;
+    const unsigned row_blocks = (unsigned)((R + 255) / 256);
     const unsigned hist_blocks = (unsigned)((R + PAIRS_HIST_ROWS - 1) / PAIRS_HIST_ROWS);
     hipLaunchKernelGGL(pair_count_kernel, dim3((unsigned)((count_threads + 255) / 256)), dim3(256), 0, st, g, R, sel_mask,
-                       sc.cnt, sc.seg_count, sc.seg_cursor, segs, flag, force, pairs_below_permille);
+                       sc.cnt, sc.seg_count, sc.seg_cursor, segs, sc.kv_sel, flag, force, pairs_below_permille);
+    hipLaunchKernelGGL(pairs_mode_kernel, dim3(1), dim3(PAIRS_MAX_KV_HEADS), 0, st, g, sc.cap,
+                       candidate_pairs(g) / (unsigned long long)g.Hkv, sc.kv_sel, force, pairs_below_permille, flag);
+    hipLaunchKernelGGL(pair_keep_kernel, dim3(row_blocks), dim3(256), 0, st, g, R, flag, sc.cnt);
     launch_exclusive_scan(sc.cnt, R, sc.tile_sum, sc.pair_ptr, st);
     hipLaunchKernelGGL((pair_transpose_kernel<false>), dim3(hist_blocks), dim3(PAIRS_HIST_ROWS), (size_t)segs * 4, st, g,
-                       R, sel_mask, sc.pair_ptr, flag, force, pairs_below_permille, sc.seg_count, sc.seg_start, sc.seg_cursor,
-                       sc.entries);
-    hipLaunchKernelGGL(pairs_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, st, sc.pair_ptr, R, sc.cap, candidate_pairs(g),
-                       force, pairs_below_permille, segs, sc.seg_count, sc.seg_start, sc.seg_chunk, flag);
+                       R, sel_mask, sc.pair_ptr, flag, sc.seg_count, sc.seg_start, sc.seg_cursor, sc.entries);
+    hipLaunchKernelGGL(pairs_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, st, segs, sc.seg_count, sc.seg_start,
+                       sc.seg_chunk, flag);
     hipLaunchKernelGGL((pair_transpose_kernel<true>), dim3(hist_blocks), dim3(PAIRS_HIST_ROWS), (size_t)segs * 8, st, g,
-                       R, sel_mask, sc.pair_ptr, flag, force, pairs_below_permille, sc.seg_count, sc.seg_start, sc.seg_cursor,
-                       sc.entries);
-    *err = hipGetLastError();
-    if (*err != hipSuccess) return true;
-    *err = g.D == 64 ? launch_pairs_d<64>(g, Q, packed, sc, flag, O, lse, st)
+                       R, sel_mask, sc.pair_ptr, flag, sc.seg_count, sc.seg_start, sc.seg_cursor, sc.entries);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return g.D == 64 ? launch_pairs_d<64>(g, Q, packed, sc, flag, O, lse, st)
                      : launch_pairs_d<128>(g, Q, packed, sc, flag, O, lse, st);
-    return true;
 }
 
 }  // namespace adaspark

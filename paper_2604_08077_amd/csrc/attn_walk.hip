@@ -58,9 +58,9 @@ template <int D, bool MASKED>
 __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
     Geom g, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ Kp, const uint16_t *__restrict__ Vt,
     const int32_t *__restrict__ csize, const uint32_t *__restrict__ sel_mask, const int *__restrict__ mode_flag,
-    int my_mode, uint16_t *__restrict__ O, float *__restrict__ lse)
+    int my_mode, int kv_modes, uint16_t *__restrict__ O, float *__restrict__ lse)
 {
-    if (mode_flag != nullptr && *mode_flag != my_mode) return;
+    if (mode_flag != nullptr && mode_flag[FLAG_MODE] != my_mode) return;
     using C = Walk<D>;
     constexpr int NS = C::NS, MMAX = C::MMAX, THREADS = C::THREADS, WAVES = C::WAVES, NST = C::NST;
     constexpr int KSTEPS = D / 32, DT = D / 16;
@@ -74,13 +74,16 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
     const int n16 = lane & 15, q4 = lane >> 4;
     const bool set_y = __builtin_amdgcn_readfirstlane(wave >> 2) != 0;
 
-    // workgroup -> (query cube, KV head, row block): as in attn_fwd_kernel
+    // workgroup -> (query cube, KV head, row block), the blocks of one (cube, head) on the same XCD
     const int nblk_max = (g.G * g.Cmax + MMAX - 1) / MMAX;
     const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
     const int grp = (seq / nblk_max) * 8 + xcd;
     const int blk = seq % nblk_max;
     if (grp >= g.N * g.Hkv) return;
-    const int kv = grp % g.Hkv;
+    // (the head is rotated with the cube, so that a KV head is not tied to one XCD: when some heads are handed to
+    // the key-stationary kernel, the others still spread over all of them)
+    const int kv = (grp % g.Hkv + grp / g.Hkv) % g.Hkv;
+    if (kv_modes && mode_flag[FLAG_KV + kv] == 3) return;  // the key-stationary kernel has this head's rows
     const int i = g.N - 1 - grp / g.Hkv;
     const CubeBox qbox = cube_box(g, i);
     const int qsize = qbox.size();
@@ -337,8 +340,9 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
     }
 }
 
-// ---- choice between the compacting and the masked kernel: the share of candidate cubes the rows select, from a
-// sample of rows.  One workgroup; writes 1 (compact) or 2 (masked) to flag[0] and the estimated share to flag[1].
+// ---- the share of candidate cubes the rows select, per KV head, from a sample of rows.  One workgroup; writes
+// flags[FLAG_MODE] = 1 (compaction) or 2 (masked walk) from the overall share, flags[FLAG_ESTIMATE] = the smallest
+// share of a KV head in permille, and (kv_modes) clears the per-head part.
 constexpr int DENSITY_THREADS = 1024;
 constexpr int DENSITY_MAX_ROWS = 2048;  // two sampled rows per thread: an estimate is all that is needed
 // Measured on MI355X with rows that select independently of each other: the compacting kernel wins only below
@@ -346,31 +350,49 @@ constexpr int DENSITY_MAX_ROWS = 2048;  // two sampled rows per thread: an estim
 constexpr int MASKED_ABOVE_PERMILLE = 15;
 
 __global__ __launch_bounds__(DENSITY_THREADS) void sel_density_kernel(Geom g, const uint32_t *__restrict__ sel_mask,
-                                                                      int *__restrict__ flag)
+                                                                      int *__restrict__ flags, int kv_modes)
 {
-    __shared__ unsigned long long acc[2];
-    if (threadIdx.x == 0) acc[0] = acc[1] = 0ull;
+    __shared__ unsigned long long acc[2][PAIRS_MAX_KV_HEADS];  // selected, candidates; heads beyond the array fold
+    for (int x = threadIdx.x; x < 2 * PAIRS_MAX_KV_HEADS; x += DENSITY_THREADS) (&acc[0][0])[x] = 0ull;
     __syncthreads();
-    const long long R = (long long)g.S * g.Hq;
-    const long long stride = max(1ll, R / DENSITY_MAX_ROWS);
-    unsigned long long sel = 0, cand = 0;
-    for (long long r = threadIdx.x * stride; r < R; r += DENSITY_THREADS * stride) {
-        cand += (unsigned long long)cube_of_token(g, (int)(r / g.Hq));
-        const uint32_t *mr = sel_mask + (size_t)r * g.words;
-        for (int w = 0; w < g.words; ++w) sel += __popc(mr[w]);
+    // sample k: token (k * tstride) mod S, query head k mod Hq -- every head gets its share of the samples
+    const int samples = (int)min((long long)DENSITY_MAX_ROWS, (long long)g.S * g.Hq);
+    const int tstride = max(1, g.S / samples) | 1;
+    for (int k = threadIdx.x; k < samples; k += DENSITY_THREADS) {
+        const int n = (int)(((long long)k * tstride) % g.S), a = k % g.Hq;
+        const int i = cube_of_token(g, n);
+        const uint32_t *mr = sel_mask + ((size_t)n * g.Hq + a) * g.words;
+        unsigned long long sel = 0;
+        for (int w = 0; 32 * w < i; ++w) sel += __popc(mr[w]);
+        const int kv = (a / g.G) % PAIRS_MAX_KV_HEADS;
+        atomicAdd(&acc[0][kv], sel);
+        atomicAdd(&acc[1][kv], (unsigned long long)i);
     }
-    atomicAdd(&acc[0], sel);
-    atomicAdd(&acc[1], cand);
     __syncthreads();
     if (threadIdx.x == 0) {
-        flag[0] = (acc[0] * 1000ull > acc[1] * (unsigned long long)MASKED_ABOVE_PERMILLE) ? 2 : 1;
-        flag[1] = (int)(acc[0] * 1000ull / (acc[1] > 0ull ? acc[1] : 1ull));  // the estimate, in permille
+        unsigned long long sel = 0, cand = 0, least = 1000ull;
+        for (int kv = 0; kv < min(g.Hkv, PAIRS_MAX_KV_HEADS); ++kv) {
+            sel += acc[0][kv];
+            cand += acc[1][kv];
+            if (acc[1][kv] > 0ull) least = min(least, acc[0][kv] * 1000ull / acc[1][kv]);
+        }
+        flags[FLAG_MODE] = (sel * 1000ull > cand * (unsigned long long)MASKED_ABOVE_PERMILLE) ? 2 : 1;
+        flags[FLAG_ESTIMATE] = (int)least;
+        flags[FLAG_ACTIVE] = 0;
+    }
+    if (kv_modes) {
+        unsigned long long *kv_sel =
+            reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(flags) + FLAG_BLOCK_BYTES);
+        for (int kv = threadIdx.x; kv < g.Hkv; kv += DENSITY_THREADS) {
+            flags[FLAG_KV + kv] = 0;
+            kv_sel[kv] = 0ull;
+        }
     }
 }
 
 template <int D, bool MASKED>
 static hipError_t launch_walk(const Geom &g, const uint16_t *Q, const void *packed, const uint32_t *sel_mask,
-                              const int *mode_flag, int my_mode, uint16_t *O, float *lse, hipStream_t st)
+                              const int *mode_flag, int my_mode, int kv_modes, uint16_t *O, float *lse, hipStream_t st)
 {
     using C = Walk<D>;
     const uint16_t *Kp = reinterpret_cast<const uint16_t *>(packed);
@@ -383,7 +405,7 @@ static hipError_t launch_walk(const Geom &g, const uint16_t *Q, const void *pack
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::BYTES);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((attn_walk_kernel<D, MASKED>), grid, dim3(C::THREADS), C::BYTES, st, g, Q, Kp, Vt, csize,
-                       sel_mask, mode_flag, my_mode, O, lse);
+                       sel_mask, mode_flag, my_mode, kv_modes, O, lse);
     return hipGetLastError();
 }
 
@@ -396,27 +418,32 @@ static hipError_t launch_attn_d(const Geom &g, const uint16_t *Q, void *packed, 
                                 int sparse_kernel, void *scratch, size_t scratch_bytes, uint16_t *O, float *lse,
                                 hipStream_t st)
 {
-    if (sel_mask == nullptr) return launch_walk<D, false>(g, Q, packed, nullptr, nullptr, 0, O, lse, st);
+    if (sel_mask == nullptr) return launch_walk<D, false>(g, Q, packed, nullptr, nullptr, 0, 0, O, lse, st);
     if (sparse_kernel == ADASPARK_SPARSE_COMPACT)
-        return launch_attn_compact(g, Q, packed, sel_mask, nullptr, 0, O, lse, st);
+        return launch_attn_compact(g, Q, packed, sel_mask, nullptr, 0, 0, O, lse, st);
     if (sparse_kernel == ADASPARK_SPARSE_MASKED)
-        return launch_walk<D, true>(g, Q, packed, sel_mask, nullptr, 0, O, lse, st);
-    // automatic (or the key-stationary kernel asked for): the choice is made on the device, every candidate kernel
-    // is enqueued, and those not chosen return at once
-    // First the selected share from a sample of rows: that decides between the two row-stationary kernels, and
-    // whether the exact count for the key-stationary one is worth taking at all.
-    int *flag = reinterpret_cast<int *>(reinterpret_cast<char *>(packed) + attn_workspace_bytes(g) - 16);
-    hipLaunchKernelGGL(sel_density_kernel, dim3(1), dim3(DENSITY_THREADS), 0, st, g, sel_mask, flag);
+        return launch_walk<D, true>(g, Q, packed, sel_mask, nullptr, 0, 0, O, lse, st);
+    // Automatic (or the key-stationary kernel asked for): the choice is made on the device, every candidate kernel
+    // is enqueued, and the workgroups of those not chosen return at once.  First the selected share from a sample
+    // of rows: that decides between the two row-stationary kernels, and whether the exact count for the
+    // key-stationary one is worth taking at all; with room for its tables the choice is then made per KV head.
+    int *flags = pairs_flags(g, scratch, scratch_bytes);
+    const int kv_modes = flags != nullptr;
+    if (!kv_modes) {
+        if (sparse_kernel == ADASPARK_SPARSE_PAIRS) return hipErrorInvalidValue;  // the entry point checks this first
+        flags = reinterpret_cast<int *>(reinterpret_cast<char *>(packed) + attn_workspace_bytes(g) - 16);
+    }
+    hipLaunchKernelGGL(sel_density_kernel, dim3(1), dim3(DENSITY_THREADS), 0, st, g, sel_mask, flags, kv_modes);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const bool counted =
-        launch_attn_pairs(g, Q, packed, sel_mask, scratch, scratch_bytes, sparse_kernel == ADASPARK_SPARSE_PAIRS,
-                          PAIRS_BELOW_PERMILLE, flag, O, lse, st, &e);
+    if (kv_modes) {
+        e = launch_attn_pairs(g, Q, packed, sel_mask, scratch, scratch_bytes, sparse_kernel == ADASPARK_SPARSE_PAIRS,
+                              PAIRS_BELOW_PERMILLE, O, lse, st);
+        if (e != hipSuccess) return e;
+    }
+    e = launch_attn_compact(g, Q, packed, sel_mask, flags, 1, kv_modes, O, lse, st);
     if (e != hipSuccess) return e;
-    if (!counted && sparse_kernel == ADASPARK_SPARSE_PAIRS) return hipErrorInvalidValue;  // the entry point checks this
-    e = launch_attn_compact(g, Q, packed, sel_mask, flag, 1, O, lse, st);
-    if (e != hipSuccess) return e;
-    return launch_walk<D, true>(g, Q, packed, sel_mask, flag, 2, O, lse, st);
+    return launch_walk<D, true>(g, Q, packed, sel_mask, flags, 2, kv_modes, O, lse, st);
 }
 
 hipError_t launch_attn(const Geom &g, const uint16_t *Q, void *packed, const uint32_t *sel_mask, int sparse_kernel,

@@ -119,25 +119,40 @@ size_t scan_tile_sum_bytes(long long n);
 void launch_exclusive_scan(const int32_t *count, long long n, long long *tile_sum, int64_t *out, hipStream_t st);
 size_t attn_workspace_bytes(const Geom &g);
 hipError_t launch_kv_pack(const Geom &g, const uint16_t *K, const uint16_t *V, void *ws, hipStream_t st);
+// Kernel-choice flags of the sparse attention entries (ints, written and read on the device only):
+//   [FLAG_MODE]      the row-stationary kernel that runs: 1 compaction, 2 masked walk
+//   [FLAG_ESTIMATE]  smallest share of selected candidate cubes over the KV heads, permille, from a sample of rows
+//   [FLAG_ACTIVE]    1 if some KV head is the key-stationary kernel's
+//   [FLAG_KV + kv]   3: the rows of KV head kv are left to the key-stationary kernel; 0: to the kernel above
+// The per-head part exists only where the caller's workspace has room for the key-stationary kernel's tables
+// (kernels take `kv_modes` = 1); the block is then 512 bytes long and followed by that kernel's per-head pair
+// totals, u64 [Hkv], which the kernel that fills the first two flags also clears.  Otherwise the block is the
+// four ints at the end of the minimum workspace.
+constexpr int FLAG_MODE = 0, FLAG_ESTIMATE = 1, FLAG_ACTIVE = 2, FLAG_KV = 4;
+constexpr int PAIRS_MAX_KV_HEADS = 64;
+constexpr int FLAG_BLOCK_BYTES = 512;
+
 // sel_mask == nullptr: dense (every preceding cube attended); otherwise sparse_kernel is an adaspark_sparse_kernel.
 // The automatic choice writes a flag into the last 16 bytes of the packed workspace.  scratch (256-byte aligned, may
 // be null): memory for the key-stationary kernel's records.
 hipError_t launch_attn(const Geom &g, const uint16_t *Q, void *packed, const uint32_t *sel_mask, int sparse_kernel,
                        void *scratch, size_t scratch_bytes, uint16_t *O, float *lse, hipStream_t st);
+// The compacting sparse kernel alone (attn_compact.hip).  flags (device, may be null): the flag block above; a
+// workgroup runs only if flags[FLAG_MODE] == my_mode and (kv_modes) its KV head is not the key-stationary kernel's.
+hipError_t launch_attn_compact(const Geom &g, const uint16_t *Q, const void *packed, const uint32_t *sel_mask,
+                               const int *flags, int my_mode, int kv_modes, uint16_t *O, float *lse, hipStream_t st);
 // The key-stationary sparse kernel (attn_pairs.hip).  pairs_scratch_bytes: scratch for max_selected selected (row,
-// cube) pairs.  On entry flag[0] holds the choice between the row-stationary kernels (1 compact, 2 masked walk) and
-// flag[1] an estimate of the selected share in permille.  launch_attn_pairs enqueues kernels that -- unless the
-// estimate is well above pairs_below_permille and force is 0 -- count the pairs exactly, set flag[0] = 3 if the
-// records fit and (force or the share is below pairs_below_permille), and then run this path (only if flag[0] ==
-// 3).  false: scratch too small even for the tables or geometry not covered, nothing enqueued.
+// cube) pairs.  pairs_flags: the flag block inside the scratch memory (with the per-head part), or null if the
+// scratch memory does not hold the tables or the geometry is not covered.  launch_attn_pairs expects
+// flags[FLAG_MODE], flags[FLAG_ESTIMATE] set and flags[FLAG_KV ...] zero; it enqueues kernels that -- unless the
+// estimate is well above pairs_below_permille and force is 0 -- count the pairs exactly per KV head, hand the heads
+// whose share is below pairs_below_permille (all heads, if force) to this path as long as their records fit, and run
+// it for those heads.
 bool pairs_supported(const Geom &g);
 size_t pairs_scratch_bytes(const Geom &g, long long max_selected);
-bool launch_attn_pairs(const Geom &g, const uint16_t *Q, const void *packed, const uint32_t *sel_mask, void *scratch,
-                       size_t scratch_bytes, int force, int pairs_below_permille, int *flag, uint16_t *O, float *lse,
-                       hipStream_t st, hipError_t *err);
-// The compacting sparse kernel alone (attn_compact.hip).  mode_flag (device, may be null): run only if
-// *mode_flag == my_mode.
-hipError_t launch_attn_compact(const Geom &g, const uint16_t *Q, const void *packed, const uint32_t *sel_mask,
-                               const int *mode_flag, int my_mode, uint16_t *O, float *lse, hipStream_t st);
+int *pairs_flags(const Geom &g, void *scratch, size_t scratch_bytes);
+hipError_t launch_attn_pairs(const Geom &g, const uint16_t *Q, const void *packed, const uint32_t *sel_mask, void *scratch,
+                             size_t scratch_bytes, int force, int pairs_below_permille, uint16_t *O, float *lse,
+                             hipStream_t st);
 
 }  // namespace adaspark
