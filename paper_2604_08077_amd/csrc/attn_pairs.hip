@@ -486,8 +486,7 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_pairs_kernel(
         // The records: m, l, s = max |O| and O / s in fp16 (round toward zero).  A lane holds 4 consecutive head-dim
         // elements per block of 16; two blocks make one 16-byte store.  Straight-line code, so that the stores are
         // counted exactly and the wait for the operands loaded above does not become a wait for them: a padding
-        // row repeats the step's last row and writes the same record with the same values again, and the four
-        // lanes of a row all write its scalars.
+        // row repeats the step's last row and writes the same record with the same values again.
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
             float amax = 0.f;
@@ -509,7 +508,8 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_pairs_kernel(
                 // written once, read once by the merge kernel: streaming stores
                 __builtin_nontemporal_store(pk.u, reinterpret_cast<u32x4 *>(orec + 16 * e));
             }
-            *reinterpret_cast<f32x4 *>(ml + (size_t)slot[s] * 4) = f32x4{m_run[s], l_run[s][0], amax, 0.f};
+            // the four lanes of a row write one of the four scalars each
+            ml[(size_t)slot[s] * 4 + q4] = q4 == 0 ? m_run[s] : q4 == 1 ? l_run[s][0] : q4 == 2 ? amax : 0.f;
         }
     };
 

@@ -80,9 +80,11 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
     const int grp = (seq / nblk_max) * 8 + xcd;
     const int blk = seq % nblk_max;
     if (grp >= g.N * g.Hkv) return;
-    // (the head is rotated with the cube, so that a KV head is not tied to one XCD: when some heads are handed to
-    // the key-stationary kernel, the others still spread over all of them)
-    const int kv = (grp % g.Hkv + grp / g.Hkv) % g.Hkv;
+    // A KV head normally stays on the same XCDs (grp % 8 = xcd: its K/V tiles are the ones that XCD's L2 holds).
+    // When some heads are handed to the key-stationary kernel, the head is rotated with the cube instead, so that
+    // the heads that remain still spread over all XCDs.
+    const int rot = (kv_modes && mode_flag[FLAG_ACTIVE]) ? grp / g.Hkv : 0;
+    const int kv = (grp % g.Hkv + rot) % g.Hkv;
     if (kv_modes && mode_flag[FLAG_KV + kv] == 3) return;  // the key-stationary kernel has this head's rows
     const int i = g.N - 1 - grp / g.Hkv;
     const CubeBox qbox = cube_box(g, i);
