@@ -86,8 +86,9 @@ typedef enum {
  *            about 40 % of the cubes are selected.  Needs extra workspace (adaspark_pairs_workspace_bytes) and
  *            cubes of at most 256 tokens.  If the selection turns out to hold more pairs than the scratch
  *            memory was sized for, the call runs MASKED instead (decided on the device).
- *   AUTO     the choice is made on the device from the selected share (no host synchronisation); PAIRS is
- *            among the candidates iff the workspace is large enough for it. */
+ *   AUTO     the choice is made on the device from the selected share (no host synchronisation).  PAIRS is
+ *            among the candidates iff the workspace is large enough for it, and the choice is then made per KV
+ *            head: heads whose rows select little go to PAIRS, the others to MASKED (or COMPACT). */
 typedef enum {
     ADASPARK_SPARSE_AUTO = 0,
     ADASPARK_SPARSE_COMPACT = 1,

@@ -121,7 +121,8 @@ def test_full_path_small(B, oracle, w):
     assert torch.isfinite(lse).all()
     # (1b) each of the sparse kernels, forced: the library's own choice above is one of them
     packed = B.kv_pack(sh, Kg, Vg, workspace=B.alloc_workspace(sh, B.CALL_SPARSE_ATTN, pairs_capacity=int(ref_count.sum())))
-    for kern in (B.SPARSE_COMPACT, B.SPARSE_MASKED, B.SPARSE_PAIRS):
+    # (and the library's own choice once more, now with room for the key-stationary kernel: per KV head)
+    for kern in (B.SPARSE_COMPACT, B.SPARSE_MASKED, B.SPARSE_PAIRS, B.SPARSE_AUTO):
         Ok, lsek = B.sparse_attn_packed(sh, Qg, packed, torch.from_numpy(ref_mask.view(np.int32)).cuda(),
                                         return_lse=True, kernel=kern)
         torch.cuda.synchronize()
