@@ -252,6 +252,46 @@ def test_pairs_kernel_falls_back_when_records_do_not_fit(B, oracle):
         check_outputs(f"{w.name} pairs, scratch for {cap} pairs", O.reshape(-1, w.D).float().cpu().numpy(), ref_out)
 
 
+def test_single_cube_and_stray_mask_bits(B, oracle):
+    """A grid smaller than one cube (no candidates at all: own-cube attention only), through every sparse kernel;
+    and a mask with bits set at and above a row's own cube, which every kernel must ignore."""
+    w1 = synth.Workload("T_onecube", 31, 2, 3, 4, 2, 4, 4, 4, 2, 64, (0.9,), (1.0, 1.0))
+    sh, osh = B.Shape.of(w1), oshape(oracle, w1)
+    assert B.num_cubes(sh) == 1
+    Q, K, V = synth.generate(w1)
+    Qg, Kg, Vg = Q.cuda(), K.cuda(), V.cuda()
+    kbar = B.cube_pool(sh, Kg)
+    mask, count, _, _ = B.cube_select(sh, Qg, kbar, 0.9)
+    torch.cuda.synchronize()
+    assert not mask.any() and not count.any()
+    ref = oracle.dense_attn(osh, Q, K, V)
+    ws = B.kv_pack(sh, Kg, Vg, workspace=B.alloc_workspace(sh, B.CALL_SPARSE_ATTN, pairs_capacity=0))
+    for kern in (B.SPARSE_AUTO, B.SPARSE_COMPACT, B.SPARSE_MASKED, B.SPARSE_PAIRS):
+        O = B.sparse_attn_packed(sh, Qg, ws, mask, kernel=kern)
+        torch.cuda.synchronize()
+        check_outputs(f"one cube, kernel {kern}", O.reshape(-1, w1.D).float().cpu().numpy(), ref)
+
+    w = synth.TEST_WORKLOADS["T_mha64"]
+    print(f"case {w.name} stray mask bits", flush=True)
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    N = B.num_cubes(sh)
+    Q, K, V = synth.generate(w)
+    Qg, Kg, Vg = Q.cuda(), K.cuda(), V.cuda()
+    kbar_ref = oracle.cube_pool(osh, K)
+    ref_mask, ref_count, _ = oracle.cube_select(osh, Q, kbar_ref, 0.7)
+    ref_out, _ = oracle.sparse_attn(osh, Q, K, V, ref_mask)
+    cube_of = oracle.cube_map(osh)[0]
+    own = np.repeat(cube_of, w.Hq)
+    bits = np.unpackbits(ref_mask.view(np.uint8), axis=1, bitorder="little")
+    bits[np.arange(bits.shape[1])[None, :] >= own[:, None]] = 1   # every bit at and above the own cube, padding included
+    dirty = torch.from_numpy(np.packbits(bits, axis=1, bitorder="little").view(np.int32).copy()).cuda()
+    ws = B.kv_pack(sh, Kg, Vg, workspace=B.alloc_workspace(sh, B.CALL_SPARSE_ATTN, pairs_capacity=int(ref_count.sum())))
+    for kern in (B.SPARSE_AUTO, B.SPARSE_COMPACT, B.SPARSE_MASKED, B.SPARSE_PAIRS):
+        O = B.sparse_attn_packed(sh, Qg, ws, dirty, kernel=kern)
+        torch.cuda.synchronize()
+        check_outputs(f"{w.name} stray bits, kernel {kern}", O.reshape(-1, w.D).float().cpu().numpy(), ref_out)
+
+
 def test_c2_sampled(B, oracle):
     sampled_case(B, oracle, synth.WORKLOADS["C2"], (0.9,), 768)
 
