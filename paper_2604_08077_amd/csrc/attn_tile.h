@@ -165,6 +165,93 @@ __device__ __forceinline__ void softmax_tile(f32x4 (&sacc)[NS][4], bf16x8 (&pf)[
     }
 }
 
+// Q operand times the softmax scale in base 2, log2(e)/sqrt(D), rounded to bf16 again: the scores then come out of
+// the MFMAs in the exponent's units (the rounding adds an error of the size of the bf16 rounding of the output).
+__device__ __forceinline__ bf16x8 prescale_q(bf16x8 q, float c2)
+{
+    bf16x8 r;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) r[x] = (__bf16)((float)q[x] * c2);
+    return r;
+}
+
+// Online softmax with the running maximum folded into the MFMA accumulator: the scores arrive as
+// s' = (scaled score) - m_run (the S^T MFMAs of a slab start from -m_run, or from -inf for a row that takes no part
+// in the tile), so that in the common case -- no score of the tile exceeds the reference m_run by more than
+// SOFTMAX_LAZY -- the probabilities are exp2(s') with no arithmetic in between.  m_run is a reference point, not
+// the exact maximum: it moves up to a tile's maximum only when that exceeds it by more than SOFTMAX_LAZY (then O
+// and l are rescaled), and to the first tile's maximum whatever it is (fresh rows).  Probabilities are at most
+// 2^SOFTMAX_LAZY; the final O / l does not depend on the reference.
+constexpr float SOFTMAX_LAZY = 4.0f;
+template <int D, int NS>
+__device__ __forceinline__ void softmax_tile_folded(f32x4 (&sacc)[NS][4], bf16x8 (&pf)[NS][2], f32x4 (&oacc)[NS][D / 16],
+                                                    float (&m_run)[NS], f32x4 (&l_run)[NS], bool (&fresh)[NS],
+                                                    const int (&lim)[NS], int key0, bool need_mask, int q4)
+{
+    if (need_mask) {
+        int kb = key0 + 8 * q4;
+        asm volatile("" : "+v"(kb));
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+#pragma unroll
+            for (int kg = 0; kg < 4; ++kg)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int kr = kb + 32 * (kg >> 1) + 4 * (kg & 1) + v;
+                    if (kr > lim[s]) sacc[s][kg][v] = -INFINITY;
+                }
+    }
+    float mx[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) mx[s] = vmax3(sacc[s][0][0], sacc[s][0][1], sacc[s][0][2]);
+#pragma unroll
+    for (int s = 0; s < NS; ++s) mx[s] = vmax3(mx[s], sacc[s][0][3], sacc[s][1][0]);
+#pragma unroll
+    for (int s = 0; s < NS; ++s) mx[s] = vmax3(mx[s], sacc[s][1][1], sacc[s][1][2]);
+#pragma unroll
+    for (int s = 0; s < NS; ++s) mx[s] = vmax3(mx[s], sacc[s][1][3], sacc[s][2][0]);
+#pragma unroll
+    for (int s = 0; s < NS; ++s) mx[s] = vmax3(mx[s], sacc[s][2][1], sacc[s][2][2]);
+#pragma unroll
+    for (int s = 0; s < NS; ++s) mx[s] = vmax3(mx[s], sacc[s][2][3], sacc[s][3][0]);
+#pragma unroll
+    for (int s = 0; s < NS; ++s) mx[s] = vmax3(mx[s], sacc[s][3][1], sacc[s][3][2]);
+#pragma unroll
+    for (int s = 0; s < NS; ++s) mx[s] = vmax(mx[s], sacc[s][3][3]);
+#pragma unroll
+    for (int s = 0; s < NS; ++s) mx[s] = quad_max(mx[s]);
+    bool grow[NS];
+    unsigned int any = 0u;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        grow[s] = (mx[s] > SOFTMAX_LAZY) | (fresh[s] & (mx[s] > -INFINITY));
+        any |= grow[s] ? 1u : 0u;
+    }
+    if (__ballot(any != 0u) != 0ull) {  // rare after a row's first tiles: move the reference, rescale O and l
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            const float d = grow[s] ? mx[s] : 0.f;
+            const float alpha = (grow[s] && !fresh[s]) ? __builtin_amdgcn_exp2f(-d) : 1.f;  // a fresh row has O = l = 0
+            m_run[s] += d;
+            fresh[s] = fresh[s] && !grow[s];
+#pragma unroll
+            for (int kg = 0; kg < 4; ++kg)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) sacc[s][kg][v] -= d;
+#pragma unroll
+            for (int e = 0; e < D / 16; ++e) oacc[s][e] *= alpha;
+            l_run[s] *= alpha;
+        }
+    }
+#pragma unroll
+    for (int kg = 0; kg < 4; ++kg)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+#pragma unroll
+            for (int s = 0; s < NS; ++s)
+                pf[s][kg >> 1][4 * (kg & 1) + v] = (__bf16)__builtin_amdgcn_exp2f(sacc[s][kg][v]);
+}
+
 // The MFMA phase of a wavefront in the counter-phase kernel: P.V of one tile, then S of the next, as one stream
 // of operand loads and MFMAs.  A wavefront that is alone in its MFMA phase cannot hide LDS latency behind a
 // neighbour, so the operands run PF loads ahead of their use through a ring of registers, and the order written
@@ -194,11 +281,13 @@ __device__ __forceinline__ void phase_prefetch(const unsigned char *vt, const un
     for (int r = 0; r < PF && r < R; ++r) ring[r] = phase_operand<D, DO_PV, DO_QK>(vt, kt, n16, q4, r);
 }
 
+// sinit: what the scores of a slab start from (0, or minus the running maximum: see softmax_tile_folded).
 template <int D, int NS, int PF, bool DO_PV, bool DO_QK>
-__device__ __forceinline__ void mfma_phase(const unsigned char *vt, const unsigned char *kt, int n16, int q4,
-                                           bf16x8 (&ring)[PF], const bf16x8 (&pf)[NS][2],
-                                           f32x4 (&oacc)[NS][D / 16], f32x4 (&l_run)[NS],
-                                           const bf16x8 (&qf)[NS][D / 32], f32x4 (&sacc)[NS][4])
+__device__ __forceinline__ void mfma_phase_from(const unsigned char *vt, const unsigned char *kt, int n16, int q4,
+                                                bf16x8 (&ring)[PF], const bf16x8 (&pf)[NS][2],
+                                                f32x4 (&oacc)[NS][D / 16], f32x4 (&l_run)[NS],
+                                                const bf16x8 (&qf)[NS][D / 32], const f32x4 (&sinit)[NS],
+                                                f32x4 (&sacc)[NS][4])
 {
     constexpr int DT = D / 16, KSTEPS = D / 32;
     constexpr int RV = DO_PV ? 2 * DT : 0, RK = DO_QK ? 4 * KSTEPS : 0, R = RV + RK;
@@ -222,11 +311,23 @@ __device__ __forceinline__ void mfma_phase(const unsigned char *vt, const unsign
 #pragma unroll
             for (int s = 0; s < NS; ++s)
                 sacc[s][kg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                    af, qf[s][c], c == 0 ? f32x4{0.f, 0.f, 0.f, 0.f} : sacc[s][kg], 0, 0, 0);
+                    af, qf[s][c], c == 0 ? sinit[s] : sacc[s][kg], 0, 0, 0);
         }
         if (r + PF < R) ring[r % PF] = phase_operand<D, DO_PV, DO_QK>(vt, kt, n16, q4, r + PF);
         __builtin_amdgcn_sched_barrier(0);
     }
+}
+
+template <int D, int NS, int PF, bool DO_PV, bool DO_QK>
+__device__ __forceinline__ void mfma_phase(const unsigned char *vt, const unsigned char *kt, int n16, int q4,
+                                           bf16x8 (&ring)[PF], const bf16x8 (&pf)[NS][2],
+                                           f32x4 (&oacc)[NS][D / 16], f32x4 (&l_run)[NS],
+                                           const bf16x8 (&qf)[NS][D / 32], f32x4 (&sacc)[NS][4])
+{
+    f32x4 zero[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) zero[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+    mfma_phase_from<D, NS, PF, DO_PV, DO_QK>(vt, kt, n16, q4, ring, pf, oacc, l_run, qf, zero, sacc);
 }
 
 // O^T += V^T.P^T and l += sum(P) for one 64-key tile; one V^T operand load serves all slabs of the range.

@@ -200,26 +200,28 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
         stream_next(sv);
     }
 
+    const float c2 = 1.44269504088896340736f / sqrtf((float)D);  // softmax scale in base 2, folded into Q
     bf16x8 qf[NS][KSTEPS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
         const uint16_t *qrow = Q + (size_t)rowid[lr[s]] * D + 8 * q4;
 #pragma unroll
-        for (int c = 0; c < KSTEPS; ++c) qf[s][c] = *reinterpret_cast<const bf16x8 *>(qrow + 32 * c);
+        for (int c = 0; c < KSTEPS; ++c) qf[s][c] = prescale_q(*reinterpret_cast<const bf16x8 *>(qrow + 32 * c), c2);
     }
 #pragma unroll
     for (int s = 0; s < NS; ++s)
 #pragma unroll
         for (int c = 0; c < KSTEPS; ++c) asm volatile("" : "+v"(qf[s][c]));
 
-    const float c2 = 1.44269504088896340736f / sqrtf((float)D);
     int lim[NS];
     float m_run[NS];
+    bool fresh[NS];
     f32x4 l_run[NS];  // every element holds the row's running sum
     f32x4 oacc[NS][DT];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-        m_run[s] = -1e30f;
+        m_run[s] = 0.f;   // reference point of the exponentials; set by the row's first tile (fresh)
+        fresh[s] = true;
         l_run[s] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int e = 0; e < DT; ++e) oacc[s][e] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -260,12 +262,22 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
         const bool own = (cc.j == i);
         const int key0 = KEY_TILE * cc.t;
         const bool need_mask = (key0 + KEY_TILE > jsize) || (own && key0 + KEY_TILE - 1 > rank_lo);
-        softmax_tile<D, 0, NS, NS, MASKED>(sacc, pf, oacc, m_run, l_run, lim, key0, need_mask, c2, q4, rsel);
+        softmax_tile_folded<D, NS>(sacc, pf, oacc, m_run, l_run, fresh, lim, key0, need_mask, q4);
         const int j0 = cc.j;
         advance(cc);
         if (cc.j != j0) enter_cube(cc.j);
     };
 
+    // what the scores of the next tile start from: minus the reference point of the row's exponentials, or -inf
+    // for a row that did not select the tile's cube (its probabilities are then 0 and its state stays as it is)
+    f32x4 sinit[NS];
+    auto set_sinit = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            const float x = (MASKED && !rsel[s]) ? -INFINITY : -m_run[s];
+            sinit[s] = f32x4{x, x, x, x};
+        }
+    };
     static_assert(NST == 3, "the stage arithmetic below is for three stages");
     int kst = 0;  // stage of K(t); V(t-1) sits in stage (kst + 2) % 3
     bf16x8 ring[PF];
@@ -293,33 +305,36 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
     // two versions of every accumulator at its end, at the price of a register copy each.
     open_slot(0);
     phase_prefetch<D, PF, false, true>(nullptr, k_tile(), n16, q4, ring);
-    mfma_phase<D, NS, PF, false, true>(nullptr, k_tile(), n16, q4, ring, pf, oacc, l_run, qf, sacc);
+    set_sinit();
+    mfma_phase_from<D, NS, PF, false, true>(nullptr, k_tile(), n16, q4, ring, pf, oacc, l_run, qf, sinit, sacc);
     if (!set_y) {
         softmax_step();
         for (int t = 1; t < ntiles; ++t) {
             kst = next_stage(kst);
             open_slot(t);
             phase_prefetch<D, PF, true, true>(v_tile(), k_tile(), n16, q4, ring);
-            mfma_phase<D, NS, PF, true, true>(v_tile(), k_tile(), n16, q4, ring, pf, oacc, l_run, qf, sacc);
+            set_sinit();
+            mfma_phase_from<D, NS, PF, true, true>(v_tile(), k_tile(), n16, q4, ring, pf, oacc, l_run, qf, sinit, sacc);
             softmax_step();
         }
         kst = next_stage(kst);
         open_slot(ntiles);
         phase_prefetch<D, PF, true, false>(v_tile(), nullptr, n16, q4, ring);
-        mfma_phase<D, NS, PF, true, false>(v_tile(), nullptr, n16, q4, ring, pf, oacc, l_run, qf, sacc);
+        mfma_phase_from<D, NS, PF, true, false>(v_tile(), nullptr, n16, q4, ring, pf, oacc, l_run, qf, sinit, sacc);
     } else {
         for (int t = 1; t < ntiles; ++t) {
             kst = next_stage(kst);
             open_slot(t);
             softmax_step();  // of tile t-1
             phase_prefetch<D, PF, true, true>(v_tile(), k_tile(), n16, q4, ring);
-            mfma_phase<D, NS, PF, true, true>(v_tile(), k_tile(), n16, q4, ring, pf, oacc, l_run, qf, sacc);
+            set_sinit();
+            mfma_phase_from<D, NS, PF, true, true>(v_tile(), k_tile(), n16, q4, ring, pf, oacc, l_run, qf, sinit, sacc);
         }
         kst = next_stage(kst);
         open_slot(ntiles);
         softmax_step();
         phase_prefetch<D, PF, true, false>(v_tile(), nullptr, n16, q4, ring);
-        mfma_phase<D, NS, PF, true, false>(v_tile(), nullptr, n16, q4, ring, pf, oacc, l_run, qf, sacc);
+        mfma_phase_from<D, NS, PF, true, false>(v_tile(), nullptr, n16, q4, ring, pf, oacc, l_run, qf, sinit, sacc);
     }
 
     // ---- normalise and write out (no direct-to-LDS load may outlive the workgroup's LDS allocation)
