@@ -38,8 +38,11 @@ struct Pairs {
     static constexpr int PF = 4;
     static constexpr int CHUNK = KEY_TILE * D * 2;
     static constexpr int PIECES = CHUNK / 1024;  // 1 KB direct-to-LDS copies per tile
+    // K and V^T tiles alternate in LDS (K0 V0 K1 V1 ...): both tiles of a step's operand loads then lie within 64 KB
+    // of one base register, the reach of the LDS instructions' immediate offset
     static constexpr int OFF_K = 0;
-    static constexpr int OFF_V = PAIRS_MAX_TPC * CHUNK;
+    static constexpr int OFF_V = CHUNK;
+    static constexpr int TILE_STRIDE = 2 * CHUNK;
     static constexpr int OFF_ROWS = 2 * PAIRS_MAX_TPC * CHUNK;  // (row id, record) of the workgroup's rows
     static constexpr int BYTES = OFF_ROWS + PAIRS_CHUNK * 8;
     static_assert(BYTES <= 160 * 1024, "LDS of one CU");
@@ -385,9 +388,10 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_pairs_kernel(
         const int per = nt * C::PIECES;  // 1 KB pieces of K, and of V^T
         for (int p = wave; p < 2 * per; p += WAVES) {
             const bool isv = p >= per;
-            const int q = isv ? p - per : p;  // = tile * PIECES + piece: the tiles of a cube are contiguous
+            const int q = isv ? p - per : p;  // = tile * PIECES + piece: the tiles of a cube are contiguous in memory
             // wave-uniform by construction; said again so that they are kept in scalar registers
-            const uint32_t dst = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)((isv ? C::OFF_V : C::OFF_K) + q * 1024));
+            const uint32_t dst = __builtin_amdgcn_readfirstlane(
+                lds0 + (uint32_t)((isv ? C::OFF_V : C::OFF_K) + (q / C::PIECES) * C::TILE_STRIDE + (q % C::PIECES) * 1024));
             const uintptr_t src = reinterpret_cast<uintptr_t>(isv ? vbase : kbase) + (size_t)q * 1024;
             // (readfirstlane returns a signed int: widen through uint32_t, or a low half with bit 31 set would
             // smear ones over the high half)
@@ -460,8 +464,8 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_pairs_kernel(
         // (OWN) rows come in rank order: no row of the step attends keys past the rank of its last row
         int nts = nt;
         if (OWN) nts = min(nt, ((int)first + min(step * C::ROWS + C::ROWS, nrows) - 1) / g.G / KEY_TILE + 1);
-        auto k_tile = [&](int t) -> const unsigned char * { return smem + C::OFF_K + t * C::CHUNK; };
-        auto v_tile = [&](int t) -> const unsigned char * { return smem + C::OFF_V + t * C::CHUNK; };
+        auto k_tile = [&](int t) -> const unsigned char * { return smem + C::OFF_K + t * C::TILE_STRIDE; };
+        auto v_tile = [&](int t) -> const unsigned char * { return smem + C::OFF_V + t * C::TILE_STRIDE; };
         auto softmax_step = [&](int t) __attribute__((always_inline)) {
             const int key0 = KEY_TILE * t;
             const bool need_mask = OWN || (key0 + KEY_TILE > jsize);
@@ -547,8 +551,10 @@ __global__ __launch_bounds__(256) void pairs_merge_kernel(long long R, const int
     constexpr int LPR = D / 4;  // lanes per row
     typedef __fp16 h4 __attribute__((ext_vector_type(4)));
     const int l = threadIdx.x % LPR;
-    const long long row = (long long)blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
-    if (row >= R || mode_flag[FLAG_KV + (int)(row % Hq) / G] != 3) return;  // another kernel writes that row
+    // grid-stride over the rows: the grid is bounded, so that a launch that has nothing to do costs little
+    for (long long row = (long long)blockIdx.x * (256 / LPR) + threadIdx.x / LPR; row < R;
+         row += (long long)gridDim.x * (256 / LPR)) {
+    if (mode_flag[FLAG_KV + (int)(row % Hq) / G] != 3) continue;  // another kernel writes that row
     const long long p0 = pair_ptr[row];
     const int n = (int)(pair_ptr[row + 1] - p0);
     const float *mlr = ml + (size_t)p0 * 4;
@@ -588,6 +594,7 @@ __global__ __launch_bounds__(256) void pairs_merge_kernel(long long R, const int
     const uint32_t w1 = (uint32_t)float_to_bf16_bits(acc[2] * inv) | ((uint32_t)float_to_bf16_bits(acc[3] * inv) << 16);
     *reinterpret_cast<uint2 *>(O + (size_t)row * D + d) = make_uint2(w0, w1);
     if (lse != nullptr && l == 0) lse[row] = (M + log2f(L)) * 0.69314718055994530942f;
+    }
 }
 
 // Number of candidate (row, cube) pairs: every row of cube i has i preceding cubes.
@@ -625,8 +632,9 @@ static hipError_t launch_pairs_d(const Geom &g, const uint16_t *Q, const void *p
     hipLaunchKernelGGL((attn_pairs_kernel<D, true>), dim3((unsigned)(segs * own_chunks)), dim3(C::THREADS), C::BYTES, st, g,
                        own_chunks, Q, Kp, Vt, csize, sc.pair_ptr, sc.seg_count, sc.seg_start, sc.seg_chunk, sc.entries, flag, sc.rec, sc.ml);
     const int rows_per_block = 256 / (D / 4);
-    hipLaunchKernelGGL((pairs_merge_kernel<D>), dim3((unsigned)((R + rows_per_block - 1) / rows_per_block)), dim3(256), 0,
-                       st, R, sc.pair_ptr, sc.rec, sc.ml, flag, g.Hq, g.G, O, lse);
+    const long long merge_blocks = std::min<long long>((R + rows_per_block - 1) / rows_per_block, 256 * 64);
+    hipLaunchKernelGGL((pairs_merge_kernel<D>), dim3((unsigned)merge_blocks), dim3(256), 0, st, R, sc.pair_ptr, sc.rec,
+                       sc.ml, flag, g.Hq, g.G, O, lse);
     return hipGetLastError();
 }
 
