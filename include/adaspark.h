@@ -106,8 +106,8 @@ int adaspark_workspace_bytes(const adaspark_shape *shape, int which_call /* adas
 const char *adaspark_status_string(int status);
 /* Workspace size for the sparse attention entries that also lets the key-stationary kernel (ADASPARK_SPARSE_PAIRS)
  * run for selections of up to max_selected selected (row, cube) pairs in total (the sum of sel_count):
- * adaspark_workspace_bytes(ADASPARK_CALL_SPARSE_ATTN) plus tables of 12 bytes per row plus 2 * head_dim + 24 bytes
- * per pair and per row.  The sparse entries use whatever lies beyond the minimum size this way. */
+ * adaspark_workspace_bytes(ADASPARK_CALL_SPARSE_ATTN) plus, per row, 12 bytes of tables and a scaled copy of its
+ * Q vector, plus 2 * head_dim + 24 bytes per pair and per row.  The sparse entries use whatever lies beyond the minimum size this way. */
 int adaspark_pairs_workspace_bytes(const adaspark_shape *shape, int64_t max_selected, size_t *bytes);
 
 /*

@@ -57,6 +57,8 @@ bool pairs_supported(const Geom &g)
 // Scratch memory of the pair path, carved from `bytes` bytes at `base` (256-byte aligned):
 //   flags      i32 [4 + Hkv]  the kernel-choice flags (geom.h)
 //   kv_sel     u64 [Hkv]      selected (row, cube) pairs per KV head
+//   qs         bf16 [R][D]    Q times the softmax scale in base 2, rounded to bf16 again (rows of the heads this
+//                             path takes): the operand of the score MFMAs, see softmax_tile_folded
 //   cnt        i32 [R]        records per row = selected cubes + 1 (the own cube); 0 for rows of heads left to a
 //                             row-stationary kernel
 //   pair_ptr   i64 [R + 1]    exclusive scan of cnt: a row's records, in cube order, the own cube last
@@ -72,6 +74,7 @@ bool pairs_supported(const Geom &g)
 struct PairsScratch {
     int *flags;
     unsigned long long *kv_sel;
+    uint16_t *qs;
     int32_t *cnt;
     int64_t *pair_ptr;
     long long *tile_sum;
@@ -87,7 +90,7 @@ static size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 static size_t pairs_table_bytes(const Geom &g)
 {
     const size_t R = (size_t)g.S * g.Hq, segs = (size_t)g.Hkv * g.N;
-    return FLAG_BLOCK_BYTES + 512 + up256(R * 4) + up256((R + 1) * 8) + up256(scan_tile_sum_bytes((long long)R)) +
+    return FLAG_BLOCK_BYTES + 512 + up256(R * (size_t)g.D * 2) + up256(R * 4) + up256((R + 1) * 8) + up256(scan_tile_sum_bytes((long long)R)) +
            4 * up256((segs + 1) * 4);
 }
 
@@ -118,6 +121,8 @@ static PairsScratch pairs_layout(const Geom &g, void *base, size_t bytes)
     p += FLAG_BLOCK_BYTES;
     s.kv_sel = reinterpret_cast<unsigned long long *>(p);  // right behind the flag block (geom.h)
     p += 512;
+    s.qs = reinterpret_cast<uint16_t *>(p);
+    p += up256(R * (size_t)g.D * 2);
     s.cnt = reinterpret_cast<int32_t *>(p);
     p += up256(R * 4);
     s.pair_ptr = reinterpret_cast<int64_t *>(p);
@@ -218,6 +223,19 @@ __global__ void pair_keep_kernel(Geom g, long long R, const int *__restrict__ fl
     if (!flags[FLAG_ACTIVE]) return;
     const long long r = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (r < R && flags[FLAG_KV + (int)(r % g.Hq) / g.G] != 3) cnt[r] = 0;
+}
+
+// qs = bf16(Q * log2(e)/sqrt(D)) for the rows of the heads this path takes; 8 elements per thread.
+__global__ void pairs_scale_q_kernel(Geom g, long long chunks, float c2, const int *__restrict__ flags,
+                                     const uint16_t *__restrict__ Q, uint16_t *__restrict__ qs)
+{
+    if (!flags[FLAG_ACTIVE]) return;
+    const long long x = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (x >= chunks) return;
+    const long long row = x / (g.D / 8);
+    if (flags[FLAG_KV + (int)(row % g.Hq) / g.G] != 3) return;
+    const bf16x8 q = *reinterpret_cast<const bf16x8 *>(Q + x * 8);
+    *reinterpret_cast<bf16x8 *>(qs + x * 8) = prescale_q(q, c2);
 }
 
 // Transposition of the selection, two passes over the set bits of PAIRS_HIST_ROWS rows per workgroup.
@@ -443,17 +461,16 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_pairs_kernel(
     // The loop below alternates between two sets of buffers, so that what is loaded here is read only after the
     // other set's step: no register copies, and the wait for these loads (which, the counter being in order, is
     // also a wait for the older stores) finds everything long done.
-    const float c2 = 1.44269504088896340736f / sqrtf((float)D);
-    bool rsel[NS];
-#pragma unroll
-    for (int s = 0; s < NS; ++s) rsel[s] = true;
     auto run_step = [&](RowIds &ids, bf16x8 (&qf)[NS][KSTEPS], int step, int refill) __attribute__((always_inline)) {
+        // (the scores start from minus the reference point of the exponentials: softmax_tile_folded)
         float m_run[NS];
-        f32x4 l_run[NS];
+        bool fresh[NS];
+        f32x4 l_run[NS], sinit[NS];
         f32x4 oacc[NS][DT];
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            m_run[s] = -1e30f;
+            m_run[s] = 0.f;
+            fresh[s] = true;
             l_run[s] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int e = 0; e < DT; ++e) oacc[s][e] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -469,18 +486,23 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_pairs_kernel(
         auto softmax_step = [&](int t) __attribute__((always_inline)) {
             const int key0 = KEY_TILE * t;
             const bool need_mask = OWN || (key0 + KEY_TILE > jsize);
-            softmax_tile<D, 0, NS, NS, false>(sacc, pf, oacc, m_run, l_run, ids.lim, key0, need_mask, c2, q4, rsel);
+            softmax_tile_folded<D, NS>(sacc, pf, oacc, m_run, l_run, fresh, ids.lim, key0, need_mask, q4);
+#pragma unroll
+            for (int s = 0; s < NS; ++s) sinit[s] = f32x4{-m_run[s], -m_run[s], -m_run[s], -m_run[s]};
         };
+#pragma unroll
+        for (int s = 0; s < NS; ++s) sinit[s] = f32x4{0.f, 0.f, 0.f, 0.f};
         phase_prefetch<D, PF, false, true>(nullptr, k_tile(0), n16, q4, ring);
-        mfma_phase<D, NS, PF, false, true>(nullptr, k_tile(0), n16, q4, ring, pf, oacc, l_run, qf, sacc);
+        mfma_phase_from<D, NS, PF, false, true>(nullptr, k_tile(0), n16, q4, ring, pf, oacc, l_run, qf, sinit, sacc);
         softmax_step(0);
         for (int t = 1; t < nts; ++t) {
             phase_prefetch<D, PF, true, true>(v_tile(t - 1), k_tile(t), n16, q4, ring);
-            mfma_phase<D, NS, PF, true, true>(v_tile(t - 1), k_tile(t), n16, q4, ring, pf, oacc, l_run, qf, sacc);
+            mfma_phase_from<D, NS, PF, true, true>(v_tile(t - 1), k_tile(t), n16, q4, ring, pf, oacc, l_run, qf, sinit,
+                                                   sacc);
             softmax_step(t);
         }
         phase_prefetch<D, PF, true, false>(v_tile(nts - 1), nullptr, n16, q4, ring);
-        mfma_phase<D, NS, PF, true, false>(v_tile(nts - 1), nullptr, n16, q4, ring, pf, oacc, l_run, qf, sacc);
+        mfma_phase_from<D, NS, PF, true, false>(v_tile(nts - 1), nullptr, n16, q4, ring, pf, oacc, l_run, qf, sinit, sacc);
 
         uint32_t slot[NS];
 #pragma unroll
@@ -627,10 +649,13 @@ static hipError_t launch_pairs_d(const Geom &g, const uint16_t *Q, const void *p
     const long long most = (long long)std::min<unsigned long long>((unsigned long long)sc.cap, candidate_pairs(g));
     const long long chunks = most / PAIRS_CHUNK + segs;
     const int own_chunks = (g.G * g.Cmax + PAIRS_CHUNK - 1) / PAIRS_CHUNK;
-    hipLaunchKernelGGL((attn_pairs_kernel<D, false>), dim3((unsigned)chunks), dim3(C::THREADS), C::BYTES, st, g, 1, Q, Kp, Vt,
+    const long long q_chunks = R * (D / 8);
+    hipLaunchKernelGGL(pairs_scale_q_kernel, dim3((unsigned)((q_chunks + 255) / 256)), dim3(256), 0, st, g, q_chunks,
+                       1.44269504088896340736f / sqrtf((float)D), flag, Q, sc.qs);
+    hipLaunchKernelGGL((attn_pairs_kernel<D, false>), dim3((unsigned)chunks), dim3(C::THREADS), C::BYTES, st, g, 1, sc.qs, Kp, Vt,
                        csize, sc.pair_ptr, sc.seg_count, sc.seg_start, sc.seg_chunk, sc.entries, flag, sc.rec, sc.ml);
     hipLaunchKernelGGL((attn_pairs_kernel<D, true>), dim3((unsigned)(segs * own_chunks)), dim3(C::THREADS), C::BYTES, st, g,
-                       own_chunks, Q, Kp, Vt, csize, sc.pair_ptr, sc.seg_count, sc.seg_start, sc.seg_chunk, sc.entries, flag, sc.rec, sc.ml);
+                       own_chunks, sc.qs, Kp, Vt, csize, sc.pair_ptr, sc.seg_count, sc.seg_start, sc.seg_chunk, sc.entries, flag, sc.rec, sc.ml);
     const int rows_per_block = 256 / (D / 4);
     const long long merge_blocks = std::min<long long>((R + rows_per_block - 1) / rows_per_block, 256 * 64);
     hipLaunchKernelGGL((pairs_merge_kernel<D>), dim3((unsigned)merge_blocks), dim3(256), 0, st, R, sc.pair_ptr, sc.rec,
