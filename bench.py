@@ -40,7 +40,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM traffic of one sparse-attention launch (bytes), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # scaled by a copy kernel of known size; keyed by (workload, top_p).  See profiles/.
 # (C3, 0.9): attn_walk_kernel<128, true>; (C3, 0.5): the key-stationary kernels together (pairs, own cubes, merge).
-MEASURED_TRAFFIC_BYTES = {("C3", 0.9): 5.2157e9, ("C3", 0.5): 3.752e10}
+MEASURED_TRAFFIC_BYTES = {("C3", 0.9): 5.2157e9, ("C3", 0.5): 3.767e10}
 
 
 def cube_tables(w):
