@@ -241,7 +241,7 @@ def main():
     hbm_bytes = {
         "cube_pool": w.S * w.Hkv * w.D * 2 + N * w.Hkv * w.D * 4,
         "cube_select": R * w.D * 2 + R * words * 4 + R * 4,
-        "kv_pack": 2 * w.S * w.Hkv * w.D * 2 + ws_att.numel(),
+        "kv_pack": 2 * w.S * w.Hkv * w.D * 2 + B.workspace_bytes(sh, B.CALL_SPARSE_ATTN),
     }
     out = {
         "metric": "AdaS-Attn tokens/s at 64K video tokens" if args.workload == "C3" else f"AdaS-Attn tokens/s ({w.name})",
