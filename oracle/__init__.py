@@ -18,3 +18,4 @@ from .adaspark_oracle import (  # noqa: F401
     dense_attn,
     num_threads,
 )
+from . import adaspark_ffn_oracle as ffn  # noqa: F401,E402  (AdaS-FFN, Sec. 3.3)

@@ -131,6 +131,21 @@ def generate(w: Workload):
     return Q, K.to(torch.bfloat16), V
 
 
+def generate_ffn(w: Workload, d_model: int, d_ff: int, norm_sigma: float = 0.6):
+    """-> (X [S,d_model], W_gate [d_ff,d_model], W_up [d_ff,d_model], W_down [d_model,d_ff]) CPU bf16 tensors.
+
+    Token embeddings are N(0,1) vectors, each multiplied by its own log-normal factor exp(norm_sigma * N(0,1)), so
+    that token norms inside a cube are spread like a layer's hidden states rather than all alike; weights are
+    N(0, 1/fan_in) like a freshly initialised layer.
+    """
+    seed = BASE_SEED + 1000 * w.config_id + 500
+    X = _randn((w.S, d_model), seed + 0) * torch.exp(norm_sigma * _randn((w.S, 1), seed + 1))
+    Wg = _randn((d_ff, d_model), seed + 2) * d_model ** -0.5
+    Wu = _randn((d_ff, d_model), seed + 3) * d_model ** -0.5
+    Wd = _randn((d_model, d_ff), seed + 4) * d_ff ** -0.5
+    return tuple(t.to(torch.bfloat16) for t in (X, Wg, Wu, Wd))
+
+
 def sample_rows(w: Workload, n: int, seed: int = 7):
     """A seeded sample of query row ids (row = token * Hq + head), sorted.
 

@@ -1,0 +1,175 @@
+"""Pins for the fp64 oracle of AdaS-FFN (Sec. 3.3): closed forms, a hand-derived worked example, brute force on
+tiny inputs, invariants of Eqs. 4-7, and torch's own linear / silu routines on the case that reduces to a dense
+layer.  Nothing here compares the oracle with itself."""
+import itertools
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_08077_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def shape_of(o, w):
+    return o.Shape(w.T, w.H, w.W, w.ct, w.ch, w.cw, w.Hq, w.Hkv, w.D, w.text, w.lead)
+
+
+def one_cube_shape(o, n):
+    """A video of n tokens in a single row that forms one cube."""
+    return o.Shape(1, 1, n, 1, 1, n, 1, 1, 64)
+
+
+def f64(t):
+    return t.to(torch.float64).numpy()
+
+
+def test_worked_example(oracle):
+    f = oracle.ffn
+    g = json.load(open(os.path.join(GOLDEN, "ffn_worked_example.json")))
+    X = np.array(g["x"], np.float64)
+    eye = np.eye(2)
+    # the fixture's numbers, re-derived from the closed form
+    assert g["ffn_x0"][0] == pytest.approx(16.0 / (1.0 + math.exp(-4.0)), rel=1e-14)
+    assert g["ffn_x1"][1] == pytest.approx(9.0 / (1.0 + math.exp(-3.0)), rel=1e-14)
+    sh = one_cube_shape(oracle, 4)
+    keep, score, _ = f.ffn_select(sh, X, 0.7, eps=g["eps"])
+    np.testing.assert_allclose(score, g["scores"], rtol=1e-15)
+    assert keep.tolist() == g["keep_p0.7"]
+    assert f.ffn_select(sh, X, 0.71, eps=g["eps"])[0].tolist() == g["keep_p0.71"]
+    np.testing.assert_allclose(f.ffn(X[:1], eye, eye, eye)[0], g["ffn_x0"], rtol=1e-14)
+    np.testing.assert_allclose(f.ffn(X[1:2], eye, eye, eye)[0], g["ffn_x1"], rtol=1e-14)
+    Y = f.ffn_sparse(sh, X, eye, eye, eye, keep)
+    np.testing.assert_allclose(Y, g["y_p0.7"], rtol=1e-14)
+
+
+def test_norm_and_importance_closed_forms(oracle):
+    f = oracle.ffn
+    X = np.array([[3.0, 4.0, 0.0], [0.0, 0.0, 0.0], [1.0, 2.0, 2.0], [-6.0, 0.0, 8.0]])
+    np.testing.assert_allclose(f.token_norms(X), [5.0, 0.0, 3.0, 10.0], rtol=1e-15)
+    s = f.importance(np.array([5.0, 0.0, 3.0, 10.0]), eps=2.0)
+    np.testing.assert_allclose(s, [0.25, 0.0, 0.15, 0.5], rtol=1e-15)          # the eps sits in the denominator
+    assert s.sum() == pytest.approx(18.0 / 20.0)
+    # eps large enough that the whole mass stays below p: every token is activated
+    sh = one_cube_shape(oracle, 4)
+    Xn = np.diag([4.0, 3.0, 2.0, 1.0])
+    keep, score, _ = f.ffn_select(sh, Xn, 0.7, eps=10.0)
+    np.testing.assert_allclose(score, [0.2, 0.15, 0.1, 0.05], rtol=1e-15)
+    assert keep.tolist() == [1, 1, 1, 1]
+    # equal norms: s_j = 1/n, ceil(p n) tokens, lowest ranks first
+    keep, _, _ = f.ffn_select(one_cube_shape(oracle, 10), np.ones((10, 3)), 0.35, eps=0.0)
+    assert keep.tolist() == [1, 1, 1, 1] + [0] * 6
+
+
+def brute_nucleus(s, p):
+    """Smallest subset reaching mass p; among those the heaviest; among those the lowest indices.  All if none does."""
+    n = len(s)
+    for k in range(1, n + 1):
+        best = None
+        for sub in itertools.combinations(range(n), k):
+            m = sum(s[j] for j in sub)
+            if best is None or m > best[0] + 1e-15:
+                best = (m, sub)
+        if best[0] >= p:
+            return set(best[1])
+    return set(range(n))
+
+
+def test_top_p_tokens_matches_brute_force(oracle):
+    f = oracle.ffn
+    rng = np.random.default_rng(5)
+    for trial in range(200):
+        n = int(rng.integers(1, 8))
+        s = rng.random(n) ** 2 + 0.01 * np.arange(n)[::-1]      # distinct values
+        s = s / s.sum() * rng.uniform(0.6, 1.0)                  # total mass may stay below p
+        p = float(rng.uniform(0.05, 0.95))
+        keep, order, before = f.top_p_tokens(s, p)
+        assert set(np.nonzero(keep)[0].tolist()) == brute_nucleus(s.tolist(), p), (trial, s, p)
+        assert list(order) == sorted(range(n), key=lambda j: -s[j])
+    # ties go to the lower index; p = 0 keeps none, p = 1 all
+    s = np.array([0.25, 0.25, 0.25, 0.25])
+    assert f.top_p_tokens(s, 0.5)[0].tolist() == [True, True, False, False]
+    assert f.top_p_tokens(s, 0.51)[0].tolist() == [True, True, True, False]
+    assert not f.top_p_tokens(s, 0.0)[0].any()
+    assert f.top_p_tokens(s * 0.9, 1.0)[0].all()
+
+
+@pytest.mark.parametrize("name", ["T_tiny", "T_ragged", "T_lead64"])
+def test_selection_on_grids(oracle, name):
+    """Cubes are those of Sec. 3.1; text tokens are always activated; every video cube keeps the heaviest tokens."""
+    f = oracle.ffn
+    w = synth.TEST_WORKLOADS[name]
+    sh = shape_of(oracle, w)
+    X = f64(synth.generate_ffn(w, 32, 64)[0])
+    keep, score, _ = f.ffn_select(sh, X, 0.6, eps=1e-6)
+    norms = np.linalg.norm(X, axis=1)
+    video = w.T * w.H * w.W
+    assert keep[: w.lead].all() and keep[w.lead + video:].all()
+    nH, nW = -(-w.H // w.ch), -(-w.W // w.cw)
+    groups = {}
+    for n in range(video):
+        t, h, x = n // (w.H * w.W), (n // w.W) % w.H, n % w.W
+        groups.setdefault(((t // w.ct) * nH + h // w.ch) * nW + x // w.cw, []).append(w.lead + n)
+    assert len(groups) == oracle.num_cubes(sh) - (-(-w.lead // (w.ct * w.ch * w.cw))) - (-(-w.text // (w.ct * w.ch * w.cw)))
+    for toks in groups.values():
+        toks = np.array(toks)
+        tot = norms[toks].sum() + 1e-6
+        np.testing.assert_allclose(score[toks], norms[toks] / tot, rtol=1e-13)
+        k = keep[toks].astype(bool)
+        assert k.any()
+        assert norms[toks][k].min() >= norms[toks][~k].max() if (~k).any() else True
+        mass = score[toks][k].sum()
+        assert mass >= 0.6 - 1e-12 or k.all()
+        assert mass - score[toks][k].min() < 0.6           # minimal: dropping the lightest kept token falls short
+
+
+def test_all_tokens_activated_is_the_dense_layer(oracle):
+    """p -> 1 (and the dense entry): y = x + W_down(silu(W_gate x) * W_up x), checked with torch's own routines."""
+    f = oracle.ffn
+    w = synth.TEST_WORKLOADS["T_tiny"]
+    sh = shape_of(oracle, w)
+    X, Wg, Wu, Wd = (t.to(torch.float64) for t in synth.generate_ffn(w, 48, 80))
+    lin = torch.nn.functional.linear
+    want = X + lin(torch.nn.functional.silu(lin(X, Wg)) * lin(X, Wu), Wd)
+    keep, _, _ = f.ffn_select(sh, X.numpy(), 1.0)
+    assert keep.all()
+    got = f.ffn_sparse(sh, X.numpy(), Wg.numpy(), Wu.numpy(), Wd.numpy(), keep)
+    np.testing.assert_allclose(got, want.numpy(), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(f.ffn_dense(X.numpy(), Wg.numpy(), Wu.numpy(), Wd.numpy()), want.numpy(), rtol=1e-12, atol=1e-12)
+
+
+def test_mean_compensation_invariants(oracle):
+    """Eq. 7: inside a cube all bypassed tokens move by the same vector, the mean of the activated tokens' moves;
+    activated tokens move exactly as in the dense layer; a cube without activated tokens does not move."""
+    f = oracle.ffn
+    w = synth.TEST_WORKLOADS["T_ragged"]
+    sh = shape_of(oracle, w)
+    X, Wg, Wu, Wd = (f64(t) for t in synth.generate_ffn(w, 32, 64))
+    keep, _, _ = f.ffn_select(sh, X, 0.5)
+    Y = f.ffn_sparse(sh, X, Wg, Wu, Wd, keep)
+    dense = f.ffn_dense(X, Wg, Wu, Wd)
+    cube_of = oracle.cube_map(sh)[0]
+    act = keep.astype(bool)
+    np.testing.assert_allclose(Y[act], dense[act], rtol=1e-13, atol=1e-13)
+    assert 0.2 < act.mean() < 0.8
+    for c in np.unique(cube_of):
+        m = cube_of == c
+        move = (Y - X)[m & ~act]
+        mean = (dense - X)[m & act].mean(axis=0)
+        np.testing.assert_allclose(move, np.broadcast_to(mean, move.shape), rtol=1e-12, atol=1e-12)
+    none = np.zeros_like(keep)
+    np.testing.assert_array_equal(f.ffn_sparse(sh, X, Wg, Wu, Wd, none), X)
+
+
+def test_near_cut_flags_the_boundary(oracle):
+    f = oracle.ffn
+    sh = one_cube_shape(oracle, 4)
+    Xn = np.diag([4.0, 3.0, 2.0, 1.0])
+    assert f.ffn_select(sh, Xn, 0.7, eps=0.0)[2][0] == 1       # the mass before token 2 equals p
+    assert f.ffn_select(sh, Xn, 0.6, eps=0.0)[2][0] == 0
+    Xt = np.diag([4.0, 3.0, 3.0, 1.0])
+    assert f.ffn_select(sh, Xt, 0.5, eps=0.0)[2][0] == 1       # last kept and first dropped tie
