@@ -207,6 +207,57 @@ int adaspark_sparse_attn_packed_with(const adaspark_shape *shape, const void *Q,
 int adaspark_dense_attn_packed(const adaspark_shape *shape, const void *Q, const void *packed, size_t packed_bytes,
                                int causal, void *O, float *lse, void *stream);
 
+/*
+ * Adaptive Token-Selective FFN (AdaS-FFN, Sec. 3.3, Eqs. 4-7).  Inside every video cube the tokens with the largest
+ * L2 norms, a Top-p nucleus of the cube's importance distribution, take the feed-forward layer; the others receive
+ * the mean of what the layer added to the activated tokens of their cube.
+ *
+ * The token sequence and its cubes are those of the attention entries (same adaspark_shape; q_heads, kv_heads and
+ * head_dim must be valid but are not used).  The layer is the gated MLP of the backbone the paper builds on:
+ *   FFN(x) = W_down . (silu(W_gate . x) * (W_up . x)),  no biases,
+ *   X, Y      bf16 [tokens][d_model]
+ *   W_gate, W_up  bf16 [d_ff][d_model];  W_down  bf16 [d_model][d_ff]   (row = output feature)
+ * Products accumulate in fp32; the hidden activations silu(.)*(.) are rounded to bf16 once, between the two
+ * matrix products; the residual sum is rounded to bf16 once, on output.
+ * Limits: d_model a multiple of 256 up to 16384; d_ff a multiple of 128 up to 65536; a cube of at most 4096 tokens;
+ * tokens * d_model < 2^30.  Otherwise ADASPARK_EUNSUPPORTED.
+ */
+typedef struct {
+    int32_t d_model; /* width of a token embedding                      */
+    int32_t d_ff;    /* hidden width of the feed-forward layer          */
+} adaspark_ffn_dims;
+
+/* Workspace of adaspark_ffn_sparse: tables of the activated tokens, their hidden activations (bf16, d_ff per
+ * token) and the layer's output for them (fp32, d_model per token), sized for all tokens activated. */
+int adaspark_ffn_workspace_bytes(const adaspark_shape *shape, const adaspark_ffn_dims *dims, size_t *bytes);
+
+/*
+ * Importance scores and Top-p token selection (Eqs. 4-5).  For every video cube C_i:
+ * s_j = ||x_j||_2 / (sum over the cube of ||x_k||_2 + eps) in fp32; tokens ranked by s_j descending (ties: lower rank
+ * inside the cube first); a token is activated iff the scores ranked before it sum to less than top_p.  top_p >= 1
+ * activates every token, top_p == 0 none.  Text tokens are always activated (end of Sec. 3.3).
+ *   X          in   bf16 [tokens][d_model]
+ *   keep       out  u8   [tokens]   1: activated (set M_i), 0: bypassed (set R_i)
+ *   score      out  fp32 [tokens]   s_j, or NULL
+ *   keep_count out  i32  [cubes]    activated tokens per cube, or NULL
+ * eps must be >= 0 and top_p in [0, 1].  No workspace.
+ */
+int adaspark_ffn_select(const adaspark_shape *shape, const adaspark_ffn_dims *dims, const void *X, float top_p,
+                        float eps, uint8_t *keep, float *score, int32_t *keep_count, void *stream);
+
+/*
+ * The layer with mean compensation (Eqs. 6-7):
+ *   y_j = x_j + FFN(x_j)                                   for activated tokens (keep[j] != 0),
+ *   y_k = x_k + mean over the activated tokens of k's cube of FFN(x_j)   for the others;
+ * a cube without activated tokens is copied unchanged.  keep == NULL activates every token: the dense layer
+ * y = x + FFN(x), the comparison point.  `keep` is honoured as given, for text cubes too.
+ *   Y          out  bf16 [tokens][d_model]   (must not alias X)
+ *   workspace       adaspark_ffn_workspace_bytes
+ */
+int adaspark_ffn_sparse(const adaspark_shape *shape, const adaspark_ffn_dims *dims, const void *X, const void *W_gate,
+                        const void *W_up, const void *W_down, const uint8_t *keep, void *Y, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -58,6 +58,10 @@ class Shape:
         return Shape(w.T, w.H, w.W, w.ct, w.ch, w.cw, w.Hq, w.Hkv, w.D, w.text, w.lead)
 
 
+class _CFfnDims(ctypes.Structure):
+    _fields_ = [("d_model", ctypes.c_int32), ("d_ff", ctypes.c_int32)]
+
+
 class AdasparkError(RuntimeError):
     def __init__(self, status: int, what: str):
         self.status = status
@@ -80,6 +84,9 @@ EXPORTS = (
     "adaspark_sparse_attn_packed",
     "adaspark_sparse_attn_packed_with",
     "adaspark_dense_attn_packed",
+    "adaspark_ffn_workspace_bytes",
+    "adaspark_ffn_select",
+    "adaspark_ffn_sparse",
 )
 
 SPARSE_AUTO, SPARSE_COMPACT, SPARSE_MASKED, SPARSE_PAIRS = 0, 1, 2, 3
@@ -113,6 +120,10 @@ def load():
         lib.adaspark_sparse_attn_packed_with.argtypes = [sp, vp, vp, ctypes.c_size_t, vp, ctypes.c_int, ctypes.c_int,
                                                          vp, vp, vp]
         lib.adaspark_dense_attn_packed.argtypes = [sp, vp, vp, ctypes.c_size_t, ctypes.c_int, vp, vp, vp]
+        dp = ctypes.POINTER(_CFfnDims)
+        lib.adaspark_ffn_workspace_bytes.argtypes = [sp, dp, ctypes.POINTER(ctypes.c_size_t)]
+        lib.adaspark_ffn_select.argtypes = [sp, dp, vp, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp]
+        lib.adaspark_ffn_sparse.argtypes = [sp, dp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         for name in EXPORTS:
             if name != "adaspark_status_string":
                 getattr(lib, name).restype = ctypes.c_int
@@ -308,3 +319,45 @@ def sparse_attn_packed(shape: Shape, Q, packed, sel_mask, causal: bool = True, O
 
 def dense_attn_packed(shape: Shape, Q, packed, causal: bool = True, O=None, lse=None, return_lse: bool = False):
     return _attn_packed("adaspark_dense_attn_packed", shape, Q, packed, None, causal, O, lse, return_lse)
+
+
+def ffn_workspace_bytes(shape: Shape, d_model: int, d_ff: int) -> int:
+    n = ctypes.c_size_t(0)
+    cs, cd = shape._c(), _CFfnDims(d_model, d_ff)
+    _check(load().adaspark_ffn_workspace_bytes(ctypes.byref(cs), ctypes.byref(cd), ctypes.byref(n)),
+           "adaspark_ffn_workspace_bytes")
+    return int(n.value)
+
+
+def ffn_select(shape: Shape, X: torch.Tensor, d_ff: int, top_p: float, eps: float = 1e-6):
+    """Sec. 3.3, Eqs. 4-5: X bf16 [S, d_model] -> (keep uint8 [S], score fp32 [S], keep_count int32 [cubes])."""
+    d_model = X.shape[-1]
+    S, N = shape.tokens, num_cubes(shape)
+    keep = torch.empty(S, dtype=torch.uint8, device=X.device)
+    score = torch.empty(S, dtype=torch.float32, device=X.device)
+    count = torch.empty(N, dtype=torch.int32, device=X.device)
+    cs, cd = shape._c(), _CFfnDims(d_model, d_ff)
+    _check(load().adaspark_ffn_select(
+        ctypes.byref(cs), ctypes.byref(cd), _dev(X, torch.bfloat16, S * d_model, "X"), ctypes.c_float(top_p),
+        ctypes.c_float(eps), _dev(keep, torch.uint8, S, "keep"), _dev(score, torch.float32, S, "score"),
+        _dev(count, torch.int32, N, "keep_count"), _stream()), "adaspark_ffn_select")
+    return keep, score, count
+
+
+def ffn_sparse(shape: Shape, X, W_gate, W_up, W_down, keep=None, Y=None, workspace=None) -> torch.Tensor:
+    """Sec. 3.3, Eqs. 6-7: the gated FFN on the activated tokens, mean compensation for the others.
+    keep None: every token takes the layer (the dense layer)."""
+    S, d_model, d_ff = shape.tokens, X.shape[-1], W_gate.shape[0]
+    if Y is None:
+        Y = torch.empty_like(X)
+    if workspace is None:
+        workspace = torch.empty(ffn_workspace_bytes(shape, d_model, d_ff), dtype=torch.uint8, device=X.device)
+    cs, cd = shape._c(), _CFfnDims(d_model, d_ff)
+    _check(load().adaspark_ffn_sparse(
+        ctypes.byref(cs), ctypes.byref(cd), _dev(X, torch.bfloat16, S * d_model, "X"),
+        _dev(W_gate, torch.bfloat16, d_ff * d_model, "W_gate"), _dev(W_up, torch.bfloat16, d_ff * d_model, "W_up"),
+        _dev(W_down, torch.bfloat16, d_ff * d_model, "W_down"),
+        None if keep is None else _dev(keep, torch.uint8, S, "keep"), _dev(Y, torch.bfloat16, S * d_model, "Y"),
+        _dev(workspace, torch.uint8, workspace.numel(), "workspace"), workspace.numel(), _stream()),
+        "adaspark_ffn_sparse")
+    return Y

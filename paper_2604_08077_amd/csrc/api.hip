@@ -1,5 +1,6 @@
 // extern "C" boundary of the library: argument validation and kernel enqueueing only.
 #include "geom.h"
+#include "ffn.h"
 
 using namespace adaspark;
 
@@ -24,6 +25,18 @@ int check_shape(const adaspark_shape *s)
                     nw = (s->width + (long long)s->cube_w - 1) / s->cube_w;
     if (nt * nh * nw + (s->text_tokens + cube - 1) / cube + (s->prefix_tokens + cube - 1) / cube > ADASPARK_MAX_CUBES)
         return ADASPARK_EUNSUPPORTED;
+    return ADASPARK_OK;
+}
+
+int check_ffn(const adaspark_shape *s, const adaspark_ffn_dims *d)
+{
+    const int rc = check_shape(s);
+    if (rc != ADASPARK_OK) return rc;
+    if (d == nullptr || d->d_model <= 0 || d->d_ff <= 0) return ADASPARK_EINVAL;
+    if (d->d_model % 256 != 0 || d->d_model > 16384 || d->d_ff % 128 != 0 || d->d_ff > 65536) return ADASPARK_EUNSUPPORTED;
+    if ((long long)s->cube_t * s->cube_h * s->cube_w > FFN_MAX_CUBE_TOKENS) return ADASPARK_EUNSUPPORTED;
+    const long long tokens = (long long)s->frames * s->height * s->width + s->text_tokens + s->prefix_tokens;
+    if (tokens * d->d_model >= (1ll << 30)) return ADASPARK_EUNSUPPORTED;
     return ADASPARK_OK;
 }
 
@@ -241,6 +254,48 @@ int adaspark_dense_attn(const adaspark_shape *shape, const void *Q, const void *
                         float *lse, void *workspace, size_t workspace_bytes, void *stream)
 {
     return attn_full(shape, Q, K, V, nullptr, false, causal, O, lse, workspace, workspace_bytes, stream);
+}
+
+int adaspark_ffn_workspace_bytes(const adaspark_shape *shape, const adaspark_ffn_dims *dims, size_t *bytes)
+{
+    const int rc = check_ffn(shape, dims);
+    if (rc != ADASPARK_OK) return rc;
+    if (bytes == nullptr) return ADASPARK_EINVAL;
+    *bytes = ffn_workspace(make_geom(*shape), dims->d_model, dims->d_ff, nullptr).bytes;
+    return ADASPARK_OK;
+}
+
+int adaspark_ffn_select(const adaspark_shape *shape, const adaspark_ffn_dims *dims, const void *X, float top_p,
+                        float eps, uint8_t *keep, float *score, int32_t *keep_count, void *stream)
+{
+    int rc = check_ffn(shape, dims);
+    if (rc != ADASPARK_OK) return rc;
+    if ((rc = check_ptrs({X, keep})) != ADASPARK_OK) return rc;
+    if ((score != nullptr && !aligned16(score)) || (keep_count != nullptr && !aligned16(keep_count))) return ADASPARK_EINVAL;
+    if (!(top_p >= 0.0f && top_p <= 1.0f) || !(eps >= 0.0f) || eps > 3.0e38f) return ADASPARK_EINVAL;
+    const hipError_t e = launch_ffn_select(make_geom(*shape), dims->d_model, static_cast<const uint16_t *>(X), top_p, eps,
+                                           keep, score, keep_count, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ADASPARK_OK : ADASPARK_EHIP;
+}
+
+int adaspark_ffn_sparse(const adaspark_shape *shape, const adaspark_ffn_dims *dims, const void *X, const void *W_gate,
+                        const void *W_up, const void *W_down, const uint8_t *keep, void *Y, void *workspace,
+                        size_t workspace_bytes, void *stream)
+{
+    int rc = check_ffn(shape, dims);
+    if (rc != ADASPARK_OK) return rc;
+    if ((rc = check_ptrs({X, W_gate, W_up, W_down, Y})) != ADASPARK_OK) return rc;
+    if (keep != nullptr && !aligned16(keep)) return ADASPARK_EINVAL;
+    if (X == Y) return ADASPARK_EINVAL;
+    const Geom g = make_geom(*shape);
+    if (workspace == nullptr || !aligned16(workspace) ||
+        workspace_bytes < ffn_workspace(g, dims->d_model, dims->d_ff, nullptr).bytes)
+        return ADASPARK_EWORKSPACE;
+    const hipError_t e = launch_ffn_sparse(g, dims->d_model, dims->d_ff, static_cast<const uint16_t *>(X),
+                                           static_cast<const uint16_t *>(W_gate), static_cast<const uint16_t *>(W_up),
+                                           static_cast<const uint16_t *>(W_down), keep, static_cast<uint16_t *>(Y), workspace,
+                                           static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ADASPARK_OK : ADASPARK_EHIP;
 }
 
 }  // extern "C"
