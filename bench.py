@@ -112,6 +112,41 @@ def cpu_baseline(w, p, Q, K, V, budget_rows_sel=262144, budget_rows_attn=24576):
     }
 
 
+# Widths of the token-selective FFN leg: the 7B backbone the 28-head attention configurations correspond to
+# (28 heads x 128 = 3584 model width, 18944 hidden width).
+FFN_D_MODEL, FFN_D_FF, FFN_TOP_P = 3584, 18944, 0.7
+
+
+def ffn_leg(B, w, steps):
+    """AdaS-FFN (Sec. 3.3) on the same token grid: selection + sparse layer at the paper's default p = 0.7, timed
+    with HIP events on the launch stream; the dense layer (every token activated) beside it."""
+    sh = B.Shape.of(w)
+    X, Wg, Wu, Wd = (t.cuda() for t in synth.generate_ffn(w, FFN_D_MODEL, FFN_D_FF))
+    ws = torch.empty(B.ffn_workspace_bytes(sh, FFN_D_MODEL, FFN_D_FF), dtype=torch.uint8, device="cuda")
+    Y = torch.empty_like(X)
+    keep, _, _ = B.ffn_select(sh, X, FFN_D_FF, FFN_TOP_P)
+    share = float(keep.float().mean().item())
+    B.ffn_sparse(sh, X, Wg, Wu, Wd, keep=keep, Y=Y, workspace=ws)  # untimed first launch
+    t_sel = timed(lambda: B.ffn_select(sh, X, FFN_D_FF, FFN_TOP_P), steps)
+    t_sparse = timed(lambda: B.ffn_sparse(sh, X, Wg, Wu, Wd, keep=keep, Y=Y, workspace=ws), steps)
+    t_dense = timed(lambda: B.ffn_sparse(sh, X, Wg, Wu, Wd, keep=None, Y=Y, workspace=ws), max(2, steps // 3))
+    flops = 6.0 * share * w.S * FFN_D_MODEL * FFN_D_FF  # three matrix products on the activated tokens
+    tf = flops / (t_sparse * 1e-3) / 1e12
+    return {
+        "workload": f"{w.name} token grid, d_model {FFN_D_MODEL}, d_ff {FFN_D_FF}, gated MLP, top_p {FFN_TOP_P}, "
+                    "synthetic bf16 embeddings with log-normal norms",
+        "tokens_per_s": w.S / ((t_sel + t_sparse) * 1e-3),
+        "activated_share": share,
+        "ms": {"ffn_select": t_sel, "ffn_sparse": t_sparse, "ffn_dense": t_dense},
+        "speedup_vs_dense": t_dense / (t_sel + t_sparse),
+        "roofline": {"kernel": "ffn_gemm_kernel<true> + ffn_gemm_kernel<false> (whole adaspark_ffn_sparse call)",
+                     "bound": "mfma", "achieved": tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tf / PEAK_BF16_TFLOPS, "traffic": None},
+        "dense_tflops": 6.0 * w.S * FFN_D_MODEL * FFN_D_FF / (t_dense * 1e-3) / 1e12,
+        "select_hbm_gbs": w.S * FFN_D_MODEL * 2 / (t_sel * 1e-3) / 1e9,
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -121,6 +156,7 @@ def main():
     ap.add_argument("--top-p", type=float, default=0.9)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-ffn", action="store_true", help="skip the token-selective FFN leg (Sec. 3.3)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 1 GiB device copy after the timed region: the known-size "
                          "reference the HBM counters of a rocprofv3 --pmc run are scaled by")
@@ -282,6 +318,10 @@ def main():
             "executed_tflops": None if executed_flops is None else executed_flops / (attn_kernel_ms * 1e-3) / 1e12,
         },
     }
+    if not args.no_ffn and w.S * FFN_D_MODEL < (1 << 30):
+        del ws_att, mask, count, O
+        torch.cuda.empty_cache()
+        out["adas_ffn"] = ffn_leg(B, w, args.steps)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, p, Q, K, V)
     print(json.dumps(out), flush=True)

@@ -11,6 +11,7 @@ namespace {
 
 constexpr int SEL_THREADS = 1024;
 constexpr int TAB_THREADS = 256;
+constexpr int FIN_THREADS = 1024;
 
 __device__ __forceinline__ float wave_sum(float x)
 {
@@ -188,43 +189,55 @@ __global__ __launch_bounds__(TAB_THREADS) void ffn_fill_kernel(Geom g, const uin
 }
 
 // Eqs. 6-7 for cube blockIdx.x: F holds FFN(x) of the activated tokens (fp32, row = index in the active list).
-__global__ __launch_bounds__(TAB_THREADS) void ffn_finish_kernel(Geom g, int d_model, const uint16_t *__restrict__ X,
+// A thread owns four columns (per block of 4 * FIN_THREADS columns): it walks the cube's activated rows once,
+// writing y = x + F and summing F (rows in list order), then gives the bypassed tokens x + mean.
+__global__ __launch_bounds__(FIN_THREADS) void ffn_finish_kernel(Geom g, int d_model, const uint16_t *__restrict__ X,
                                                                  const float *__restrict__ F,
                                                                  const int32_t *__restrict__ cube_ptr,
+                                                                 const int32_t *__restrict__ active,
                                                                  const int32_t *__restrict__ slot, uint16_t *__restrict__ Y)
 {
-    extern __shared__ float mean[];  // [d_model]
     const int c = blockIdx.x;
     const CubeBox b = cube_box(g, c);
     const int n = b.size();
     const int first = cube_ptr[c], count = cube_ptr[c + 1] - first;
-    // column means of the cube's rows of F, rows added in list order
     const float inv = count > 0 ? 1.0f / (float)count : 0.f;
-    for (int col = 4 * threadIdx.x; col < d_model; col += 4 * TAB_THREADS) {
+    auto add_store = [&](int tok, int col, const f32x4 &f) __attribute__((always_inline)) {
+        const uint2 xv = *reinterpret_cast<const uint2 *>(X + (size_t)tok * d_model + col);
+        uint2 o;
+        o.x = (uint32_t)float_to_bf16_bits(__uint_as_float(xv.x << 16) + f[0]) |
+              ((uint32_t)float_to_bf16_bits(__uint_as_float(xv.x & 0xffff0000u) + f[1]) << 16);
+        o.y = (uint32_t)float_to_bf16_bits(__uint_as_float(xv.y << 16) + f[2]) |
+              ((uint32_t)float_to_bf16_bits(__uint_as_float(xv.y & 0xffff0000u) + f[3]) << 16);
+        *reinterpret_cast<uint2 *>(Y + (size_t)tok * d_model + col) = o;
+    };
+    for (int col = 4 * threadIdx.x; col < d_model; col += 4 * FIN_THREADS) {
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         const float *f = F + (size_t)first * d_model + col;
-        for (int r = 0; r < count; ++r) acc += *reinterpret_cast<const f32x4 *>(f + (size_t)r * d_model);
-        *reinterpret_cast<f32x4 *>(mean + col) = acc * inv;
-    }
-    __syncthreads();
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    for (int j = wave; j < n; j += TAB_THREADS / 64) {
-        const int tok = token_of(g, b, j);
-        const int sl = slot[tok];
-        const uint16_t *x = X + (size_t)tok * d_model;
-        uint16_t *y = Y + (size_t)tok * d_model;
-        const float *f = sl >= 0 ? F + (size_t)sl * d_model : mean;
-        for (int k = 8 * lane; k < d_model; k += 8 * 64) {
-            const u32x4 xv = *reinterpret_cast<const u32x4 *>(x + k);
-            const f32x4 f0 = *reinterpret_cast<const f32x4 *>(f + k), f1 = *reinterpret_cast<const f32x4 *>(f + k + 4);
-            u32x4 out;
+        int r = 0;
+        for (; r + 4 <= count; r += 4) {
+            f32x4 v[4];
+            int tok[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float lo = __uint_as_float(xv[e] << 16) + (e < 2 ? f0[2 * e] : f1[2 * e - 4]);
-                const float hi = __uint_as_float(xv[e] & 0xffff0000u) + (e < 2 ? f0[2 * e + 1] : f1[2 * e - 3]);
-                out[e] = (uint32_t)float_to_bf16_bits(lo) | ((uint32_t)float_to_bf16_bits(hi) << 16);
+            for (int u = 0; u < 4; ++u) {
+                v[u] = *reinterpret_cast<const f32x4 *>(f + (size_t)(r + u) * d_model);
+                tok[u] = active[first + r + u];
             }
-            *reinterpret_cast<u32x4 *>(y + k) = out;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                acc += v[u];
+                add_store(tok[u], col, v[u]);
+            }
+        }
+        for (; r < count; ++r) {
+            const f32x4 v = *reinterpret_cast<const f32x4 *>(f + (size_t)r * d_model);
+            acc += v;
+            add_store(active[first + r], col, v);
+        }
+        const f32x4 mean = acc * inv;
+        for (int j = 0; j < n; ++j) {
+            const int tok = token_of(g, b, j);
+            if (slot[tok] < 0) add_store(tok, col, mean);
         }
     }
 }
@@ -274,8 +287,8 @@ hipError_t launch_ffn_sparse(const Geom &g, int d_model, int d_ff, const uint16_
     if (e != hipSuccess) return e;
     e = launch_ffn_gemm_down(w.H, Wd, d_ff, d_model, m_tiles, w.cube_ptr + g.N, w.F, st);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(ffn_finish_kernel, dim3(g.N), dim3(TAB_THREADS), (size_t)d_model * sizeof(float), st, g, d_model,
-                       X, w.F, w.cube_ptr, w.slot, Y);
+    hipLaunchKernelGGL(ffn_finish_kernel, dim3(g.N), dim3(FIN_THREADS), 0, st, g, d_model, X, w.F, w.cube_ptr, w.active,
+                       w.slot, Y);
     return hipGetLastError();
 }
 

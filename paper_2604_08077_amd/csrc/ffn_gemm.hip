@@ -99,21 +99,34 @@ __global__ __launch_bounds__(GEMM_THREADS) void ffn_gemm_kernel(const uint16_t *
 #pragma unroll
         for (int g = 0; g < 4; ++g) acc[s][g] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    // One reduction step: 16 groups of four MFMAs (half c of the step, slab s), each needing one activation operand
+    // and the half's four weight operands.  Operand loads run three groups ahead of their use through a ring of
+    // four registers, the second half's weights arrive under the first half's MFMAs, and the written order is kept.
     auto compute = [&](int stage) __attribute__((always_inline)) {
         const unsigned char *ta = smem + stage * STAGE_BYTES + wm * (128 * 128);
         const unsigned char *tw = smem + stage * STAGE_BYTES + TILE_BYTES;
+        auto load_a = [&](int i) __attribute__((always_inline)) {
+            return *reinterpret_cast<const bf16x8 *>(ta + (i & 7) * 2048 + lo[i >> 3]);
+        };
+        auto load_w = [&](int c, int g) __attribute__((always_inline)) {
+            return *reinterpret_cast<const bf16x8 *>(tw + wrow[g] * 128 + lo[c]);
+        };
+        bf16x8 wf[2][4], ring[4];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            bf16x8 wf[4];
+        for (int g = 0; g < 4; ++g) wf[0][g] = load_w(0, g);
 #pragma unroll
-            for (int g = 0; g < 4; ++g) wf[g] = *reinterpret_cast<const bf16x8 *>(tw + wrow[g] * 128 + lo[c]);
+        for (int i = 0; i < 3; ++i) ring[i] = load_a(i);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int s = 0; s < 8; ++s) {
-                const bf16x8 af = *reinterpret_cast<const bf16x8 *>(ta + s * 2048 + lo[c]);
+        for (int i = 0; i < 16; ++i) {
+            const int c = i >> 3, sl = i & 7;
 #pragma unroll
-                for (int g = 0; g < 4; ++g)
-                    acc[s][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[g], af, acc[s][g], 0, 0, 0);
-            }
+            for (int g = 0; g < 4; ++g)
+                acc[sl][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[c][g], ring[i & 3], acc[sl][g], 0, 0, 0);
+            if (i + 3 < 16) ring[(i + 3) & 3] = load_a(i + 3);
+            if (i >= 1 && i <= 4) wf[1][i - 1] = load_w(1, i - 1);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 

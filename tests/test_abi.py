@@ -109,6 +109,33 @@ def test_bad_pointers_and_arguments_are_rejected_before_launch(lib):
     assert lib.adaspark_pairs_workspace_bytes(ctypes.byref(huge), 1, ctypes.byref(big)) == -2
 
 
+def test_ffn_arguments_are_validated_before_launch(lib):
+    cs = _raw_shape()._c()
+    ok_ptr = ctypes.c_void_p(4096)      # never dereferenced: validation fails first
+    dims = lambda m, f: ctypes.byref(binding._CFfnDims(m, f))
+    n = ctypes.c_size_t(0)
+    assert lib.adaspark_ffn_workspace_bytes(ctypes.byref(cs), dims(256, 384), ctypes.byref(n)) == 0
+    tokens, rows = 4 * 8 * 8, 256
+    assert n.value >= rows * 384 * 2 + rows * 256 * 4 + 2 * tokens * 4     # hidden activations, FFN values, tables
+    assert lib.adaspark_ffn_workspace_bytes(ctypes.byref(cs), dims(256, 384), None) == -1
+    assert lib.adaspark_ffn_workspace_bytes(ctypes.byref(cs), None, ctypes.byref(n)) == -1
+    for m, f, code in ((0, 384, -1), (256, -128, -1), (200, 384, -2), (256, 100, -2), (32768, 384, -2), (256, 1 << 17, -2)):
+        assert lib.adaspark_ffn_workspace_bytes(ctypes.byref(cs), dims(m, f), ctypes.byref(n)) == code
+    big_cube = binding.Shape(8, 32, 32, 8, 32, 32, 4, 4, 64)._c()           # a cube of 8192 tokens
+    assert lib.adaspark_ffn_workspace_bytes(ctypes.byref(big_cube), dims(256, 384), ctypes.byref(n)) == -2
+    long_video = binding.Shape(4096, 16, 16, 4, 8, 8, 4, 4, 64)._c()        # tokens * d_model does not fit 2^30
+    assert lib.adaspark_ffn_workspace_bytes(ctypes.byref(long_video), dims(4096, 384), ctypes.byref(n)) == -2
+    sel = lambda p, eps, x=ok_ptr, keep=ok_ptr: lib.adaspark_ffn_select(
+        ctypes.byref(cs), dims(256, 384), x, ctypes.c_float(p), ctypes.c_float(eps), keep, None, None, None)
+    assert sel(1.5, 1e-6) == -1 and sel(float("nan"), 1e-6) == -1 and sel(0.7, -1.0) == -1
+    assert sel(0.7, 1e-6, x=None) == -1 and sel(0.7, 1e-6, keep=ctypes.c_void_p(4097)) == -1
+    run = lambda ws, nbytes, x=ok_ptr, y=ctypes.c_void_p(8192): lib.adaspark_ffn_sparse(
+        ctypes.byref(cs), dims(256, 384), x, ok_ptr, ok_ptr, ok_ptr, None, y, ws, nbytes, None)
+    assert run(None, 1 << 30) == -3 and run(ok_ptr, 64) == -3
+    assert run(ok_ptr, 1 << 30, y=ok_ptr) == -1                              # Y aliases X
+    assert run(ok_ptr, 1 << 30, x=None) == -1
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
     w = synth.TEST_WORKLOADS["T_tiny"]
