@@ -115,9 +115,12 @@ def cpu_baseline(w, p, Q, K, V, budget_rows_sel=262144, budget_rows_attn=24576):
 # Widths of the token-selective FFN leg: the 7B backbone the 28-head attention configurations correspond to
 # (28 heads x 128 = 3584 model width, 18944 hidden width).
 FFN_D_MODEL, FFN_D_FF, FFN_TOP_P = 3584, 18944, 0.7
+# Bytes the two matrix-product kernels of one adaspark_ffn_sparse call move between the L2 caches and the fabric
+# (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size; see profiles/), keyed by workload.
+FFN_MEASURED_TRAFFIC_BYTES = {"C3": 2.237e10}
 
 
-def ffn_leg(B, w, steps):
+def ffn_leg(B, w, steps, dense=True):
     """AdaS-FFN (Sec. 3.3) on the same token grid: selection + sparse layer at the paper's default p = 0.7, timed
     with HIP events on the launch stream; the dense layer (every token activated) beside it."""
     sh = B.Shape.of(w)
@@ -129,7 +132,7 @@ def ffn_leg(B, w, steps):
     B.ffn_sparse(sh, X, Wg, Wu, Wd, keep=keep, Y=Y, workspace=ws)  # untimed first launch
     t_sel = timed(lambda: B.ffn_select(sh, X, FFN_D_FF, FFN_TOP_P), steps)
     t_sparse = timed(lambda: B.ffn_sparse(sh, X, Wg, Wu, Wd, keep=keep, Y=Y, workspace=ws), steps)
-    t_dense = timed(lambda: B.ffn_sparse(sh, X, Wg, Wu, Wd, keep=None, Y=Y, workspace=ws), max(2, steps // 3))
+    t_dense = timed(lambda: B.ffn_sparse(sh, X, Wg, Wu, Wd, keep=None, Y=Y, workspace=ws), max(2, steps // 3)) if dense else None
     flops = 6.0 * share * w.S * FFN_D_MODEL * FFN_D_FF  # three matrix products on the activated tokens
     tf = flops / (t_sparse * 1e-3) / 1e12
     return {
@@ -138,11 +141,11 @@ def ffn_leg(B, w, steps):
         "tokens_per_s": w.S / ((t_sel + t_sparse) * 1e-3),
         "activated_share": share,
         "ms": {"ffn_select": t_sel, "ffn_sparse": t_sparse, "ffn_dense": t_dense},
-        "speedup_vs_dense": t_dense / (t_sel + t_sparse),
+        "speedup_vs_dense": None if t_dense is None else t_dense / (t_sel + t_sparse),
         "roofline": {"kernel": "ffn_gemm_kernel<true> + ffn_gemm_kernel<false> (whole adaspark_ffn_sparse call)",
                      "bound": "mfma", "achieved": tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": tf / PEAK_BF16_TFLOPS, "traffic": None},
-        "dense_tflops": 6.0 * w.S * FFN_D_MODEL * FFN_D_FF / (t_dense * 1e-3) / 1e12,
+                     "frac": tf / PEAK_BF16_TFLOPS, "traffic": FFN_MEASURED_TRAFFIC_BYTES.get(w.name)},
+        "dense_tflops": None if t_dense is None else 6.0 * w.S * FFN_D_MODEL * FFN_D_FF / (t_dense * 1e-3) / 1e12,
         "select_hbm_gbs": w.S * FFN_D_MODEL * 2 / (t_sel * 1e-3) / 1e9,
     }
 
@@ -321,7 +324,7 @@ def main():
     if not args.no_ffn and w.S * FFN_D_MODEL < (1 << 30):
         del ws_att, mask, count, O
         torch.cuda.empty_cache()
-        out["adas_ffn"] = ffn_leg(B, w, args.steps)
+        out["adas_ffn"] = ffn_leg(B, w, args.steps, dense=not args.no_dense)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, p, Q, K, V)
     print(json.dumps(out), flush=True)

@@ -7,8 +7,6 @@
 
 namespace adaspark {
 
-namespace {
-
 constexpr int SEL_THREADS = 1024;
 constexpr int TAB_THREADS = 256;
 constexpr int FIN_THREADS = 1024;
@@ -241,8 +239,6 @@ __global__ __launch_bounds__(FIN_THREADS) void ffn_finish_kernel(Geom g, int d_m
         }
     }
 }
-
-}  // namespace
 
 hipError_t launch_ffn_select(const Geom &g, int d_model, const uint16_t *X, float top_p, float eps, uint8_t *keep,
                              float *score, int32_t *keep_count, hipStream_t st)

@@ -15,8 +15,6 @@
 
 namespace adaspark {
 
-namespace {
-
 constexpr int GT = FFN_ROW_TILE;            // rows of a tile, both operands
 constexpr int GK = 64;                      // reduction elements per step: 128 bytes per row
 constexpr int GEMM_THREADS = 512;
@@ -187,8 +185,6 @@ hipError_t launch_gemm(const uint16_t *A, const int32_t *gather, const uint16_t 
                        gather, W0, W1, K, n_tiles, m_tiles, n_rows, out, ldo);
     return hipGetLastError();
 }
-
-}  // namespace
 
 hipError_t launch_ffn_gemm_gated(const uint16_t *X, const int32_t *active, const uint16_t *Wg, const uint16_t *Wu,
                                  int d_model, int d_ff, int m_tiles, const int32_t *n_rows, uint16_t *H, hipStream_t st)
