@@ -19,3 +19,4 @@ from .adaspark_oracle import (  # noqa: F401
     num_threads,
 )
 from . import adaspark_ffn_oracle as ffn  # noqa: F401,E402  (AdaS-FFN, Sec. 3.3)
+from . import adaspark_bwd_oracle as bwd  # noqa: F401,E402  (backward of Eq. 3, selection constant)

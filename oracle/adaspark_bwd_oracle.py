@@ -1,0 +1,80 @@
+"""fp64 oracle of the backward pass of cube-selective attention (Eq. 3 differentiated, selection held constant).
+
+TEST INFRASTRUCTURE, NOT PRODUCT CODE.  Plain numpy in float64, one query row at a time, no blocking or fusion; it
+shares nothing with the GPU path.  The paper trains through the operator (supplementary material, "AdaSpark
+Training Algorithm") and states no gradient of its own: the gradient here is the textbook derivative of softmax
+attention restricted to each row's attended keys, with the selected set S_r treated as a constant (the Top-p rule is
+piecewise constant in Q and K, so its derivative is zero wherever it exists).
+
+For row r = (token n, head a) with attended keys A_r (tokens of the selected cubes, and the tokens of the own cube
+up to n's rank), scale c = 1/sqrt(D), KV head g = a / (Hq / Hkv):
+    s_j = c q.k_j,  p = softmax(s),  o = sum_j p_j v_j                      (forward, Eq. 3)
+    dv_j += p_j do,  dp_j = do.v_j,  delta = do.o,  ds_j = p_j (dp_j - delta),
+    dq = c sum_j ds_j k_j,  dk_j += c ds_j q                                  (backward)
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import adaspark_oracle as base
+
+
+def attended_tokens(shape: base.Shape, sel_mask_row: np.ndarray, token: int, tables):
+    """Token indices row attends, in cube-major order: selected cubes in full, then the own cube up to the row's rank."""
+    cube_of, rank_of, members = tables
+    own = cube_of[token]
+    parts = [members[j] for j in range(own) if (sel_mask_row[j >> 5] >> (j & 31)) & 1]
+    parts.append(members[own][: rank_of[token] + 1])
+    return np.concatenate(parts)
+
+
+def cube_tables(shape: base.Shape):
+    cube_of, rank_of, size_of, _ = base.cube_map(shape)
+    members = [np.zeros(int(n), np.int64) for n in size_of]
+    for n in range(shape.S):
+        members[cube_of[n]][rank_of[n]] = n
+    return cube_of, rank_of, members
+
+
+def forward_row(q, Ka, Va, D):
+    """Eq. 3 for one row on its attended keys -> (o, p)."""
+    s = (Ka @ q) / np.sqrt(D)
+    e = np.exp(s - s.max())
+    p = e / e.sum()
+    return p @ Va, p
+
+
+def sparse_attn_fwd(shape: base.Shape, Q, K, V, sel_mask, rows=None):
+    """Forward in numpy on float64 inputs Q [S,Hq,D], K, V [S,Hkv,D] -> O [nrows, D] (rows: row ids n*Hq + a)."""
+    tables = cube_tables(shape)
+    G = shape.Hq // shape.Hkv
+    rows = np.arange(shape.S * shape.Hq) if rows is None else np.asarray(rows)
+    out = np.zeros((rows.size, shape.D))
+    for x, r in enumerate(rows):
+        n, a = divmod(int(r), shape.Hq)
+        att = attended_tokens(shape, sel_mask[x], n, tables)
+        out[x], _ = forward_row(Q[n, a], K[att, a // G], V[att, a // G], shape.D)
+    return out
+
+
+def sparse_attn_bwd(shape: base.Shape, Q, K, V, sel_mask, dO):
+    """All rows.  Q [S,Hq,D], K, V [S,Hkv,D], dO [S*Hq, D] float64; sel_mask uint32 [S*Hq, words].
+    -> (dQ [S,Hq,D], dK [S,Hkv,D], dV [S,Hkv,D], delta [S*Hq])."""
+    tables = cube_tables(shape)
+    G, D = shape.Hq // shape.Hkv, shape.D
+    c = 1.0 / np.sqrt(D)
+    dQ, dK, dV = np.zeros_like(Q), np.zeros_like(K), np.zeros_like(V)
+    delta = np.zeros(shape.S * shape.Hq)
+    for r in range(shape.S * shape.Hq):
+        n, a = divmod(r, shape.Hq)
+        g = a // G
+        att = attended_tokens(shape, sel_mask[r], n, tables)
+        Ka, Va = K[att, g], V[att, g]
+        o, p = forward_row(Q[n, a], Ka, Va, D)
+        do = dO[r]
+        delta[r] = do @ o
+        ds = p * (Va @ do - delta[r])
+        dQ[n, a] = c * (ds @ Ka)
+        np.add.at(dK[:, g], att, c * np.outer(ds, Q[n, a]))
+        np.add.at(dV[:, g], att, np.outer(p, do))
+    return dQ, dK, dV, delta
