@@ -72,7 +72,8 @@ typedef enum {
     ADASPARK_CALL_CUBE_POOL = 0,
     ADASPARK_CALL_CUBE_SELECT = 1,
     ADASPARK_CALL_SPARSE_ATTN = 2,
-    ADASPARK_CALL_DENSE_ATTN = 3
+    ADASPARK_CALL_DENSE_ATTN = 3,
+    ADASPARK_CALL_ATTN_BWD = 4
 } adaspark_call;
 
 /* Which kernel a sparse-attention call runs.  All compute the same result (Eq. 3).
@@ -206,6 +207,27 @@ int adaspark_sparse_attn_packed_with(const adaspark_shape *shape, const void *Q,
                                      void *stream);
 int adaspark_dense_attn_packed(const adaspark_shape *shape, const void *Q, const void *packed, size_t packed_bytes,
                                int causal, void *O, float *lse, void *stream);
+
+/*
+ * Backward pass of the attention entries (the paper post-trains through the operator: supplementary material,
+ * "AdaSpark Training Algorithm"; it states no gradient of its own).  Eq. 3 differentiated with the selected sets held
+ * constant -- the Top-p rule is piecewise constant in Q and K.  For row r with attended keys A_r, c = 1/sqrt(head_dim):
+ *   p = softmax(c q.k_j over A_r),  delta = dO.O,
+ *   dV_j += p_j dO,   dS_j = p_j (dO.v_j - delta),   dQ = c sum_j dS_j k_j,   dK_j += c dS_j q
+ * (dK, dV summed over all rows and all query heads of the KV head's group).
+ *   Q, dO, O   in   bf16 [tokens][q_heads][head_dim]   (O and lse as the forward entry returned them)
+ *   K, V       in   bf16 [tokens][kv_heads][head_dim]
+ *   lse        in   fp32 [tokens*q_heads]   natural-log sum-exp of the scaled logits over A_r
+ *   sel_mask   in   u32  [tokens*q_heads][ceil(cubes/32)], or NULL for dense causal attention
+ *   dQ         out  bf16 [tokens][q_heads][head_dim];  dK, dV  out  bf16 [tokens][kv_heads][head_dim]
+ *   workspace       adaspark_workspace_bytes(ADASPARK_CALL_ATTN_BWD): packed copies of K, V (natural and
+ *                   transposed), of Q and dO (natural and transposed, in cube order) and two floats per row
+ * p is rebuilt from lse in fp32; p and dS are rounded to bf16 for the MFMA products, sums are fp32, outputs are
+ * rounded to bf16 once.  Limits as for the forward, and tokens*q_heads*ceil(cubes/32) < 2^30; causal != 0 only.
+ */
+int adaspark_sparse_attn_bwd(const adaspark_shape *shape, const void *Q, const void *K, const void *V, const void *O,
+                             const float *lse, const void *dO, const uint32_t *sel_mask, int causal, void *dQ,
+                             void *dK, void *dV, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Adaptive Token-Selective FFN (AdaS-FFN, Sec. 3.3, Eqs. 4-7).  Inside every video cube the tokens with the largest

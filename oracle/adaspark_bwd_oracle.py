@@ -57,14 +57,21 @@ def sparse_attn_fwd(shape: base.Shape, Q, K, V, sel_mask, rows=None):
     return out
 
 
-def sparse_attn_bwd(shape: base.Shape, Q, K, V, sel_mask, dO):
+def sparse_attn_bwd(shape: base.Shape, Q, K, V, sel_mask, dO, O=None, scales=None):
     """All rows.  Q [S,Hq,D], K, V [S,Hkv,D], dO [S*Hq, D] float64; sel_mask uint32 [S*Hq, words].
+    O (optional, [S*Hq, D]): the forward output as the caller stored it; delta = dO.O is then taken from it, as an
+    implementation that is handed a rounded O does, instead of from the exact o recomputed here.
+    scales (optional dict): filled with 'dQ', 'dK', 'dV' arrays of the gradients' shapes holding, per element, the
+    root of the sum of squares of the terms that add up to it -- the natural unit for the error of an implementation
+    that rounds every term (diagnostic for tolerances; it does not influence the gradients).
     -> (dQ [S,Hq,D], dK [S,Hkv,D], dV [S,Hkv,D], delta [S*Hq])."""
     tables = cube_tables(shape)
     G, D = shape.Hq // shape.Hkv, shape.D
     c = 1.0 / np.sqrt(D)
     dQ, dK, dV = np.zeros_like(Q), np.zeros_like(K), np.zeros_like(V)
     delta = np.zeros(shape.S * shape.Hq)
+    if scales is not None:
+        scales.update(dQ=np.zeros_like(Q), dK=np.zeros_like(K), dV=np.zeros_like(V))
     for r in range(shape.S * shape.Hq):
         n, a = divmod(r, shape.Hq)
         g = a // G
@@ -72,9 +79,15 @@ def sparse_attn_bwd(shape: base.Shape, Q, K, V, sel_mask, dO):
         Ka, Va = K[att, g], V[att, g]
         o, p = forward_row(Q[n, a], Ka, Va, D)
         do = dO[r]
-        delta[r] = do @ o
+        delta[r] = do @ (o if O is None else O[r])
         ds = p * (Va @ do - delta[r])
         dQ[n, a] = c * (ds @ Ka)
-        np.add.at(dK[:, g], att, c * np.outer(ds, Q[n, a]))
-        np.add.at(dV[:, g], att, np.outer(p, do))
+        dK[att, g] += c * np.outer(ds, Q[n, a])   # a row's attended tokens are distinct
+        dV[att, g] += np.outer(p, do)
+        if scales is not None:
+            scales["dQ"][n, a] = c * np.sqrt((ds * ds) @ (Ka * Ka))
+            scales["dK"][att, g] += (c * np.outer(ds, Q[n, a])) ** 2
+            scales["dV"][att, g] += np.outer(p, do) ** 2
+    if scales is not None:
+        scales["dK"], scales["dV"] = np.sqrt(scales["dK"]), np.sqrt(scales["dV"])
     return dQ, dK, dV, delta

@@ -15,7 +15,7 @@ import torch
 
 from .build import lib_path
 
-CALL_CUBE_POOL, CALL_CUBE_SELECT, CALL_SPARSE_ATTN, CALL_DENSE_ATTN = 0, 1, 2, 3
+CALL_CUBE_POOL, CALL_CUBE_SELECT, CALL_SPARSE_ATTN, CALL_DENSE_ATTN, CALL_ATTN_BWD = 0, 1, 2, 3, 4
 
 
 class _CShape(ctypes.Structure):
@@ -84,6 +84,7 @@ EXPORTS = (
     "adaspark_sparse_attn_packed",
     "adaspark_sparse_attn_packed_with",
     "adaspark_dense_attn_packed",
+    "adaspark_sparse_attn_bwd",
     "adaspark_ffn_workspace_bytes",
     "adaspark_ffn_select",
     "adaspark_ffn_sparse",
@@ -120,6 +121,8 @@ def load():
         lib.adaspark_sparse_attn_packed_with.argtypes = [sp, vp, vp, ctypes.c_size_t, vp, ctypes.c_int, ctypes.c_int,
                                                          vp, vp, vp]
         lib.adaspark_dense_attn_packed.argtypes = [sp, vp, vp, ctypes.c_size_t, ctypes.c_int, vp, vp, vp]
+        lib.adaspark_sparse_attn_bwd.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp, vp, vp,
+                                                 ctypes.c_size_t, vp]
         dp = ctypes.POINTER(_CFfnDims)
         lib.adaspark_ffn_workspace_bytes.argtypes = [sp, dp, ctypes.POINTER(ctypes.c_size_t)]
         lib.adaspark_ffn_select.argtypes = [sp, dp, vp, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp]
@@ -361,3 +364,24 @@ def ffn_sparse(shape: Shape, X, W_gate, W_up, W_down, keep=None, Y=None, workspa
         _dev(workspace, torch.uint8, workspace.numel(), "workspace"), workspace.numel(), _stream()),
         "adaspark_ffn_sparse")
     return Y
+
+
+def sparse_attn_bwd(shape: Shape, Q, K, V, O, lse, dO, sel_mask=None, causal: bool = True, workspace=None):
+    """Backward of the attention entries with the selection held constant -> (dQ, dK, dV) bf16.
+    sel_mask None: dense causal attention."""
+    R, D = shape.rows, shape.head_dim
+    kvn = shape.tokens * shape.kv_heads * D
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    if workspace is None:
+        workspace = alloc_workspace(shape, CALL_ATTN_BWD, device=Q.device)
+    words = (num_cubes(shape) + 31) // 32
+    cs = shape._c()
+    _check(load().adaspark_sparse_attn_bwd(
+        ctypes.byref(cs), _dev(Q, torch.bfloat16, R * D, "Q"), _dev(K, torch.bfloat16, kvn, "K"),
+        _dev(V, torch.bfloat16, kvn, "V"), _dev(O, torch.bfloat16, R * D, "O"), _dev(lse, torch.float32, R, "lse"),
+        _dev(dO, torch.bfloat16, R * D, "dO"),
+        None if sel_mask is None else _dev(sel_mask, torch.int32, R * words, "sel_mask"), int(bool(causal)),
+        _dev(dQ, torch.bfloat16, R * D, "dQ"), _dev(dK, torch.bfloat16, kvn, "dK"), _dev(dV, torch.bfloat16, kvn, "dV"),
+        _dev(workspace, torch.uint8, workspace.numel(), "workspace"), workspace.numel(), _stream()),
+        "adaspark_sparse_attn_bwd")
+    return dQ, dK, dV

@@ -71,6 +71,7 @@ int adaspark_workspace_bytes(const adaspark_shape *shape, int which_call, size_t
     case ADASPARK_CALL_CUBE_SELECT: *bytes = select_workspace_bytes(g); return ADASPARK_OK;
     case ADASPARK_CALL_SPARSE_ATTN:
     case ADASPARK_CALL_DENSE_ATTN: *bytes = attn_workspace_bytes(g); return ADASPARK_OK;
+    case ADASPARK_CALL_ATTN_BWD: *bytes = attn_bwd_workspace_bytes(g); return ADASPARK_OK;
     default: return ADASPARK_EINVAL;
     }
 }
@@ -254,6 +255,27 @@ int adaspark_dense_attn(const adaspark_shape *shape, const void *Q, const void *
                         float *lse, void *workspace, size_t workspace_bytes, void *stream)
 {
     return attn_full(shape, Q, K, V, nullptr, false, causal, O, lse, workspace, workspace_bytes, stream);
+}
+
+int adaspark_sparse_attn_bwd(const adaspark_shape *shape, const void *Q, const void *K, const void *V, const void *O,
+                             const float *lse, const void *dO, const uint32_t *sel_mask, int causal, void *dQ,
+                             void *dK, void *dV, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_shape(shape);
+    if (rc != ADASPARK_OK) return rc;
+    if ((rc = check_ptrs({Q, K, V, O, lse, dO, dQ, dK, dV})) != ADASPARK_OK) return rc;
+    if (sel_mask != nullptr && !aligned16(sel_mask)) return ADASPARK_EINVAL;
+    if (!causal) return ADASPARK_EUNSUPPORTED;
+    const Geom g = make_geom(*shape);
+    if ((long long)g.S * g.Hq * g.words >= (1ll << 30)) return ADASPARK_EUNSUPPORTED;
+    if (workspace == nullptr || !aligned16(workspace) || workspace_bytes < attn_bwd_workspace_bytes(g))
+        return ADASPARK_EWORKSPACE;
+    const hipError_t e = launch_attn_bwd(g, static_cast<const uint16_t *>(Q), static_cast<const uint16_t *>(K),
+                                         static_cast<const uint16_t *>(V), static_cast<const uint16_t *>(O), lse,
+                                         static_cast<const uint16_t *>(dO), sel_mask, static_cast<uint16_t *>(dQ),
+                                         static_cast<uint16_t *>(dK), static_cast<uint16_t *>(dV), workspace,
+                                         static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ADASPARK_OK : ADASPARK_EHIP;
 }
 
 int adaspark_ffn_workspace_bytes(const adaspark_shape *shape, const adaspark_ffn_dims *dims, size_t *bytes)

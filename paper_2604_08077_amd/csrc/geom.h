@@ -155,4 +155,11 @@ hipError_t launch_attn_pairs(const Geom &g, const uint16_t *Q, const void *packe
                              size_t scratch_bytes, int force, int pairs_below_permille, uint16_t *O, float *lse,
                              hipStream_t st);
 
+// Backward of the attention entries (attn_bwd.hip): dQ, dK, dV in bf16 from Q, K, V, the forward's O and
+// log-sum-exp, and dO.  sel_mask == nullptr: dense causal attention.  ws: attn_bwd_workspace_bytes(g).
+size_t attn_bwd_workspace_bytes(const Geom &g);
+hipError_t launch_attn_bwd(const Geom &g, const uint16_t *Q, const uint16_t *K, const uint16_t *V, const uint16_t *O,
+                           const float *lse, const uint16_t *dO, const uint32_t *sel_mask, uint16_t *dQ, uint16_t *dK,
+                           uint16_t *dV, void *ws, hipStream_t st);
+
 }  // namespace adaspark

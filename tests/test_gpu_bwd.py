@@ -1,0 +1,91 @@
+"""GPU parity of the attention backward pass (selection held constant): the HIP library through its C ABI against
+the fp64 oracle on the same seeded bf16 inputs.
+
+The GPU takes O and the log-sum-exp from its own forward (as a training step does), rebuilds the probabilities in
+fp32, rounds P and dS to bf16 for the MFMA products, sums in fp32 and rounds the gradients to bf16.  A gradient
+element is therefore a sum of terms each off by up to 2^-9 of itself, independently (standard deviation
+2^-9/sqrt(3) of the root-sum-square T of its terms, which the oracle reports), plus the output rounding:
+    |g_gpu - g_oracle| <= 2^-8 |g_oracle| + 2^-7 T + 1e-4          (2^-7 T is about seven standard deviations),
+and the mean error must stay below a fifth of the mean bound.  Terms may cancel (rows that attend few keys with
+large scores), so T, not |g|, is the unit.  delta = dO.O is a function of the O the caller hands over: the oracle is
+given the same bf16 O (the oracle's own pins use the exact one).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_08077_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2604_08077_amd import binding
+
+    binding.load()  # raises if the HIP library was not built: there is no fallback
+    return binding
+
+
+def oshape(o, w):
+    return o.Shape(w.T, w.H, w.W, w.ct, w.ch, w.cw, w.Hq, w.Hkv, w.D, w.text, w.lead)
+
+
+def f64(t):
+    return t.to(torch.float64).numpy()
+
+
+def check_grad(name, got, want, terms):
+    got, want, terms = (x.reshape(-1, x.shape[-1]) for x in (got, want, terms))
+    err = np.abs(got - want)
+    bound = 2.0 ** -8 * np.abs(want) + 2.0 ** -7 * terms + 1e-4
+    print(f"[{name}] elements={err.size} max-abs={err.max():.3e} mean-abs={err.mean():.3e} "
+          f"worst err/bound={np.max(err / bound):.3f} mean err/mean bound={err.mean() / bound.mean():.3f}", flush=True)
+    assert np.isfinite(got).all()
+    assert (err <= bound).all()
+    assert err.mean() <= 0.2 * bound.mean()
+
+
+def workload(name):
+    return synth.TEST_WORKLOADS.get(name) or synth.WORKLOADS[name]
+
+
+def run_case(B, oracle, name, p, dense=False):
+    w = workload(name)
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    Q, K, V = synth.generate(w)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(synth.BASE_SEED + 31 * w.config_id)
+    dO = torch.randn((w.S, w.Hq, w.D), generator=g, dtype=torch.float32).to(torch.bfloat16)
+    kbar = oracle.cube_pool(osh, K)
+    mask = oracle.cube_select(osh, Q, kbar, 1.0 if dense else p)[0]
+    Qg, Kg, Vg, dOg = Q.cuda(), K.cuda(), V.cuda(), dO.cuda()
+    mg = torch.from_numpy(mask.view(np.int32)).cuda()
+    print(f"[{name}] forward p={p} dense={dense}", flush=True)
+    if dense:
+        O, lse = B.dense_attn(sh, Qg, Kg, Vg, return_lse=True)
+    else:
+        O, lse = B.sparse_attn(sh, Qg, Kg, Vg, mg, return_lse=True)
+    torch.cuda.synchronize()
+    print(f"[{name}] backward", flush=True)
+    dQ, dK, dV = B.sparse_attn_bwd(sh, Qg, Kg, Vg, O, lse, dOg, sel_mask=None if dense else mg)
+    torch.cuda.synchronize()
+    T = {}
+    rq, rk, rv, _ = oracle.bwd.sparse_attn_bwd(osh, f64(Q), f64(K), f64(V), mask, f64(dO).reshape(-1, w.D),
+                                               O=f64(O.cpu()).reshape(-1, w.D), scales=T)
+    check_grad(f"{name} dV", f64(dV.cpu()), rv, T["dV"])
+    check_grad(f"{name} dQ", f64(dQ.cpu()), rq, T["dQ"])
+    check_grad(f"{name} dK", f64(dK.cpu()), rk, T["dK"])
+
+
+@pytest.mark.parametrize("name,p", [("T_tiny", 0.8), ("T_mha64", 0.7), ("T_ragged", 0.9), ("T_text64", 0.8),
+                                    ("T_lead64", 0.8), ("T_manycubes", 0.6), ("T_lead128", 0.9), ("C1", 0.9)])
+def test_backward_matches_oracle(B, oracle, name, p):
+    run_case(B, oracle, name, p)
+
+
+@pytest.mark.parametrize("name", ["T_ragged", "T_mha64"])
+def test_dense_backward_matches_oracle(B, oracle, name):
+    run_case(B, oracle, name, 1.0, dense=True)
