@@ -15,6 +15,8 @@
 // Streamed tiles come from packed, pre-swizzled copies (kvtile.h layouts) straight into LDS: K natural / V natural
 // / K transposed per 64 keys (two runs of the forward's pack kernel), Q, dO natural and transposed per 64 rows in
 // (cube, rank, head of the group) order (bwd_pack_rows_kernel, which also leaves log2-domain log-sum-exp and delta).
+#include <type_traits>
+
 #include "attn_tile.h"
 
 namespace adaspark {
@@ -28,6 +30,7 @@ struct BwdWorkspace {
     void *packB;             // launch_kv_pack(V, K): natural V, then K transposed
     uint16_t *Qn, *Qt, *dOn, *dOt;  // [Hkv][N][tpcr][64 * D]
     float *lse2, *delta;     // [Hkv][N][tpcr * 64]; padding rows: +inf, 0
+    unsigned long long *colmask;  // [Hkv][N (key cube j)][N (row cube i)][tpcr]: bit k = row 64 t + k of cube i selects j
     int tpcr;                // 64-row tiles per cube = ceil(Cmax * G / 64)
     size_t bytes;
 };
@@ -48,6 +51,7 @@ BwdWorkspace bwd_workspace(const Geom &g, void *ws)
     w.dOt = reinterpret_cast<uint16_t *>(p + off); off = up(off + tile_elems * 2);
     w.lse2 = reinterpret_cast<float *>(p + off); off = up(off + (size_t)g.Hkv * g.N * w.tpcr * 64 * 4);
     w.delta = reinterpret_cast<float *>(p + off); off = up(off + (size_t)g.Hkv * g.N * w.tpcr * 64 * 4);
+    w.colmask = reinterpret_cast<unsigned long long *>(p + off); off = up(off + (size_t)g.Hkv * g.N * g.N * w.tpcr * 8);
     w.bytes = off;
     return w;
 }
@@ -135,6 +139,53 @@ __global__ __launch_bounds__(256) void bwd_pack_rows_kernel(Geom g, const uint16
     }
 }
 
+// The selection bits transposed for the key-stationary kernels: one wavefront per (KV head, row cube i, row tile t);
+// lane k holds row 64 t + k's mask words, a ballot per cube turns 64 rows' bits into one 64-bit word.
+__global__ __launch_bounds__(64) void bwd_colmask_kernel(Geom g, const uint32_t *__restrict__ sel_mask, int tpcr,
+                                                        unsigned long long *__restrict__ colmask)
+{
+    const int t = blockIdx.x, i = blockIdx.y, kv = blockIdx.z;
+    const int lane = threadIdx.x;
+    const CubeBox box = cube_box(g, i);
+    const int r = 64 * t + lane;
+    const bool valid = r < box.size() * g.G;
+    const size_t rowid = valid ? (size_t)token_of(g, box, r / g.G) * g.Hq + kv * g.G + r % g.G : 0;
+    for (int jw = 0; jw < g.words; ++jw) {
+        const uint32_t word = valid ? sel_mask[rowid * g.words + jw] : 0u;
+        unsigned long long mine = 0ull;
+#pragma unroll
+        for (int b = 0; b < 32; ++b) {
+            const unsigned long long bal = __ballot((word >> b) & 1u);
+            if (lane == b) mine = bal;
+        }
+        const int j = 32 * jw + lane;
+        if (lane < 32 && j < g.N) colmask[(((size_t)kv * g.N + j) * g.N + i) * tpcr + t] = mine;
+    }
+}
+
+// Half H of qk_tile: the products of a natural tile's rows 32 H .. 32 H + 31 with the B operands of NS slabs.
+// acc[s][k2][v] belongs to tile row 32 H + 8 q4 + 4 k2 + v.  Working a tile in two halves keeps half as many
+// accumulators alive.
+template <int D, int NS, int H>
+__device__ __forceinline__ void nat_half(const unsigned char *kt, int n16, int q4, const bf16x8 (&bf)[NS][D / 32],
+                                         f32x4 (&acc)[NS][2])
+{
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) acc[s][k2] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < D / 32; ++c)
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) {
+            const int krow = 32 * H + 8 * (n16 >> 2) + 4 * k2 + (n16 & 3);
+            const bf16x8 af = *reinterpret_cast<const bf16x8 *>(kt + k_tile_off<D>(krow, 4 * c + q4));
+#pragma unroll
+            for (int s = 0; s < NS; ++s)
+                acc[s][k2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bf[s][c], acc[s][k2], 0, 0, 0);
+        }
+}
+
 // acc^T[d, n] += T[d, 0..63] . B[0..63, n] for slabs 0..NS-1: T a transposed tile in LDS (rows = head-dim), B in
 // registers in the operand order qk_tile's outputs pack into (bf[s][half] = entities 32*half + 8*q4 + 0..7).
 template <int D, int NS>
@@ -171,7 +222,6 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const 
     constexpr int TILE = 64 * D * 2;       // bytes of one tile
     constexpr int STAGE = 3 * TILE;        // K natural, V natural, K transposed
     constexpr int PIECES = TILE / 1024;    // 1 KB pieces per tile
-    constexpr int PER_WAVE = 3 * PIECES / 8;
     extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
 
     const int nblk = (g.Cmax * g.G + BWD_ROWS - 1) / BWD_ROWS;
@@ -218,15 +268,18 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const 
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem);
     auto issue = [&](int stage, int j, int t) __attribute__((always_inline)) {
         const size_t toff = (head_tiles + (size_t)j * g.TPC + t) * (size_t)TILE;
+        // every wavefront moves its eighth of each of the three tiles (the tile is a compile-time index: a run-time
+        // choice among kernel arguments would be made through a table in scratch memory)
 #pragma unroll
-        for (int u = 0; u < PER_WAVE; ++u) {
-            const int piece = wave * PER_WAVE + u;  // 0 .. 3*PIECES-1, wave-uniform
-            const int which = piece / PIECES, sub = piece % PIECES;
-            const unsigned char *src =
-                reinterpret_cast<const unsigned char *>(which == 0 ? Kn : which == 1 ? Vn : Kt) + toff + sub * 1024;
-            dma_1k_s(__builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(stage * STAGE + which * TILE + sub * 1024)),
-                     bwd_uniform_ptr(src), (uint32_t)(lane * 16));
-        }
+        for (int which = 0; which < 3; ++which)
+#pragma unroll
+            for (int u = 0; u < PIECES / 8; ++u) {
+                const int sub = wave * (PIECES / 8) + u;
+                const unsigned char *src =
+                    reinterpret_cast<const unsigned char *>(which == 0 ? Kn : which == 1 ? Vn : Kt) + toff + sub * 1024;
+                dma_1k_s(__builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(stage * STAGE + which * TILE + sub * 1024)),
+                         bwd_uniform_ptr(src), (uint32_t)(lane * 16));
+            }
     };
     auto tiles_of = [&](int j) { return (csize[j] + 63) >> 6; };
 
@@ -244,14 +297,14 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const 
     for (int j = 0; j <= i; ++j) {
         const int nt = tiles_of(j);
         const int size_j = csize[j];
-        bool rsel[NS];
+        // a row that did not select cube j takes no part: with +inf as its log-sum-exp its probabilities are 0
+        float le[NS];
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
+            le[s] = lse2[s];
             if (MASKED && j < i) {
-                if ((j & 31) == 0 || j == 0) mw[s] = sel_mask[rowid[s] * g.words + (j >> 5)];
-                rsel[s] = (mw[s] >> (j & 31)) & 1u;
-            } else {
-                rsel[s] = true;
+                if ((j & 31) == 0) mw[s] = sel_mask[rowid[s] * g.words + (j >> 5)];
+                if (!((mw[s] >> (j & 31)) & 1u)) le[s] = INFINITY;
             }
         }
         for (int t = 0; t < nt; ++t) {
@@ -261,23 +314,41 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const 
                 if (++it == int_) { ++ij; it = 0; int_ = ij <= i ? tiles_of(ij) : 0; }
             }
             const unsigned char *kt = smem + stage * STAGE, *vt = kt + TILE, *ktt = vt + TILE;
-            f32x4 sacc[NS][4], pacc[NS][4];
-            qk_tile<D, 0, NS, NS>(kt, n16, q4, qf, sacc);
-            qk_tile<D, 0, NS, NS>(vt, n16, q4, gf, pacc);
+            const bool edge = j == i || 64 * t + 64 > size_j;  // the own cube's causal edge, padding keys: few tiles
             bf16x8 ds[NS][2];
-            const int kb = 64 * t + 8 * q4;
+            auto half = [&](auto hc) __attribute__((always_inline)) {
+                constexpr int H = decltype(hc)::value;
+                f32x4 sacc[NS][2], pacc[NS][2];
+                __builtin_amdgcn_sched_barrier(0);  // phases are not overlapped: that would not fit the register file
+                nat_half<D, NS, H>(kt, n16, q4, qf, sacc);
+                nat_half<D, NS, H>(vt, n16, q4, gf, pacc);
+                if (edge) {
+                    int kb = 64 * t + 32 * H + 8 * q4;
+                    asm volatile("" : "+v"(kb));
 #pragma unroll
-            for (int s = 0; s < NS; ++s)
+                    for (int s = 0; s < NS; ++s)
 #pragma unroll
-                for (int kg = 0; kg < 4; ++kg)
+                        for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int key = kb + 32 * (kg >> 1) + 4 * (kg & 1) + v;
-                        const bool on = rsel[s] && key < size_j && (j < i || key <= rank[s]);
-                        const float p = on ? __builtin_amdgcn_exp2f(fmaf(sacc[s][kg][v], c2, -lse2[s])) : 0.f;
-                        psum[s] += p;
-                        ds[s][kg >> 1][4 * (kg & 1) + v] = (__bf16)(p * (pacc[s][kg][v] - delta[s]));
-                    }
+                            for (int v = 0; v < 4; ++v) {
+                                const int key = kb + 4 * k2 + v;
+                                if (key >= size_j || (j == i && key > rank[s])) sacc[s][k2][v] = -INFINITY;
+                            }
+                }
+#pragma unroll
+                for (int s = 0; s < NS; ++s)
+#pragma unroll
+                    for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const float p = __builtin_amdgcn_exp2f(fmaf(sacc[s][k2][v], c2, -le[s]));
+                            psum[s] += p;
+                            ds[s][H][4 * k2 + v] = (__bf16)(p * (pacc[s][k2][v] - delta[s]));
+                        }
+            };
+            half(std::integral_constant<int, 0>{});
+            half(std::integral_constant<int, 1>{});
+            __builtin_amdgcn_sched_barrier(0);
             tn_tile<D, NS>(ktt, n16, q4, ds, acc);
             stage ^= 1;
         }
@@ -317,16 +388,16 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
                                                                    const uint16_t *__restrict__ dOt,
                                                                    const float *__restrict__ lse2p,
                                                                    const float *__restrict__ deltap, int tpcr,
-                                                                   const uint32_t *__restrict__ sel_mask,
+                                                                   const int32_t *__restrict__ csize,
+                                                                   const unsigned long long *__restrict__ colmask,
                                                                    uint16_t *__restrict__ dOut)
 {
     constexpr int NS = 2, KSTEPS = D / 32;
     constexpr int TILE = 64 * D * 2;
     constexpr int NT = WHICH == 0 ? 2 : 3;   // dV: Q natural, dO transposed; dK: Q natural, dO natural, Q transposed
-    constexpr int VEC = NT * TILE;           // per stage: then 64 floats lse2, 64 floats delta, 64 mask words
-    constexpr int STAGE = VEC + 3 * 256;
+    constexpr int VEC = NT * TILE;           // per stage: then 64 floats lse2, 64 floats delta
+    constexpr int STAGE = VEC + 2 * 256;
     constexpr int PIECES = TILE / 1024;
-    constexpr int PER_WAVE = NT * PIECES / 8;
     extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
 
     const int nkb = (g.Cmax + BWD_ROWS - 1) / BWD_ROWS;
@@ -362,32 +433,27 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
 
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem);
     const size_t head_tiles = (size_t)kv * g.N * tpcr;
-    // row tile t of cube i into `stage`: the tiles by all wavefronts, the three per-row vectors by wavefront 0
+    const size_t cm_base = ((size_t)kv * g.N + j) * g.N;
+    // row tile t of cube i into `stage`: the tiles by all wavefronts, the two per-row vectors by wavefront 0
     auto issue = [&](int stage, int i, int t) __attribute__((always_inline)) {
         const size_t tile = head_tiles + (size_t)i * tpcr + t;
 #pragma unroll
-        for (int u = 0; u < PER_WAVE; ++u) {
-            const int piece = wave * PER_WAVE + u;
-            const int which = piece / PIECES, sub = piece % PIECES;
-            const uint16_t *base = WHICH == 0 ? (which == 0 ? Qn : dOt) : (which == 0 ? Qn : which == 1 ? dOn : Qt);
-            const unsigned char *src = reinterpret_cast<const unsigned char *>(base) + tile * (size_t)TILE + sub * 1024;
-            dma_1k_s(__builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(stage * STAGE + which * TILE + sub * 1024)),
-                     bwd_uniform_ptr(src), (uint32_t)(lane * 16));
-        }
+        for (int which = 0; which < NT; ++which)
+#pragma unroll
+            for (int u = 0; u < PIECES / 8; ++u) {
+                const int sub = wave * (PIECES / 8) + u;
+                const uint16_t *base = WHICH == 0 ? (which == 0 ? Qn : dOt) : (which == 0 ? Qn : which == 1 ? dOn : Qt);
+                const unsigned char *src = reinterpret_cast<const unsigned char *>(base) + tile * (size_t)TILE + sub * 1024;
+                dma_1k_s(__builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(stage * STAGE + which * TILE + sub * 1024)),
+                         bwd_uniform_ptr(src), (uint32_t)(lane * 16));
+            }
         if (wave == 0) {
             const uint32_t vec = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(stage * STAGE + VEC));
             dma_dword_s(vec, bwd_uniform_ptr(lse2p + tile * 64), (uint32_t)(lane * 4));
             dma_dword_s(vec + 256, bwd_uniform_ptr(deltap + tile * 64), (uint32_t)(lane * 4));
-            if (MASKED) {
-                // the selection word that holds cube j's bit, for row 64 t + lane of cube i (any valid row if padding)
-                const CubeBox bi = cube_box(g, i);
-                const int r = min(64 * t + lane, bi.size() * g.G - 1);
-                const size_t rowid = (size_t)token_of(g, bi, r / g.G) * g.Hq + kv * g.G + r % g.G;
-                dma_dword_s(vec + 512, bwd_uniform_ptr(sel_mask), (uint32_t)((rowid * g.words + (j >> 5)) * 4));
-            }
         }
     };
-    auto tiles_of = [&](int i) { return (cube_box(g, i).size() * g.G + 63) >> 6; };
+    auto tiles_of = [&](int i) { return (csize[i] * g.G + 63) >> 6; };
 
     f32x4 acc[NS][D / 16];
 #pragma unroll
@@ -410,30 +476,50 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
             const unsigned char *t0 = smem + stage * STAGE;
             const float *lv = reinterpret_cast<const float *>(t0 + VEC);
             const float *dv = lv + 64;
-            const uint32_t *mv = reinterpret_cast<const uint32_t *>(lv + 128);
+            // bit k: row k of the tile selected cube j (rows of the own cube attend it by rule)
+            unsigned long long cm = ~0ull;
+            if (MASKED && i > j) cm = colmask[(cm_base + i) * tpcr + t];
             // S[row, key]: the streamed rows take the place the keys have in the forward (qk_tile's row order)
-            f32x4 sacc[NS][4], pacc[NS][4];
-            qk_tile<D, 0, NS, NS>(t0, n16, q4, kf, sacc);
-            if (WHICH == 1) qk_tile<D, 0, NS, NS>(t0 + TILE, n16, q4, vf, pacc);
             bf16x8 pf[NS][2];
-            const int rb = 8 * q4;
+            auto half = [&](auto hc) __attribute__((always_inline)) {
+                constexpr int H = decltype(hc)::value;
+                f32x4 sacc[NS][2], pacc[NS][2];
+                __builtin_amdgcn_sched_barrier(0);  // phases are not overlapped: that would not fit the register file
+                nat_half<D, NS, H>(t0, n16, q4, kf, sacc);
+                if (WHICH == 1) nat_half<D, NS, H>(t0 + TILE, n16, q4, vf, pacc);
+                const int rb = 32 * H + 8 * q4;  // the lane's eight rows of this half: rb .. rb + 7
+                const uint32_t bits = (uint32_t)(cm >> rb);  // their selection bits
+                if (i == j) {  // causal edge inside the own cube: a row attends keys up to its own rank
+                    int r0 = 64 * t + rb;
+                    asm volatile("" : "+v"(r0));
 #pragma unroll
-            for (int kg = 0; kg < 4; ++kg)
+                    for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int rl = rb + 32 * (kg >> 1) + 4 * (kg & 1) + v;  // row of the tile
-                    const float l2 = lv[rl];
-                    const float dl = WHICH == 1 ? dv[rl] : 0.f;
-                    bool ron = true;
-                    if (MASKED && i > j) ron = (mv[rl] >> (j & 31)) & 1u;
-                    const int rrank = (64 * t + rl) / g.G;  // only compared inside the own cube
+                        for (int v = 0; v < 4; ++v) {
+                            const int rrank = (r0 + 4 * k2 + v) / g.G;
 #pragma unroll
-                    for (int s = 0; s < NS; ++s) {
-                        const bool on = ron && (i > j || key[s] <= rrank);
-                        const float p = on ? __builtin_amdgcn_exp2f(fmaf(sacc[s][kg][v], c2, -l2)) : 0.f;
-                        pf[s][kg >> 1][4 * (kg & 1) + v] = (__bf16)(WHICH == 1 ? p * (pacc[s][kg][v] - dl) : p);
-                    }
+                            for (int s = 0; s < NS; ++s)
+                                if (key[s] > rrank) sacc[s][k2][v] = -INFINITY;
+                        }
                 }
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int rl = rb + 4 * k2 + v;
+                        float l2 = lv[rl];
+                        if (MASKED && !((bits >> (4 * k2 + v)) & 1u)) l2 = INFINITY;
+                        const float dl = WHICH == 1 ? dv[rl] : 0.f;
+#pragma unroll
+                        for (int s = 0; s < NS; ++s) {
+                            const float p = __builtin_amdgcn_exp2f(fmaf(sacc[s][k2][v], c2, -l2));
+                            pf[s][H][4 * k2 + v] = (__bf16)(WHICH == 1 ? p * (pacc[s][k2][v] - dl) : p);
+                        }
+                    }
+            };
+            half(std::integral_constant<int, 0>{});
+            half(std::integral_constant<int, 1>{});
+            __builtin_amdgcn_sched_barrier(0);
             tn_tile<D, NS>(t0 + (WHICH == 0 ? TILE : 2 * TILE), n16, q4, pf, acc);
             stage ^= 1;
         }
@@ -468,6 +554,10 @@ static hipError_t launch_bwd_d(const Geom &g, const uint16_t *Q, const uint16_t 
     hipLaunchKernelGGL((bwd_pack_rows_kernel<D>), dim3(w.tpcr, g.N, g.Hkv), dim3(256), 0, st, g, Q, dO, O, lse, w.tpcr,
                        w.Qn, w.Qt, w.dOn, w.dOt, w.lse2, w.delta);
     if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (sel_mask != nullptr) {
+        hipLaunchKernelGGL(bwd_colmask_kernel, dim3(w.tpcr, g.N, g.Hkv), dim3(64), 0, st, g, sel_mask, w.tpcr, w.colmask);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
 
     const size_t half_elems = (size_t)g.Hkv * g.N * g.TPC * KEY_TILE * D;
     const uint16_t *Kn = reinterpret_cast<const uint16_t *>(w.packA);
@@ -481,7 +571,7 @@ static hipError_t launch_bwd_d(const Geom &g, const uint16_t *Q, const uint16_t 
     const int lds_q = 2 * 3 * TILE;
     const int nkb = (g.Cmax + BWD_ROWS - 1) / BWD_ROWS;
     const dim3 grid_k((unsigned)((size_t)g.N * g.Hkv * nkb));
-    const int lds_v = 2 * (2 * TILE + 768), lds_k = 2 * (3 * TILE + 768);
+    const int lds_v = 2 * (2 * TILE + 512), lds_k = 2 * (3 * TILE + 512);
 #define ADASPARK_BWD_LAUNCH(MASKED)                                                                                    \
     do {                                                                                                               \
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bwd_dq_kernel<D, MASKED>),                        \
@@ -493,12 +583,12 @@ static hipError_t launch_bwd_d(const Geom &g, const uint16_t *Q, const uint16_t 
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_v);                                    \
         if (e != hipSuccess) return e;                                                                                 \
         hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, 0, MASKED>), grid_k, dim3(BWD_THREADS), lds_v, st, g, K, V, w.Qn,   \
-                           w.Qt, w.dOn, w.dOt, w.lse2, w.delta, w.tpcr, sel_mask, dV);                                 \
+                           w.Qt, w.dOn, w.dOt, w.lse2, w.delta, w.tpcr, csize, w.colmask, dV);                                 \
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bwd_dkv_kernel<D, 1, MASKED>),                    \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_k);                                    \
         if (e != hipSuccess) return e;                                                                                 \
         hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, 1, MASKED>), grid_k, dim3(BWD_THREADS), lds_k, st, g, K, V, w.Qn,   \
-                           w.Qt, w.dOn, w.dOt, w.lse2, w.delta, w.tpcr, sel_mask, dK);                                 \
+                           w.Qt, w.dOn, w.dOt, w.lse2, w.delta, w.tpcr, csize, w.colmask, dK);                                 \
     } while (0)
     if (sel_mask != nullptr)
         ADASPARK_BWD_LAUNCH(true);
