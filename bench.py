@@ -150,6 +150,28 @@ def ffn_leg(B, w, steps, dense=True):
     }
 
 
+def bwd_leg(B, w, sh, Qg, Kg, Vg, ws_att, mask, eff_flops, dense_flops, steps):
+    """Backward of the sparse attention (selection constant) on the headline inputs: O and the log-sum-exp from the
+    library's forward, a seeded dO; the whole adaspark_sparse_attn_bwd call timed with HIP events."""
+    O, lse = B.sparse_attn_packed(sh, Qg, ws_att, mask, return_lse=True)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(synth.BASE_SEED + 31 * w.config_id)
+    dO = torch.randn((w.S, w.Hq, w.D), generator=g, dtype=torch.float32).to(torch.bfloat16).cuda()
+    ws = B.alloc_workspace(sh, B.CALL_ATTN_BWD)
+    B.sparse_attn_bwd(sh, Qg, Kg, Vg, O, lse, dO, sel_mask=mask, workspace=ws)  # untimed first launch
+    ms = timed(lambda: B.sparse_attn_bwd(sh, Qg, Kg, Vg, O, lse, dO, sel_mask=mask, workspace=ws), max(2, steps // 2))
+    # five matrix products on the attended keys against the forward's two; the kernels execute eight on every
+    # preceding cube (S three times, dP twice, dV, dK, dQ), with the selection as a mask
+    tf = 2.5 * eff_flops / (ms * 1e-3) / 1e12
+    return {
+        "ms": ms,
+        "roofline": {"kernel": "attn_bwd_dq_kernel + attn_bwd_dkv_kernel<dV> + attn_bwd_dkv_kernel<dK> (whole call)",
+                     "bound": "mfma", "achieved": tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tf / PEAK_BF16_TFLOPS, "traffic": None,
+                     "executed_tflops": 4.0 * dense_flops / (ms * 1e-3) / 1e12},
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -160,6 +182,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-ffn", action="store_true", help="skip the token-selective FFN leg (Sec. 3.3)")
+    ap.add_argument("--no-bwd", action="store_true", help="skip the attention backward leg")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 1 GiB device copy after the timed region: the known-size "
                          "reference the HBM counters of a rocprofv3 --pmc run are scaled by")
@@ -321,6 +344,8 @@ def main():
             "executed_tflops": None if executed_flops is None else executed_flops / (attn_kernel_ms * 1e-3) / 1e12,
         },
     }
+    if not args.no_bwd and w.S * w.Hq * words < (1 << 30) and w.S <= 131072:
+        out["attn_bwd"] = bwd_leg(B, w, sh, Qg, Kg, Vg, ws_att, mask, eff_flops, dense_flops, args.steps)
     if not args.no_ffn and w.S * FFN_D_MODEL < (1 << 30):
         del ws_att, mask, count, O
         torch.cuda.empty_cache()

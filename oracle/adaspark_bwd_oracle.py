@@ -57,6 +57,21 @@ def sparse_attn_fwd(shape: base.Shape, Q, K, V, sel_mask, rows=None):
     return out
 
 
+def row_backward(shape: base.Shape, Q, K, V, sel_mask_row, r: int, do, o_given, tables):
+    """One query row r = n*Hq + a.  -> (att, dq, dk_terms [len(att), D], dv_terms [len(att), D], delta, ds, p):
+    the tokens it attends, its dQ row, and what it adds to dK and dV of those tokens."""
+    G, D = shape.Hq // shape.Hkv, shape.D
+    c = 1.0 / np.sqrt(D)
+    n, a = divmod(int(r), shape.Hq)
+    g = a // G
+    att = attended_tokens(shape, sel_mask_row, n, tables)
+    Ka, Va = K[att, g], V[att, g]
+    o, p = forward_row(Q[n, a], Ka, Va, D)
+    delta = do @ (o if o_given is None else o_given)
+    ds = p * (Va @ do - delta)
+    return att, c * (ds @ Ka), c * np.outer(ds, Q[n, a]), np.outer(p, do), delta, ds, p
+
+
 def sparse_attn_bwd(shape: base.Shape, Q, K, V, sel_mask, dO, O=None, scales=None):
     """All rows.  Q [S,Hq,D], K, V [S,Hkv,D], dO [S*Hq, D] float64; sel_mask uint32 [S*Hq, words].
     O (optional, [S*Hq, D]): the forward output as the caller stored it; delta = dO.O is then taken from it, as an
@@ -75,19 +90,16 @@ def sparse_attn_bwd(shape: base.Shape, Q, K, V, sel_mask, dO, O=None, scales=Non
     for r in range(shape.S * shape.Hq):
         n, a = divmod(r, shape.Hq)
         g = a // G
-        att = attended_tokens(shape, sel_mask[r], n, tables)
-        Ka, Va = K[att, g], V[att, g]
-        o, p = forward_row(Q[n, a], Ka, Va, D)
-        do = dO[r]
-        delta[r] = do @ (o if O is None else O[r])
-        ds = p * (Va @ do - delta[r])
-        dQ[n, a] = c * (ds @ Ka)
-        dK[att, g] += c * np.outer(ds, Q[n, a])   # a row's attended tokens are distinct
-        dV[att, g] += np.outer(p, do)
+        att, dq, dk_terms, dv_terms, delta[r], ds, _ = row_backward(
+            shape, Q, K, V, sel_mask[r], r, dO[r], None if O is None else O[r], tables)
+        dQ[n, a] = dq
+        dK[att, g] += dk_terms   # a row's attended tokens are distinct
+        dV[att, g] += dv_terms
         if scales is not None:
+            Ka = K[att, g]
             scales["dQ"][n, a] = c * np.sqrt((ds * ds) @ (Ka * Ka))
-            scales["dK"][att, g] += (c * np.outer(ds, Q[n, a])) ** 2
-            scales["dV"][att, g] += np.outer(p, do) ** 2
+            scales["dK"][att, g] += dk_terms ** 2
+            scales["dV"][att, g] += dv_terms ** 2
     if scales is not None:
         scales["dK"], scales["dV"] = np.sqrt(scales["dK"]), np.sqrt(scales["dV"])
     return dQ, dK, dV, delta

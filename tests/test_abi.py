@@ -109,6 +109,22 @@ def test_bad_pointers_and_arguments_are_rejected_before_launch(lib):
     assert lib.adaspark_pairs_workspace_bytes(ctypes.byref(huge), 1, ctypes.byref(big)) == -2
 
 
+def test_backward_arguments_are_validated_before_launch(lib):
+    cs = _raw_shape()._c()
+    ok_ptr = ctypes.c_void_p(4096)      # never dereferenced: validation fails first
+    need = ctypes.c_size_t(0)
+    assert lib.adaspark_workspace_bytes(ctypes.byref(cs), binding.CALL_ATTN_BWD, ctypes.byref(need)) == 0
+    fwd = ctypes.c_size_t(0)
+    assert lib.adaspark_workspace_bytes(ctypes.byref(cs), binding.CALL_SPARSE_ATTN, ctypes.byref(fwd)) == 0
+    rows, D = 4 * 8 * 8 * 4, 64
+    assert need.value >= 2 * fwd.value + 4 * rows * D * 2 + 2 * rows * 4      # two K/V packs, four row packs, two vectors
+    run = lambda q=ok_ptr, mask=ok_ptr, causal=1, ws=ok_ptr, nbytes=1 << 30, dq=ok_ptr: lib.adaspark_sparse_attn_bwd(
+        ctypes.byref(cs), q, ok_ptr, ok_ptr, ok_ptr, ok_ptr, ok_ptr, mask, causal, dq, ok_ptr, ok_ptr, ws, nbytes, None)
+    assert run(q=None) == -1 and run(dq=ctypes.c_void_p(4097)) == -1 and run(mask=ctypes.c_void_p(4100)) == -1
+    assert run(causal=0) == -2
+    assert run(ws=None) == -3 and run(nbytes=need.value - 1) == -3
+
+
 def test_ffn_arguments_are_validated_before_launch(lib):
     cs = _raw_shape()._c()
     ok_ptr = ctypes.c_void_p(4096)      # never dereferenced: validation fails first

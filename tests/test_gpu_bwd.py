@@ -49,7 +49,7 @@ def check_grad(name, got, want, terms):
 
 
 def workload(name):
-    return synth.TEST_WORKLOADS.get(name) or synth.WORKLOADS[name]
+    return synth.TEST_WORKLOADS.get(name) or synth.SAMPLED_WORKLOADS.get(name) or synth.WORKLOADS[name]
 
 
 def run_case(B, oracle, name, p, dense=False):
@@ -81,7 +81,8 @@ def run_case(B, oracle, name, p, dense=False):
 
 
 @pytest.mark.parametrize("name,p", [("T_tiny", 0.8), ("T_mha64", 0.7), ("T_ragged", 0.9), ("T_text64", 0.8),
-                                    ("T_lead64", 0.8), ("T_manycubes", 0.6), ("T_lead128", 0.9), ("C1", 0.9)])
+                                    ("T_lead64", 0.8), ("T_manycubes", 0.6), ("T_lead128", 0.9), ("C1", 0.9),
+                                    ("M_bwd256", 0.8)])
 def test_backward_matches_oracle(B, oracle, name, p):
     run_case(B, oracle, name, p)
 
@@ -89,3 +90,74 @@ def test_backward_matches_oracle(B, oracle, name, p):
 @pytest.mark.parametrize("name", ["T_ragged", "T_mha64"])
 def test_dense_backward_matches_oracle(B, oracle, name):
     run_case(B, oracle, name, 1.0, dense=True)
+
+
+def test_backward_full_size_sampled(B, oracle):
+    """65,536 tokens, p = 0.9, the launch configuration the benchmark times.  dQ: sampled rows recomputed by the
+    oracle.  dK, dV: the last eight tokens of the last cube of one KV head (few rows attend them: the oracle takes
+    them all), and two identities that hold at any size because every row's probabilities sum to one and its dS to
+    zero: sum over tokens of dV = sum over the group's rows of dO, sum over tokens of dK = 0."""
+    w = synth.WORKLOADS["C3"]
+    p = 0.9
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    Q, K, V = synth.generate(w)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(synth.BASE_SEED + 31 * w.config_id)
+    dO = torch.randn((w.S, w.Hq, w.D), generator=g, dtype=torch.float32).to(torch.bfloat16)
+    Qg, Kg, Vg, dOg = Q.cuda(), K.cuda(), V.cuda(), dO.cuda()
+    kbar = B.cube_pool(sh, Kg)
+    mask_g, _, _, _ = B.cube_select(sh, Qg, kbar, p)
+    print("[C3] forward", flush=True)
+    O, lse = B.sparse_attn(sh, Qg, Kg, Vg, mask_g, return_lse=True)
+    torch.cuda.synchronize()
+    print("[C3] backward", flush=True)
+    dQ, dK, dV = B.sparse_attn_bwd(sh, Qg, Kg, Vg, O, lse, dOg, sel_mask=mask_g)
+    torch.cuda.synchronize()
+    mask = mask_g.cpu().numpy().view(np.uint32)
+    q, k, v, do = f64(Q), f64(K), f64(V), f64(dO).reshape(-1, w.D)
+    o = f64(O.cpu()).reshape(-1, w.D)
+    tables = oracle.bwd.cube_tables(osh)
+    G, c = w.Hq // w.Hkv, 1.0 / np.sqrt(w.D)
+
+    rows = synth.sample_rows(w, 24, seed=5)
+    want, terms = [], []
+    for r in rows:
+        att, dq, _, _, _, ds, _ = oracle.bwd.row_backward(osh, q, k, v, mask[r], r, do[r], o[r], tables)
+        want.append(dq)
+        terms.append(c * np.sqrt((ds * ds) @ (k[att, (r % w.Hq) // G] ** 2)))
+    got = f64(dQ.reshape(-1, w.D)[torch.as_tensor(rows).cuda()].cpu())
+    check_grad("C3 dQ sampled rows", got, np.array(want), np.array(terms))
+
+    # keys: the last eight tokens (in cube order) of the last cube, KV head 1; the rows that attend them are the
+    # rows of those tokens themselves and of the later ones among them
+    members = tables[2][-1]
+    toks = members[-8:]
+    gk = 1
+    wk, wv = np.zeros((8, w.D)), np.zeros((8, w.D))
+    tk, tv = np.zeros((8, w.D)), np.zeros((8, w.D))
+    for x, n in enumerate(toks):
+        for a in range(gk * G, (gk + 1) * G):
+            r = n * w.Hq + a
+            att, _, dk_t, dv_t, _, _, _ = oracle.bwd.row_backward(osh, q, k, v, mask[r], r, do[r], o[r], tables)
+            for y in range(x + 1):                      # this row attends toks[0..x]
+                pos = int(np.nonzero(att == toks[y])[0][0])
+                wk[y] += dk_t[pos]
+                wv[y] += dv_t[pos]
+                tk[y] += dk_t[pos] ** 2
+                tv[y] += dv_t[pos] ** 2
+    idx = torch.as_tensor(toks).cuda()
+    check_grad("C3 dK last tokens", f64(dK[idx, gk].cpu()), wk, np.sqrt(tk))
+    check_grad("C3 dV last tokens", f64(dV[idx, gk].cpu()), wv, np.sqrt(tv))
+
+    dVs = dV.to(torch.float64).sum(dim=0).cpu().numpy()                      # [Hkv, D]
+    dKs = dK.to(torch.float64).sum(dim=0).cpu().numpy()
+    dOs = f64(dO).reshape(w.S, w.Hkv, G, w.D).sum(axis=(0, 2))
+    # every element of dV, dK carries its own bf16 rounding (relative 2^-9) and the noise of its rounded terms, which
+    # cancel in part (measured: about 7 x 2^-9 of the column's root-sum-square); over 65,536 tokens these add up like
+    # a random walk
+    tol_v = 16.0 * 2.0 ** -9 * np.sqrt((f64(dV.cpu()) ** 2).sum(axis=0)) + 1e-3 * np.abs(dOs)
+    tol_k = 16.0 * 2.0 ** -9 * np.sqrt((f64(dK.cpu()) ** 2).sum(axis=0))
+    print(f"[C3] sum dV - sum dO: max {np.abs(dVs - dOs).max():.3e} (tolerance {tol_v.min():.3e}..{tol_v.max():.3e}); "
+          f"sum dK: max {np.abs(dKs).max():.3e} (tolerance {tol_k.min():.3e}..{tol_k.max():.3e})", flush=True)
+    assert (np.abs(dVs - dOs) <= tol_v).all()
+    assert (np.abs(dKs) <= tol_k).all()
