@@ -150,7 +150,12 @@ def ffn_leg(B, w, steps, dense=True):
     }
 
 
-def bwd_leg(B, w, sh, Qg, Kg, Vg, ws_att, mask, eff_flops, dense_flops, steps):
+# Bytes the three backward kernels of one call move between the L2 caches and the fabric (rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE, scaled by a copy of known size; see profiles/), keyed by (workload, top_p).
+BWD_MEASURED_TRAFFIC_BYTES = {("C3", 0.9): 4.58e10}
+
+
+def bwd_leg(B, w, sh, Qg, Kg, Vg, ws_att, mask, eff_flops, dense_flops, steps, top_p):
     """Backward of the sparse attention (selection constant) on the headline inputs: O and the log-sum-exp from the
     library's forward, a seeded dO; the whole adaspark_sparse_attn_bwd call timed with HIP events."""
     O, lse = B.sparse_attn_packed(sh, Qg, ws_att, mask, return_lse=True)
@@ -167,7 +172,7 @@ def bwd_leg(B, w, sh, Qg, Kg, Vg, ws_att, mask, eff_flops, dense_flops, steps):
         "ms": ms,
         "roofline": {"kernel": "attn_bwd_dq_kernel + attn_bwd_dkv_kernel<dV> + attn_bwd_dkv_kernel<dK> (whole call)",
                      "bound": "mfma", "achieved": tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": tf / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": tf / PEAK_BF16_TFLOPS, "traffic": BWD_MEASURED_TRAFFIC_BYTES.get((w.name, top_p)),
                      "executed_tflops": 4.0 * dense_flops / (ms * 1e-3) / 1e12},
     }
 
@@ -345,7 +350,7 @@ def main():
         },
     }
     if not args.no_bwd and w.S * w.Hq * words < (1 << 30) and w.S <= 131072:
-        out["attn_bwd"] = bwd_leg(B, w, sh, Qg, Kg, Vg, ws_att, mask, eff_flops, dense_flops, args.steps)
+        out["attn_bwd"] = bwd_leg(B, w, sh, Qg, Kg, Vg, ws_att, mask, eff_flops, dense_flops, args.steps, args.top_p)
     if not args.no_ffn and w.S * FFN_D_MODEL < (1 << 30):
         del ws_att, mask, count, O
         torch.cuda.empty_cache()

@@ -8,7 +8,7 @@
 //                        MFMA B operands, walks the key tiles of every cube up to its own, and accumulates dQ^T.
 //                        S^T = K.Q^T, dP^T = V.dO^T, dQ^T += K^T.dS^T.
 //   attn_bwd_dkv_kernel  key-stationary: a wavefront keeps K (and V) of 32 keys as B operands, walks the 64-row
-//                        tiles of its own and every later cube, and accumulates dV^T (WHICH = 0: S = Q.K^T,
+//                        tiles of every later cube and its own, and accumulates dV^T (WHICH = 0: S = Q.K^T,
 //                        dV^T += dO^T.P) or dK^T (WHICH = 1: S, dP = dO.V^T, dK^T += Q^T.dS).  Two passes because the
 //                        two accumulators together with both operand sets do not fit the register file.
 // In both, a row's selection bit for the key cube acts as a mask (dense work, like the forward's masked walk).
@@ -57,6 +57,31 @@ BwdWorkspace bwd_workspace(const Geom &g, void *ws)
 }
 
 size_t attn_bwd_workspace_bytes(const Geom &g) { return bwd_workspace(g, nullptr).bytes; }
+
+// Workgroup -> (KV head, slot among the head's workgroups).  Consecutive workgroups go to different XCDs, each with
+// its own L2; the workgroups of one KV head stream the same tiles, so where the head count allows a head's
+// workgroups stay on as few XCDs as possible.  bwd_grid is the matching launch size.
+__host__ __device__ inline bool bwd_head_slot(int b, int Hkv, int per_head, int &kv, int &slot)
+{
+    if (Hkv <= 8 && 8 % Hkv == 0) {
+        const int x = b & 7, idx = b >> 3, share = 8 / Hkv;
+        kv = x % Hkv;
+        slot = idx * share + x / Hkv;
+    } else if (Hkv % 8 == 0) {
+        const int x = b & 7, idx = b >> 3, m = Hkv / 8;
+        kv = x + 8 * (idx % m);
+        slot = idx / m;
+    } else {
+        kv = b % Hkv;
+        slot = b / Hkv;
+    }
+    return slot < per_head;
+}
+inline unsigned bwd_grid(int Hkv, int per_head)
+{
+    if (Hkv <= 8 && 8 % Hkv == 0) return (unsigned)((per_head + 8 / Hkv - 1) / (8 / Hkv) * 8);
+    return (unsigned)per_head * (unsigned)Hkv;
+}
 
 // One wavefront copies 64 dwords from global memory straight into LDS: lane l moves the 4 bytes at sbase + voff to
 // lds_addr + 4*l.
@@ -204,7 +229,7 @@ __device__ __forceinline__ void tn_tile(const unsigned char *tt, int n16, int q4
 }
 
 // ---------------------------------------------------------------------------------------------------------------
-// dQ: workgroup = 256 rows (packed row order) of one (cube i, KV head); grid: late cubes first.
+// dQ: workgroup = 256 rows (packed row order) of one (cube i, KV head); late cubes (the long walks) first.
 // ---------------------------------------------------------------------------------------------------------------
 template <int D, bool MASKED>
 __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const uint16_t *__restrict__ Q,
@@ -225,10 +250,10 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const 
     extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
 
     const int nblk = (g.Cmax * g.G + BWD_ROWS - 1) / BWD_ROWS;
-    const int blk = blockIdx.x % nblk;
-    const int rest = blockIdx.x / nblk;
-    const int kv = rest % g.Hkv;
-    const int i = g.N - 1 - rest / g.Hkv;
+    int kv, slot;
+    if (!bwd_head_slot(blockIdx.x, g.Hkv, g.N * nblk, kv, slot)) return;
+    const int blk = slot % nblk;
+    const int i = g.N - 1 - slot / nblk;
     const CubeBox box = cube_box(g, i);
     const int mrows = box.size() * g.G;
     if (blk * BWD_ROWS >= mrows) return;
@@ -377,7 +402,7 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const 
 
 // ---------------------------------------------------------------------------------------------------------------
 // dV (WHICH = 0) / dK (WHICH = 1): workgroup = 256 keys of one (cube j, KV head); walks the row tiles of cube j
-// and of every later cube.  grid: early cubes (the long walks) first.
+// and of every later cube, from the last one down.  Early cubes (the long walks) first.
 // ---------------------------------------------------------------------------------------------------------------
 template <int D, int WHICH, bool MASKED>
 __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const uint16_t *__restrict__ K,
@@ -401,10 +426,10 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
     extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
 
     const int nkb = (g.Cmax + BWD_ROWS - 1) / BWD_ROWS;
-    const int kb = blockIdx.x % nkb;
-    const int rest = blockIdx.x / nkb;
-    const int kv = rest % g.Hkv;
-    const int j = rest / g.Hkv;
+    int kv, slot;
+    if (!bwd_head_slot(blockIdx.x, g.Hkv, g.N * nkb, kv, slot)) return;
+    const int kb = slot % nkb;
+    const int j = slot / nkb;
     const CubeBox box = cube_box(g, j);
     const int size_j = box.size();
     if (kb * BWD_ROWS >= size_j) return;
@@ -461,17 +486,19 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
 #pragma unroll
         for (int e = 0; e < D / 16; ++e) acc[s][e] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    int ii = j, it = 0, int_ = tiles_of(j);
-    issue(0, j, 0);
-    if (++it == int_) { ++ii; it = 0; int_ = ii < g.N ? tiles_of(ii) : 0; }
+    // Row cubes from the last one down to the own cube: workgroups that start together then stream the same tiles at
+    // the same time, whatever their key cube, and one copy in L2 serves them all.
+    int ii = g.N - 1, it = 0, int_ = tiles_of(g.N - 1);
+    issue(0, ii, 0);
+    if (++it == int_) { --ii; it = 0; int_ = ii >= j ? tiles_of(ii) : 0; }
     int stage = 0;
-    for (int i = j; i < g.N; ++i) {
+    for (int i = g.N - 1; i >= j; --i) {
         const int nt = tiles_of(i);
         for (int t = 0; t < nt; ++t) {
             tile_barrier();
-            if (ii < g.N) {
+            if (ii >= j) {
                 issue(stage ^ 1, ii, it);
-                if (++it == int_) { ++ii; it = 0; int_ = ii < g.N ? tiles_of(ii) : 0; }
+                if (++it == int_) { --ii; it = 0; int_ = ii >= j ? tiles_of(ii) : 0; }
             }
             const unsigned char *t0 = smem + stage * STAGE;
             const float *lv = reinterpret_cast<const float *>(t0 + VEC);
@@ -567,10 +594,10 @@ static hipError_t launch_bwd_d(const Geom &g, const uint16_t *Q, const uint16_t 
     constexpr int TILE = 64 * D * 2;
 
     const int nblk = (g.Cmax * g.G + BWD_ROWS - 1) / BWD_ROWS;
-    const dim3 grid_q((unsigned)((size_t)g.N * g.Hkv * nblk));
+    const dim3 grid_q(bwd_grid(g.Hkv, g.N * nblk));
     const int lds_q = 2 * 3 * TILE;
     const int nkb = (g.Cmax + BWD_ROWS - 1) / BWD_ROWS;
-    const dim3 grid_k((unsigned)((size_t)g.N * g.Hkv * nkb));
+    const dim3 grid_k(bwd_grid(g.Hkv, g.N * nkb));
     const int lds_v = 2 * (2 * TILE + 512), lds_k = 2 * (3 * TILE + 512);
 #define ADASPARK_BWD_LAUNCH(MASKED)                                                                                    \
     do {                                                                                                               \
