@@ -91,14 +91,6 @@ __device__ __forceinline__ void dma_dword_s(uint32_t lds_addr, const void *sbase
                  : "memory", "m0");
 }
 
-__device__ __forceinline__ const void *bwd_uniform_ptr(const void *p)
-{
-    const uintptr_t u = reinterpret_cast<uintptr_t>(p);
-    const uintptr_t r = (uintptr_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)u) |
-                        ((uintptr_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(u >> 32)) << 32);
-    return reinterpret_cast<const void *>(r);
-}
-
 // Row r of cube c in the packed row order: rank r / G, head r % G of the group.
 // Q, dO natural and transposed per 64-row tile; delta = dO.O; lse2 = lse * log2(e).
 template <int D>
@@ -303,7 +295,7 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const 
                 const unsigned char *src =
                     reinterpret_cast<const unsigned char *>(which == 0 ? Kn : which == 1 ? Vn : Kt) + toff + sub * 1024;
                 dma_1k_s(__builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(stage * STAGE + which * TILE + sub * 1024)),
-                         bwd_uniform_ptr(src), (uint32_t)(lane * 16));
+                         uniform_ptr(src), (uint32_t)(lane * 16));
             }
     };
     auto tiles_of = [&](int j) { return (csize[j] + 63) >> 6; };
@@ -470,12 +462,12 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
                 const uint16_t *base = WHICH == 0 ? (which == 0 ? Qn : dOt) : (which == 0 ? Qn : which == 1 ? dOn : Qt);
                 const unsigned char *src = reinterpret_cast<const unsigned char *>(base) + tile * (size_t)TILE + sub * 1024;
                 dma_1k_s(__builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(stage * STAGE + which * TILE + sub * 1024)),
-                         bwd_uniform_ptr(src), (uint32_t)(lane * 16));
+                         uniform_ptr(src), (uint32_t)(lane * 16));
             }
         if (wave == 0) {
             const uint32_t vec = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(stage * STAGE + VEC));
-            dma_dword_s(vec, bwd_uniform_ptr(lse2p + tile * 64), (uint32_t)(lane * 4));
-            dma_dword_s(vec + 256, bwd_uniform_ptr(deltap + tile * 64), (uint32_t)(lane * 4));
+            dma_dword_s(vec, uniform_ptr(lse2p + tile * 64), (uint32_t)(lane * 4));
+            dma_dword_s(vec + 256, uniform_ptr(deltap + tile * 64), (uint32_t)(lane * 4));
         }
     };
     auto tiles_of = [&](int i) { return (csize[i] * g.G + 63) >> 6; };

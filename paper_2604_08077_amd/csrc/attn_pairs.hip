@@ -410,12 +410,8 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_pairs_kernel(
             // wave-uniform by construction; said again so that they are kept in scalar registers
             const uint32_t dst = __builtin_amdgcn_readfirstlane(
                 lds0 + (uint32_t)((isv ? C::OFF_V : C::OFF_K) + (q / C::PIECES) * C::TILE_STRIDE + (q % C::PIECES) * 1024));
-            const uintptr_t src = reinterpret_cast<uintptr_t>(isv ? vbase : kbase) + (size_t)q * 1024;
-            // (readfirstlane returns a signed int: widen through uint32_t, or a low half with bit 31 set would
-            // smear ones over the high half)
-            const uintptr_t src_u = (uintptr_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)src) |
-                                    ((uintptr_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(src >> 32)) << 32);
-            dma_1k_s(dst, reinterpret_cast<const void *>(src_u), (uint32_t)(lane * 16));
+            const unsigned char *src = reinterpret_cast<const unsigned char *>(isv ? vbase : kbase) + (size_t)q * 1024;
+            dma_1k_s(dst, uniform_ptr(src), (uint32_t)(lane * 16));
         }
     }
 

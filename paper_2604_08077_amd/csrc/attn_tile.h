@@ -29,6 +29,16 @@ __device__ __forceinline__ void dma_1k_s(uint32_t lds_addr, const void *sbase, u
                  : "memory", "m0");
 }
 
+// A wave-uniform pointer moved into scalar registers, as dma_1k_s wants its base (readfirstlane returns a signed
+// int: each half is widened through uint32_t, or a low half with bit 31 set would smear ones over the high half).
+__device__ __forceinline__ const void *uniform_ptr(const void *p)
+{
+    const uintptr_t u = reinterpret_cast<uintptr_t>(p);
+    const uintptr_t r = (uintptr_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)u) |
+                        ((uintptr_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(u >> 32)) << 32);
+    return reinterpret_cast<const void *>(r);
+}
+
 // Plain hardware max.  fmaxf() would first canonicalise each operand (one extra instruction per MFMA result);
 // the scores are never signalling NaNs, and -inf (masked keys) orders as it should.
 __device__ __forceinline__ float vmax(float a, float b)

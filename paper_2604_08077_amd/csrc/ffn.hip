@@ -9,7 +9,7 @@ namespace adaspark {
 
 constexpr int SEL_THREADS = 1024;
 constexpr int TAB_THREADS = 256;
-constexpr int FIN_THREADS = 1024;
+constexpr int FIN_THREADS = 512;
 
 __device__ __forceinline__ float wave_sum(float x)
 {
@@ -51,28 +51,35 @@ __global__ __launch_bounds__(SEL_THREADS) void ffn_select_kernel(Geom g, int d_m
     const int chunks = d_model / 8;  // 16-byte pieces of a token
     if (threadIdx.x == 0) *cnt = 0;
 
-    // token norms: a wavefront per token, two tokens in flight
-    for (int r = wave; r < n; r += 2 * (SEL_THREADS / 64)) {
-        const int r2 = r + SEL_THREADS / 64;
-        const uint16_t *x0 = X + (size_t)token_of(g, b, r) * d_model;
-        const uint16_t *x1 = X + (size_t)token_of(g, b, r2 < n ? r2 : r) * d_model;
-        float a0 = 0.f, a1 = 0.f;
-        for (int k = lane; k < chunks; k += 64) {
-            const u32x4 v0 = *reinterpret_cast<const u32x4 *>(x0 + 8 * k);
-            const u32x4 v1 = *reinterpret_cast<const u32x4 *>(x1 + 8 * k);
+    // token norms: a wavefront per token, four tokens in flight
+    constexpr int NW = SEL_THREADS / 64, INFLIGHT = 4;
+    for (int r0 = wave; r0 < n; r0 += INFLIGHT * NW) {
+        const uint16_t *x[INFLIGHT];
+        float a[INFLIGHT];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float l0 = __uint_as_float(v0[e] << 16), h0 = __uint_as_float(v0[e] & 0xffff0000u);
-                const float l1 = __uint_as_float(v1[e] << 16), h1 = __uint_as_float(v1[e] & 0xffff0000u);
-                a0 = fmaf(l0, l0, a0); a0 = fmaf(h0, h0, a0);
-                a1 = fmaf(l1, l1, a1); a1 = fmaf(h1, h1, a1);
-            }
+        for (int u = 0; u < INFLIGHT; ++u) {
+            const int r = r0 + u * NW;
+            x[u] = X + (size_t)token_of(g, b, r < n ? r : r0) * d_model;
+            a[u] = 0.f;
         }
-        a0 = wave_sum(a0);
-        a1 = wave_sum(a1);
-        if (lane == 0) {
-            sc[r] = sqrtf(a0);
-            if (r2 < n) sc[r2] = sqrtf(a1);
+        for (int k = lane; k < chunks; k += 64) {
+            u32x4 v[INFLIGHT];
+#pragma unroll
+            for (int u = 0; u < INFLIGHT; ++u) v[u] = *reinterpret_cast<const u32x4 *>(x[u] + 8 * k);
+#pragma unroll
+            for (int u = 0; u < INFLIGHT; ++u)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float lo = __uint_as_float(v[u][e] << 16), hi = __uint_as_float(v[u][e] & 0xffff0000u);
+                    a[u] = fmaf(lo, lo, a[u]);
+                    a[u] = fmaf(hi, hi, a[u]);
+                }
+        }
+#pragma unroll
+        for (int u = 0; u < INFLIGHT; ++u) {
+            const float tot = wave_sum(a[u]);
+            const int r = r0 + u * NW;
+            if (lane == 0 && r < n) sc[r] = sqrtf(tot);
         }
     }
     __syncthreads();
@@ -187,7 +194,7 @@ __global__ __launch_bounds__(TAB_THREADS) void ffn_fill_kernel(Geom g, const uin
 }
 
 // Eqs. 6-7 for cube blockIdx.x: F holds FFN(x) of the activated tokens (fp32, row = index in the active list).
-// A thread owns four columns (per block of 4 * FIN_THREADS columns): it walks the cube's activated rows once,
+// A thread owns eight columns (per block of 8 * FIN_THREADS columns): it walks the cube's activated rows once,
 // writing y = x + F and summing F (rows in list order), then gives the bypassed tokens x + mean.
 __global__ __launch_bounds__(FIN_THREADS) void ffn_finish_kernel(Geom g, int d_model, const uint16_t *__restrict__ X,
                                                                  const float *__restrict__ F,
@@ -200,42 +207,48 @@ __global__ __launch_bounds__(FIN_THREADS) void ffn_finish_kernel(Geom g, int d_m
     const int n = b.size();
     const int first = cube_ptr[c], count = cube_ptr[c + 1] - first;
     const float inv = count > 0 ? 1.0f / (float)count : 0.f;
-    auto add_store = [&](int tok, int col, const f32x4 &f) __attribute__((always_inline)) {
-        const uint2 xv = *reinterpret_cast<const uint2 *>(X + (size_t)tok * d_model + col);
-        uint2 o;
-        o.x = (uint32_t)float_to_bf16_bits(__uint_as_float(xv.x << 16) + f[0]) |
-              ((uint32_t)float_to_bf16_bits(__uint_as_float(xv.x & 0xffff0000u) + f[1]) << 16);
-        o.y = (uint32_t)float_to_bf16_bits(__uint_as_float(xv.y << 16) + f[2]) |
-              ((uint32_t)float_to_bf16_bits(__uint_as_float(xv.y & 0xffff0000u) + f[3]) << 16);
-        *reinterpret_cast<uint2 *>(Y + (size_t)tok * d_model + col) = o;
+    auto add_store = [&](int tok, int col, const f32x4 &f0, const f32x4 &f1) __attribute__((always_inline)) {
+        const u32x4 xv = *reinterpret_cast<const u32x4 *>(X + (size_t)tok * d_model + col);
+        u32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float lo = __uint_as_float(xv[e] << 16) + (e < 2 ? f0[2 * e] : f1[2 * e - 4]);
+            const float hi = __uint_as_float(xv[e] & 0xffff0000u) + (e < 2 ? f0[2 * e + 1] : f1[2 * e - 3]);
+            o[e] = (uint32_t)float_to_bf16_bits(lo) | ((uint32_t)float_to_bf16_bits(hi) << 16);
+        }
+        *reinterpret_cast<u32x4 *>(Y + (size_t)tok * d_model + col) = o;
     };
-    for (int col = 4 * threadIdx.x; col < d_model; col += 4 * FIN_THREADS) {
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int col = 8 * threadIdx.x; col < d_model; col += 8 * FIN_THREADS) {
+        f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
         const float *f = F + (size_t)first * d_model + col;
         int r = 0;
         for (; r + 4 <= count; r += 4) {
-            f32x4 v[4];
+            f32x4 v0[4], v1[4];
             int tok[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                v[u] = *reinterpret_cast<const f32x4 *>(f + (size_t)(r + u) * d_model);
+                v0[u] = *reinterpret_cast<const f32x4 *>(f + (size_t)(r + u) * d_model);
+                v1[u] = *reinterpret_cast<const f32x4 *>(f + (size_t)(r + u) * d_model + 4);
                 tok[u] = active[first + r + u];
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                acc += v[u];
-                add_store(tok[u], col, v[u]);
+                acc0 += v0[u];
+                acc1 += v1[u];
+                add_store(tok[u], col, v0[u], v1[u]);
             }
         }
         for (; r < count; ++r) {
-            const f32x4 v = *reinterpret_cast<const f32x4 *>(f + (size_t)r * d_model);
-            acc += v;
-            add_store(active[first + r], col, v);
+            const f32x4 v0 = *reinterpret_cast<const f32x4 *>(f + (size_t)r * d_model);
+            const f32x4 v1 = *reinterpret_cast<const f32x4 *>(f + (size_t)r * d_model + 4);
+            acc0 += v0;
+            acc1 += v1;
+            add_store(active[first + r], col, v0, v1);
         }
-        const f32x4 mean = acc * inv;
+        const f32x4 mean0 = acc0 * inv, mean1 = acc1 * inv;
         for (int j = 0; j < n; ++j) {
             const int tok = token_of(g, b, j);
-            if (slot[tok] < 0) add_store(tok, col, mean);
+            if (slot[tok] < 0) add_store(tok, col, mean0, mean1);
         }
     }
 }

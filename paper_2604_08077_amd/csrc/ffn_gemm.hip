@@ -22,15 +22,6 @@ constexpr int TILE_BYTES = GT * GK * 2;     // 32 KB
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;  // activations, weights
 constexpr int GEMM_LDS = 2 * STAGE_BYTES;   // 128 KB
 
-// A wave-uniform pointer moved into scalar registers (readfirstlane returns a signed int: widen through uint32_t).
-__device__ __forceinline__ const void *uniform_ptr(const void *p)
-{
-    const uintptr_t u = reinterpret_cast<uintptr_t>(p);
-    const uintptr_t r = (uintptr_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)u) |
-                        ((uintptr_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(u >> 32)) << 32);
-    return reinterpret_cast<const void *>(r);
-}
-
 template <bool GATED>
 __global__ __launch_bounds__(GEMM_THREADS) void ffn_gemm_kernel(const uint16_t *__restrict__ A,
                                                                 const int32_t *__restrict__ gather,
