@@ -90,6 +90,8 @@ TEST_WORKLOADS = {
     "T_text128": _wl("T_text128", 19, (5, 10, 12), (4, 4, 8), 6, 2, 128, 0.9, (0.0, 2.0), text=37),
     # text on both sides of the video: 70 leading tokens (two full text cubes and one of 6), 45 trailing
     "T_lead64": _wl("T_lead64", 21, (6, 8, 8), (2, 4, 4), 4, 2, 64, 0.8, 1.0, text=45, lead=70),
+    # two cubes of 2,048 tokens: 32 key tiles per cube, several key blocks per cube in the key-stationary kernels
+    "T_cube2048": _wl("T_cube2048", 25, (8, 16, 32), (4, 16, 32), 2, 1, 64, 0.9, 1.0),
     # a short leading prompt only (a single text cube of 50), ragged video grid, D 128
     "T_lead128": _wl("T_lead128", 22, (5, 10, 12), (4, 4, 8), 6, 2, 128, 0.9, (0.0, 2.0), lead=50),
 }

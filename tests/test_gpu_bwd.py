@@ -82,7 +82,7 @@ def run_case(B, oracle, name, p, dense=False):
 
 @pytest.mark.parametrize("name,p", [("T_tiny", 0.8), ("T_mha64", 0.7), ("T_ragged", 0.9), ("T_text64", 0.8),
                                     ("T_lead64", 0.8), ("T_manycubes", 0.6), ("T_lead128", 0.9), ("C1", 0.9),
-                                    ("M_bwd256", 0.8)])
+                                    ("M_bwd256", 0.8), ("T_cube2048", 0.9)])
 def test_backward_matches_oracle(B, oracle, name, p):
     run_case(B, oracle, name, p)
 

@@ -58,6 +58,7 @@ CASES = [
     ("T_text64", 512, 256, 0.7),
     ("T_lead64", 256, 640, 0.5),
     ("T_gqa128", 768, 1152, 0.7),
+    ("T_cube2048", 256, 256, 0.6),      # 2,048 tokens per cube: more tokens than threads in every per-cube kernel
 ]
 
 

@@ -453,3 +453,37 @@ def test_lse_matches_attended_logits(B, oracle):
         causal = pos <= pos[n]
         ref_d = np.log(np.exp(logits[causal] - logits[causal].max()).sum()) + logits[causal].max()
         assert abs(lse_d[r].item() - ref_d) < LSE_ABS, (r, lse_d[r].item(), ref_d)
+
+
+def test_cubes_of_2048_tokens(B, oracle):
+    """Two cubes of 2,048 tokens (32 key tiles each, eight row blocks per cube): the row-stationary kernels and the
+    dense entry against the oracle; the key-stationary kernel covers cubes up to 256 tokens and says so."""
+    w = synth.TEST_WORKLOADS["T_cube2048"]
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    Q, K, V = synth.generate(w)
+    Qg, Kg, Vg = Q.cuda(), K.cuda(), V.cuda()
+    p32 = float(np.float32(w.top_p[0]))
+    kbar_ref = oracle.cube_pool(osh, K)
+    ref_mask, ref_count, near = oracle.cube_select(osh, Q, kbar_ref, p32)
+    print(f"[{w.name}] pool + select", flush=True)
+    kbar = B.cube_pool(sh, Kg)
+    mask, count, _, _ = B.cube_select(sh, Qg, kbar, p32)
+    torch.cuda.synchronize()
+    assert np.abs(kbar.cpu().numpy().astype(np.float64) - kbar_ref).max() <= KBAR_ABS
+    check_selection(w.name, to_u32(mask), count.cpu().numpy(), ref_mask, ref_count, near)
+    ref_out, _ = oracle.sparse_attn(osh, Q, K, V, ref_mask)
+    mg = torch.from_numpy(ref_mask.view(np.int32)).cuda()
+    packed = B.kv_pack(sh, Kg, Vg)
+    for kern in (B.SPARSE_AUTO, B.SPARSE_MASKED, B.SPARSE_COMPACT):
+        print(f"[{w.name}] sparse attention, kernel {kern}", flush=True)
+        O = B.sparse_attn_packed(sh, Qg, packed, mg, kernel=kern)
+        torch.cuda.synchronize()
+        check_outputs(f"{w.name} kernel {kern}", O.reshape(-1, w.D).float().cpu().numpy(), ref_out)
+    with pytest.raises(B.AdasparkError) as e:
+        B.pairs_workspace_bytes(sh, 1000)
+    assert e.value.status == -2
+    print(f"[{w.name}] dense", flush=True)
+    Od = B.dense_attn(sh, Qg, Kg, Vg)
+    torch.cuda.synchronize()
+    check_outputs(f"{w.name} dense", Od.reshape(-1, w.D).float().cpu().numpy(), oracle.dense_attn(osh, Q, K, V))
+
