@@ -412,8 +412,10 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
     constexpr int NS = 2, KSTEPS = D / 32;
     constexpr int TILE = 64 * D * 2;
     constexpr int NT = WHICH == 0 ? 2 : 3;   // dV: Q natural, dO transposed; dK: Q natural, dO natural, Q transposed
-    constexpr int VEC = NT * TILE;           // per stage: then 64 floats lse2, 64 floats delta
-    constexpr int STAGE = VEC + 2 * 256;
+    constexpr int VEC = NT * TILE;           // per row tile: then 64 floats lse2, 64 floats delta
+    constexpr int SLOT = VEC + 2 * 256;
+    constexpr int TPS = WHICH == 0 ? 2 : 1;  // row tiles per step (per barrier): as many as two stages of them fit
+    constexpr int STAGE = TPS * SLOT;
     constexpr int PIECES = TILE / 1024;
     extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
 
@@ -451,9 +453,11 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem);
     const size_t head_tiles = (size_t)kv * g.N * tpcr;
     const size_t cm_base = ((size_t)kv * g.N + j) * g.N;
-    // row tile t of cube i into `stage`: the tiles by all wavefronts, the two per-row vectors by wavefront 0
-    auto issue = [&](int stage, int i, int t) __attribute__((always_inline)) {
+    // row tile t of cube i into slot `slot` of `stage`: the tiles by all wavefronts, the two per-row vectors by
+    // wavefront 0
+    auto issue_tile = [&](int stage, int slot, int i, int t) __attribute__((always_inline)) {
         const size_t tile = head_tiles + (size_t)i * tpcr + t;
+        stage = stage * TPS + slot;  // in units of SLOT
 #pragma unroll
         for (int which = 0; which < NT; ++which)
 #pragma unroll
@@ -461,16 +465,22 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
                 const int sub = wave * (PIECES / 8) + u;
                 const uint16_t *base = WHICH == 0 ? (which == 0 ? Qn : dOt) : (which == 0 ? Qn : which == 1 ? dOn : Qt);
                 const unsigned char *src = reinterpret_cast<const unsigned char *>(base) + tile * (size_t)TILE + sub * 1024;
-                dma_1k_s(__builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(stage * STAGE + which * TILE + sub * 1024)),
+                dma_1k_s(__builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(stage * SLOT + which * TILE + sub * 1024)),
                          uniform_ptr(src), (uint32_t)(lane * 16));
             }
         if (wave == 0) {
-            const uint32_t vec = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(stage * STAGE + VEC));
+            const uint32_t vec = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)(stage * SLOT + VEC));
             dma_dword_s(vec, uniform_ptr(lse2p + tile * 64), (uint32_t)(lane * 4));
             dma_dword_s(vec + 256, uniform_ptr(deltap + tile * 64), (uint32_t)(lane * 4));
         }
     };
     auto tiles_of = [&](int i) { return (csize[i] * g.G + 63) >> 6; };
+    // the TPS tiles t .. t + TPS - 1 of cube i, as far as the cube has them (nt tiles)
+    auto issue = [&](int stage, int i, int t, int nt) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < TPS; ++u)
+            if (t + u < nt) issue_tile(stage, u, i, t + u);
+    };
 
     f32x4 acc[NS][D / 16];
 #pragma unroll
@@ -481,18 +491,20 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
     // Row cubes from the last one down to the own cube: workgroups that start together then stream the same tiles at
     // the same time, whatever their key cube, and one copy in L2 serves them all.
     int ii = g.N - 1, it = 0, int_ = tiles_of(g.N - 1);
-    issue(0, ii, 0);
-    if (++it == int_) { --ii; it = 0; int_ = ii >= j ? tiles_of(ii) : 0; }
+    issue(0, ii, 0, int_);
+    if ((it += TPS) >= int_) { --ii; it = 0; int_ = ii >= j ? tiles_of(ii) : 0; }
     int stage = 0;
     for (int i = g.N - 1; i >= j; --i) {
         const int nt = tiles_of(i);
-        for (int t = 0; t < nt; ++t) {
+        for (int tb = 0; tb < nt; tb += TPS) {
             tile_barrier();
             if (ii >= j) {
-                issue(stage ^ 1, ii, it);
-                if (++it == int_) { --ii; it = 0; int_ = ii >= j ? tiles_of(ii) : 0; }
+                issue(stage ^ 1, ii, it, int_);
+                if ((it += TPS) >= int_) { --ii; it = 0; int_ = ii >= j ? tiles_of(ii) : 0; }
             }
-            const unsigned char *t0 = smem + stage * STAGE;
+            auto tile_work = [&](int slot) __attribute__((always_inline)) {
+            const int t = tb + slot;
+            const unsigned char *t0 = smem + stage * STAGE + slot * SLOT;
             const float *lv = reinterpret_cast<const float *>(t0 + VEC);
             const float *dv = lv + 64;
             // bit k: row k of the tile selected cube j (rows of the own cube attend it by rule)
@@ -540,6 +552,9 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
             half(std::integral_constant<int, 1>{});
             __builtin_amdgcn_sched_barrier(0);
             tn_tile<D, NS>(t0 + (WHICH == 0 ? TILE : 2 * TILE), n16, q4, pf, acc);
+            };
+            tile_work(0);
+            if (TPS > 1 && tb + 1 < nt) tile_work(1);
             stage ^= 1;
         }
     }
@@ -590,7 +605,7 @@ static hipError_t launch_bwd_d(const Geom &g, const uint16_t *Q, const uint16_t 
     const int lds_q = 2 * 3 * TILE;
     const int nkb = (g.Cmax + BWD_ROWS - 1) / BWD_ROWS;
     const dim3 grid_k(bwd_grid(g.Hkv, g.N * nkb));
-    const int lds_v = 2 * (2 * TILE + 512), lds_k = 2 * (3 * TILE + 512);
+    const int lds_v = 2 * 2 * (2 * TILE + 512), lds_k = 2 * (3 * TILE + 512);
 #define ADASPARK_BWD_LAUNCH(MASKED)                                                                                    \
     do {                                                                                                               \
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bwd_dq_kernel<D, MASKED>),                        \
