@@ -185,6 +185,9 @@ def main():
     ap.add_argument("--workload", default="C3", choices=sorted(synth.WORKLOADS))
     ap.add_argument("--top-p", type=float, default=0.9)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--shared-selection", action="store_true",
+                    help="select once per (token, KV head) from the group's mean query (adaspark_cube_select_shared) "
+                         "instead of per query head; a variant, not the headline configuration")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-ffn", action="store_true", help="skip the token-selective FFN leg (Sec. 3.3)")
     ap.add_argument("--no-bwd", action="store_true", help="skip the attention backward leg")
@@ -231,7 +234,11 @@ def main():
         B.cube_pool(sh, Kg, kbar)
 
     def f_select():
-        B.cube_select(sh, Qg, kbar, p, sel_mask=mask, sel_count=count, workspace=ws_sel)
+        nonlocal mask, count
+        if args.shared_selection:
+            mask, count = B.cube_select_shared(sh, Qg, kbar, p)
+        else:
+            B.cube_select(sh, Qg, kbar, p, sel_mask=mask, sel_count=count, workspace=ws_sel)
 
     def f_pack():
         B.kv_pack(sh, Kg, Vg, ws_att)
@@ -327,6 +334,7 @@ def main():
             "workload": f"{w.name}: {w.T}x{w.H}x{w.W} tokens={w.S}, cube {w.ct}x{w.ch}x{w.cw} ({N} cubes), "
                         f"{w.Hq}q/{w.Hkv}kv heads, head_dim {w.D}, top_p {args.top_p}, causal, batch 1",
             "top_p": args.top_p,
+            "selection": "shared by the GQA group" if args.shared_selection else "per query head",
         },
         "effective_tflops": attn_tflops,
         "effective_flops_per_step": eff_flops,
@@ -355,7 +363,7 @@ def main():
         del ws_att, mask, count, O
         torch.cuda.empty_cache()
         out["adas_ffn"] = ffn_leg(B, w, args.steps, dense=not args.no_dense)
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.shared_selection:
         out["cpu_baseline"] = cpu_baseline(w, p, Q, K, V)
     print(json.dumps(out), flush=True)
 

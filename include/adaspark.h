@@ -73,7 +73,8 @@ typedef enum {
     ADASPARK_CALL_CUBE_SELECT = 1,
     ADASPARK_CALL_SPARSE_ATTN = 2,
     ADASPARK_CALL_DENSE_ATTN = 3,
-    ADASPARK_CALL_ATTN_BWD = 4
+    ADASPARK_CALL_ATTN_BWD = 4,
+    ADASPARK_CALL_CUBE_SELECT_SHARED = 5
 } adaspark_call;
 
 /* Which kernel a sparse-attention call runs.  All compute the same result (Eq. 3).
@@ -153,6 +154,20 @@ int adaspark_cube_select(const adaspark_shape *shape, const void *Q, const float
 int adaspark_cube_select_topk(const adaspark_shape *shape, const void *Q, const float *kbar, int32_t top_k, int causal,
                               uint32_t *sel_mask, int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx,
                               int64_t capacity, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Group-shared Top-p selection: a variant in which the query heads of a GQA group share one set of cubes per token
+ * (the paper selects per query head and does not discuss grouped-query attention).  The cubes are scored by the
+ * group's mean query -- equivalently, by the mean of the group's logits of Eq. 1 -- and Eq. 2 is applied once per
+ * (token, KV head); every row of the group gets that set.  The mean query is part of the definition, precision
+ * included: the group's bf16 queries added in head order in float32, times float32(1)/float32(group size), rounded
+ * to bf16 (nearest even).  With one query head per KV head this is adaspark_cube_select.
+ *   outputs as adaspark_cube_select (no compact list);
+ *   workspace  adaspark_workspace_bytes(ADASPARK_CALL_CUBE_SELECT_SHARED)
+ */
+int adaspark_cube_select_shared(const adaspark_shape *shape, const void *Q, const float *kbar, float top_p, int causal,
+                                uint32_t *sel_mask, int32_t *sel_count, void *workspace, size_t workspace_bytes,
+                                void *stream);
 
 /*
  * Sparse attention (Eq. 3 plus the own-cube rule of Sec. 3.2): row r attends

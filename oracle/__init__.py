@@ -14,6 +14,8 @@ from .adaspark_oracle import (  # noqa: F401
     top_k,
     cube_select,
     cube_select_topk,
+    cube_select_shared,
+    group_mean_query,
     sparse_attn,
     dense_attn,
     num_threads,

@@ -235,3 +235,37 @@ def dense_attn(shape: Shape, Q, K, V, rows=None) -> np.ndarray:
     lib.oracle_dense_attn(ctypes.byref(cs), _p(q, ctypes.c_uint16), _p(k, ctypes.c_uint16), _p(v, ctypes.c_uint16),
                           _p(r, ctypes.c_int64), ctypes.c_int64(nrows), _p(out, ctypes.c_double))
     return out
+
+
+def bf16_round(x32: np.ndarray) -> np.ndarray:
+    """float32 -> bf16 bit patterns (uint16), round to nearest even (NaN inputs are not expected here)."""
+    u = np.ascontiguousarray(x32, np.float32).view(np.uint32)
+    return ((u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)).astype(np.uint16)
+
+
+def group_mean_query(shape: Shape, Q) -> np.ndarray:
+    """The query that scores the cubes for a whole GQA group: bf16 bit patterns [S, Hkv, D].
+
+    The precision is part of the definition (a selection is decided by it, so both sides compute it alike): the
+    group's queries are added in head order in float32, the sum is multiplied by float32(1)/float32(G), and the
+    product is rounded to bf16 (nearest even)."""
+    q = _u16(Q).reshape(shape.S, shape.Hkv, shape.Hq // shape.Hkv, shape.D)
+    q32 = (q.astype(np.uint32) << 16).view(np.float32)
+    acc = np.zeros((shape.S, shape.Hkv, shape.D), np.float32)
+    for g in range(shape.Hq // shape.Hkv):
+        acc = acc + q32[:, :, g, :]
+    inv = np.float32(1.0) / np.float32(shape.Hq // shape.Hkv)
+    return bf16_round(acc * inv)
+
+
+def cube_select_shared(shape: Shape, Q, kbar: np.ndarray, p: float, eps: float = 1e-5):
+    """Group-shared selection (a variant, not in the paper): Eqs. 1-2 applied once per (token, KV head) to the
+    group's mean query (group_mean_query), the kept set shared by all query heads of the group.
+    -> (sel_mask uint32 [S*Hq, words], sel_count int32 [S*Hq], near_cut bool [S*Hq]), rows n*Hq + a."""
+    G = shape.Hq // shape.Hkv
+    one = Shape(shape.T, shape.H, shape.W, shape.ct, shape.ch, shape.cw, shape.Hkv, shape.Hkv, shape.D, shape.text,
+                shape.lead)
+    mask, count, near = cube_select(one, group_mean_query(shape, Q), kbar, p, eps=eps)
+    rows = np.arange(shape.S * shape.Hq)
+    src = (rows // shape.Hq) * shape.Hkv + (rows % shape.Hq) // G
+    return mask[src], count[src], near[src]

@@ -15,7 +15,7 @@ import torch
 
 from .build import lib_path
 
-CALL_CUBE_POOL, CALL_CUBE_SELECT, CALL_SPARSE_ATTN, CALL_DENSE_ATTN, CALL_ATTN_BWD = 0, 1, 2, 3, 4
+CALL_CUBE_POOL, CALL_CUBE_SELECT, CALL_SPARSE_ATTN, CALL_DENSE_ATTN, CALL_ATTN_BWD, CALL_CUBE_SELECT_SHARED = 0, 1, 2, 3, 4, 5
 
 
 class _CShape(ctypes.Structure):
@@ -78,6 +78,7 @@ EXPORTS = (
     "adaspark_cube_pool",
     "adaspark_cube_select",
     "adaspark_cube_select_topk",
+    "adaspark_cube_select_shared",
     "adaspark_sparse_attn",
     "adaspark_dense_attn",
     "adaspark_kv_pack",
@@ -114,6 +115,8 @@ def load():
                                              ctypes.c_int64, vp, ctypes.c_size_t, vp]
         lib.adaspark_cube_select_topk.argtypes = [sp, vp, vp, ctypes.c_int32, ctypes.c_int, vp, vp, vp, vp,
                                                   ctypes.c_int64, vp, ctypes.c_size_t, vp]
+        lib.adaspark_cube_select_shared.argtypes = [sp, vp, vp, ctypes.c_float, ctypes.c_int, vp, vp, vp, ctypes.c_size_t,
+                                                    vp]
         lib.adaspark_sparse_attn.argtypes = [sp, vp, vp, vp, vp, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
         lib.adaspark_dense_attn.argtypes = [sp, vp, vp, vp, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
         lib.adaspark_kv_pack.argtypes = [sp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -385,3 +388,20 @@ def sparse_attn_bwd(shape: Shape, Q, K, V, O, lse, dO, sel_mask=None, causal: bo
         _dev(workspace, torch.uint8, workspace.numel(), "workspace"), workspace.numel(), _stream()),
         "adaspark_sparse_attn_bwd")
     return dQ, dK, dV
+
+
+def cube_select_shared(shape: Shape, Q: torch.Tensor, kbar: torch.Tensor, top_p: float, causal: bool = True):
+    """Group-shared selection: one Top-p set per (token, KV head) from the group's mean query, copied to the rows
+    of all its query heads -> (sel_mask int32-viewed-u32 [R, words], sel_count int32 [R])."""
+    R, N = shape.rows, num_cubes(shape)
+    words = (N + 31) // 32
+    sel_mask = torch.empty((R, words), dtype=torch.int32, device=Q.device)
+    sel_count = torch.empty((R,), dtype=torch.int32, device=Q.device)
+    workspace = alloc_workspace(shape, CALL_CUBE_SELECT_SHARED, Q.device)
+    cs = shape._c()
+    _check(load().adaspark_cube_select_shared(
+        ctypes.byref(cs), _dev(Q, torch.bfloat16, R * shape.head_dim, "Q"),
+        _dev(kbar, torch.float32, N * shape.kv_heads * shape.head_dim, "kbar"), ctypes.c_float(top_p), int(bool(causal)),
+        _dev(sel_mask, torch.int32, R * words, "sel_mask"), _dev(sel_count, torch.int32, R, "sel_count"),
+        workspace.data_ptr(), workspace.numel(), _stream()), "adaspark_cube_select_shared")
+    return sel_mask, sel_count

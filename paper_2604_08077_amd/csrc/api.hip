@@ -72,6 +72,7 @@ int adaspark_workspace_bytes(const adaspark_shape *shape, int which_call, size_t
     case ADASPARK_CALL_SPARSE_ATTN:
     case ADASPARK_CALL_DENSE_ATTN: *bytes = attn_workspace_bytes(g); return ADASPARK_OK;
     case ADASPARK_CALL_ATTN_BWD: *bytes = attn_bwd_workspace_bytes(g); return ADASPARK_OK;
+    case ADASPARK_CALL_CUBE_SELECT_SHARED: *bytes = select_shared_workspace_bytes(g); return ADASPARK_OK;
     default: return ADASPARK_EINVAL;
     }
 }
@@ -146,6 +147,23 @@ int adaspark_cube_select_topk(const adaspark_shape *shape, const void *Q, const 
     if (top_k < 0) return ADASPARK_EINVAL;
     return cube_select(shape, Q, kbar, 0.f, top_k, causal, sel_mask, sel_count, row_ptr, cube_idx, capacity, workspace,
                        workspace_bytes, stream);
+}
+
+int adaspark_cube_select_shared(const adaspark_shape *shape, const void *Q, const float *kbar, float top_p, int causal,
+                                uint32_t *sel_mask, int32_t *sel_count, void *workspace, size_t workspace_bytes,
+                                void *stream)
+{
+    if (!(top_p >= 0.f && top_p <= 1.f)) return ADASPARK_EINVAL;  // also rejects NaN
+    int rc = check_shape(shape);
+    if (rc != ADASPARK_OK) return rc;
+    if ((rc = check_ptrs({Q, kbar, sel_mask, sel_count})) != ADASPARK_OK) return rc;
+    if (!causal) return ADASPARK_EUNSUPPORTED;
+    const Geom g = make_geom(*shape);
+    if (workspace == nullptr || !aligned16(workspace) || workspace_bytes < select_shared_workspace_bytes(g))
+        return ADASPARK_EWORKSPACE;
+    const hipError_t e = launch_cube_select_shared(g, static_cast<const uint16_t *>(Q), kbar, top_p, sel_mask, sel_count,
+                                                   workspace, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ADASPARK_OK : ADASPARK_EHIP;
 }
 
 static int attn_check(const adaspark_shape *shape, const void *Q, const uint32_t *sel_mask, bool sparse, int causal,

@@ -114,6 +114,10 @@ size_t select_workspace_bytes(const Geom &g);
 hipError_t launch_cube_select(const Geom &g, const uint16_t *Q, const float *kbar, float top_p, int top_k,
                               uint32_t *sel_mask, int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx,
                               int64_t capacity, void *ws, hipStream_t st);
+// Group-shared variant: one selection per (token, KV head) from the group's mean query, copied to the group's rows.
+size_t select_shared_workspace_bytes(const Geom &g);
+hipError_t launch_cube_select_shared(const Geom &g, const uint16_t *Q, const float *kbar, float top_p, uint32_t *sel_mask,
+                                     int32_t *sel_count, void *ws, hipStream_t st);
 // out[0..n] = exclusive prefix sums of count[0..n-1]; tile_sum: scan_tile_sum_bytes(n) bytes of scratch (select.hip)
 size_t scan_tile_sum_bytes(long long n);
 void launch_exclusive_scan(const int32_t *count, long long n, long long *tile_sum, int64_t *out, hipStream_t st);

@@ -16,6 +16,8 @@
 // of candidate cubes.  Query cubes with up to 256 candidates are handled by cube_select_mfma_kernel (a wavefront
 // holds all candidates of its rows), later ones by cube_select_wide_kernel (four or eight wavefronts share the
 // rows and split the candidates).
+#include <algorithm>
+
 #include "geom.h"
 
 namespace adaspark {
@@ -902,6 +904,95 @@ hipError_t launch_cube_select(const Geom &g, const uint16_t *Q, const float *kba
         hipLaunchKernelGGL(csr_fill_kernel, dim3((unsigned)((R + 255) / 256)), dim3(256), 0, st, g, R, sel_mask, row_ptr,
                            cube_idx, (long long)capacity);
     }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// Group-shared selection (a variant: one set per token and KV head, shared by the group's query heads).  The
+// group's queries are added in head order in float32, multiplied by float32(1)/float32(G) and rounded to bf16; the
+// selection kernels then run on that query with one "query head" per KV head, and the result is copied to the rows
+// of all heads of the group.
+// ---------------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void group_mean_query_kernel(Geom g, float inv_g, const uint16_t *__restrict__ Q,
+                                                               uint16_t *__restrict__ Qbar)
+{
+    const int chunks = g.D / 8;
+    const size_t total = (size_t)g.S * g.Hkv * chunks;
+    for (size_t x = blockIdx.x * (size_t)blockDim.x + threadIdx.x; x < total; x += (size_t)gridDim.x * blockDim.x) {
+        const int c = (int)(x % chunks);
+        const size_t nk = x / chunks;  // token * Hkv + kv
+        const size_t n = nk / g.Hkv, kv = nk % g.Hkv;
+        float acc[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+        for (int h = 0; h < g.G; ++h) {
+            const sel_u32x4 v = *reinterpret_cast<const sel_u32x4 *>(Q + ((n * g.Hq + kv * g.G + h) * g.D + 8 * c));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc[2 * e] = acc[2 * e] + __uint_as_float(v[e] << 16);
+                acc[2 * e + 1] = acc[2 * e + 1] + __uint_as_float(v[e] & 0xffff0000u);
+            }
+        }
+        sel_u32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            o[e] = (uint32_t)float_to_bf16_bits(acc[2 * e] * inv_g) | ((uint32_t)float_to_bf16_bits(acc[2 * e + 1] * inv_g) << 16);
+        *reinterpret_cast<sel_u32x4 *>(Qbar + (nk * g.D + 8 * c)) = o;
+    }
+}
+
+__global__ __launch_bounds__(256) void group_expand_kernel(Geom g, const uint32_t *__restrict__ mask1,
+                                                           const int32_t *__restrict__ count1,
+                                                           uint32_t *__restrict__ sel_mask, int32_t *__restrict__ sel_count)
+{
+    const size_t total = (size_t)g.S * g.Hq * g.words;
+    for (size_t x = blockIdx.x * (size_t)blockDim.x + threadIdx.x; x < total; x += (size_t)gridDim.x * blockDim.x) {
+        const int w = (int)(x % g.words);
+        const size_t r = x / g.words;
+        const size_t src = (r / g.Hq) * g.Hkv + (r % g.Hq) / g.G;
+        sel_mask[x] = mask1[src * g.words + w];
+        if (w == 0) sel_count[r] = count1[src];
+    }
+}
+
+static Geom one_head_per_group(const Geom &g)
+{
+    Geom o = g;
+    o.Hq = g.Hkv;
+    o.G = 1;
+    return o;
+}
+
+size_t select_shared_workspace_bytes(const Geom &g)
+{
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    const size_t rows1 = (size_t)g.S * g.Hkv;
+    return up(select_workspace_bytes(one_head_per_group(g))) + up(rows1 * g.D * 2) + up(rows1 * g.words * 4) + up(rows1 * 4);
+}
+
+hipError_t launch_cube_select_shared(const Geom &g, const uint16_t *Q, const float *kbar, float top_p, uint32_t *sel_mask,
+                                     int32_t *sel_count, void *ws, hipStream_t st)
+{
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    const Geom g1 = one_head_per_group(g);
+    const size_t rows1 = (size_t)g.S * g.Hkv;
+    unsigned char *p = static_cast<unsigned char *>(ws);
+    void *ws1 = p;
+    p += up(select_workspace_bytes(g1));
+    uint16_t *Qbar = reinterpret_cast<uint16_t *>(p);
+    p += up(rows1 * g.D * 2);
+    uint32_t *mask1 = reinterpret_cast<uint32_t *>(p);
+    p += up(rows1 * g.words * 4);
+    int32_t *count1 = reinterpret_cast<int32_t *>(p);
+    const float inv_g = 1.0f / (float)g.G;
+    const size_t n1 = rows1 * (g.D / 8);
+    hipLaunchKernelGGL(group_mean_query_kernel, dim3((unsigned)std::min<size_t>((n1 + 255) / 256, 65536)), dim3(256), 0, st,
+                       g, inv_g, Q, Qbar);
+    hipError_t e = launch_cube_select(g1, Qbar, kbar, top_p, -1, mask1, count1, nullptr, nullptr, 0, ws1, st);
+    if (e != hipSuccess) return e;
+    const size_t n2 = (size_t)g.S * g.Hq * g.words;
+    hipLaunchKernelGGL(group_expand_kernel, dim3((unsigned)std::min<size_t>((n2 + 255) / 256, 65536)), dim3(256), 0, st, g,
+                       mask1, count1, sel_mask, sel_count);
     return hipGetLastError();
 }
 

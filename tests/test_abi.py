@@ -158,3 +158,18 @@ def test_binding_refuses_cpu_tensors(lib):
     _, K, _ = synth.generate(w)
     with pytest.raises(ValueError):
         binding.cube_pool(binding.Shape.of(w), K)
+
+
+def test_shared_selection_arguments_are_validated(lib):
+    cs = _raw_shape()._c()
+    ok_ptr = ctypes.c_void_p(4096)      # never dereferenced: validation fails first
+    need, plain = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    assert lib.adaspark_workspace_bytes(ctypes.byref(cs), binding.CALL_CUBE_SELECT_SHARED, ctypes.byref(need)) == 0
+    assert lib.adaspark_workspace_bytes(ctypes.byref(cs), binding.CALL_CUBE_SELECT, ctypes.byref(plain)) == 0
+    tokens, kv, D = 4 * 8 * 8, 2, 64
+    assert need.value >= tokens * kv * D * 2 + tokens * kv * 8          # the mean queries and their selection
+    run = lambda p=0.9, causal=1, ws=ok_ptr, nbytes=1 << 30, q=ok_ptr: lib.adaspark_cube_select_shared(
+        ctypes.byref(cs), q, ok_ptr, ctypes.c_float(p), causal, ok_ptr, ok_ptr, ws, nbytes, None)
+    assert run(p=1.5) == -1 and run(p=float("nan")) == -1 and run(q=None) == -1
+    assert run(causal=0) == -2
+    assert run(ws=None) == -3 and run(nbytes=need.value - 1) == -3

@@ -487,3 +487,26 @@ def test_cubes_of_2048_tokens(B, oracle):
     torch.cuda.synchronize()
     check_outputs(f"{w.name} dense", Od.reshape(-1, w.D).float().cpu().numpy(), oracle.dense_attn(osh, Q, K, V))
 
+
+@pytest.mark.parametrize("name", ["T_tiny", "T_ragged", "T_gqa128", "T_text64", "T_lead64", "T_cubes280"])
+def test_group_shared_selection(B, oracle, name):
+    """One Top-p set per (token, KV head) from the group's mean query: sets against the oracle's (which computes the
+    mean query in the same float32 steps), shared inside every group, and usable by the attention entry."""
+    w = synth.TEST_WORKLOADS[name]
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    Q, K, V = synth.generate(w)
+    Qg, Kg, Vg = Q.cuda(), K.cuda(), V.cuda()
+    p32 = float(np.float32(w.top_p[0]))
+    kbar = B.cube_pool(sh, Kg)
+    print(f"[{name}] shared selection", flush=True)
+    mask, count = B.cube_select_shared(sh, Qg, kbar, p32)
+    torch.cuda.synchronize()
+    ref_mask, ref_count, near = oracle.cube_select_shared(osh, Q, oracle.cube_pool(osh, K), p32)
+    same = check_selection(f"{name} shared", to_u32(mask), count.cpu().numpy(), ref_mask, ref_count, near)
+    G = w.Hq // w.Hkv
+    m3 = to_u32(mask).reshape(w.S, w.Hkv, G, -1)
+    assert (m3 == m3[:, :, :1]).all()
+    O = B.sparse_attn(sh, Qg, Kg, Vg, mask)
+    torch.cuda.synchronize()
+    ref_out, _ = oracle.sparse_attn(osh, Q, K, V, ref_mask)
+    check_outputs(f"{name} attn(shared sel)", O.reshape(-1, w.D).float().cpu().numpy()[same], ref_out[same])

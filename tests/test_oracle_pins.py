@@ -555,3 +555,40 @@ def test_near_cut_flag_marks_rows_at_the_boundary(oracle):
     kbar2 = oracle.cube_pool(sh, K2)
     _, count2, near2 = oracle.cube_select(sh, Q, kbar2, 0.6)
     assert count2[-1] == 1 and not near2[-1]
+
+
+def test_group_shared_selection_reduces_to_per_head_selection(oracle):
+    """The group-shared variant: with one query head per KV head the mean query is the query itself, so the variant
+    is Eq. 2 unchanged; with the heads of every group made identical (groups of 2 and 4: halving and quartering are
+    exact in float32 and bf16) it equals the per-head selection of that query, copied to the group; and rows of one
+    group always share their set."""
+    w = synth.TEST_WORKLOADS["T_mha64"]                       # 3 query heads, 3 KV heads
+    sh = shape_of(oracle, w)
+    Q, K, _ = synth.generate(w)
+    kbar = oracle.cube_pool(sh, K)
+    a, b = oracle.cube_select_shared(sh, Q, kbar, 0.7), oracle.cube_select(sh, Q, kbar, 0.7)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    for name in ("T_tiny", "T_text64"):                       # 4 query heads, 2 KV heads: groups of 2
+        w = synth.TEST_WORKLOADS[name]
+        sh = shape_of(oracle, w)
+        Q, K, _ = synth.generate(w)
+        kbar = oracle.cube_pool(sh, K)
+        G = w.Hq // w.Hkv
+        Qs = Q.clone()
+        Qs[:, 1::2] = Qs[:, 0::2]                             # both heads of a group carry the first one's query
+        m, c, _ = oracle.cube_select_shared(sh, Qs, kbar, 0.8)
+        pm, pc, _ = oracle.cube_select(sh, Qs, kbar, 0.8)
+        assert np.array_equal(m, pm) and np.array_equal(c, pc)
+        m, c, _ = oracle.cube_select_shared(sh, Q, kbar, 0.8)
+        m3 = m.reshape(w.S, w.Hkv, G, -1)
+        assert (m3 == m3[:, :, :1]).all()
+        # the mean of two bf16 values: exact in float32, then one rounding -- against exact rational arithmetic
+        q = widen(Q).reshape(w.S, w.Hkv, G, w.D)
+        mean = q.mean(axis=2)
+        got = (oracle.group_mean_query(sh, Q).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        assert np.all(np.abs(got - mean) <= np.abs(mean) * 2.0 ** -8 + 1e-30)       # within half a bf16 step
+    # the rounding itself against torch's own float32 -> bfloat16 conversion (round to nearest even), ties included
+    x = np.concatenate([np.random.default_rng(1).standard_normal(4096).astype(np.float32),
+                        np.array([1.00390625, 1.01171875, -1.00390625, 3.0e38, 1e-40, 0.0], np.float32)])
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(oracle.adaspark_oracle.bf16_round(x), want)
