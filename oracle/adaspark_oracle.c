@@ -371,9 +371,9 @@ void oracle_cube_select_topk(const oracle_shape *s, const uint16_t *Q, const dou
  * Q bf16 [S][Hq][D], K,V bf16 [S][Hkv][D]; out fp64 [nrows][D];
  * n_keys (optional) int64 [nrows] = size of the attended key set.
  * ------------------------------------------------------------------------- */
-void oracle_sparse_attn(const oracle_shape *s, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
-                        const int64_t *rows, int64_t nrows, const uint32_t *sel_mask,
-                        double *out, int64_t *n_keys)
+static void sparse_attn_impl(const oracle_shape *s, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
+                             const int64_t *rows, int64_t nrows, const uint32_t *sel_mask,
+                             double *out, int64_t *n_keys, int causal)
 {
     const int S = all_tokens(s), N = oracle_num_cubes(s);
     const int Hq = s->Hq, Hkv = s->Hkv, D = s->D, G = Hq / Hkv;
@@ -401,7 +401,7 @@ void oracle_sparse_attn(const oracle_shape *s, const uint16_t *Q, const uint16_t
             for (int m = 0; m < S; ++m) {
                 const int c = cube_of[m];
                 const int in_selected = (c != i) && ((mrow[c >> 5] >> (c & 31)) & 1u);
-                const int in_own = (c == i) && (rank_of[m] <= rank_of[n]);
+                const int in_own = (c == i) && (!causal || rank_of[m] <= rank_of[n]);
                 if (in_selected || in_own) key[nk++] = m;
             }
             double mx = -INFINITY;
@@ -429,14 +429,30 @@ void oracle_sparse_attn(const oracle_shape *s, const uint16_t *Q, const uint16_t
     free(cube_of); free(rank_of); free(size_of); free(start);
 }
 
+void oracle_sparse_attn(const oracle_shape *s, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
+                        const int64_t *rows, int64_t nrows, const uint32_t *sel_mask,
+                        double *out, int64_t *n_keys)
+{
+    sparse_attn_impl(s, Q, K, V, rows, nrows, sel_mask, out, n_keys, 1);
+}
+
+/* Non-causal mode (causal = 0 of the interface; the paper's operator is causal): the selected cubes may lie on
+ * either side of the own cube, and the own cube is attended in full. */
+void oracle_sparse_attn_noncausal(const oracle_shape *s, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
+                                  const int64_t *rows, int64_t nrows, const uint32_t *sel_mask,
+                                  double *out, int64_t *n_keys)
+{
+    sparse_attn_impl(s, Q, K, V, rows, nrows, sel_mask, out, n_keys, 0);
+}
+
 /* ---------------------------------------------------------------------------
  * Dense causal attention in cube-major order (the comparison point; supp.
  * "Detail of FLOPs Calculation"): a query attends every token whose cube-major
  * position is <= its own.  Coded separately from oracle_sparse_attn (positions,
  * no masks) so that "p -> 1 equals dense" tests two independent loops.
  * ------------------------------------------------------------------------- */
-void oracle_dense_attn(const oracle_shape *s, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
-                       const int64_t *rows, int64_t nrows, double *out)
+static void dense_attn_impl(const oracle_shape *s, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
+                            const int64_t *rows, int64_t nrows, double *out, int causal)
 {
     const int S = all_tokens(s), N = oracle_num_cubes(s);
     const int Hq = s->Hq, Hkv = s->Hkv, D = s->D, G = Hq / Hkv;
@@ -458,7 +474,7 @@ void oracle_dense_attn(const oracle_shape *s, const uint16_t *Q, const uint16_t 
             const uint16_t *qr = Q + ((size_t)n * Hq + a) * D;
             double mx = -INFINITY;
             for (int m = 0; m < S; ++m) {
-                if (pos[m] > pos[n]) { w[m] = -INFINITY; continue; }
+                if (causal && pos[m] > pos[n]) { w[m] = -INFINITY; continue; }
                 double dot = 0.0;
                 const uint16_t *kr = K + ((size_t)m * Hkv + g) * D;
                 for (int d = 0; d < D; ++d) dot += bf16_widen(qr[d]) * bf16_widen(kr[d]);
@@ -466,11 +482,11 @@ void oracle_dense_attn(const oracle_shape *s, const uint16_t *Q, const uint16_t 
                 if (w[m] > mx) mx = w[m];
             }
             double Z = 0.0;
-            for (int m = 0; m < S; ++m) { w[m] = (pos[m] > pos[n]) ? 0.0 : exp(w[m] - mx); Z += w[m]; }
+            for (int m = 0; m < S; ++m) { w[m] = (causal && pos[m] > pos[n]) ? 0.0 : exp(w[m] - mx); Z += w[m]; }
             double *o = out + (size_t)x * D;
             for (int d = 0; d < D; ++d) o[d] = 0.0;
             for (int m = 0; m < S; ++m) {
-                if (pos[m] > pos[n]) continue;
+                if (causal && pos[m] > pos[n]) continue;
                 const uint16_t *vr = V + ((size_t)m * Hkv + g) * D;
                 for (int d = 0; d < D; ++d) o[d] += w[m] * bf16_widen(vr[d]);
             }
@@ -480,3 +496,83 @@ void oracle_dense_attn(const oracle_shape *s, const uint16_t *Q, const uint16_t 
     }
     free(cube_of); free(rank_of); free(size_of); free(start); free(pos);
 }
+
+void oracle_dense_attn(const oracle_shape *s, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
+                       const int64_t *rows, int64_t nrows, double *out)
+{
+    dense_attn_impl(s, Q, K, V, rows, nrows, out, 1);
+}
+
+/* Plain bidirectional attention over all tokens: what the non-causal mode computes when every cube is selected. */
+void oracle_dense_attn_noncausal(const oracle_shape *s, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
+                                 const int64_t *rows, int64_t nrows, double *out)
+{
+    dense_attn_impl(s, Q, K, V, rows, nrows, out, 0);
+}
+
+/* ---------------------------------------------------------------------------
+ * Cube selection in non-causal mode (causal = 0 of the interface; the paper's
+ * operator is causal, Eq. 1 lists the cubes before the own one).  The
+ * candidates of Eqs. 1-2 are ALL video cubes other than the row's own cube;
+ * every text cube other than the own one is attended and its bit set.  Same
+ * outputs and near_cut rule as oracle_cube_select.
+ * ------------------------------------------------------------------------- */
+void oracle_cube_select_noncausal(const oracle_shape *s, const uint16_t *Q, const double *kbar, double p,
+                                  const int64_t *rows, int64_t nrows,
+                                  uint32_t *sel_mask, int32_t *sel_count, uint8_t *near_cut, double eps)
+{
+    const int S = all_tokens(s), N = oracle_num_cubes(s), Nv = oracle_num_video_cubes(s);
+    const int Np = oracle_num_lead_cubes(s);
+    const int Hq = s->Hq, Hkv = s->Hkv, D = s->D, G = Hq / Hkv;
+    const int words = ceil_div(N, 32);
+    int32_t *cube_of = malloc(sizeof(int32_t) * S), *rank_of = malloc(sizeof(int32_t) * S);
+    int32_t *size_of = malloc(sizeof(int32_t) * N);
+    int64_t *start = malloc(sizeof(int64_t) * (N + 1));
+    oracle_cube_map(s, cube_of, rank_of, size_of, start);
+
+    #pragma omp parallel
+    {
+        double *q = malloc(sizeof(double) * D);
+        double *rowsbuf = malloc(sizeof(double) * (size_t)N * D);  /* the candidates' mean keys, gathered */
+        double *logits = malloc(sizeof(double) * N), *probs = malloc(sizeof(double) * N);
+        double *cum = malloc(sizeof(double) * N);
+        uint8_t *keep = malloc(N);
+        int32_t *order = malloc(sizeof(int32_t) * N), *cand = malloc(sizeof(int32_t) * N);
+        #pragma omp for schedule(dynamic, 64)
+        for (int64_t x = 0; x < nrows; ++x) {
+            const int64_t r = rows ? rows[x] : x;
+            const int n = (int)(r / Hq), a = (int)(r % Hq), g = a / G;
+            const int own = cube_of[n];
+            uint32_t *mrow = sel_mask + (size_t)x * words;
+            for (int w = 0; w < words; ++w) mrow[w] = 0;
+            sel_count[x] = 0;
+            if (near_cut) near_cut[x] = 0;
+            int nc = 0;
+            for (int j = 0; j < N; ++j) {
+                if (j == own) continue;
+                if (j < Np || j >= Np + Nv) { mrow[j >> 5] |= (uint32_t)1 << (j & 31); sel_count[x] += 1; }
+                else cand[nc++] = j;
+            }
+            if (nc == 0) continue;
+            for (int d = 0; d < D; ++d) q[d] = bf16_widen(Q[((size_t)n * Hq + a) * D + d]);
+            for (int c = 0; c < nc; ++c)
+                for (int d = 0; d < D; ++d) rowsbuf[(size_t)c * D + d] = kbar[((size_t)cand[c] * Hkv + g) * D + d];
+            oracle_relevance(q, rowsbuf, (int64_t)D, nc, D, logits, probs);
+            const int kept = oracle_top_p(probs, nc, p, keep, order, cum);
+            for (int c = 0; c < nc; ++c) if (keep[c]) mrow[cand[c] >> 5] |= (uint32_t)1 << (cand[c] & 31);
+            sel_count[x] += kept;
+            if (near_cut && p < 1.0 && p > 0.0) {
+                int flag = 0;
+                const double after = cum[kept - 1];
+                const double before = kept >= 2 ? cum[kept - 2] : 0.0;
+                if (after - p < eps || p - before < eps) flag = 1;
+                if (kept < nc && logits[order[kept - 1]] - logits[order[kept]] < eps) flag = 1;
+                if (kept >= 2 && logits[order[kept - 2]] - logits[order[kept - 1]] < eps) flag = 1;
+                near_cut[x] = (uint8_t)flag;
+            }
+        }
+        free(q); free(rowsbuf); free(logits); free(probs); free(cum); free(keep); free(order); free(cand);
+    }
+    free(cube_of); free(rank_of); free(size_of); free(start);
+}
+

@@ -155,7 +155,7 @@ def _rows(rows):
     return np.ascontiguousarray(rows, np.int64)
 
 
-def cube_select(shape: Shape, Q, kbar: np.ndarray, p: float, rows=None, eps: float = 1e-5):
+def cube_select(shape: Shape, Q, kbar: np.ndarray, p: float, rows=None, eps: float = 1e-5, causal: bool = True):
     """Selection for the given rows (all if None).
 
     -> (sel_mask uint32 [nrows, ceil(N/32)], sel_count int32 [nrows], near_cut bool [nrows])
@@ -171,9 +171,10 @@ def cube_select(shape: Shape, Q, kbar: np.ndarray, p: float, rows=None, eps: flo
     mask = np.zeros((nrows, words), np.uint32)
     count = np.zeros(nrows, np.int32)
     near = np.zeros(nrows, np.uint8)
-    lib.oracle_cube_select(ctypes.byref(cs), _p(q, ctypes.c_uint16), _p(kb, ctypes.c_double), ctypes.c_double(p),
-                           _p(r, ctypes.c_int64), ctypes.c_int64(nrows), _p(mask, ctypes.c_uint32),
-                           _p(count, ctypes.c_int32), _p(near, ctypes.c_uint8), ctypes.c_double(eps))
+    fn = lib.oracle_cube_select if causal else lib.oracle_cube_select_noncausal
+    fn(ctypes.byref(cs), _p(q, ctypes.c_uint16), _p(kb, ctypes.c_double), ctypes.c_double(p),
+       _p(r, ctypes.c_int64), ctypes.c_int64(nrows), _p(mask, ctypes.c_uint32),
+       _p(count, ctypes.c_int32), _p(near, ctypes.c_uint8), ctypes.c_double(eps))
     return mask, count, near.astype(bool)
 
 
@@ -208,8 +209,9 @@ def cube_select_topk(shape: Shape, Q, kbar: np.ndarray, k: int, rows=None, eps: 
     return mask, count, near.astype(bool)
 
 
-def sparse_attn(shape: Shape, Q, K, V, sel_mask: np.ndarray, rows=None):
-    """Eq. 3 on the given rows -> (out fp64 [nrows, D], n_keys int64 [nrows])."""
+def sparse_attn(shape: Shape, Q, K, V, sel_mask: np.ndarray, rows=None, causal: bool = True):
+    """Eq. 3 on the given rows -> (out fp64 [nrows, D], n_keys int64 [nrows]).  causal False: the own cube is
+    attended in full and selected cubes may lie after it."""
     lib, cs, N = _load(), shape._c(), num_cubes(shape)
     q, k, v = _u16(Q), _u16(K), _u16(V)
     r = _rows(rows)
@@ -219,21 +221,24 @@ def sparse_attn(shape: Shape, Q, K, V, sel_mask: np.ndarray, rows=None):
     assert m.shape == (nrows, words)
     out = np.empty((nrows, shape.D), np.float64)
     nk = np.empty(nrows, np.int64)
-    lib.oracle_sparse_attn(ctypes.byref(cs), _p(q, ctypes.c_uint16), _p(k, ctypes.c_uint16), _p(v, ctypes.c_uint16),
-                           _p(r, ctypes.c_int64), ctypes.c_int64(nrows), _p(m, ctypes.c_uint32),
-                           _p(out, ctypes.c_double), _p(nk, ctypes.c_int64))
+    fn = lib.oracle_sparse_attn if causal else lib.oracle_sparse_attn_noncausal
+    fn(ctypes.byref(cs), _p(q, ctypes.c_uint16), _p(k, ctypes.c_uint16), _p(v, ctypes.c_uint16),
+       _p(r, ctypes.c_int64), ctypes.c_int64(nrows), _p(m, ctypes.c_uint32),
+       _p(out, ctypes.c_double), _p(nk, ctypes.c_int64))
     return out, nk
 
 
-def dense_attn(shape: Shape, Q, K, V, rows=None) -> np.ndarray:
-    """Causal attention in cube-major order on the given rows -> fp64 [nrows, D]."""
+def dense_attn(shape: Shape, Q, K, V, rows=None, causal: bool = True) -> np.ndarray:
+    """Causal attention in cube-major order on the given rows -> fp64 [nrows, D]; causal False: attention over all
+    tokens."""
     lib, cs = _load(), shape._c()
     q, k, v = _u16(Q), _u16(K), _u16(V)
     r = _rows(rows)
     nrows = shape.S * shape.Hq if r is None else r.size
     out = np.empty((nrows, shape.D), np.float64)
-    lib.oracle_dense_attn(ctypes.byref(cs), _p(q, ctypes.c_uint16), _p(k, ctypes.c_uint16), _p(v, ctypes.c_uint16),
-                          _p(r, ctypes.c_int64), ctypes.c_int64(nrows), _p(out, ctypes.c_double))
+    fn = lib.oracle_dense_attn if causal else lib.oracle_dense_attn_noncausal
+    fn(ctypes.byref(cs), _p(q, ctypes.c_uint16), _p(k, ctypes.c_uint16), _p(v, ctypes.c_uint16),
+       _p(r, ctypes.c_int64), ctypes.c_int64(nrows), _p(out, ctypes.c_double))
     return out
 
 

@@ -592,3 +592,64 @@ def test_group_shared_selection_reduces_to_per_head_selection(oracle):
                         np.array([1.00390625, 1.01171875, -1.00390625, 3.0e38, 1e-40, 0.0], np.float32)])
     want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     assert np.array_equal(oracle.adaspark_oracle.bf16_round(x), want)
+
+
+def test_noncausal_mode_against_library_softmax_and_brute_force(oracle):
+    """causal = 0: (1) every cube selected = plain attention over all tokens, against scipy's softmax; (2) the dense
+    non-causal entry likewise; (3) the selection takes all other video cubes as candidates: brute force per row on
+    a tiny grid; text cubes other than the own one are always set; (4) the attended set of a row = selected cubes
+    + its whole own cube (key counts)."""
+    w = synth.TEST_WORKLOADS["T_tiny"]
+    sh = shape_of(oracle, w)
+    Q, K, V = synth.generate(w)
+    q, k, v = widen(Q), widen(K), widen(V)
+    G = w.Hq // w.Hkv
+    N = oracle.num_cubes(sh)
+    kbar = oracle.cube_pool(sh, K)
+    full, cnt, _ = oracle.cube_select(sh, Q, kbar, 1.0, causal=False)
+    assert (cnt == N - 1).all()
+    out, nk = oracle.sparse_attn(sh, Q, K, V, full, causal=False)
+    assert (nk == w.S).all()
+    want = np.zeros_like(out)
+    for n in range(w.S):
+        for a in range(w.Hq):
+            p = sp_softmax(k[:, a // G] @ q[n, a] / math.sqrt(w.D))
+            want[n * w.Hq + a] = p @ v[:, a // G]
+    np.testing.assert_allclose(out, want, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(oracle.dense_attn(sh, Q, K, V, causal=False), want, rtol=1e-11, atol=1e-12)
+    # brute-force selection
+    bc, _, sizes = brute_cube_table(w)
+    mask, count, _ = oracle.cube_select(sh, Q, kbar, 0.6, causal=False)
+    for r in range(0, w.S * w.Hq, 7):
+        n, a = divmod(r, w.Hq)
+        own = bc[n]
+        cand = [j for j in range(N) if j != own]
+        logits = np.array([kbar[j, a // G] @ q[n, a] / math.sqrt(w.D) for j in cand])
+        probs = sp_softmax(logits)
+        order = sorted(range(len(cand)), key=lambda t: (-probs[t], t))
+        kept, before = set(), 0.0
+        for t in order:
+            if before < 0.6:
+                kept.add(cand[t])
+            before += probs[t]
+        got = {j for j in range(N) if (mask[r, j >> 5] >> (j & 31)) & 1}
+        assert got == kept and count[r] == len(kept) and own not in got
+    out2, nk2 = oracle.sparse_attn(sh, Q, K, V, mask, causal=False)
+    for r in range(0, w.S * w.Hq, 11):
+        own = bc[r // w.Hq]
+        sel = [j for j in range(N) if (mask[r, j >> 5] >> (j & 31)) & 1]
+        assert nk2[r] == sizes[own] + sum(sizes[j] for j in sel)
+    # with text on both sides: every text cube except the own one is set, whatever p
+    w = synth.TEST_WORKLOADS["T_lead64"]
+    sh = shape_of(oracle, w)
+    Q, K, _ = synth.generate(w)
+    bc, _, _ = brute_cube_table(w)
+    N = oracle.num_cubes(sh)
+    full_c = w.ct * w.ch * w.cw
+    Np, Nt = -(-w.lead // full_c), -(-w.text // full_c)
+    mask, count, _ = oracle.cube_select(sh, Q, oracle.cube_pool(sh, K), 0.0, causal=False)
+    text_cubes = list(range(Np)) + list(range(N - Nt, N))
+    for r in range(0, w.S * w.Hq, 5):
+        own = bc[r // w.Hq]
+        got = {j for j in range(N) if (mask[r, j >> 5] >> (j & 31)) & 1}
+        assert got == {j for j in text_cubes if j != own}
