@@ -99,7 +99,12 @@ typedef enum {
 } adaspark_sparse_kernel;
 
 /* Limits: head_dim in {64,128}; number of cubes (text cubes included) <= ADASPARK_MAX_CUBES;
- * tokens*q_heads < 2^31; only causal != 0 (the paper's method) is implemented. */
+ * tokens*q_heads < 2^31.
+ * causal: non-zero is the paper's operator (candidates: the video cubes before the own cube; the own cube up to the
+ * row's rank).  causal == 0 is a variant of the selection and forward attention entries: the candidates of Eqs. 1-2 are
+ * ALL video cubes other than the row's own, every text cube other than the own one is attended (its bit set), the own
+ * cube is attended in full, and the dense entries are plain attention over all tokens; it runs on the masked-walk /
+ * dense kernel (a forced COMPACT or PAIRS gives ADASPARK_EUNSUPPORTED), and the backward entry is causal only. */
 #define ADASPARK_MAX_CUBES 2048
 
 /* Host-only helpers (no GPU work). */

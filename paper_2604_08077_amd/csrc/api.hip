@@ -121,8 +121,8 @@ static int cube_select(const adaspark_shape *shape, const void *Q, const float *
     if ((rc = check_ptrs({Q, kbar, sel_mask, sel_count})) != ADASPARK_OK) return rc;
     if ((row_ptr == nullptr) != (cube_idx == nullptr)) return ADASPARK_EINVAL;
     if (row_ptr != nullptr && (!aligned16(row_ptr) || !aligned16(cube_idx) || capacity < 0)) return ADASPARK_EINVAL;
-    if (!causal) return ADASPARK_EUNSUPPORTED;
-    const Geom g = make_geom(*shape);
+    Geom g = make_geom(*shape);
+    g.causal = causal != 0;
     if (workspace == nullptr || !aligned16(workspace) || workspace_bytes < select_workspace_bytes(g))
         return ADASPARK_EWORKSPACE;
     const hipError_t e =
@@ -157,8 +157,8 @@ int adaspark_cube_select_shared(const adaspark_shape *shape, const void *Q, cons
     int rc = check_shape(shape);
     if (rc != ADASPARK_OK) return rc;
     if ((rc = check_ptrs({Q, kbar, sel_mask, sel_count})) != ADASPARK_OK) return rc;
-    if (!causal) return ADASPARK_EUNSUPPORTED;
-    const Geom g = make_geom(*shape);
+    Geom g = make_geom(*shape);
+    g.causal = causal != 0;
     if (workspace == nullptr || !aligned16(workspace) || workspace_bytes < select_shared_workspace_bytes(g))
         return ADASPARK_EWORKSPACE;
     const hipError_t e = launch_cube_select_shared(g, static_cast<const uint16_t *>(Q), kbar, top_p, sel_mask, sel_count,
@@ -174,7 +174,7 @@ static int attn_check(const adaspark_shape *shape, const void *Q, const uint32_t
     if ((rc = check_ptrs({Q, O})) != ADASPARK_OK) return rc;
     if (sparse && (sel_mask == nullptr || !aligned16(sel_mask))) return ADASPARK_EINVAL;
     if (lse != nullptr && !aligned16(lse)) return ADASPARK_EINVAL;
-    if (!causal) return ADASPARK_EUNSUPPORTED;
+    (void)causal;  // both modes are implemented (non-causal: by the masked-walk / dense kernel only)
     return ADASPARK_OK;
 }
 
@@ -207,7 +207,10 @@ static int attn_packed(const adaspark_shape *shape, const void *Q, void *packed,
     if (sparse_kernel != ADASPARK_SPARSE_AUTO && sparse_kernel != ADASPARK_SPARSE_COMPACT &&
         sparse_kernel != ADASPARK_SPARSE_MASKED && sparse_kernel != ADASPARK_SPARSE_PAIRS)
         return ADASPARK_EINVAL;
-    const Geom g = make_geom(*shape);
+    if (!causal && sparse && (sparse_kernel == ADASPARK_SPARSE_COMPACT || sparse_kernel == ADASPARK_SPARSE_PAIRS))
+        return ADASPARK_EUNSUPPORTED;  // those two kernels walk the cubes before the own one only
+    Geom g = make_geom(*shape);
+    g.causal = causal != 0;
     if ((rc = workspace_check(g, packed, packed_bytes)) != ADASPARK_OK) return rc;
     // whatever lies beyond the minimum workspace, from the next 256-byte boundary on, is scratch memory
     const uintptr_t begin = reinterpret_cast<uintptr_t>(packed);

@@ -95,7 +95,9 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
     const int row0 = (int)((long long)blk * P / nblk), row1 = (int)((long long)(blk + 1) * P / nblk);
     const int Mrows = row1 - row0;
     const int max_rank = (row1 - 1) / g.G;
-    const int own_tiles = min((qsize + KEY_TILE - 1) / KEY_TILE, max_rank / KEY_TILE + 1);
+    // (non-causal mode: the whole own cube, and the walk goes on over the cubes after it)
+    const int own_tiles = g.causal ? min((qsize + KEY_TILE - 1) / KEY_TILE, max_rank / KEY_TILE + 1)
+                                   : (qsize + KEY_TILE - 1) / KEY_TILE;
 
     for (int r = tid; r < Mrows; r += THREADS) {
         const int rho = row0 + r, rank = rho / g.G, hg = rho % g.G;
@@ -111,7 +113,7 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
     __syncthreads();
 
     // the tile stream: cubes 0..i in order, the own cube i last and only up to the largest rank of the block
-    const int ncubes = i + 1;
+    const int ncubes = g.causal ? i + 1 : g.N;
     auto tiles_of = [&](int j) -> int {
         if (j == i) return own_tiles;
         return g.ragged ? (csize[j] + KEY_TILE - 1) / KEY_TILE : g.TPC;
@@ -160,7 +162,7 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
             q.tile += C::CHUNK;
         } else {
             q.tile += (size_t)(g.TPC - q.t) * C::CHUNK;
-            q.j = min(q.j + 1, i);  // past the end nothing is issued; the index only has to stay valid
+            q.j = min(q.j + 1, ncubes - 1);  // past the end nothing is issued; the index only has to stay valid
             q.t = 0;
             q.nt = tiles_of(q.j);
         }
@@ -237,7 +239,7 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
         const bool own = (j == i);
         jsize = own ? qsize : (g.ragged ? csize[j] : g.Cmax);
 #pragma unroll
-        for (int s = 0; s < NS; ++s) lim[s] = own ? min(rrank[lr[s]], jsize - 1) : jsize - 1;
+        for (int s = 0; s < NS; ++s) lim[s] = (own && g.causal) ? min(rrank[lr[s]], jsize - 1) : jsize - 1;
         if (MASKED) {
             if (own) {
 #pragma unroll
@@ -261,7 +263,7 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
     auto softmax_step = [&]() __attribute__((always_inline)) {
         const bool own = (cc.j == i);
         const int key0 = KEY_TILE * cc.t;
-        const bool need_mask = (key0 + KEY_TILE > jsize) || (own && key0 + KEY_TILE - 1 > rank_lo);
+        const bool need_mask = (key0 + KEY_TILE > jsize) || (own && g.causal && key0 + KEY_TILE - 1 > rank_lo);
         softmax_tile_folded<D, NS>(sacc, pf, oacc, m_run, l_run, fresh, lim, key0, need_mask, q4);
         const int j0 = cc.j;
         advance(cc);
@@ -436,9 +438,9 @@ static hipError_t launch_attn_d(const Geom &g, const uint16_t *Q, void *packed, 
                                 hipStream_t st)
 {
     if (sel_mask == nullptr) return launch_walk<D, false>(g, Q, packed, nullptr, nullptr, 0, 0, O, lse, st);
-    if (sparse_kernel == ADASPARK_SPARSE_COMPACT)
+    if (sparse_kernel == ADASPARK_SPARSE_COMPACT && g.causal)
         return launch_attn_compact(g, Q, packed, sel_mask, nullptr, 0, 0, O, lse, st);
-    if (sparse_kernel == ADASPARK_SPARSE_MASKED)
+    if (sparse_kernel == ADASPARK_SPARSE_MASKED || !g.causal)  // non-causal mode: the masked walk is the one kernel
         return launch_walk<D, true>(g, Q, packed, sel_mask, nullptr, 0, 0, O, lse, st);
     // Automatic (or the key-stationary kernel asked for): the choice is made on the device, every candidate kernel
     // is enqueued, and the workgroups of those not chosen return at once.  First the selected share from a sample

@@ -25,6 +25,8 @@ struct Geom {
     int TPC;            // key tiles per cube in the packed layout = ceil(Cmax / KEY_TILE)
     int words;          // u32 words per selection-mask row = ceil(N / 32)
     int ragged;         // some cubes are smaller than Cmax (clipped at the grid edge, or the last text cube)
+    int causal;         // 1: the paper's operator.  0 (selection and forward attention only): candidates are all other
+                        // video cubes, the own cube is attended in full
 };
 
 inline Geom make_geom(const adaspark_shape &s)
@@ -44,6 +46,7 @@ inline Geom make_geom(const adaspark_shape &s)
     g.S = g.Sp + g.Sv + g.St;
     g.TPC = (g.Cmax + KEY_TILE - 1) / KEY_TILE;
     g.words = (g.N + 31) / 32;
+    g.causal = 1;
     g.ragged = (g.T % g.ct != 0) || (g.H % g.ch != 0) || (g.W % g.cw != 0) || (g.St % g.Cmax != 0) ||
                (g.Sp % g.Cmax != 0);
     return g;

@@ -87,7 +87,41 @@ __device__ __forceinline__ uint32_t sel_range_bits(int w, int lo, int hi)
 // [0, Np), trailing ones follow the video cubes), which are attended whatever the rule selects.
 __device__ __forceinline__ uint32_t sel_forced_bits(const Geom &g, int w, int i)
 {
-    return sel_range_bits(w, 0, min(i, g.Np)) | sel_range_bits(w, g.Np + g.Nv, i);
+    if (g.causal) return sel_range_bits(w, 0, min(i, g.Np)) | sel_range_bits(w, g.Np + g.Nv, i);
+    // non-causal: every text cube but the own one
+    const uint32_t own = (i >> 5) == w ? 1u << (i & 31) : 0u;
+    return (sel_range_bits(w, 0, g.Np) | sel_range_bits(w, g.Np + g.Nv, g.N)) & ~own;
+}
+
+// The candidates of a row of cube i (Eqs. 1-2): video cubes [Np, cend) -- those before the own cube, or, in
+// non-causal mode, all of them but the own one (`skip`, -1 if none) -- and the text cubes it always attends.
+struct SelRange {
+    int cend, skip, ncand, nforced;
+};
+__device__ __forceinline__ SelRange sel_range(const Geom &g, int i)
+{
+    SelRange r;
+    const int vend = g.Np + g.Nv;
+    if (g.causal) {
+        r.cend = min(i, vend);
+        r.skip = -1;
+        r.ncand = max(r.cend - g.Np, 0);
+        r.nforced = i - r.ncand;
+    } else {
+        const bool own_video = i >= g.Np && i < vend;
+        r.cend = vend;
+        r.skip = own_video ? i : -1;
+        r.ncand = g.Nv - (own_video ? 1 : 0);
+        r.nforced = g.N - g.Nv - (own_video ? 0 : 1);
+    }
+    return r;
+}
+// bits of word w for "every candidate kept" (all = true) or "none"
+__device__ __forceinline__ uint32_t sel_all_candidates(const Geom &g, int w, const SelRange &r, bool all)
+{
+    if (!all) return 0u;
+    const uint32_t own = (r.skip >= 0 && (r.skip >> 5) == w) ? 1u << (r.skip & 31) : 0u;
+    return sel_range_bits(w, g.Np, r.cend) & ~own;
 }
 
 // OR / sum / max over the four lanes {n, n+16, n+32, n+48} that share a query row
@@ -143,9 +177,8 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
     // Candidates are the video cubes before the own cube: cubes [Np, cend).  A query after the video scores every
     // video cube; the text cubes before a row's own are always attended: those bits are set whatever the rule
     // selects.
-    const int cend = min(i, g.Np + g.Nv);
-    const int ncand = max(cend - g.Np, 0);
-    const int nforced = i - ncand;
+    const SelRange cr = sel_range(g, i);
+    const int cend = cr.cend, ncand = cr.ncand, nforced = cr.nforced;
 
     int rowg[SELM_SLABS];  // global row id of this lane's column, -1: past the end
     int rowq[SELM_SLABS];  // row whose Q is loaded (a valid one also for padding columns)
@@ -165,7 +198,7 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
         for (int s = 0; s < SELM_SLABS; ++s) {
             if (rowg[s] < 0) continue;
             for (int w = q4; w < g.words; w += 4)
-                sel_mask[(size_t)rowg[s] * g.words + w] = sel_range_bits(w, g.Np, g.Np + keep) | sel_forced_bits(g, w, i);
+                sel_mask[(size_t)rowg[s] * g.words + w] = sel_all_candidates(g, w, cr, keep != 0) | sel_forced_bits(g, w, i);
             if (q4 == 0) sel_count[rowg[s]] = keep + nforced;
         }
         return;
@@ -227,7 +260,7 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int cube = 16 * cg + 4 * q4 + v;
-                const bool valid = cube >= g.Np && cube < cend;
+                const bool valid = cube >= g.Np && cube < cend && cube != cr.skip;
                 const float x = valid ? acc[s][cg][v] * scale : -INFINITY;
                 acc[s][cg][v] = x;
                 mx = fmaxf(mx, x);
@@ -418,9 +451,8 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
     const int P = g.G * qbox.size();
     if (blk * SELW_ROWS >= P) return;  // the whole workgroup
     // candidates: the video cubes before the own cube, [Np, cend); text cubes before it are forced
-    const int cend = min(i, g.Np + g.Nv);
-    const int ncand = max(cend - g.Np, 0);
-    const int nforced = i - ncand;
+    const SelRange cr = sel_range(g, i);
+    const int cend = cr.cend, ncand = cr.ncand, nforced = cr.nforced;
 
     int rowg[SLABS], rowq[SLABS];
 #pragma unroll
@@ -440,7 +472,7 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
         for (int s = 0; s < SLABS; ++s) {
             if (rowg[s] < 0) continue;
             for (int w = q4; w < g.words; w += 4)
-                sel_mask[(size_t)rowg[s] * g.words + w] = sel_range_bits(w, g.Np, g.Np + keep) | sel_forced_bits(g, w, i);
+                sel_mask[(size_t)rowg[s] * g.words + w] = sel_all_candidates(g, w, cr, keep != 0) | sel_forced_bits(g, w, i);
             if (q4 == 0) sel_count[rowg[s]] = keep + nforced;
         }
         return;
@@ -526,7 +558,7 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int cube = 16 * (g0 + lg) + 4 * q4 + v;
-                const bool valid = cube >= g.Np && cube < cend;
+                const bool valid = cube >= g.Np && cube < cend && cube != cr.skip;
                 const float x = valid ? acc[s][lg][v] * scale : -INFINITY;
                 acc[s][lg][v] = x;
                 mx = fmaxf(mx, x);
@@ -845,8 +877,9 @@ static void launch_select_d(const Geom &g, int NG, const uint16_t *Q, const uint
                             uint32_t *sel_mask, int32_t *sel_count, hipStream_t st)
 {
     // query cubes below SELM_MAX_CUBES have at most that many candidates: one wavefront holds a row's logits
-    const int i_narrow = g.N < SELM_MAX_CUBES ? g.N : SELM_MAX_CUBES;
-    {
+    // (in non-causal mode every query cube has all video cubes as candidates)
+    const int i_narrow = g.N <= SELM_MAX_CUBES ? g.N : (g.causal ? SELM_MAX_CUBES : 0);
+    if (i_narrow > 0) {
         const int nblk_max = (g.G * g.Cmax + SELM_ROWS - 1) / SELM_ROWS;
         const dim3 grid((unsigned)((size_t)i_narrow * g.Hkv * nblk_max)), block(SELM_THREADS);
         if (i_narrow <= 64)

@@ -78,9 +78,10 @@ def test_bad_pointers_and_arguments_are_rejected_before_launch(lib):
     args[3] = ctypes.c_float(float("nan"))
     assert lib.adaspark_cube_select(*args) == -1
     args[3] = ctypes.c_float(0.9)
-    args[4] = 0
-    assert lib.adaspark_cube_select(*args) == -2                       # non-causal not implemented
-    args[4] = 1
+    # non-causal mode runs on the masked-walk kernel only: the other two sparse kernels refuse it
+    nc = lambda kernel: lib.adaspark_sparse_attn_packed_with(
+        ctypes.byref(cs), ok_ptr, ok_ptr, 1 << 30, ok_ptr, 0, kernel, ok_ptr, None, None)
+    assert nc(binding.SPARSE_COMPACT) == -2 and nc(binding.SPARSE_PAIRS) == -2
     args[11] = 8
     assert lib.adaspark_cube_select(*args) == -3                       # workspace too small
     args[11] = 1 << 30
@@ -171,5 +172,4 @@ def test_shared_selection_arguments_are_validated(lib):
     run = lambda p=0.9, causal=1, ws=ok_ptr, nbytes=1 << 30, q=ok_ptr: lib.adaspark_cube_select_shared(
         ctypes.byref(cs), q, ok_ptr, ctypes.c_float(p), causal, ok_ptr, ok_ptr, ws, nbytes, None)
     assert run(p=1.5) == -1 and run(p=float("nan")) == -1 and run(q=None) == -1
-    assert run(causal=0) == -2
     assert run(ws=None) == -3 and run(nbytes=need.value - 1) == -3

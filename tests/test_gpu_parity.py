@@ -510,3 +510,41 @@ def test_group_shared_selection(B, oracle, name):
     torch.cuda.synchronize()
     ref_out, _ = oracle.sparse_attn(osh, Q, K, V, ref_mask)
     check_outputs(f"{name} attn(shared sel)", O.reshape(-1, w.D).float().cpu().numpy()[same], ref_out[same])
+
+@pytest.mark.parametrize("name", ["T_tiny", "T_ragged", "T_gqa128", "T_text64", "T_lead64", "T_cubes280", "T_cubes1100"])
+def test_noncausal_mode(B, oracle, name):
+    """causal = 0: every other video cube is a candidate, the own cube is attended in full, selected cubes may lie
+    after the own one.  Selection, sparse attention (the library's choice and the masked walk forced) and the dense
+    entry against the oracle's non-causal functions; the other two sparse kernels refuse the mode."""
+    w = synth.TEST_WORKLOADS[name]
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    Q, K, V = synth.generate(w)
+    Qg, Kg, Vg = Q.cuda(), K.cuda(), V.cuda()
+    p32 = float(np.float32(w.top_p[0]))
+    kbar = B.cube_pool(sh, Kg)
+    kbar_ref = oracle.cube_pool(osh, K)
+    for p in (p32, 1.0, 0.0):
+        print(f"[{name}] non-causal selection p={p}", flush=True)
+        mask, count, _, _ = B.cube_select(sh, Qg, kbar, p, causal=False)
+        torch.cuda.synchronize()
+        ref_mask, ref_count, near = oracle.cube_select(osh, Q, kbar_ref, p, causal=False)
+        check_selection(f"{name} non-causal p={p}", to_u32(mask), count.cpu().numpy(), ref_mask, ref_count, near)
+    ref_mask, _, _ = oracle.cube_select(osh, Q, kbar_ref, p32, causal=False)
+    rows = synth.sample_rows(w, 1500)
+    ref_out, _ = oracle.sparse_attn(osh, Q, K, V, ref_mask[rows], rows=rows, causal=False)
+    mg = torch.from_numpy(ref_mask.view(np.int32)).cuda()
+    packed = B.kv_pack(sh, Kg, Vg)
+    for kern in (None, B.SPARSE_MASKED):
+        print(f"[{name}] non-causal sparse attention, kernel {kern}", flush=True)
+        O = B.sparse_attn_packed(sh, Qg, packed, mg, causal=False, kernel=kern)
+        torch.cuda.synchronize()
+        check_outputs(f"{name} non-causal kernel {kern}", rows_of(O, rows, w), ref_out)
+    for kern in (B.SPARSE_COMPACT, B.SPARSE_PAIRS):
+        with pytest.raises(B.AdasparkError) as e:
+            B.sparse_attn_packed(sh, Qg, packed, mg, causal=False, kernel=kern)
+        assert e.value.status == -2
+    print(f"[{name}] non-causal dense", flush=True)
+    Od = B.dense_attn(sh, Qg, Kg, Vg, causal=False)
+    torch.cuda.synchronize()
+    drows = rows[:: max(1, len(rows) // 200)]
+    check_outputs(f"{name} non-causal dense", rows_of(Od, drows, w), oracle.dense_attn(osh, Q, K, V, rows=drows, causal=False))
