@@ -191,6 +191,8 @@ def main():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-ffn", action="store_true", help="skip the token-selective FFN leg (Sec. 3.3)")
     ap.add_argument("--no-bwd", action="store_true", help="skip the attention backward leg")
+    ap.add_argument("--no-sweep", action="store_true",
+                    help="do not time the workload's other Top-p values (C3: 0.5, 0.7, 0.99; the top_p_sweep object)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 1 GiB device copy after the timed region: the known-size "
                          "reference the HBM counters of a rocprofv3 --pmc run are scaled by")
@@ -357,6 +359,37 @@ def main():
             "executed_tflops": None if executed_flops is None else executed_flops / (attn_kernel_ms * 1e-3) / 1e12,
         },
     }
+    if not args.no_sweep and not args.shared_selection and len(w.top_p) > 1:
+        # the workload's other Top-p values (the configuration names the sweep): same inputs, same workspaces; step =
+        # pool + select + pack + sparse attention, host clock around `steps` steps; effective FLOPs from the selection
+        sweep = {}
+        for ps in w.top_p:
+            psf = float(np.float32(ps))
+            if abs(psf - p) < 1e-6:
+                continue
+            B.cube_select(sh, Qg, kbar, psf, sel_mask=mask, sel_count=count, workspace=ws_sel)
+
+            def step_p():
+                B.cube_pool(sh, Kg, kbar)
+                B.cube_select(sh, Qg, kbar, psf, sel_mask=mask, sel_count=count, workspace=ws_sel)
+                B.kv_pack(sh, Kg, Vg, ws_att)
+                B.sparse_attn_packed(sh, Qg, ws_att, mask, O=O)
+
+            step_p()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(max(2, args.steps // 2)):
+                step_p()
+            torch.cuda.synchronize()
+            ms_p = (time.perf_counter() - t0) * 1e3 / max(2, args.steps // 2)
+            keys_p, pairs_p = attended_keys_total(w, mask, sizes, rank)
+            att_p = timed(f_attn, max(2, args.steps // 2))
+            sweep[str(ps)] = {"ms_per_step": ms_p, "tokens_per_s": w.S / (ms_p * 1e-3), "sparse_attn_ms": att_p,
+                              "selected_fraction_of_preceding_cubes": pairs_p / max(1, preceding),
+                              "effective_tflops": 4.0 * w.D * keys_p / (att_p * 1e-3) / 1e12,
+                              "speedup_vs_dense": None if dense_ms is None else (k_ms["kv_pack"] + dense_ms) / ms_p}
+        out["top_p_sweep"] = sweep
+        B.cube_select(sh, Qg, kbar, p, sel_mask=mask, sel_count=count, workspace=ws_sel)  # back to the headline p
     if not args.no_bwd and w.S * w.Hq * words < (1 << 30) and w.S <= 131072:
         out["attn_bwd"] = bwd_leg(B, w, sh, Qg, Kg, Vg, ws_att, mask, eff_flops, dense_flops, args.steps, args.top_p)
     if not args.no_ffn and w.S * FFN_D_MODEL < (1 << 30):
