@@ -161,3 +161,47 @@ def test_backward_full_size_sampled(B, oracle):
           f"sum dK: max {np.abs(dKs).max():.3e} (tolerance {tol_k.min():.3e}..{tol_k.max():.3e})", flush=True)
     assert (np.abs(dVs - dOs) <= tol_v).all()
     assert (np.abs(dKs) <= tol_k).all()
+
+
+def test_backward_quarter_million_tokens(B, oracle):
+    """262,144 tokens (1,024 cubes, the largest configuration): offsets and tables at full scale.  A few dQ rows
+    against the oracle, and the identities sum(dV) = sum(dO) per KV head, sum(dK) = 0."""
+    w = synth.WORKLOADS["C4"]
+    p = 0.9
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    Q, K, V = synth.generate(w)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(synth.BASE_SEED + 31 * w.config_id)
+    dO = torch.randn((w.S, w.Hq, w.D), generator=g, dtype=torch.float32).to(torch.bfloat16)
+    Qg, Kg, Vg, dOg = Q.cuda(), K.cuda(), V.cuda(), dO.cuda()
+    kbar = B.cube_pool(sh, Kg)
+    mask_g, _, _, _ = B.cube_select(sh, Qg, kbar, p)
+    print("[C4] forward", flush=True)
+    O, lse = B.sparse_attn(sh, Qg, Kg, Vg, mask_g, return_lse=True)
+    torch.cuda.synchronize()
+    print("[C4] backward", flush=True)
+    dQ, dK, dV = B.sparse_attn_bwd(sh, Qg, Kg, Vg, O, lse, dOg, sel_mask=mask_g)
+    torch.cuda.synchronize()
+    G, c = w.Hq // w.Hkv, 1.0 / np.sqrt(w.D)
+    q, k, v = f64(Q), f64(K), f64(V)
+    tables = oracle.bwd.cube_tables(osh)
+    rows = np.array([0, w.Hq * 4097 + 3, w.Hq * (w.S // 2) + 11, w.Hq * (w.S - 300) + 27, w.S * w.Hq - 1])
+    idx = torch.as_tensor(rows).cuda()
+    mrows = mask_g[idx].cpu().numpy().view(np.uint32)
+    do_rows, o_rows = f64(dO.reshape(-1, w.D)[rows]), f64(O.reshape(-1, w.D)[idx].cpu())
+    want, terms = [], []
+    for x, r in enumerate(rows):
+        att, dq, _, _, _, ds, _ = oracle.bwd.row_backward(osh, q, k, v, mrows[x], r, do_rows[x], o_rows[x], tables)
+        want.append(dq)
+        terms.append(c * np.sqrt((ds * ds) @ (k[att, (r % w.Hq) // G] ** 2)))
+    check_grad("C4 dQ sampled rows", f64(dQ.reshape(-1, w.D)[idx].cpu()), np.array(want), np.array(terms))
+    dVs = dV.to(torch.float64).sum(dim=0).cpu().numpy()
+    dKs = dK.to(torch.float64).sum(dim=0).cpu().numpy()
+    dOs = dOg.view(w.S, w.Hkv, G, w.D).to(torch.float64).sum(dim=(0, 2)).cpu().numpy()
+    tol_v = 16.0 * 2.0 ** -9 * torch.sqrt((dV.to(torch.float64) ** 2).sum(dim=0)).cpu().numpy() + 1e-3 * np.abs(dOs)
+    tol_k = 16.0 * 2.0 ** -9 * torch.sqrt((dK.to(torch.float64) ** 2).sum(dim=0)).cpu().numpy()
+    print(f"[C4] sum dV - sum dO: max {np.abs(dVs - dOs).max():.3e} (tolerance {tol_v.min():.3e}..{tol_v.max():.3e}); "
+          f"sum dK: max {np.abs(dKs).max():.3e} (tolerance {tol_k.min():.3e}..{tol_k.max():.3e})", flush=True)
+    assert np.isfinite(dVs).all() and np.isfinite(dKs).all()
+    assert (np.abs(dVs - dOs) <= tol_v).all()
+    assert (np.abs(dKs) <= tol_k).all()
