@@ -1,4 +1,4 @@
-"""fp64 CPU oracle for AdaS-Attn -- test infrastructure only.
+"""fp64 CPU oracle for AdaS-Attn, the token-selective FFN and the attention backward -- test infrastructure only.
 
 Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
 ``bench.py`` may import this package.  It imports nothing from the HIP package.
