@@ -92,6 +92,12 @@ def test_dense_backward_matches_oracle(B, oracle, name):
     run_case(B, oracle, name, 1.0, dense=True)
 
 
+def test_backward_with_nothing_selected(B, oracle):
+    """p = 0: every row attends the causal part of its own cube only (and earlier text cubes, if any)."""
+    run_case(B, oracle, "T_ragged", 0.0)
+    run_case(B, oracle, "T_lead64", 0.0)
+
+
 def test_backward_full_size_sampled(B, oracle):
     """65,536 tokens, p = 0.9, the launch configuration the benchmark times.  dQ: sampled rows recomputed by the
     oracle.  dK, dV: the last eight tokens of the last cube of one KV head (few rows attend them: the oracle takes

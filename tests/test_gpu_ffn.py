@@ -168,3 +168,33 @@ def test_ffn_full_size_sampled(B, oracle):
         got = f64(Y[torch.from_numpy(np.concatenate([act, rest])).cuda()].cpu())
         check_outputs(f"C3 cube {c} ({act.size} activated, {rest.size} bypassed)", got, want,
                       x64[np.concatenate([act, rest])])
+
+
+def test_ffn_zero_tokens_and_zero_cube(B, oracle):
+    """Tokens of norm zero rank last; a cube whose tokens are all zero has an all-zero distribution, whose mass never
+    reaches p: every token is activated (and FFN(0) = 0 leaves them unchanged)."""
+    w = workload("T_ragged")
+    d_model, d_ff = 256, 384
+    X, Wg, Wu, Wd = synth.generate_ffn(w, d_model, d_ff)
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    cube_of = oracle.cube_map(osh)[0]
+    X = X.clone()
+    X[cube_of == 3] = 0                                  # a whole cube
+    X[torch.from_numpy(np.nonzero(cube_of == 5)[0][::3])] = 0   # every third token of another
+    x64 = f64(X)
+    for p in (0.6, 0.999):
+        print(f"[T_ragged zeros] ffn_select p={p}", flush=True)
+        keep, score, _ = B.ffn_select(sh, X.cuda(), d_ff, p)
+        torch.cuda.synchronize()
+        rk, rs, near = oracle.ffn.ffn_select(osh, x64, p)
+        k = keep.cpu().numpy()
+        differ = np.unique(cube_of[k != rk])
+        assert all(near[c] for c in differ)
+        assert k[cube_of == 3].all() and (score.cpu().numpy()[cube_of == 3] == 0).all()
+        if p == 0.6:
+            assert not k[np.nonzero(cube_of == 5)[0][::3]].any()
+    keep = oracle.ffn.ffn_select(osh, x64, 0.6)[0]
+    Y = B.ffn_sparse(sh, X.cuda(), Wg.cuda(), Wu.cuda(), Wd.cuda(), keep=torch.from_numpy(keep).cuda())
+    torch.cuda.synchronize()
+    check_outputs("T_ragged zeros", f64(Y.cpu()), oracle.ffn.ffn_sparse(osh, x64, f64(Wg), f64(Wu), f64(Wd), keep), x64)
+    assert (Y.cpu()[cube_of == 3] == 0).all()

@@ -548,3 +548,34 @@ def test_noncausal_mode(B, oracle, name):
     torch.cuda.synchronize()
     drows = rows[:: max(1, len(rows) // 200)]
     check_outputs(f"{name} non-causal dense", rows_of(Od, drows, w), oracle.dense_attn(osh, Q, K, V, rows=drows, causal=False))
+
+
+def test_noncausal_topk(B, oracle):
+    """Fixed Top-K selection in non-causal mode: the K best of all other video cubes."""
+    w = synth.TEST_WORKLOADS["T_manycubes"]
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    Q, K, _ = synth.generate(w)
+    kbar = B.cube_pool(sh, K.cuda())
+    kbar_ref = oracle.cube_pool(osh, K)
+    N = oracle.num_cubes(osh)
+    cube_of = oracle.cube_map(osh)[0]
+    G = w.Hq // w.Hkv
+    q = Q.to(torch.float64).numpy()
+    for k in (1, 5, N + 3):
+        mask, count, _, _ = B.cube_select_topk(sh, Q.cuda(), kbar, k, causal=False)
+        torch.cuda.synchronize()
+        m = to_u32(mask)
+        assert (count.cpu().numpy() == min(k, N - 1)).all()
+        rng = np.random.default_rng(k)
+        for r in rng.choice(w.S * w.Hq, 200, replace=False):
+            n, a = divmod(int(r), w.Hq)
+            own = cube_of[n]
+            logits = kbar_ref[:, a // G] @ q[n, a]
+            cand = [j for j in range(N) if j != own]
+            order = sorted(cand, key=lambda j: (-logits[j], j))
+            got = {j for j in range(N) if (m[r, j >> 5] >> (j & 31)) & 1}
+            want = set(order[:k])
+            if got != want:   # a tie within float32 resolution at the cut is the only legitimate difference
+                cut = sorted(logits[j] for j in (got ^ want))
+                assert cut[-1] - cut[0] < 1e-4 * max(1.0, abs(cut[0])), (r, got ^ want)
+
