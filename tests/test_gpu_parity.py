@@ -579,3 +579,76 @@ def test_noncausal_topk(B, oracle):
                 cut = sorted(logits[j] for j in (got ^ want))
                 assert cut[-1] - cut[0] < 1e-4 * max(1.0, abs(cut[0])), (r, got ^ want)
 
+
+def _random_workloads(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for k in range(count):
+        T, H, W = (int(rng.integers(1, 7)), int(rng.integers(1, 10)), int(rng.integers(1, 10)))
+        ct, ch, cw = (int(rng.integers(1, T + 1)), int(rng.integers(1, H + 1)), int(rng.integers(1, W + 1)))
+        hkv = int(rng.choice([1, 2, 3]))
+        grp = int(rng.choice([1, 2, 4, 7]))
+        D = int(rng.choice([64, 128]))
+        text = int(rng.choice([0, 0, int(rng.integers(1, 40))]))
+        lead = int(rng.choice([0, 0, int(rng.integers(1, 40))]))
+        p = float(rng.choice([0.3, 0.6, 0.9]))
+        scale = float(rng.choice([0.0, 1.0, 3.0]))
+        out.append(synth.Workload(f"R{k}", 100 + k, T, H, W, ct, ch, cw, hkv * grp, hkv, D, (p,), (scale,) * hkv, text, lead))
+    return out
+
+
+@pytest.mark.parametrize("w", _random_workloads(16, 2604), ids=lambda w: f"{w.name}-{w.T}x{w.H}x{w.W}-c{w.ct}x{w.ch}x{w.cw}-h{w.Hq}/{w.Hkv}-d{w.D}-t{w.text}-l{w.lead}")
+def test_random_small_geometries(B, oracle, w):
+    """Seeded random grids, cube shapes (down to single-token cubes), head groupings and text spans: selection,
+    sparse attention through every kernel that takes the geometry, the backward pass and the token-selective FFN,
+    against the oracle."""
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    Q, K, V = synth.generate(w)
+    Qg, Kg, Vg = Q.cuda(), K.cuda(), V.cuda()
+    p32 = float(np.float32(w.top_p[0]))
+    print(f"[{w.name}] {w}", flush=True)
+    kbar = B.cube_pool(sh, Kg)
+    mask, count, _, _ = B.cube_select(sh, Qg, kbar, p32)
+    torch.cuda.synchronize()
+    kbar_ref = oracle.cube_pool(osh, K)
+    assert np.abs(kbar.cpu().numpy().astype(np.float64) - kbar_ref).max() <= KBAR_ABS
+    ref_mask, ref_count, near = oracle.cube_select(osh, Q, kbar_ref, p32)
+    check_selection(w.name, to_u32(mask), count.cpu().numpy(), ref_mask, ref_count, near)
+    ref_out, _ = oracle.sparse_attn(osh, Q, K, V, ref_mask)
+    mg = torch.from_numpy(ref_mask.view(np.int32)).cuda()
+    try:
+        packed = B.kv_pack(sh, Kg, Vg, workspace=B.alloc_workspace(sh, B.CALL_SPARSE_ATTN, pairs_capacity=int(ref_count.sum())))
+        kernels = (B.SPARSE_AUTO, B.SPARSE_COMPACT, B.SPARSE_MASKED, B.SPARSE_PAIRS)
+    except B.AdasparkError:
+        packed = B.kv_pack(sh, Kg, Vg)
+        kernels = (B.SPARSE_AUTO, B.SPARSE_COMPACT, B.SPARSE_MASKED)
+    for kern in kernels:
+        print(f"[{w.name}] kernel {kern}", flush=True)
+        O, lse = B.sparse_attn_packed(sh, Qg, packed, mg, return_lse=True, kernel=kern)
+        torch.cuda.synchronize()
+        check_outputs(f"{w.name} kernel {kern}", O.reshape(-1, w.D).float().cpu().numpy(), ref_out)
+    print(f"[{w.name}] backward", flush=True)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(w.config_id)
+    dO = torch.randn((w.S, w.Hq, w.D), generator=g, dtype=torch.float32).to(torch.bfloat16)
+    dQ, dK, dV = B.sparse_attn_bwd(sh, Qg, Kg, Vg, O, lse, dO.cuda(), sel_mask=mg)
+    torch.cuda.synchronize()
+    f64 = lambda t: t.to(torch.float64).cpu().numpy()
+    T = {}
+    rq, rk, rv, _ = oracle.bwd.sparse_attn_bwd(osh, f64(Q), f64(K), f64(V), ref_mask, f64(dO).reshape(-1, w.D),
+                                               O=f64(O).reshape(-1, w.D), scales=T)
+    for name, got, want in (("dQ", dQ, rq), ("dK", dK, rk), ("dV", dV, rv)):
+        err = np.abs(f64(got) - want)
+        bound = 2.0 ** -8 * np.abs(want) + 2.0 ** -7 * T[name] + 1e-4
+        assert np.isfinite(f64(got)).all() and (err <= bound).all(), (name, float(np.max(err / bound)))
+    print(f"[{w.name}] token-selective FFN", flush=True)
+    X, Wg, Wu, Wd = synth.generate_ffn(w, 256, 128)
+    keep, _, _ = B.ffn_select(sh, X.cuda(), 128, p32)
+    rk, _, near_c = oracle.ffn.ffn_select(osh, f64(X), p32)
+    assert all(near_c[c] for c in np.unique(oracle.cube_map(osh)[0][keep.cpu().numpy() != rk]))
+    Y = B.ffn_sparse(sh, X.cuda(), Wg.cuda(), Wu.cuda(), Wd.cuda(), keep=torch.from_numpy(rk).cuda())
+    torch.cuda.synchronize()
+    want = oracle.ffn.ffn_sparse(osh, f64(X), f64(Wg), f64(Wu), f64(Wd), rk)
+    err = np.abs(f64(Y) - want)
+    bound = 2.0 ** -8 * np.abs(want) + 2.0 ** -6 * np.sqrt(np.mean((want - f64(X)) ** 2, axis=1, keepdims=True)) + 1e-30
+    assert (err <= bound).all(), float(np.max(err / bound))
