@@ -177,6 +177,61 @@ def bwd_leg(B, w, sh, Qg, Kg, Vg, ws_att, mask, eff_flops, dense_flops, steps, t
     }
 
 
+def workload_line(B, w, steps):
+    """One of the configuration's other workloads at its first Top-p value, measured like the headline step (pool +
+    select + pack + sparse attention, host clock; dense entry beside it) but reported in a few figures only."""
+    p = float(np.float32(w.top_p[0]))
+    sh = B.Shape.of(w)
+    N = B.num_cubes(sh)
+    Q, K, V = synth.generate(w)
+    Qg, Kg, Vg = Q.cuda(), K.cuda(), V.cuda()
+    del Q, K, V
+    R, words = sh.rows, (N + 31) // 32
+    kbar = torch.empty((N, w.Hkv, w.D), dtype=torch.float32, device="cuda")
+    mask = torch.empty((R, words), dtype=torch.int32, device="cuda")
+    count = torch.empty((R,), dtype=torch.int32, device="cuda")
+    O = torch.empty((w.S, w.Hq, w.D), dtype=torch.bfloat16, device="cuda")
+    ws_sel = B.alloc_workspace(sh, B.CALL_CUBE_SELECT)
+    cube, rank, sizes = cube_tables(w)
+    preceding = int(cube.astype(np.int64).sum()) * w.Hq
+    pairs_capacity = int(0.41 * preceding)
+    free_bytes, _ = torch.cuda.mem_get_info()
+    try:
+        if B.pairs_workspace_bytes(sh, pairs_capacity) > 0.4 * free_bytes:
+            pairs_capacity = None
+    except B.AdasparkError:
+        pairs_capacity = None
+    ws_att = B.alloc_workspace(sh, B.CALL_SPARSE_ATTN, pairs_capacity=pairs_capacity)
+
+    def step():
+        B.cube_pool(sh, Kg, kbar)
+        B.cube_select(sh, Qg, kbar, p, sel_mask=mask, sel_count=count, workspace=ws_sel)
+        B.kv_pack(sh, Kg, Vg, ws_att)
+        B.sparse_attn_packed(sh, Qg, ws_att, mask, O=O)
+
+    step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    att_ms = timed(lambda: B.sparse_attn_packed(sh, Qg, ws_att, mask, O=O), steps)
+    pack_ms = timed(lambda: B.kv_pack(sh, Kg, Vg, ws_att), steps)
+    B.dense_attn_packed(sh, Qg, ws_att, O=O)
+    dense_ms = timed(lambda: B.dense_attn_packed(sh, Qg, ws_att, O=O), max(1, min(steps, 3)))
+    keys_total, pairs = attended_keys_total(w, mask, sizes, rank)
+    dense_keys = int((np.cumsum(np.concatenate([[0], sizes[:-1]]))[cube] + rank + 1).sum()) * w.Hq
+    tf = 4.0 * w.D * keys_total / (att_ms * 1e-3) / 1e12
+    return {"workload": f"{w.T}x{w.H}x{w.W} tokens={w.S}, cube {w.ct}x{w.ch}x{w.cw} ({N} cubes), {w.Hq}q/{w.Hkv}kv "
+                        f"heads, head_dim {w.D}, top_p {w.top_p[0]}",
+            "ms_per_step": ms, "tokens_per_s": w.S / (ms * 1e-3), "sparse_attn_ms": att_ms,
+            "selected_fraction_of_preceding_cubes": pairs / max(1, preceding),
+            "effective_tflops": tf, "frac_of_mfma_peak": tf / PEAK_BF16_TFLOPS,
+            "dense_attn_ms": dense_ms, "dense_tflops": 4.0 * w.D * dense_keys / (dense_ms * 1e-3) / 1e12,
+            "speedup_vs_dense": (pack_ms + dense_ms) / ms}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -192,7 +247,8 @@ def main():
     ap.add_argument("--no-ffn", action="store_true", help="skip the token-selective FFN leg (Sec. 3.3)")
     ap.add_argument("--no-bwd", action="store_true", help="skip the attention backward leg")
     ap.add_argument("--no-sweep", action="store_true",
-                    help="do not time the workload's other Top-p values (C3: 0.5, 0.7, 0.99; the top_p_sweep object)")
+                    help="do not time the workload's other Top-p values (C3: 0.5, 0.7, 0.99; the top_p_sweep object) "
+                         "nor, in a default C3 run, the four other workloads (the other_workloads object)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 1 GiB device copy after the timed region: the known-size "
                          "reference the HBM counters of a rocprofv3 --pmc run are scaled by")
@@ -398,6 +454,15 @@ def main():
         out["adas_ffn"] = ffn_leg(B, w, args.steps, dense=not args.no_dense)
     if not args.no_cpu_baseline and not args.shared_selection:
         out["cpu_baseline"] = cpu_baseline(w, p, Q, K, V)
+    if not args.no_sweep and not args.shared_selection and args.workload == "C3" and abs(p - 0.9) < 1e-6:
+        # the four other workloads of the configuration list, one after the other on the emptied device
+        del Qg, Kg, Vg, kbar, Q, K, V
+        torch.cuda.empty_cache()
+        out["other_workloads"] = {}
+        for name in sorted(synth.WORKLOADS):
+            if name != "C3":
+                out["other_workloads"][name] = workload_line(B, synth.WORKLOADS[name], 3 if name == "C4" else args.steps)
+                torch.cuda.empty_cache()
     print(json.dumps(out), flush=True)
 
 
