@@ -216,6 +216,24 @@ def workload_line(B, w, steps):
         step()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / steps
+    graph_ms = None
+    if ms < 10.0:  # short steps are launch-bound: the same step recorded as a HIP graph and replayed
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / steps
     att_ms = timed(lambda: B.sparse_attn_packed(sh, Qg, ws_att, mask, O=O), steps)
     pack_ms = timed(lambda: B.kv_pack(sh, Kg, Vg, ws_att), steps)
     B.dense_attn_packed(sh, Qg, ws_att, O=O)
@@ -225,7 +243,8 @@ def workload_line(B, w, steps):
     tf = 4.0 * w.D * keys_total / (att_ms * 1e-3) / 1e12
     return {"workload": f"{w.T}x{w.H}x{w.W} tokens={w.S}, cube {w.ct}x{w.ch}x{w.cw} ({N} cubes), {w.Hq}q/{w.Hkv}kv "
                         f"heads, head_dim {w.D}, top_p {w.top_p[0]}",
-            "ms_per_step": ms, "tokens_per_s": w.S / (ms * 1e-3), "sparse_attn_ms": att_ms,
+            "ms_per_step": ms, "tokens_per_s": w.S / (ms * 1e-3), "graph_replay_ms_per_step": graph_ms,
+            "sparse_attn_ms": att_ms,
             "selected_fraction_of_preceding_cubes": pairs / max(1, preceding),
             "effective_tflops": tf, "frac_of_mfma_peak": tf / PEAK_BF16_TFLOPS,
             "dense_attn_ms": dense_ms, "dense_tflops": 4.0 * w.D * dense_keys / (dense_ms * 1e-3) / 1e12,

@@ -369,12 +369,15 @@ def ffn_sparse(shape: Shape, X, W_gate, W_up, W_down, keep=None, Y=None, workspa
     return Y
 
 
-def sparse_attn_bwd(shape: Shape, Q, K, V, O, lse, dO, sel_mask=None, causal: bool = True, workspace=None):
+def sparse_attn_bwd(shape: Shape, Q, K, V, O, lse, dO, sel_mask=None, causal: bool = True, workspace=None,
+                    dQ=None, dK=None, dV=None):
     """Backward of the attention entries with the selection held constant -> (dQ, dK, dV) bf16.
     sel_mask None: dense causal attention."""
     R, D = shape.rows, shape.head_dim
     kvn = shape.tokens * shape.kv_heads * D
-    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
     if workspace is None:
         workspace = alloc_workspace(shape, CALL_ATTN_BWD, device=Q.device)
     words = (num_cubes(shape) + 31) // 32
