@@ -9,7 +9,7 @@
 
 namespace adaspark {
 
-constexpr int POOL_THREADS = 256;
+constexpr int POOL_THREADS = 1024;  // 16 wavefronts: one workgroup (one cube) per CU has to keep that CU's share of HBM busy
 
 __global__ __launch_bounds__(POOL_THREADS) void cube_pool_kernel(Geom g, const uint16_t *__restrict__ K,
                                                                  float *__restrict__ kbar)
