@@ -161,9 +161,18 @@ __device__ __forceinline__ uint32_t valid_bits(uint32_t word, int w, int i)
 
 // The counting kernels are skipped when the sampled estimate of the selected share (flag[1], permille) says that
 // this path will not be chosen anyway: well above the threshold, and not forced.
+// The break-even share was measured against a masked walk that computes every candidate cube; it computes only the
+// share flag[FLAG_UNION] of them (cubes no row of a workgroup selected are left out), and the break-even moves with it.
+__device__ __forceinline__ int pairs_threshold(const int *flag, int pairs_below_permille)
+{
+    // (a tenth of the candidates on top: the walk's fixed costs do not shrink with the union)
+    return (int)((long long)pairs_below_permille * min(1000, flag[FLAG_UNION] + 100) / 1000);
+}
+
 __device__ __forceinline__ bool pairs_gate_closed(const int *flag, int force, int pairs_below_permille)
 {
-    return !force && flag[FLAG_ESTIMATE] > pairs_below_permille + pairs_below_permille / 4;
+    const int below = pairs_threshold(flag, pairs_below_permille);
+    return !force && flag[FLAG_ESTIMATE] > below + below / 4;
 }
 
 __global__ __launch_bounds__(256) void pair_count_kernel(Geom g, long long R, const uint32_t *__restrict__ sel_mask,
@@ -207,7 +216,7 @@ __global__ __launch_bounds__(PAIRS_MAX_KV_HEADS) void pairs_mode_kernel(Geom g, 
     const int kv = threadIdx.x;
     bool take = false;
     if (kv < g.Hkv) {
-        take = force || kv_sel[kv] * 1000ull < candidates_per_head * (unsigned long long)pairs_below_permille;
+        take = force || kv_sel[kv] * 1000ull < candidates_per_head * (unsigned long long)pairs_threshold(flags, pairs_below_permille);
         need[kv] = take ? kv_sel[kv] + (unsigned long long)g.S * g.G : 0ull;
     }
     __syncthreads();

@@ -40,7 +40,12 @@ struct Walk {
     static constexpr int OFF_ROWID = OFF_V + NST * CHUNK;
     static constexpr int OFF_RANK = OFF_ROWID + SMALL;
     static constexpr int OFF_MISC = OFF_RANK + SMALL;
-    static constexpr int BYTES = OFF_MISC + 16;
+    // the cubes some row of the workgroup attends (sparse entry): union of the rows' mask words, then the list of
+    // its set bits in cube order; grids with more cubes than LIST_MAX walk every cube
+    static constexpr int LIST_MAX = 8192;
+    static constexpr int OFF_UNION = OFF_MISC + 16;
+    static constexpr int OFF_LIST = OFF_UNION + LIST_MAX / 8;
+    static constexpr int BYTES = OFF_LIST + LIST_MAX * 2;
     static_assert(DMA >= 1, "a tile is at least 1 KB per wavefront");
     static_assert(BYTES <= 160 * 1024, "LDS of one CU");
 };
@@ -94,13 +99,16 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
     if (blk >= nblk) return;
     const int row0 = (int)((long long)blk * P / nblk), row1 = (int)((long long)(blk + 1) * P / nblk);
     const int Mrows = row1 - row0;
-    const int max_rank = (row1 - 1) / g.G;
+    // Rows of a (cube, KV head) are numbered head by head (row = head-in-group * tokens + rank): a workgroup's rows
+    // are neighbouring tokens of one query head (of two, where a head has fewer rows than the workgroup), the rows
+    // most likely to select the same cubes.
+    const int max_rank = (row0 / qsize == (row1 - 1) / qsize) ? (row1 - 1) % qsize : qsize - 1;
     // (non-causal mode: the whole own cube, and the walk goes on over the cubes after it)
     const int own_tiles = g.causal ? min((qsize + KEY_TILE - 1) / KEY_TILE, max_rank / KEY_TILE + 1)
                                    : (qsize + KEY_TILE - 1) / KEY_TILE;
 
     for (int r = tid; r < Mrows; r += THREADS) {
-        const int rho = row0 + r, rank = rho / g.G, hg = rho % g.G;
+        const int rho = row0 + r, hg = rho / qsize, rank = rho - hg * qsize;
         const int rid = token_of(g, qbox, rank) * g.Hq + kv * g.G + hg;
         rowid[r] = rid;
         rrank[r] = rank;
@@ -118,9 +126,47 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
         if (j == i) return own_tiles;
         return g.ragged ? (csize[j] + KEY_TILE - 1) / KEY_TILE : g.TPC;
     };
+    // Sparse entry: a cube that no row of the workgroup selected is left out of the stream altogether.  Rows that
+    // select independently of each other leave no such cube; rows of neighbouring tokens with similar queries do.
+    const bool listed = MASKED && g.N <= C::LIST_MAX;
+    const uint16_t *clist = reinterpret_cast<const uint16_t *>(smem + C::OFF_LIST);
+    int nlist = ncubes;
+    if (listed) {
+        uint32_t *uni = reinterpret_cast<uint32_t *>(smem + C::OFF_UNION);
+        uint16_t *wlist = reinterpret_cast<uint16_t *>(smem + C::OFF_LIST);
+        const int wlim = (ncubes + 31) >> 5;  // mask words that hold cubes of the stream
+        for (int w = tid; w < wlim; w += THREADS) uni[w] = 0u;
+        __syncthreads();
+        for (int x = tid; x < Mrows * wlim; x += THREADS) {
+            const int r = x / wlim, w = x - r * wlim;
+            const uint32_t m = sel_mask[(size_t)rowid[r] * g.words + w];
+            if (m) atomicOr(&uni[w], m);
+        }
+        __syncthreads();
+        if (wave == 0) {  // set bits in cube order; the own cube is always there
+            int n = 0;
+            for (int c0 = 0; c0 < ncubes; c0 += 64) {
+                const int c = c0 + lane;
+                const bool in = c < ncubes && (c == i || ((uni[c >> 5] >> (c & 31)) & 1u));
+                const unsigned long long b = __ballot(in);
+                if (in) wlist[n + __popcll(b & ((1ull << lane) - 1ull))] = (uint16_t)c;
+                n += __popcll(b);
+            }
+            if (lane == 0) misc[1] = n;
+        }
+        __syncthreads();
+        nlist = __builtin_amdgcn_readfirstlane(misc[1]);
+    }
+    auto cube_at = [&](int k) -> int { return listed ? (int)__builtin_amdgcn_readfirstlane((int)clist[k]) : k; };
+    // The list entry after position k, fetched when position k is entered and used a whole cube later: the LDS
+    // read is long over by then (read and used at the same cube boundary, its latency showed in every stream).
+    auto peek_after = [&](int k) -> int {
+        const int kk = min(k + 1, nlist - 1);  // past the end the entry only has to be a valid cube
+        return listed ? (int)clist[kk] : kk;
+    };
     {
         int part = 0;
-        for (int k = tid; k < ncubes; k += THREADS) part += tiles_of(k);
+        for (int k = tid; k < nlist; k += THREADS) part += tiles_of(listed ? (int)clist[k] : k);
         for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
         if (lane == 0) atomicAdd(&misc[0], part);
         __syncthreads();
@@ -129,15 +175,18 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
 
     auto first_tile = [&]() -> TilePos {
         TilePos p;
-        p.k = p.j = 0;
+        p.k = 0;
+        p.j = cube_at(0);
         p.t = 0;
-        p.nt = tiles_of(0);
+        p.nt = tiles_of(p.j);
         return p;
     };
+    int cc_next = peek_after(0);  // for the position that `advance` moves (there is one: the softmax's)
     auto advance = [&](TilePos &p) __attribute__((always_inline)) {
         if (p.t + 1 < p.nt) ++p.t;
-        else if (p.j + 1 < ncubes) {
-            p.k = ++p.j;
+        else if (p.k + 1 < nlist) {
+            p.j = __builtin_amdgcn_readfirstlane(cc_next);
+            cc_next = peek_after(++p.k);
             p.t = 0;
             p.nt = tiles_of(p.j);
         }  // the last tile stays where it is: nothing is issued or computed past the end
@@ -145,15 +194,20 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
     // The K and V^T tiles are fetched as two streams: a wave-uniform pointer to the current tile and a countdown
     // to the end of its cube (cubes are padded to TPC tiles in memory; a ragged cube's padding tiles are skipped).
     struct Stream {
+        const unsigned char *head;  // first tile of the KV head
         const unsigned char *tile;
-        int j, t, nt;
+        int k, t, nt;  // position in the list of cubes, tile in the cube, tiles of the cube
+        int next;      // the cube at position k + 1 (per lane, as read from the list)
     };
     auto stream_begin = [&](const uint16_t *base) -> Stream {
         Stream q;
-        q.tile = reinterpret_cast<const unsigned char *>(base + (size_t)kv * g.N * g.TPC * (KEY_TILE * D));
-        q.j = 0;
+        q.head = reinterpret_cast<const unsigned char *>(base + (size_t)kv * g.N * g.TPC * (KEY_TILE * D));
+        q.k = 0;
+        const int j = cube_at(0);
+        q.tile = q.head + (size_t)j * g.TPC * C::CHUNK;
         q.t = 0;
-        q.nt = tiles_of(0);
+        q.nt = tiles_of(j);
+        q.next = peek_after(0);
         return q;
     };
     auto stream_next = [&](Stream &q) __attribute__((always_inline)) {
@@ -161,10 +215,12 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
             ++q.t;
             q.tile += C::CHUNK;
         } else {
-            q.tile += (size_t)(g.TPC - q.t) * C::CHUNK;
-            q.j = min(q.j + 1, ncubes - 1);  // past the end nothing is issued; the index only has to stay valid
+            q.k = min(q.k + 1, nlist - 1);  // past the end nothing is issued; the index only has to stay valid
+            const int j = __builtin_amdgcn_readfirstlane(q.next);
+            q.next = peek_after(q.k);
+            q.tile = q.head + (size_t)j * g.TPC * C::CHUNK;
             q.t = 0;
-            q.nt = tiles_of(q.j);
+            q.nt = tiles_of(j);
         }
     };
     const uint32_t lds_piece =
@@ -186,9 +242,12 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
         lr[s] = idx < Mrows ? idx : MMAX;
         if (16 * (wave + WAVES * s) < Mrows) ns = s + 1;
     }
-    int rank_lo = 0;
-    if (ns > 0) rank_lo = rrank[16 * wave];
-    rank_lo = __builtin_amdgcn_readfirstlane(rank_lo);
+    int rank_lo = 0x7fffffff;  // lowest rank among the wavefront's rows
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+        if (lr[s] != MMAX) rank_lo = min(rank_lo, rrank[lr[s]]);
+    for (int off = 32; off > 0; off >>= 1) rank_lo = min(rank_lo, __shfl_xor(rank_lo, off, 64));
+    rank_lo = __builtin_amdgcn_readfirstlane(rank_lo == 0x7fffffff ? 0 : rank_lo);
 
     // prologue: K(0), K(1), V(0)
     Stream sk = stream_begin(Kp), sv = stream_begin(Vt);
@@ -364,6 +423,8 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
 // share of a KV head in permille, and (kv_modes) clears the per-head part.
 constexpr int DENSITY_THREADS = 1024;
 constexpr int DENSITY_MAX_ROWS = 2048;  // two sampled rows per thread: an estimate is all that is needed
+constexpr int DENSITY_GROUPS = 16;          // sampled (cube, query head) pairs for the union estimate
+constexpr int DENSITY_UNION_WORDS = 256;    // up to 8192 cubes; beyond that the union is taken as everything
 // Measured on MI355X with rows that select independently of each other: the compacting kernel wins only below
 // about 1.5 % selected cubes.
 constexpr int MASKED_ABOVE_PERMILLE = 15;
@@ -398,6 +459,57 @@ __global__ __launch_bounds__(DENSITY_THREADS) void sel_density_kernel(Geom g, co
         flags[FLAG_MODE] = (sel * 1000ull > cand * (unsigned long long)MASKED_ABOVE_PERMILLE) ? 2 : 1;
         flags[FLAG_ESTIMATE] = (int)least;
         flags[FLAG_ACTIVE] = 0;
+    }
+    // What the masked walk cannot leave out: the share of candidate cubes in the union of the selections of one
+    // query head's tokens in a cube (a workgroup's rows), over DENSITY_GROUPS sampled (cube, head) pairs, one per
+    // wavefront, all at once.
+    {
+        static_assert(DENSITY_THREADS / 64 == DENSITY_GROUPS, "one sampled (cube, head) pair per wavefront");
+        __shared__ uint32_t uni[DENSITY_GROUPS][DENSITY_UNION_WORDS];
+        __shared__ unsigned long long ucount[2];  // cubes in the unions, candidate cubes
+        if (threadIdx.x < 2) ucount[threadIdx.x] = 0ull;
+        const int k = threadIdx.x >> 6, t = threadIdx.x & 63;
+        const bool measured = g.causal && g.words <= DENSITY_UNION_WORDS;
+        const int i = g.N - 1 - (int)((long long)k * g.N / DENSITY_GROUPS);  // late cubes weigh most, as in the walk
+        const int a = (k * 5 + 1) % g.Hq;
+        const int wlim = (i + 31) >> 5;
+        if (measured)
+            for (int w = t; w < wlim; w += 64) uni[k][w] = 0u;
+        __syncthreads();
+        if (measured) {
+            const CubeBox box = cube_box(g, i);
+            const int size = box.size();
+            // every second token of the cube: each row read is a cache line of its own, and one CU fetches them all
+            for (int r0 = 0; r0 < size; r0 += 512)
+                for (int w0 = 0; w0 < wlim; w0 += 8) {  // 4 tokens x 8 words in flight per lane, then combined
+                    uint32_t m[4][8];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int r = r0 + 2 * (64 * q + t);
+                        const uint32_t *mr =
+                            sel_mask + ((size_t)token_of(g, box, min(r, size - 1)) * g.Hq + a) * g.words;
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) m[q][u] = (r < size && w0 + u < wlim) ? mr[w0 + u] : 0u;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        uint32_t x = m[0][u] | m[1][u] | m[2][u] | m[3][u];
+                        for (int off = 32; off > 0; off >>= 1) x |= __shfl_xor(x, off, 64);
+                        if (t == 0 && x) uni[k][w0 + u] |= x;  // the wavefront owns this row of `uni`
+                    }
+                }
+        }
+        __syncthreads();
+        if (measured) {
+            unsigned long long n = 0;
+            for (int w = t; w < wlim; w += 64)
+                n += __popc(uni[k][w] & (w == (i >> 5) ? (1u << (i & 31)) - 1u : ~0u));
+            if (n) atomicAdd(&ucount[0], n);
+            if (t == 0) atomicAdd(&ucount[1], (unsigned long long)i);
+        }
+        __syncthreads();
+        if (threadIdx.x == 0)
+            flags[FLAG_UNION] = ucount[1] > 0ull ? max(1, (int)(ucount[0] * 1000ull / ucount[1])) : 1000;
     }
     if (kv_modes) {
         unsigned long long *kv_sel =

@@ -130,12 +130,14 @@ hipError_t launch_kv_pack(const Geom &g, const uint16_t *K, const uint16_t *V, v
 //   [FLAG_MODE]      the row-stationary kernel that runs: 1 compaction, 2 masked walk
 //   [FLAG_ESTIMATE]  smallest share of selected candidate cubes over the KV heads, permille, from a sample of rows
 //   [FLAG_ACTIVE]    1 if some KV head is the key-stationary kernel's
+//   [FLAG_UNION]     share of the candidate cubes that some row of a masked-walk workgroup selected (that kernel skips
+//                    the others), permille, from a sample of workgroups; 1000 where rows select independently
 //   [FLAG_KV + kv]   3: the rows of KV head kv are left to the key-stationary kernel; 0: to the kernel above
 // The per-head part exists only where the caller's workspace has room for the key-stationary kernel's tables
 // (kernels take `kv_modes` = 1); the block is then 512 bytes long and followed by that kernel's per-head pair
 // totals, u64 [Hkv], which the kernel that fills the first two flags also clears.  Otherwise the block is the
 // four ints at the end of the minimum workspace.
-constexpr int FLAG_MODE = 0, FLAG_ESTIMATE = 1, FLAG_ACTIVE = 2, FLAG_KV = 4;
+constexpr int FLAG_MODE = 0, FLAG_ESTIMATE = 1, FLAG_ACTIVE = 2, FLAG_UNION = 3, FLAG_KV = 4;
 constexpr int PAIRS_MAX_KV_HEADS = 64;
 constexpr int FLAG_BLOCK_BYTES = 512;
 

@@ -114,16 +114,28 @@ def _randn(shape, seed):
     return torch.randn(shape, generator=g, dtype=torch.float32)
 
 
-def generate(w: Workload):
+def generate(w: Workload, query_corr: float = 0.0):
     """-> (Q [S,Hq,D], K [S,Hkv,D], V [S,Hkv,D]) CPU bf16 tensors.
 
     Q, V ~ N(0,1).  K = N(0,1) + scale[g] * mu, mu ~ N(0, I) drawn once per
     (cube, KV head) and shared by all tokens of that cube.  Text tokens (the first
     ``w.lead`` and the last ``w.text`` rows) have plain N(0,1) keys.
+
+    ``query_corr`` = rho > 0 (a variant, not one of the listed configurations): the
+    queries of the video tokens of a cube share a component per query head,
+    q = sqrt(1 - rho^2) * N(0,1) + rho * c[cube, head], still of unit variance, the way
+    neighbouring video tokens resemble each other; rho = 0 is the listed recipe.
     """
     seed = BASE_SEED + 1000 * w.config_id
     S, Sv = w.S, w.S_video
-    Q = _randn((S, w.Hq, w.D), seed + 0).to(torch.bfloat16)
+    Q = _randn((S, w.Hq, w.D), seed + 0)
+    if query_corr > 0.0:
+        nt, nh, nw = -(-w.T // w.ct), -(-w.H // w.ch), -(-w.W // w.cw)
+        c = _randn((nt, nh, nw, w.Hq, w.D), seed + 4)
+        field = c.repeat_interleave(w.ct, 0).repeat_interleave(w.ch, 1).repeat_interleave(w.cw, 2)
+        field = field[: w.T, : w.H, : w.W].reshape(Sv, w.Hq, w.D)
+        Q[w.lead : w.lead + Sv] = (1.0 - query_corr ** 2) ** 0.5 * Q[w.lead : w.lead + Sv] + query_corr * field
+    Q = Q.to(torch.bfloat16)
     V = _randn((S, w.Hkv, w.D), seed + 2).to(torch.bfloat16)
     K = _randn((S, w.Hkv, w.D), seed + 1)
     if any(s != 0.0 for s in w.k_mean_scale):

@@ -184,10 +184,11 @@ def test_value_indicator_recovers_attended_set(B, oracle):
     assert np.abs(out.sum(1) - 1.0).max() < 2e-2
 
 
-def sampled_case(B, oracle, w, p_list, n_rows, check_dense=True):
-    print(f"case {w.name} grid={w.grid} cube={w.cube} heads={w.Hq}/{w.Hkv} D={w.D} sampled rows={n_rows}", flush=True)
+def sampled_case(B, oracle, w, p_list, n_rows, check_dense=True, query_corr=0.0):
+    print(f"case {w.name} grid={w.grid} cube={w.cube} heads={w.Hq}/{w.Hkv} D={w.D} sampled rows={n_rows} "
+          f"query_corr={query_corr}", flush=True)
     sh, osh = B.Shape.of(w), oshape(oracle, w)
-    Q, K, V = synth.generate(w)
+    Q, K, V = synth.generate(w, query_corr=query_corr)
     Qg, Kg, Vg = Q.cuda(), K.cuda(), V.cuda()
     rows = synth.sample_rows(w, n_rows)
     kbar_ref = oracle.cube_pool(osh, K)
@@ -236,6 +237,13 @@ def sampled_case(B, oracle, w, p_list, n_rows, check_dense=True):
         torch.cuda.synchronize()
         drows = rows[:: max(1, len(rows) // 96)]
         check_outputs(f"{w.name} dense(sampled)", rows_of(Od, drows, w), oracle.dense_attn(osh, Q, K, V, rows=drows))
+
+
+def test_correlated_queries_sampled(B, oracle):
+    """Queries of a cube's tokens that share a component per head: rows of a workgroup then agree on many cubes and
+    the masked walk leaves out the cubes none of them selected.  Same checks as for the listed recipe."""
+    sampled_case(B, oracle, synth.WORKLOADS["C2"], (0.3, 0.9), 512, check_dense=False, query_corr=0.97)
+    sampled_case(B, oracle, synth.WORKLOADS["C5"], (0.5,), 384, check_dense=False, query_corr=0.9)
 
 
 def test_pairs_kernel_falls_back_when_records_do_not_fit(B, oracle):
