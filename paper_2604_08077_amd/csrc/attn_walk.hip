@@ -41,8 +41,8 @@ struct Walk {
     static constexpr int OFF_RANK = OFF_ROWID + SMALL;
     static constexpr int OFF_MISC = OFF_RANK + SMALL;
     // the cubes some row of the workgroup attends (sparse entry): union of the rows' mask words, then the list of
-    // its set bits in cube order; grids with more cubes than LIST_MAX walk every cube
-    static constexpr int LIST_MAX = 8192;
+    // its set bits in cube order
+    static constexpr int LIST_MAX = ADASPARK_MAX_CUBES;
     static constexpr int OFF_UNION = OFF_MISC + 16;
     static constexpr int OFF_LIST = OFF_UNION + LIST_MAX / 8;
     static constexpr int BYTES = OFF_LIST + LIST_MAX * 2;
@@ -128,7 +128,7 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
     };
     // Sparse entry: a cube that no row of the workgroup selected is left out of the stream altogether.  Rows that
     // select independently of each other leave no such cube; rows of neighbouring tokens with similar queries do.
-    const bool listed = MASKED && g.N <= C::LIST_MAX;
+    constexpr bool listed = MASKED;  // (the entry points admit at most LIST_MAX cubes)
     const uint16_t *clist = reinterpret_cast<const uint16_t *>(smem + C::OFF_LIST);
     int nlist = ncubes;
     if (listed) {
@@ -424,7 +424,7 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
 constexpr int DENSITY_THREADS = 1024;
 constexpr int DENSITY_MAX_ROWS = 2048;  // two sampled rows per thread: an estimate is all that is needed
 constexpr int DENSITY_GROUPS = 16;          // sampled (cube, query head) pairs for the union estimate
-constexpr int DENSITY_UNION_WORDS = 256;    // up to 8192 cubes; beyond that the union is taken as everything
+constexpr int DENSITY_UNION_WORDS = ADASPARK_MAX_CUBES / 32;
 // Measured on MI355X with rows that select independently of each other: the compacting kernel wins only below
 // about 1.5 % selected cubes.
 constexpr int MASKED_ABOVE_PERMILLE = 15;
@@ -469,7 +469,7 @@ __global__ __launch_bounds__(DENSITY_THREADS) void sel_density_kernel(Geom g, co
         __shared__ unsigned long long ucount[2];  // cubes in the unions, candidate cubes
         if (threadIdx.x < 2) ucount[threadIdx.x] = 0ull;
         const int k = threadIdx.x >> 6, t = threadIdx.x & 63;
-        const bool measured = g.causal && g.words <= DENSITY_UNION_WORDS;
+        const bool measured = g.causal != 0;
         const int i = g.N - 1 - (int)((long long)k * g.N / DENSITY_GROUPS);  // late cubes weigh most, as in the walk
         const int a = (k * 5 + 1) % g.Hq;
         const int wlim = (i + 31) >> 5;
@@ -526,6 +526,7 @@ static hipError_t launch_walk(const Geom &g, const uint16_t *Q, const void *pack
                               const int *mode_flag, int my_mode, int kv_modes, uint16_t *O, float *lse, hipStream_t st)
 {
     using C = Walk<D>;
+    if (g.N > C::LIST_MAX) return hipErrorInvalidValue;  // the kernel's cube list is that long (the entry points check)
     const uint16_t *Kp = reinterpret_cast<const uint16_t *>(packed);
     const size_t half_elems = (size_t)g.Hkv * g.N * g.TPC * KEY_TILE * D;
     const uint16_t *Vt = Kp + half_elems;
