@@ -198,3 +198,37 @@ def test_ffn_zero_tokens_and_zero_cube(B, oracle):
     torch.cuda.synchronize()
     check_outputs("T_ragged zeros", f64(Y.cpu()), oracle.ffn.ffn_sparse(osh, x64, f64(Wg), f64(Wu), f64(Wd), keep), x64)
     assert (Y.cpu()[cube_of == 3] == 0).all()
+
+
+def test_ffn_full_size_every_token(B, oracle):
+    """The benchmark's configuration (65,536 tokens, 3584 / 18944, p = 0.7) compared on EVERY output element: cube by
+    cube, the oracle's layer on the activated tokens and its mean on the others."""
+    w = synth.WORKLOADS["C3"]
+    d_model, d_ff, p = 3584, 18944, 0.7
+    X, Wg, Wu, Wd = synth.generate_ffn(w, d_model, d_ff)
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    x64 = f64(X)
+    rk, _, _ = oracle.ffn.ffn_select(osh, x64, p)
+    Y = B.ffn_sparse(sh, X.cuda(), Wg.cuda(), Wu.cuda(), Wd.cuda(), keep=torch.from_numpy(rk).cuda())
+    torch.cuda.synchronize()
+    got_all = Y.cpu()
+    g64, u64, d64 = (f64(t) for t in (Wg, Wu, Wd))
+    cube_of = oracle.cube_map(osh)[0]
+    worst, err_sum, bound_sum, n = 0.0, 0.0, 0.0, 0
+    for c in range(int(cube_of.max()) + 1):
+        toks = np.nonzero(cube_of == c)[0]
+        act, rest = toks[rk[toks] != 0], toks[rk[toks] == 0]
+        order = np.concatenate([act, rest])
+        Fc = oracle.ffn.ffn(x64[act], g64, u64, d64)
+        want = np.concatenate([x64[act] + Fc, x64[rest] + Fc.mean(axis=0)])
+        err = np.abs(f64(got_all[torch.from_numpy(order)]) - want)
+        move = np.sqrt(np.mean((want - x64[order]) ** 2, axis=1, keepdims=True))
+        bound = 2.0 ** -8 * np.abs(want) + 2.0 ** -6 * move + 1e-30
+        assert (err <= bound).all(), f"cube {c}"
+        worst = max(worst, float(np.max(err / bound)))
+        err_sum, bound_sum, n = err_sum + float(err.sum()), bound_sum + float(bound.sum()), n + err.size
+        if c % 16 == 15:
+            print(f"[C3 ffn every token] cubes 0..{c}: worst err/bound so far {worst:.3f}", flush=True)
+    print(f"[C3 ffn every token] elements={n} worst err/bound={worst:.3f} mean err/mean bound={err_sum / bound_sum:.3f}",
+          flush=True)
+    assert err_sum <= 0.2 * bound_sum
