@@ -666,12 +666,13 @@ def test_random_small_geometries(B, oracle, w):
 
 @pytest.mark.skipif(os.environ.get("ADASPARK_FULL_SIZE") != "1",
                     reason="about ten minutes of oracle time on 16 cores: set ADASPARK_FULL_SIZE=1 to run it")
-@pytest.mark.parametrize("p", [0.9, 0.5])
-def test_c3_every_row(B, oracle, p):
-    """The headline configuration (65,536 tokens; Top-p 0.9, and 0.5 where the key-stationary kernel runs) compared
-    on EVERY row, not a sample: the selected sets and the outputs of the whole path.  The oracle is called on slices
-    of the rows so that the run keeps printing."""
-    w = synth.WORKLOADS["C3"]
+@pytest.mark.parametrize("name,p", [("C3", 0.9), ("C3", 0.5), ("C5", 0.9), ("C2", 0.9)])
+def test_every_row(B, oracle, name, p):
+    """The headline configuration (65,536 tokens; Top-p 0.9, and 0.5 where the key-stationary kernel runs), the
+    ragged 32/8-head configuration (kernels mixed per KV head) and the 16,384-token one compared on EVERY row, not a
+    sample: the selected sets and the outputs of the whole path.  The oracle is called on slices of the rows so that
+    the run keeps printing."""
+    w = synth.WORKLOADS[name]
     p32 = float(np.float32(p))
     sh, osh = B.Shape.of(w), oshape(oracle, w)
     Q, K, V = synth.generate(w)
@@ -689,7 +690,7 @@ def test_c3_every_row(B, oracle, p):
     got = O.reshape(-1, w.D).float().cpu().numpy()
     R = w.S * w.Hq
     worst, total, n_same, n_near, n_differ = 0.0, 0.0, 0, 0, 0
-    step = R // 32
+    step = -(-R // 32)
     for r0 in range(0, R, step):
         rows = np.arange(r0, min(R, r0 + step), dtype=np.int64)
         ref_mask, ref_count, near = oracle.cube_select(osh, Q, kbar_ref, p32, rows=rows)
@@ -700,8 +701,8 @@ def test_c3_every_row(B, oracle, p):
         err = np.abs(got[rows][same].astype(np.float64) - ref_out[same])
         worst, total = max(worst, float(err.max())), total + float(err.sum())
         n_same, n_near, n_differ = n_same + int(same.sum()), n_near + int(near.sum()), n_differ + int((~same).sum())
-        print(f"[C3 p={p} every row] rows {r0}..{rows[-1]}: max-abs so far {worst:.3e}", flush=True)
+        print(f"[{name} p={p} every row] rows {r0}..{rows[-1]}: max-abs so far {worst:.3e}", flush=True)
     mean = total / (n_same * w.D)
-    print(f"[C3 p={p} every row] rows={R} near-boundary(exempt)={n_near} differing={n_differ} (all exempt) "
+    print(f"[{name} p={p} every row] rows={R} near-boundary(exempt)={n_near} differing={n_differ} (all exempt) "
           f"max-abs={worst:.3e} mean-abs={mean:.3e}", flush=True)
     assert worst <= MAX_ABS and mean <= MEAN_ABS
