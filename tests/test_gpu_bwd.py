@@ -87,6 +87,51 @@ def test_backward_matches_oracle(B, oracle, name, p):
     run_case(B, oracle, name, p)
 
 
+@pytest.mark.parametrize("name,p", [("T_tiny", 0.8), ("T_ragged", 0.9), ("T_lead64", 0.8), ("M_bwd256", 0.8)])
+def test_backward_matches_the_exact_gradient(B, oracle, name, p):
+    """Against the oracle's own gradient: delta = dO.o from the exact fp64 forward, not from the bf16 O the GPU
+    backward is handed.  What the forward's rounding of O does to the gradients enters through delta alone (dS_j =
+    p_j (dO.v_j - delta)), so the bound of the other tests grows by the oracle's `dQ_delta` / `dK_delta`: the
+    element's sensitivity to delta times the row's delta_error_bound (dV does not depend on delta).  The forward's
+    O itself must be within that model too: |dO.O_gpu - dO.o| <= delta_error_bound, row by row."""
+    w = workload(name)
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    Q, K, V = synth.generate(w)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(synth.BASE_SEED + 31 * w.config_id)
+    dO = torch.randn((w.S, w.Hq, w.D), generator=g, dtype=torch.float32).to(torch.bfloat16)
+    mask = oracle.cube_select(osh, Q, oracle.cube_pool(osh, K), p)[0]
+    Qg, Kg, Vg, dOg = Q.cuda(), K.cuda(), V.cuda(), dO.cuda()
+    mg = torch.from_numpy(mask.view(np.int32)).cuda()
+    print(f"[{name}] forward + backward, exact-delta comparison", flush=True)
+    O, lse = B.sparse_attn(sh, Qg, Kg, Vg, mg, return_lse=True)
+    dQ, dK, dV = B.sparse_attn_bwd(sh, Qg, Kg, Vg, O, lse, dOg, sel_mask=mg)
+    torch.cuda.synchronize()
+    T = {}
+    q, k, v, do = f64(Q), f64(K), f64(V), f64(dO).reshape(-1, w.D)
+    rq, rk, rv, delta = oracle.bwd.sparse_attn_bwd(osh, q, k, v, mask, do, O=None, scales=T)
+    # the forward's effect on delta, row by row, against the model the extra tolerance is built from
+    tables = oracle.bwd.cube_tables(osh)
+    d_gpu = (do * f64(O.cpu()).reshape(-1, w.D)).sum(axis=1)
+    worst = 0.0
+    for r in synth.sample_rows(w, 200):
+        att, _, _, _, _, _, pr = oracle.bwd.row_backward(osh, q, k, v, mask[r], r, do[r], None, tables)
+        n, a = divmod(int(r), w.Hq)
+        gk = a // (w.Hq // w.Hkv)
+        absdot = (np.abs(k[att, gk]) @ np.abs(q[n, a])).max() / np.sqrt(w.D)
+        worst = max(worst, abs(d_gpu[r] - delta[r]) / oracle.bwd.delta_error_bound(do[r], pr @ v[att, gk], pr, v[att, gk], absdot))
+    print(f"[{name}] |delta_gpu - delta_exact| / bound, worst of the sampled rows: {worst:.3f}", flush=True)
+    assert worst <= 1.0
+    for nm, got, want in (("dV", dV, rv), ("dQ", dQ, rq), ("dK", dK, rk)):
+        got, want_, terms = (x.reshape(-1, w.D) for x in (f64(got.cpu()), want, T[nm]))
+        extra = T[nm + "_delta"].reshape(-1, w.D) if nm != "dV" else 0.0
+        err = np.abs(got - want_)
+        bound = 2.0 ** -8 * np.abs(want_) + 2.0 ** -7 * terms + 1e-4 + extra
+        print(f"[{name} {nm} vs exact] max-abs={err.max():.3e} worst err/bound={np.max(err / bound):.3f} "
+              f"share of the bound that is the delta term: {np.mean(extra / bound):.2f}", flush=True)
+        assert (err <= bound).all()
+
+
 @pytest.mark.parametrize("name", ["T_ragged", "T_mha64"])
 def test_dense_backward_matches_oracle(B, oracle, name):
     run_case(B, oracle, name, 1.0, dense=True)
