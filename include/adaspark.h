@@ -148,6 +148,23 @@ int adaspark_cube_select(const adaspark_shape *shape, const void *Q, const float
                          int64_t capacity, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * adaspark_cube_select for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc) and so cannot bring a workspace: the same kernels and the same results,
+ * with the workspace -- the bf16 split of the mean keys and the tile sums of the compact list's scan -- in a device
+ * array that is part of the library (ADASPARK_NOALLOC_SCRATCH_BYTES per GPU, held from the library's load to the end
+ * of the process).  The call allocates and frees nothing.  A shape whose selection workspace
+ * (adaspark_workspace_bytes(ADASPARK_CALL_CUBE_SELECT)) exceeds that size is refused with ADASPARK_EWORKSPACE before
+ * anything is enqueued; 4 MiB covers 262,144 tokens in 1,024 cubes with 4 KV heads of 128.  All calls on one GPU share
+ * that GPU's array: it holds whatever the last call left, every call rewrites what it reads, and two calls that
+ * overlap in time on one GPU (different streams or threads) race -- serialise them, or use adaspark_cube_select
+ * with a workspace each.  Other arguments and outputs as adaspark_cube_select.
+ */
+#define ADASPARK_NOALLOC_SCRATCH_BYTES (4u << 20)
+int adaspark_cube_select_noalloc(const adaspark_shape *shape, const void *Q, const float *kbar, float top_p, int causal,
+                                 uint32_t *sel_mask, int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx,
+                                 int64_t capacity, void *stream);
+
+/*
  * Fixed Top-K cube selection, the comparison baseline of the paper's ablation
  * "Effect of Top-P Adaptive Selection" (Sec. 4) and of its table of selection
  * strategies: row r keeps the top_k preceding cubes of highest relevance (Eq. 1),

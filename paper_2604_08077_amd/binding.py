@@ -77,6 +77,7 @@ EXPORTS = (
     "adaspark_pairs_workspace_bytes",
     "adaspark_cube_pool",
     "adaspark_cube_select",
+    "adaspark_cube_select_noalloc",
     "adaspark_cube_select_topk",
     "adaspark_cube_select_shared",
     "adaspark_sparse_attn",
@@ -92,6 +93,7 @@ EXPORTS = (
 )
 
 SPARSE_AUTO, SPARSE_COMPACT, SPARSE_MASKED, SPARSE_PAIRS = 0, 1, 2, 3
+NOALLOC_SCRATCH_BYTES = 4 << 20  # ADASPARK_NOALLOC_SCRATCH_BYTES
 
 
 def load():
@@ -113,6 +115,8 @@ def load():
         lib.adaspark_cube_pool.argtypes = [sp, vp, vp, vp]
         lib.adaspark_cube_select.argtypes = [sp, vp, vp, ctypes.c_float, ctypes.c_int, vp, vp, vp, vp,
                                              ctypes.c_int64, vp, ctypes.c_size_t, vp]
+        lib.adaspark_cube_select_noalloc.argtypes = [sp, vp, vp, ctypes.c_float, ctypes.c_int, vp, vp, vp, vp,
+                                                     ctypes.c_int64, vp]
         lib.adaspark_cube_select_topk.argtypes = [sp, vp, vp, ctypes.c_int32, ctypes.c_int, vp, vp, vp, vp,
                                                   ctypes.c_int64, vp, ctypes.c_size_t, vp]
         lib.adaspark_cube_select_shared.argtypes = [sp, vp, vp, ctypes.c_float, ctypes.c_int, vp, vp, vp, ctypes.c_size_t,
@@ -207,6 +211,26 @@ def cube_select(shape: Shape, Q: torch.Tensor, kbar: torch.Tensor, top_p: float,
     """Eqs. 1-2: -> (sel_mask int32-viewed-u32 [R, words], sel_count int32 [R], row_ptr|None, cube_idx|None)."""
     return _cube_select("adaspark_cube_select", ctypes.c_float(top_p), shape, Q, kbar, causal, sel_mask, sel_count,
                         csr_capacity, workspace)
+
+
+def cube_select_noalloc(shape: Shape, Q: torch.Tensor, kbar: torch.Tensor, top_p: float, sel_mask: torch.Tensor,
+                        sel_count: torch.Tensor, row_ptr=None, cube_idx=None, causal: bool = True):
+    """adaspark_cube_select_noalloc: the selection with the library's own scratch array instead of a workspace.
+    Every output tensor is the caller's; nothing is allocated here or in the library."""
+    N = num_cubes(shape)
+    words = (N + 31) // 32
+    R = shape.rows
+    rp = ci = None
+    cap = 0
+    if row_ptr is not None:
+        rp, ci, cap = _dev(row_ptr, torch.int64, R + 1, "row_ptr"), cube_idx.data_ptr(), cube_idx.numel()
+    cs = shape._c()
+    _check(load().adaspark_cube_select_noalloc(
+        ctypes.byref(cs), _dev(Q, torch.bfloat16, R * shape.head_dim, "Q"),
+        _dev(kbar, torch.float32, N * shape.kv_heads * shape.head_dim, "kbar"), ctypes.c_float(top_p),
+        int(bool(causal)), _dev(sel_mask, torch.int32, R * words, "sel_mask"),
+        _dev(sel_count, torch.int32, R, "sel_count"), rp, ci, cap, _stream()), "adaspark_cube_select_noalloc")
+    return sel_mask, sel_count, row_ptr, cube_idx
 
 
 def cube_select_topk(shape: Shape, Q: torch.Tensor, kbar: torch.Tensor, top_k: int, causal: bool = True,

@@ -1,4 +1,6 @@
 // extern "C" boundary of the library: argument validation and kernel enqueueing only.
+#include <mutex>
+
 #include "geom.h"
 #include "ffn.h"
 
@@ -48,6 +50,38 @@ int check_ptrs(std::initializer_list<const void *> ps)
 }
 
 }  // namespace
+
+// Scratch memory of adaspark_cube_select_noalloc: the selection kernels' workspace (the three-term bf16 split of the
+// mean keys and the tile sums of the compact list's scan) as a device array of the library itself, so that callers
+// who cannot allocate need not bring a workspace.  One copy per GPU, held until the process ends; every call on a
+// GPU uses that GPU's copy.  Host code never uses the array's name as an address: the device address is asked for
+// once per device (static_scratch) and that pointer is what the kernels get.
+constexpr size_t STATIC_SCRATCH_BYTES = ADASPARK_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+constexpr int STATIC_SCRATCH_MAX_DEVICES = 64;
+static std::mutex scratch_lock;
+static void *scratch_ptr[STATIC_SCRATCH_MAX_DEVICES] = {};
+
+// The calling thread's current device's copy of `scratch`; nullptr (and *err set) if the runtime refuses.
+static void *static_scratch(hipError_t *err)
+{
+    int dev = -1;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= STATIC_SCRATCH_MAX_DEVICES) {
+        *err = hipErrorInvalidDevice;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> hold(scratch_lock);
+    if (scratch_ptr[dev] == nullptr) {
+        void *p = nullptr;
+        *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess) return nullptr;
+        scratch_ptr[dev] = p;
+    }
+    return scratch_ptr[dev];
+}
 
 extern "C" {
 
@@ -138,6 +172,22 @@ int adaspark_cube_select(const adaspark_shape *shape, const void *Q, const float
     if (!(top_p >= 0.f && top_p <= 1.f)) return ADASPARK_EINVAL;  // also rejects NaN
     return cube_select(shape, Q, kbar, top_p, -1, causal, sel_mask, sel_count, row_ptr, cube_idx, capacity, workspace,
                        workspace_bytes, stream);
+}
+
+int adaspark_cube_select_noalloc(const adaspark_shape *shape, const void *Q, const float *kbar, float top_p, int causal,
+                                 uint32_t *sel_mask, int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx,
+                                 int64_t capacity, void *stream)
+{
+    if (!(top_p >= 0.f && top_p <= 1.f)) return ADASPARK_EINVAL;
+    const int rc = check_shape(shape);
+    if (rc != ADASPARK_OK) return rc;
+    // a workspace that does not fit the library's own array: said before anything is asked of the runtime
+    if (select_workspace_bytes(make_geom(*shape)) > STATIC_SCRATCH_BYTES) return ADASPARK_EWORKSPACE;
+    hipError_t err = hipSuccess;
+    void *ws = static_scratch(&err);
+    if (ws == nullptr) return ADASPARK_EHIP;
+    return cube_select(shape, Q, kbar, top_p, -1, causal, sel_mask, sel_count, row_ptr, cube_idx, capacity, ws,
+                       STATIC_SCRATCH_BYTES, stream);
 }
 
 int adaspark_cube_select_topk(const adaspark_shape *shape, const void *Q, const float *kbar, int32_t top_k, int causal,

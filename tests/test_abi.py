@@ -173,3 +173,21 @@ def test_shared_selection_arguments_are_validated(lib):
         ctypes.byref(cs), q, ok_ptr, ctypes.c_float(p), causal, ok_ptr, ok_ptr, ws, nbytes, None)
     assert run(p=1.5) == -1 and run(p=float("nan")) == -1 and run(q=None) == -1
     assert run(ws=None) == -3 and run(nbytes=need.value - 1) == -3
+
+
+def test_allocation_free_selection_refuses_what_its_array_cannot_hold(lib):
+    """adaspark_cube_select_noalloc keeps its workspace in an array of the library (ADASPARK_NOALLOC_SCRATCH_BYTES):
+    a shape that needs more is refused before anything is asked of the runtime, and so are a bad top_p or shape."""
+    ok_ptr = ctypes.c_void_p(4096)
+    call = lambda cs, p: lib.adaspark_cube_select_noalloc(ctypes.byref(cs), ok_ptr, ok_ptr, ctypes.c_float(p), 1,
+                                                          ok_ptr, ok_ptr, None, None, 0, None)
+    big = binding.Shape(2048, 16, 16, 1, 16, 16, 8, 8, 128)            # 2,048 cubes, 8 KV heads of 128
+    assert binding.workspace_bytes(big, binding.CALL_CUBE_SELECT) > binding.NOALLOC_SCRATCH_BYTES
+    assert call(big._c(), 0.9) == -3
+    for name in ("C1", "C2", "C3", "C4", "C5"):                        # every benchmark configuration fits
+        assert binding.workspace_bytes(binding.Shape.of(synth.WORKLOADS[name]), binding.CALL_CUBE_SELECT) \
+            <= binding.NOALLOC_SCRATCH_BYTES
+    assert call(_raw_shape()._c(), 1.5) == -1
+    assert call(_raw_shape(head_dim=96)._c(), 0.5) == -2
+    header = open(os.path.join(ROOT, "include", "adaspark.h")).read()
+    assert "#define ADASPARK_NOALLOC_SCRATCH_BYTES (4u << 20)" in header and binding.NOALLOC_SCRATCH_BYTES == 4 << 20
