@@ -15,6 +15,8 @@ Readings of the paper fixed here:
   * A cube with no activated token (p = 0) has no mean transformation: its tokens
     keep their value (m-bar = 0).
   * Text tokens all take the dense FFN (last paragraph of Sec. 3.3).
+  * Eq. 4 with a zero denominator (every token of the cube has norm 0 and eps = 0): all
+    scores are 0.
 """
 from __future__ import annotations
 
@@ -34,8 +36,14 @@ def token_norms(X: np.ndarray) -> np.ndarray:
 
 
 def importance(norms: np.ndarray, eps: float) -> np.ndarray:
-    """s_j = ||x_j|| / (sum_k ||x_k|| + eps) over the tokens of ONE cube  (Eq. 4)."""
-    return norms / (norms.sum() + eps)
+    """s_j = ||x_j|| / (sum_k ||x_k|| + eps) over the tokens of ONE cube  (Eq. 4).  The epsilon is there for a cube
+    whose tokens all have zero norm; with eps = 0 as well the quotient 0/0 is read as 0: such a cube has no
+    importance to hand out, every score is 0, and the Top-p rule then keeps every token for p > 0 (nothing is
+    ranked before anybody with positive mass) and none for p = 0."""
+    total = norms.sum() + eps
+    if total == 0.0:
+        return np.zeros_like(norms)
+    return norms / total
 
 
 def top_p_tokens(s: np.ndarray, p: float):

@@ -84,7 +84,8 @@ __global__ __launch_bounds__(SEL_THREADS) void ffn_select_kernel(Geom g, int d_m
     }
     __syncthreads();
     const float total = block_sum<SEL_THREADS>(sc, n, red);
-    const float inv = 1.0f / (total + eps);
+    // a cube of zero-norm tokens with eps = 0: every score is 0 (Eq. 4's epsilon is there for this cube)
+    const float inv = (total + eps > 0.f) ? 1.0f / (total + eps) : 0.f;
     __syncthreads();
     for (int j = threadIdx.x; j < n; j += SEL_THREADS) sc[j] = sc[j] * inv;
     __syncthreads();

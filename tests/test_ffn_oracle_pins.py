@@ -60,6 +60,16 @@ def test_norm_and_importance_closed_forms(oracle):
     keep, score, _ = f.ffn_select(sh, Xn, 0.7, eps=10.0)
     np.testing.assert_allclose(score, [0.2, 0.15, 0.1, 0.05], rtol=1e-15)
     assert keep.tolist() == [1, 1, 1, 1]
+    # a cube of zero-norm tokens: the eps of Eq. 4 makes every score 0/eps = 0; without it 0/0 is read as 0 too.
+    # Nothing with positive mass is ranked before anybody: every token is activated for p > 0, none for p = 0.
+    for eps in (1e-6, 0.0):
+        assert f.importance(np.zeros(5), eps).tolist() == [0.0] * 5
+        for p, want in ((0.7, 1), (1e-9, 1), (0.0, 0)):
+            keep, score, _ = f.ffn_select(one_cube_shape(oracle, 6), np.zeros((6, 3)), p, eps=eps)
+            assert keep.tolist() == [want] * 6 and score.tolist() == [0.0] * 6
+    # (a single token of norm zero among others ranks last and is dropped once the others reach p)
+    keep, score, _ = f.ffn_select(one_cube_shape(oracle, 3), np.array([[0.0, 0.0], [3.0, 4.0], [0.0, 5.0]]), 0.9, eps=0.0)
+    assert keep.tolist() == [0, 1, 1] and score.tolist() == [0.0, 0.5, 0.5]
     # equal norms: s_j = 1/n, ceil(p n) tokens, lowest ranks first
     keep, _, _ = f.ffn_select(one_cube_shape(oracle, 10), np.ones((10, 3)), 0.35, eps=0.0)
     assert keep.tolist() == [1, 1, 1, 1] + [0] * 6

@@ -182,11 +182,12 @@ def test_ffn_zero_tokens_and_zero_cube(B, oracle):
     X[cube_of == 3] = 0                                  # a whole cube
     X[torch.from_numpy(np.nonzero(cube_of == 5)[0][::3])] = 0   # every third token of another
     x64 = f64(X)
-    for p in (0.6, 0.999):
-        print(f"[T_ragged zeros] ffn_select p={p}", flush=True)
-        keep, score, _ = B.ffn_select(sh, X.cuda(), d_ff, p)
+    for p, eps in ((0.6, 1e-6), (0.999, 1e-6), (0.6, 0.0)):   # eps = 0: the all-zero cube's 0/0 scores are 0, not NaN
+        print(f"[T_ragged zeros] ffn_select p={p} eps={eps}", flush=True)
+        keep, score, _ = B.ffn_select(sh, X.cuda(), d_ff, p, eps=eps)
         torch.cuda.synchronize()
-        rk, rs, near = oracle.ffn.ffn_select(osh, x64, p)
+        assert torch.isfinite(score).all()
+        rk, rs, near = oracle.ffn.ffn_select(osh, x64, p, eps=eps)
         k = keep.cpu().numpy()
         differ = np.unique(cube_of[k != rk])
         assert all(near[c] for c in differ)
