@@ -82,6 +82,33 @@ def timed(fn, n):
     return ev0.elapsed_time(ev1) / n
 
 
+def measured_ceilings(B):
+    """What this GPU sustains, from the library's two probes (outside every timed region): a plain 1 GiB streaming
+    copy (bytes read + written per second) and back-to-back bf16 MFMAs on every SIMD.  The roofline fractions are
+    given against the datasheet peaks and, as *_measured, against these."""
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    src.zero_()
+    B.probe_copy(dst, src)
+    moved = [0]
+
+    def copy():
+        moved[0] = B.probe_copy(dst, src)
+
+    copy_ms = timed(copy, 5)
+    del src, dst
+    out = torch.empty(1024, dtype=torch.float32, device="cuda")
+    flops = [0.0]
+
+    def mfma():
+        flops[0] = B.probe_mfma(out, 1024, 8192)
+
+    mfma()
+    mfma_ms = timed(mfma, 3)
+    torch.cuda.empty_cache()
+    return {"copy_gbs": moved[0] / (copy_ms * 1e-3) / 1e9, "mfma_bf16_tflops": flops[0] / (mfma_ms * 1e-3) / 1e12}
+
+
 def cpu_baseline(w, p, Q, K, V, budget_rows_sel=262144, budget_rows_attn=24576):
     """The fp64 oracle on a bounded row sample of the same workload, extrapolated to tokens/s."""
     import oracle
@@ -366,6 +393,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    ceilings = measured_ceilings(B)
     keys_total, pairs = attended_keys_total(w, mask, sizes, rank)
     eff_flops = 4.0 * w.D * keys_total
     dense_keys = int((np.cumsum(np.concatenate([[0], sizes[:-1]]))[cube] + rank + 1).sum()) * w.Hq
@@ -431,6 +459,9 @@ def main():
         "selected_fraction_of_preceding_cubes": share,
         "kernel_ms": k_ms,
         "kernel_hbm_gbs": {k: hbm_bytes[k] / (k_ms[k] * 1e-3) / 1e9 for k in hbm_bytes},
+        "kernel_hbm_frac": {k: hbm_bytes[k] / (k_ms[k] * 1e-3) / 1e9 / PEAK_HBM_GBS for k in hbm_bytes},
+        "kernel_hbm_frac_measured": {k: hbm_bytes[k] / (k_ms[k] * 1e-3) / 1e9 / ceilings["copy_gbs"] for k in hbm_bytes},
+        "measured_ceilings": ceilings,
         "dense_attn_ms": dense_ms,
         "dense_tflops": None if dense_ms is None else dense_flops / (dense_ms * 1e-3) / 1e12,
         "speedup_vs_dense": None if dense_ms is None else (k_ms["kv_pack"] + dense_ms) / ms_per_step,
@@ -442,7 +473,10 @@ def main():
             "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s",
             "frac": attn_tflops / PEAK_BF16_TFLOPS,
+            "peak_measured": ceilings["mfma_bf16_tflops"],
+            "frac_measured": attn_tflops / ceilings["mfma_bf16_tflops"],
             "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, args.top_p)),
+            "traffic_source": "stored figure from the rocprofv3 --pmc summaries under profiles/ (not counted in this run)",
             "executed_tflops": None if executed_flops is None else executed_flops / (attn_kernel_ms * 1e-3) / 1e12,
         },
     }

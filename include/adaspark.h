@@ -65,7 +65,9 @@ typedef enum {
     ADASPARK_EINVAL = -1,       /* null/misaligned pointer, bad shape, top_p outside [0,1]     */
     ADASPARK_EUNSUPPORTED = -2, /* valid request outside what the kernels cover (see below)    */
     ADASPARK_EWORKSPACE = -3,   /* workspace missing or smaller than adaspark_workspace_bytes  */
-    ADASPARK_EHIP = -4          /* the HIP runtime refused a launch                            */
+    ADASPARK_EHIP = -4,         /* the HIP runtime refused a launch                            */
+    ADASPARK_ECAPACITY = -5     /* never returned by a call: the value a selection call leaves */
+                                /* in its device status word when the compact list overflowed  */
 } adaspark_status;
 
 typedef enum {
@@ -74,7 +76,8 @@ typedef enum {
     ADASPARK_CALL_SPARSE_ATTN = 2,
     ADASPARK_CALL_DENSE_ATTN = 3,
     ADASPARK_CALL_ATTN_BWD = 4,
-    ADASPARK_CALL_CUBE_SELECT_SHARED = 5
+    ADASPARK_CALL_CUBE_SELECT_SHARED = 5,
+    ADASPARK_CALL_SPARSE_ATTN_CSR = 6
 } adaspark_call;
 
 /* Which kernel a sparse-attention call runs.  All compute the same result (Eq. 3).
@@ -142,10 +145,16 @@ int adaspark_cube_pool(const adaspark_shape *shape, const void *K, float *kbar, 
  *                  >= capacity are dropped, so the list is complete iff
  *                  row_ptr[tokens*q_heads] <= capacity.  NULL iff row_ptr is NULL.
  *   workspace      adaspark_workspace_bytes(ADASPARK_CALL_CUBE_SELECT)
+ * Overflow of the compact list is found on the device (the call never waits for it): every selection call leaves
+ * an int32 status word in its workspace, at byte adaspark_select_status_offset(shape): ADASPARK_OK, or
+ * ADASPARK_ECAPACITY if the rows' lists needed more than `capacity` entries.  The caller reads it (a 4-byte copy)
+ * after the stream has reached the end of the call.  The mask and the counts are complete either way.
  */
 int adaspark_cube_select(const adaspark_shape *shape, const void *Q, const float *kbar, float top_p, int causal,
                          uint32_t *sel_mask, int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx,
                          int64_t capacity, void *workspace, size_t workspace_bytes, void *stream);
+/* Host-only: where in the selection workspace the device status word of the call lies. */
+int adaspark_select_status_offset(const adaspark_shape *shape, size_t *offset);
 
 /*
  * adaspark_cube_select for callers that cannot allocate device memory (code under HIP graph capture, tight serving
@@ -208,6 +217,19 @@ int adaspark_cube_select_shared(const adaspark_shape *shape, const void *Q, cons
 int adaspark_sparse_attn(const adaspark_shape *shape, const void *Q, const void *K, const void *V,
                          const uint32_t *sel_mask, int causal, void *O, float *lse,
                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * adaspark_sparse_attn fed the compact list instead of the mask rows (Eq. 3 on the sets S_r as
+ * adaspark_cube_select lists them): row r attends the cubes cube_idx[row_ptr[r] .. row_ptr[r+1]) -- ascending,
+ * complete (status word ADASPARK_OK) -- and the causal part of its own cube.  The list is first turned back into
+ * mask rows inside the workspace; results are bit-identical to the mask-fed entry.
+ *   row_ptr   in   i64  [tokens*q_heads + 1];   cube_idx  in  i32  [row_ptr[tokens*q_heads]]
+ *   workspace      adaspark_workspace_bytes(ADASPARK_CALL_SPARSE_ATTN_CSR) (the packed K/V copy and the mask rows),
+ *                  or more: what lies beyond is scratch for the key-stationary kernel, as above
+ */
+int adaspark_sparse_attn_csr(const adaspark_shape *shape, const void *Q, const void *K, const void *V,
+                             const int64_t *row_ptr, const int32_t *cube_idx, int causal, void *O, float *lse,
+                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Dense causal attention in the same cube-major order (the comparison point of
@@ -316,6 +338,18 @@ int adaspark_ffn_select(const adaspark_shape *shape, const adaspark_ffn_dims *di
 int adaspark_ffn_sparse(const adaspark_shape *shape, const adaspark_ffn_dims *dims, const void *X, const void *W_gate,
                         const void *W_up, const void *W_down, const uint8_t *keep, void *Y, void *workspace,
                         size_t workspace_bytes, void *stream);
+
+/*
+ * Measurement probes (not part of the method: they exist so that a benchmark can state what this GPU sustains next
+ * to the datasheet peaks its kernels are priced against).
+ *   adaspark_probe_copy  a plain streaming copy of `bytes` bytes (a multiple of 16) from src to dst, device buffers
+ *                        that do not overlap; bytes read + bytes written over its duration is the attainable HBM rate.
+ *   adaspark_probe_mfma  `workgroups` workgroups of eight wavefronts each run 16 * trips back-to-back
+ *                        mfma_f32_16x16x32_bf16 on independent accumulators; *flops (host, may be NULL) receives the
+ *                        floating-point operations of the launch; out: device, `workgroups` floats, overwritten.
+ */
+int adaspark_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
+int adaspark_probe_mfma(float *out, int32_t workgroups, int32_t trips, double *flops, void *stream);
 
 #ifdef __cplusplus
 }

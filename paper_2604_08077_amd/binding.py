@@ -16,6 +16,8 @@ import torch
 from .build import lib_path
 
 CALL_CUBE_POOL, CALL_CUBE_SELECT, CALL_SPARSE_ATTN, CALL_DENSE_ATTN, CALL_ATTN_BWD, CALL_CUBE_SELECT_SHARED = 0, 1, 2, 3, 4, 5
+CALL_SPARSE_ATTN_CSR = 6
+ECAPACITY = -5  # ADASPARK_ECAPACITY: what a selection call leaves in its device status word on list overflow
 
 
 class _CShape(ctypes.Structure):
@@ -77,10 +79,12 @@ EXPORTS = (
     "adaspark_pairs_workspace_bytes",
     "adaspark_cube_pool",
     "adaspark_cube_select",
+    "adaspark_select_status_offset",
     "adaspark_cube_select_noalloc",
     "adaspark_cube_select_topk",
     "adaspark_cube_select_shared",
     "adaspark_sparse_attn",
+    "adaspark_sparse_attn_csr",
     "adaspark_dense_attn",
     "adaspark_kv_pack",
     "adaspark_sparse_attn_packed",
@@ -90,6 +94,8 @@ EXPORTS = (
     "adaspark_ffn_workspace_bytes",
     "adaspark_ffn_select",
     "adaspark_ffn_sparse",
+    "adaspark_probe_copy",
+    "adaspark_probe_mfma",
 )
 
 SPARSE_AUTO, SPARSE_COMPACT, SPARSE_MASKED, SPARSE_PAIRS = 0, 1, 2, 3
@@ -115,6 +121,10 @@ def load():
         lib.adaspark_cube_pool.argtypes = [sp, vp, vp, vp]
         lib.adaspark_cube_select.argtypes = [sp, vp, vp, ctypes.c_float, ctypes.c_int, vp, vp, vp, vp,
                                              ctypes.c_int64, vp, ctypes.c_size_t, vp]
+        lib.adaspark_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        lib.adaspark_probe_mfma.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_double), vp]
+        lib.adaspark_select_status_offset.argtypes = [sp, ctypes.POINTER(ctypes.c_size_t)]
+        lib.adaspark_sparse_attn_csr.argtypes = [sp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp, vp, ctypes.c_size_t, vp]
         lib.adaspark_cube_select_noalloc.argtypes = [sp, vp, vp, ctypes.c_float, ctypes.c_int, vp, vp, vp, vp,
                                                      ctypes.c_int64, vp]
         lib.adaspark_cube_select_topk.argtypes = [sp, vp, vp, ctypes.c_int32, ctypes.c_int, vp, vp, vp, vp,
@@ -211,6 +221,39 @@ def cube_select(shape: Shape, Q: torch.Tensor, kbar: torch.Tensor, top_p: float,
     """Eqs. 1-2: -> (sel_mask int32-viewed-u32 [R, words], sel_count int32 [R], row_ptr|None, cube_idx|None)."""
     return _cube_select("adaspark_cube_select", ctypes.c_float(top_p), shape, Q, kbar, causal, sel_mask, sel_count,
                         csr_capacity, workspace)
+
+
+def select_status(shape: Shape, workspace: torch.Tensor) -> int:
+    """The device status word a selection call left in its workspace (0, or ECAPACITY if the compact list did not
+    fit): a 4-byte copy to the host, which waits for the stream."""
+    off = ctypes.c_size_t(0)
+    cs = shape._c()
+    _check(load().adaspark_select_status_offset(ctypes.byref(cs), ctypes.byref(off)), "adaspark_select_status_offset")
+    return int(workspace[off.value: off.value + 4].view(torch.int32).item())
+
+
+def sparse_attn_csr(shape: Shape, Q, K, V, row_ptr, cube_idx, causal: bool = True, O=None, lse=None, workspace=None,
+                    return_lse: bool = False):
+    """adaspark_sparse_attn_csr: Eq. 3 + own-cube rule over the cubes each row's compact list names."""
+    R = shape.rows
+    dev = Q.device
+    if O is None:
+        O = torch.empty((shape.tokens, shape.q_heads, shape.head_dim), dtype=torch.bfloat16, device=dev)
+    if lse is None and return_lse:
+        lse = torch.empty((R,), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = alloc_workspace(shape, CALL_SPARSE_ATTN_CSR, dev)
+    kvn = shape.tokens * shape.kv_heads * shape.head_dim
+    if cube_idx.dtype != torch.int32 or not cube_idx.is_contiguous() or cube_idx.device.type != "cuda":
+        raise ValueError("cube_idx must be a contiguous int32 GPU tensor")
+    cs = shape._c()
+    _check(load().adaspark_sparse_attn_csr(
+        ctypes.byref(cs), _dev(Q, torch.bfloat16, R * shape.head_dim, "Q"), _dev(K, torch.bfloat16, kvn, "K"),
+        _dev(V, torch.bfloat16, kvn, "V"), _dev(row_ptr, torch.int64, R + 1, "row_ptr"), cube_idx.data_ptr(),
+        int(bool(causal)), _dev(O, torch.bfloat16, R * shape.head_dim, "O"),
+        None if lse is None else _dev(lse, torch.float32, R, "lse"), workspace.data_ptr(), workspace.numel(),
+        _stream()), "adaspark_sparse_attn_csr")
+    return (O, lse) if return_lse else O
 
 
 def cube_select_noalloc(shape: Shape, Q: torch.Tensor, kbar: torch.Tensor, top_p: float, sel_mask: torch.Tensor,
@@ -432,3 +475,22 @@ def cube_select_shared(shape: Shape, Q: torch.Tensor, kbar: torch.Tensor, top_p:
         _dev(sel_mask, torch.int32, R * words, "sel_mask"), _dev(sel_count, torch.int32, R, "sel_count"),
         workspace.data_ptr(), workspace.numel(), _stream()), "adaspark_cube_select_shared")
     return sel_mask, sel_count
+
+
+def probe_copy(dst: torch.Tensor, src: torch.Tensor) -> int:
+    """adaspark_probe_copy: src -> dst (same size, GPU, no overlap); returns the bytes moved (read + written)."""
+    n = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != n or dst.device.type != "cuda" or src.device.type != "cuda":
+        raise ValueError("probe_copy: two GPU tensors of the same size")
+    _check(load().adaspark_probe_copy(dst.data_ptr(), src.data_ptr(), n, _stream()), "adaspark_probe_copy")
+    return 2 * n
+
+
+def probe_mfma(out: torch.Tensor, workgroups: int, trips: int) -> float:
+    """adaspark_probe_mfma: enqueue the back-to-back MFMA probe; returns the floating-point operations it performs."""
+    if out.numel() < workgroups:
+        raise ValueError("probe_mfma: out needs one float per workgroup")
+    flops = ctypes.c_double(0.0)
+    _check(load().adaspark_probe_mfma(_dev(out, torch.float32, out.numel(), "out"), workgroups, trips,
+                                      ctypes.byref(flops), _stream()), "adaspark_probe_mfma")
+    return flops.value

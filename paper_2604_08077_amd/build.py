@@ -16,7 +16,7 @@ LIB = os.path.join(_HERE, "libadaspark.so")
 OBJ_DIR = os.path.join(_HERE, "_build")
 
 SOURCES = ["api.hip", "pool.hip", "select.hip", "kvpack.hip", "attn_compact.hip", "attn_walk.hip", "attn_pairs.hip", "ffn.hip",
-           "ffn_gemm.hip", "attn_bwd.hip"]
+           "ffn_gemm.hip", "attn_bwd.hip", "probe.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950",
     "-O3",

@@ -42,6 +42,9 @@ int check_ffn(const adaspark_shape *s, const adaspark_ffn_dims *d)
     return ADASPARK_OK;
 }
 
+// adaspark_sparse_attn_csr: the mask rows rebuilt from the compact list lie behind the packed K/V copy
+size_t csr_mask_bytes(const Geom &g) { return ((size_t)g.S * g.Hq * g.words * 4 + 255) / 256 * 256; }
+
 int check_ptrs(std::initializer_list<const void *> ps)
 {
     for (const void *p : ps)
@@ -107,8 +110,20 @@ int adaspark_workspace_bytes(const adaspark_shape *shape, int which_call, size_t
     case ADASPARK_CALL_DENSE_ATTN: *bytes = attn_workspace_bytes(g); return ADASPARK_OK;
     case ADASPARK_CALL_ATTN_BWD: *bytes = attn_bwd_workspace_bytes(g); return ADASPARK_OK;
     case ADASPARK_CALL_CUBE_SELECT_SHARED: *bytes = select_shared_workspace_bytes(g); return ADASPARK_OK;
+    case ADASPARK_CALL_SPARSE_ATTN_CSR:  // (256 more: the mask rows start on a 256-byte boundary of the address)
+        *bytes = (attn_workspace_bytes(g) + 255) / 256 * 256 + 256 + csr_mask_bytes(g);
+        return ADASPARK_OK;
     default: return ADASPARK_EINVAL;
     }
+}
+
+int adaspark_select_status_offset(const adaspark_shape *shape, size_t *offset)
+{
+    if (offset == nullptr) return ADASPARK_EINVAL;
+    const int rc = check_shape(shape);
+    if (rc != ADASPARK_OK) return rc;
+    *offset = select_status_offset(make_geom(*shape));
+    return ADASPARK_OK;
 }
 
 int adaspark_pairs_workspace_bytes(const adaspark_shape *shape, int64_t max_selected, size_t *bytes)
@@ -131,6 +146,7 @@ const char *adaspark_status_string(int status)
     case ADASPARK_EUNSUPPORTED: return "unsupported configuration";
     case ADASPARK_EWORKSPACE: return "workspace missing or too small";
     case ADASPARK_EHIP: return "HIP launch failed";
+    case ADASPARK_ECAPACITY: return "compact list capacity exceeded";
     default: return "unknown status";
     }
 }
@@ -248,9 +264,11 @@ int adaspark_kv_pack(const adaspark_shape *shape, const void *K, const void *V, 
     return e == hipSuccess ? ADASPARK_OK : ADASPARK_EHIP;
 }
 
+// skip: bytes behind the minimum workspace (rounded up to 256) that are not scratch memory (the CSR entry keeps its
+// mask rows there)
 static int attn_packed(const adaspark_shape *shape, const void *Q, void *packed, size_t packed_bytes,
                        const uint32_t *sel_mask, bool sparse, int sparse_kernel, int causal, void *O, float *lse,
-                       void *stream)
+                       void *stream, size_t skip = 0)
 {
     int rc = attn_check(shape, Q, sel_mask, sparse, causal, O, lse);
     if (rc != ADASPARK_OK) return rc;
@@ -264,7 +282,7 @@ static int attn_packed(const adaspark_shape *shape, const void *Q, void *packed,
     if ((rc = workspace_check(g, packed, packed_bytes)) != ADASPARK_OK) return rc;
     // whatever lies beyond the minimum workspace, from the next 256-byte boundary on, is scratch memory
     const uintptr_t begin = reinterpret_cast<uintptr_t>(packed);
-    const uintptr_t sbegin = (begin + attn_workspace_bytes(g) + 255) & ~static_cast<uintptr_t>(255);
+    const uintptr_t sbegin = ((begin + attn_workspace_bytes(g) + 255) & ~static_cast<uintptr_t>(255)) + skip;
     void *scratch = nullptr;
     size_t scratch_bytes = 0;
     if (sparse && begin + packed_bytes > sbegin) {
@@ -320,6 +338,30 @@ int adaspark_sparse_attn(const adaspark_shape *shape, const void *Q, const void 
                          size_t workspace_bytes, void *stream)
 {
     return attn_full(shape, Q, K, V, sel_mask, true, causal, O, lse, workspace, workspace_bytes, stream);
+}
+
+int adaspark_sparse_attn_csr(const adaspark_shape *shape, const void *Q, const void *K, const void *V,
+                             const int64_t *row_ptr, const int32_t *cube_idx, int causal, void *O, float *lse,
+                             void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_shape(shape);
+    if (rc != ADASPARK_OK) return rc;
+    if ((rc = check_ptrs({Q, K, V, O, row_ptr, cube_idx})) != ADASPARK_OK) return rc;
+    if (lse != nullptr && !aligned16(lse)) return ADASPARK_EINVAL;
+    const Geom g = make_geom(*shape);
+    // the mask rows start at the first 256-byte boundary (of the address) behind the minimum workspace
+    const uintptr_t begin = reinterpret_cast<uintptr_t>(workspace);
+    const uintptr_t mbegin = (begin + attn_workspace_bytes(g) + 255) & ~static_cast<uintptr_t>(255);
+    const size_t mbytes = csr_mask_bytes(g);
+    if (workspace == nullptr || !aligned16(workspace) || begin + workspace_bytes < mbegin + mbytes)
+        return ADASPARK_EWORKSPACE;
+    uint32_t *mask = reinterpret_cast<uint32_t *>(mbegin);
+    if ((rc = adaspark_kv_pack(shape, K, V, workspace, workspace_bytes, stream)) != ADASPARK_OK) return rc;
+    launch_mask_from_csr(g, row_ptr, cube_idx, mask, static_cast<hipStream_t>(stream));
+    if (hipGetLastError() != hipSuccess) return ADASPARK_EHIP;
+    // (what lies behind the mask rows is scratch memory for the key-stationary kernel, as in the mask-fed entry)
+    return attn_packed(shape, Q, workspace, workspace_bytes, mask, true, ADASPARK_SPARSE_AUTO, causal, O, lse, stream,
+                       mbytes);
 }
 
 int adaspark_dense_attn(const adaspark_shape *shape, const void *Q, const void *K, const void *V, int causal, void *O,
@@ -379,8 +421,12 @@ int adaspark_ffn_sparse(const adaspark_shape *shape, const adaspark_ffn_dims *di
     if (rc != ADASPARK_OK) return rc;
     if ((rc = check_ptrs({X, W_gate, W_up, W_down, Y})) != ADASPARK_OK) return rc;
     if (keep != nullptr && !aligned16(keep)) return ADASPARK_EINVAL;
-    if (X == Y) return ADASPARK_EINVAL;
     const Geom g = make_geom(*shape);
+    {   // Y must not overlap X at all: the mean compensation reads X rows of other tokens while Y is written
+        const uintptr_t x0 = reinterpret_cast<uintptr_t>(X), y0 = reinterpret_cast<uintptr_t>(Y);
+        const uintptr_t n = (uintptr_t)g.S * (uintptr_t)dims->d_model * 2u;
+        if (x0 < y0 + n && y0 < x0 + n) return ADASPARK_EINVAL;
+    }
     if (workspace == nullptr || !aligned16(workspace) ||
         workspace_bytes < ffn_workspace(g, dims->d_model, dims->d_ff, nullptr).bytes)
         return ADASPARK_EWORKSPACE;

@@ -608,18 +608,16 @@ static hipError_t launch_bwd_d(const Geom &g, const uint16_t *Q, const uint16_t 
     const int lds_v = 2 * 2 * (2 * TILE + 512), lds_k = 2 * (3 * TILE + 512);
 #define ADASPARK_BWD_LAUNCH(MASKED)                                                                                    \
     do {                                                                                                               \
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bwd_dq_kernel<D, MASKED>),                        \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_q);                                    \
+        static LdsOptIn opted_q, opted_v, opted_k;                                                                     \
+        e = opted_q.ensure(reinterpret_cast<const void *>(&attn_bwd_dq_kernel<D, MASKED>), lds_q);                     \
         if (e != hipSuccess) return e;                                                                                 \
         hipLaunchKernelGGL((attn_bwd_dq_kernel<D, MASKED>), grid_q, dim3(BWD_THREADS), lds_q, st, g, Q, dO, Kn, Vn,    \
                            Kt, csize, w.lse2, w.delta, w.tpcr, sel_mask, dQ);                                          \
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bwd_dkv_kernel<D, 0, MASKED>),                    \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_v);                                    \
+        e = opted_v.ensure(reinterpret_cast<const void *>(&attn_bwd_dkv_kernel<D, 0, MASKED>), lds_v);                 \
         if (e != hipSuccess) return e;                                                                                 \
         hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, 0, MASKED>), grid_k, dim3(BWD_THREADS), lds_v, st, g, K, V, w.Qn,   \
                            w.Qt, w.dOn, w.dOt, w.lse2, w.delta, w.tpcr, csize, w.colmask, dV);                                 \
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bwd_dkv_kernel<D, 1, MASKED>),                    \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_k);                                    \
+        e = opted_k.ensure(reinterpret_cast<const void *>(&attn_bwd_dkv_kernel<D, 1, MASKED>), lds_k);                 \
         if (e != hipSuccess) return e;                                                                                 \
         hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, 1, MASKED>), grid_k, dim3(BWD_THREADS), lds_k, st, g, K, V, w.Qn,   \
                            w.Qt, w.dOn, w.dOt, w.lse2, w.delta, w.tpcr, csize, w.colmask, dK);                                 \

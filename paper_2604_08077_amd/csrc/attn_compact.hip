@@ -439,8 +439,8 @@ static hipError_t launch_compact_d(const Geom &g, const uint16_t *Q, const void 
     const int32_t *csize = reinterpret_cast<const int32_t *>(Vt + half_elems);
     const int nblk_max = (g.G * g.Cmax + C::MMAX - 1) / C::MMAX;
     const dim3 grid((unsigned)((size_t)((g.N * g.Hkv + 7) / 8) * nblk_max * 8));
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_compact_kernel<D>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::BYTES);
+    static LdsOptIn opted;
+    const hipError_t e = opted.ensure(reinterpret_cast<const void *>(&attn_compact_kernel<D>), C::BYTES);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((attn_compact_kernel<D>), grid, dim3(C::THREADS), C::BYTES, st, g, Q, Kp, Vt, csize, sel_mask,
                        mode_flag, my_mode, kv_modes, O, lse);

@@ -491,7 +491,9 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_pairs_kernel(
         auto softmax_step = [&](int t) __attribute__((always_inline)) {
             const int key0 = KEY_TILE * t;
             const bool need_mask = OWN || (key0 + KEY_TILE > jsize);
-            softmax_tile_folded<D, NS>(sacc, pf, oacc, m_run, l_run, fresh, ids.lim, key0, need_mask, q4);
+            // (after a step's first tile every row has its reference point: fresh is false for all)
+            if (need_mask || !softmax_tile_fast<NS>(sacc, pf, t > 0))
+                softmax_tile_folded<D, NS>(sacc, pf, oacc, m_run, l_run, fresh, ids.lim, key0, need_mask, q4);
 #pragma unroll
             for (int s = 0; s < NS; ++s) sinit[s] = f32x4{-m_run[s], -m_run[s], -m_run[s], -m_run[s]};
         };
@@ -545,8 +547,13 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_pairs_kernel(
     };
 
     // This wavefront's steps are wave, wave + WAVES, ...; even ones use buffer set A, odd ones set B.  Past the end
-    // a step index is clamped to the last step: that step is then done again (by this wavefront too), writing the
-    // same records with the same values -- everything in the loop stays unconditional.
+    // a step index is clamped to the last step: that step is then done again -- by this wavefront, and possibly by
+    // other wavefronts of the workgroup at the same time -- and every such repetition writes the same records.
+    // The duplicates are benign because they are bit-identical: a step's result depends only on its rows' Q, the
+    // cube's tiles and a fixed instruction sequence (no atomics, no data-dependent order), so concurrent writers
+    // store the same bytes to the same addresses.  Everything in the loop stays unconditional (a guarded store
+    // would make the compiler merge its wait counts with the operand loads').  The tests that force this kernel
+    // run geometries whose step counts are not multiples of the wavefront count, so the repeated step is covered.
     if (wave >= nsteps) return;
     const int last = nsteps - 1;
     RowIds ids_a{}, ids_b{};
@@ -625,7 +632,7 @@ __global__ __launch_bounds__(256) void pairs_merge_kernel(long long R, const int
 }
 
 // Number of candidate (row, cube) pairs: every row of cube i has i preceding cubes.
-static unsigned long long candidate_pairs(const Geom &g)
+unsigned long long candidate_pairs(const Geom &g)
 {
     unsigned long long c = 0;
     for (int i = 0; i < g.N; ++i) c += (unsigned long long)i * (unsigned long long)cube_box(g, i).size();
@@ -642,11 +649,10 @@ static hipError_t launch_pairs_d(const Geom &g, const uint16_t *Q, const void *p
     const uint16_t *Vt = Kp + half_elems;
     const int32_t *csize = reinterpret_cast<const int32_t *>(Vt + half_elems);
     const long long R = (long long)g.S * g.Hq;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_pairs_kernel<D, false>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::BYTES);
+    static LdsOptIn opted_lists, opted_own;  // one per kernel instantiation
+    hipError_t e = opted_lists.ensure(reinterpret_cast<const void *>(&attn_pairs_kernel<D, false>), C::BYTES);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_pairs_kernel<D, true>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, C::BYTES);
+    e = opted_own.ensure(reinterpret_cast<const void *>(&attn_pairs_kernel<D, true>), C::BYTES);
     if (e != hipSuccess) return e;
     // Chunks of all lists together: at most one partly filled chunk per list, and no more entries than records fit
     // (or than there are candidate pairs).  Workgroups past the actual number of chunks return at once.

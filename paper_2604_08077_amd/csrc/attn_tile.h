@@ -192,7 +192,11 @@ __device__ __forceinline__ bf16x8 prescale_q(bf16x8 q, float c2)
 // the exact maximum: it moves up to a tile's maximum only when that exceeds it by more than SOFTMAX_LAZY (then O
 // and l are rescaled), and to the first tile's maximum whatever it is (fresh rows).  Probabilities are at most
 // 2^SOFTMAX_LAZY; the final O / l does not depend on the reference.
-constexpr float SOFTMAX_LAZY = 4.0f;
+constexpr float SOFTMAX_LAZY = 1.0f;
+// When the reference moves it is put SOFTMAX_HEADROOM above the tile's maximum, so that the scores may rise by
+// SOFTMAX_LAZY + SOFTMAX_HEADROOM before it has to move again; probabilities then lie below 2^-SOFTMAX_HEADROOM
+// most of the time, which the normalisation cancels.
+constexpr float SOFTMAX_HEADROOM = 8.0f;
 template <int D, int NS>
 __device__ __forceinline__ void softmax_tile_folded(f32x4 (&sacc)[NS][4], bf16x8 (&pf)[NS][2], f32x4 (&oacc)[NS][D / 16],
                                                     float (&m_run)[NS], f32x4 (&l_run)[NS], bool (&fresh)[NS],
@@ -234,13 +238,13 @@ __device__ __forceinline__ void softmax_tile_folded(f32x4 (&sacc)[NS][4], bf16x8
     unsigned int any = 0u;
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-        grow[s] = (mx[s] > SOFTMAX_LAZY) | (fresh[s] & (mx[s] > -INFINITY));
+        grow[s] = (mx[s] >= SOFTMAX_LAZY) | (fresh[s] & (mx[s] > -INFINITY));
         any |= grow[s] ? 1u : 0u;
     }
     if (__ballot(any != 0u) != 0ull) {  // rare after a row's first tiles: move the reference, rescale O and l
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            const float d = grow[s] ? mx[s] : 0.f;
+            const float d = grow[s] ? mx[s] + SOFTMAX_HEADROOM : 0.f;
             const float alpha = (grow[s] && !fresh[s]) ? __builtin_amdgcn_exp2f(-d) : 1.f;  // a fresh row has O = l = 0
             m_run[s] += d;
             fresh[s] = fresh[s] && !grow[s];
@@ -260,6 +264,37 @@ __device__ __forceinline__ void softmax_tile_folded(f32x4 (&sacc)[NS][4], bf16x8
 #pragma unroll
             for (int s = 0; s < NS; ++s)
                 pf[s][kg >> 1][4 * (kg & 1) + v] = (__bf16)__builtin_amdgcn_exp2f(sacc[s][kg][v]);
+}
+
+// The common case of softmax_tile_folded without its row maximum.  The probabilities are taken as exp2(s') straight
+// away, rounded to bf16, and only then is the tile checked: a probability of 2 or more -- a score at least
+// SOFTMAX_LAZY = 1 above the row's reference -- has the top exponent bit of its bf16 pattern set, and no smaller
+// one has, so the OR of the tile's probability words tells whether any row needs its reference moved.  If so
+// (rare after a row's first tiles), or if the tile needs masking or some row of the wavefront has no reference yet
+// (`settled` false), the function returns false with nothing but pf changed, and the caller runs
+// softmax_tile_folded on the untouched scores.  Vector instructions are not hidden behind another wavefront's
+// MFMAs on this chip (only the exponentials are), so the maximum's 14 instructions per slab and tile, the lane
+// exchanges and the compare are time saved in full.
+template <int NS>
+__device__ __forceinline__ bool softmax_tile_fast(const f32x4 (&sacc)[NS][4], bf16x8 (&pf)[NS][2], bool settled)
+{
+    if (!settled) return false;
+#pragma unroll
+    for (int kg = 0; kg < 4; ++kg)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+#pragma unroll
+            for (int s = 0; s < NS; ++s)
+                pf[s][kg >> 1][4 * (kg & 1) + v] = (__bf16)__builtin_amdgcn_exp2f(sacc[s][kg][v]);
+    uint32_t big = 0u;
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl) {
+            const u32x4 w = __builtin_bit_cast(u32x4, pf[s][sl]);
+            big |= (w[0] | w[1]) | (w[2] | w[3]);
+        }
+    return __ballot((big & 0x40004000u) != 0u) == 0ull;
 }
 
 // The MFMA phase of a wavefront in the counter-phase kernel: P.V of one tile, then S of the next, as one stream

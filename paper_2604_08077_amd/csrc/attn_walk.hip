@@ -319,11 +319,18 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
 
     f32x4 sacc[NS][4];
     bf16x8 pf[NS][2];
+    bool settled = false;  // wave-uniform: no row of the wavefront is fresh any more (softmax_tile_fast may be tried)
     auto softmax_step = [&]() __attribute__((always_inline)) {
         const bool own = (cc.j == i);
         const int key0 = KEY_TILE * cc.t;
         const bool need_mask = (key0 + KEY_TILE > jsize) || (own && g.causal && key0 + KEY_TILE - 1 > rank_lo);
-        softmax_tile_folded<D, NS>(sacc, pf, oacc, m_run, l_run, fresh, lim, key0, need_mask, q4);
+        if (need_mask || !softmax_tile_fast<NS>(sacc, pf, settled)) {
+            softmax_tile_folded<D, NS>(sacc, pf, oacc, m_run, l_run, fresh, lim, key0, need_mask, q4);
+            bool open = false;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) open = open || fresh[s];
+            settled = __ballot(open) == 0ull;  // every row of the wavefront has a reference point by now
+        }
         const int j0 = cc.j;
         advance(cc);
         if (cc.j != j0) enter_cube(cc.j);
@@ -533,13 +540,16 @@ static hipError_t launch_walk(const Geom &g, const uint16_t *Q, const void *pack
     const int32_t *csize = reinterpret_cast<const int32_t *>(Vt + half_elems);
     const int nblk_max = (g.G * g.Cmax + C::MMAX - 1) / C::MMAX;
     const dim3 grid((unsigned)((size_t)((g.N * g.Hkv + 7) / 8) * nblk_max * 8));
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_walk_kernel<D, MASKED>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::BYTES);
+    static LdsOptIn opted;  // one per kernel instantiation
+    const hipError_t e = opted.ensure(reinterpret_cast<const void *>(&attn_walk_kernel<D, MASKED>), C::BYTES);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((attn_walk_kernel<D, MASKED>), grid, dim3(C::THREADS), C::BYTES, st, g, Q, Kp, Vt, csize,
                        sel_mask, mode_flag, my_mode, kv_modes, O, lse);
     return hipGetLastError();
 }
+
+// Below this many candidate (row, cube) pairs the automatic choice is the masked walk outright (see launch_attn_d).
+constexpr unsigned long long AUTO_MIN_CANDIDATE_PAIRS = 2ull << 20;
 
 // Measured on MI355X (65,536 tokens, 28/4 heads, head_dim 128, rows selecting independently): the key-stationary
 // kernel is the faster one below this share of selected candidate cubes (break-even at 44 %).
@@ -554,6 +564,11 @@ static hipError_t launch_attn_d(const Geom &g, const uint16_t *Q, void *packed, 
     if (sparse_kernel == ADASPARK_SPARSE_COMPACT && g.causal)
         return launch_attn_compact(g, Q, packed, sel_mask, nullptr, 0, 0, O, lse, st);
     if (sparse_kernel == ADASPARK_SPARSE_MASKED || !g.causal)  // non-causal mode: the masked walk is the one kernel
+        return launch_walk<D, true>(g, Q, packed, sel_mask, nullptr, 0, 0, O, lse, st);
+    // Small problems (8,192 rows of 64 cubes, say) are bound by the latency from one dependent kernel to the next:
+    // the dozen kernels that measure the selection and prepare the other paths would cost more than any choice
+    // among them can win back.  The masked walk is the one kernel then.
+    if (sparse_kernel == ADASPARK_SPARSE_AUTO && candidate_pairs(g) < AUTO_MIN_CANDIDATE_PAIRS)
         return launch_walk<D, true>(g, Q, packed, sel_mask, nullptr, 0, 0, O, lse, st);
     // Automatic (or the key-stationary kernel asked for): the choice is made on the device, every candidate kernel
     // is enqueued, and the workgroups of those not chosen return at once.  First the selected share from a sample

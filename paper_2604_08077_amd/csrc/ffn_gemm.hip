@@ -167,8 +167,8 @@ template <bool GATED>
 hipError_t launch_gemm(const uint16_t *A, const int32_t *gather, const uint16_t *W0, const uint16_t *W1, int K,
                        int n_tiles, int m_tiles, const int32_t *n_rows, void *out, int ldo, hipStream_t st)
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&ffn_gemm_kernel<GATED>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
+    static LdsOptIn opted;  // one per instantiation
+    const hipError_t e = opted.ensure(reinterpret_cast<const void *>(&ffn_gemm_kernel<GATED>), GEMM_LDS);
     if (e != hipSuccess) return e;
     const long long total = (long long)((m_tiles + 3) / 4 * 4) * n_tiles;
     const long long blocks32 = ((total + 31) / 32 + 7) / 8 * 8;  // whole rounds over the eight XCDs

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/adaspark.h"
 
 namespace adaspark {
@@ -113,6 +115,11 @@ __device__ inline uint16_t float_to_bf16_bits(float f)
 // Kernel launchers (defined one per .hip file).  All return hipError_t from the launch.
 hipError_t launch_cube_pool(const Geom &g, const uint16_t *K, float *kbar, hipStream_t st);
 size_t select_workspace_bytes(const Geom &g);
+// byte offset of the call's int32 status word inside that workspace (ADASPARK_OK or ADASPARK_ECAPACITY, on the device)
+size_t select_status_offset(const Geom &g);
+// sel_mask rows from a compact list (row_ptr, cube_idx as launch_cube_select writes them)
+void launch_mask_from_csr(const Geom &g, const int64_t *row_ptr, const int32_t *cube_idx, uint32_t *sel_mask,
+                          hipStream_t st);
 // top_k < 0: Top-p selection with threshold top_p; top_k >= 0: fixed Top-K selection (top_p ignored).
 hipError_t launch_cube_select(const Geom &g, const uint16_t *Q, const float *kbar, float top_p, int top_k,
                               uint32_t *sel_mask, int32_t *sel_count, int64_t *row_ptr, int32_t *cube_idx,
@@ -140,6 +147,29 @@ hipError_t launch_kv_pack(const Geom &g, const uint16_t *K, const uint16_t *V, v
 constexpr int FLAG_MODE = 0, FLAG_ESTIMATE = 1, FLAG_ACTIVE = 2, FLAG_UNION = 3, FLAG_KV = 4;
 constexpr int PAIRS_MAX_KV_HEADS = 64;
 constexpr int FLAG_BLOCK_BYTES = 512;
+
+// A kernel that uses more than 64 KB of dynamic LDS has to be allowed to, once per device, before its first launch.
+// One object per kernel: ensure() asks the runtime only the first time a device (or a larger size) comes by, so a
+// launch costs no runtime call beyond itself afterwards.  Thread-safe without a lock: the worst a race does is ask
+// twice.
+struct LdsOptIn {
+    static constexpr int MAX_DEVICES = 64;
+    std::atomic<int> bytes_set[MAX_DEVICES] = {};
+    hipError_t ensure(const void *kernel, int bytes)
+    {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        const bool tracked = dev >= 0 && dev < MAX_DEVICES;
+        if (tracked && bytes_set[dev].load(std::memory_order_acquire) >= bytes) return hipSuccess;
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (e == hipSuccess && tracked) bytes_set[dev].store(bytes, std::memory_order_release);
+        return e;
+    }
+};
+
+// Number of candidate (row, cube) pairs of a causal selection: every row of cube i has i preceding cubes.
+unsigned long long candidate_pairs(const Geom &g);
 
 // sel_mask == nullptr: dense (every preceding cube attended); otherwise sparse_kernel is an adaspark_sparse_kernel.
 // The automatic choice writes a flag into the last 16 bytes of the packed workspace.  scratch (256-byte aligned, may

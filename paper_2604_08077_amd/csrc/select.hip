@@ -34,8 +34,11 @@ typedef unsigned int sel_u32x4 __attribute__((ext_vector_type(4)));
 // kbar [N][Hkv][D] fp32 -> ksplit [Hkv][NG][D/32][3][64 lanes][8] bf16: the A operands of
 // mfma_f32_16x16x32_bf16 for cube group cg (cubes 16cg..16cg+15), k-step c, term (hi, mid, lo): lane (n16, q4)
 // holds cube 16cg + n16, head-dim elements 32c + 8*q4 .. +7.  Cubes beyond N are zero.
-__global__ void kbar_split_kernel(Geom g, int NG, const float *__restrict__ kbar, uint16_t *__restrict__ ksplit)
+__global__ void kbar_split_kernel(Geom g, int NG, const float *__restrict__ kbar, uint16_t *__restrict__ ksplit,
+                                  int32_t *__restrict__ status)
 {
+    // the call's status word starts out as "ok"; the compact list's kernel, which runs later, may change it
+    if (blockIdx.x == 0 && threadIdx.x == 0) *status = (int32_t)ADASPARK_OK;
     const int KS = g.D / 32;
     const size_t total = (size_t)g.Hkv * NG * KS * 64;
     for (size_t x = blockIdx.x * (size_t)blockDim.x + threadIdx.x; x < total; x += (size_t)gridDim.x * blockDim.x) {
@@ -840,10 +843,14 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_write_kernel(const int32_t 
     }
 }
 
+// status (device): ADASPARK_ECAPACITY if the rows' lists do not fit `capacity` entries (the overflowing entries are
+// dropped), else ADASPARK_OK.
 __global__ void csr_fill_kernel(Geom g, long long R, const uint32_t *__restrict__ sel_mask,
-                                const int64_t *__restrict__ row_ptr, int32_t *__restrict__ cube_idx, long long capacity)
+                                const int64_t *__restrict__ row_ptr, int32_t *__restrict__ cube_idx, long long capacity,
+                                int32_t *__restrict__ status)
 {
     const long long row = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (row == 0) *status = row_ptr[R] > capacity ? (int32_t)ADASPARK_ECAPACITY : (int32_t)ADASPARK_OK;
     if (row >= R) return;
     long long out = row_ptr[row];
     const uint32_t *mrow = sel_mask + (size_t)row * g.words;
@@ -858,6 +865,37 @@ __global__ void csr_fill_kernel(Geom g, long long R, const uint32_t *__restrict_
     }
 }
 
+// The compact list back into mask rows (the form the attention kernels read): row r gets the bits of
+// cube_idx[row_ptr[r] .. row_ptr[r+1]).  Entries that name no cube are ignored.
+__global__ void mask_from_csr_kernel(Geom g, long long R, const int64_t *__restrict__ row_ptr,
+                                     const int32_t *__restrict__ cube_idx, uint32_t *__restrict__ sel_mask)
+{
+    const long long row = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (row >= R) return;
+    uint32_t *mrow = sel_mask + (size_t)row * g.words;
+    const long long p0 = row_ptr[row], p1 = row_ptr[row + 1];
+    // the list of a row is ascending: one pass, a word at a time
+    long long p = p0;
+    for (int w = 0; w < g.words; ++w) {
+        uint32_t bits = 0u;
+        while (p < p1) {
+            const int c = cube_idx[p];
+            if (c >= 32 * (w + 1)) break;
+            if (c >= 32 * w && c < g.N) bits |= 1u << (c & 31);
+            ++p;
+        }
+        mrow[w] = bits;
+    }
+}
+
+void launch_mask_from_csr(const Geom &g, const int64_t *row_ptr, const int32_t *cube_idx, uint32_t *sel_mask,
+                          hipStream_t st)
+{
+    const long long R = (long long)g.S * g.Hq;
+    hipLaunchKernelGGL(mask_from_csr_kernel, dim3((unsigned)((R + 255) / 256)), dim3(256), 0, st, g, R, row_ptr, cube_idx,
+                       sel_mask);
+}
+
 static int select_groups(const Geom &g) { return (g.N + 15) / 16; }
 static size_t select_ksplit_bytes(const Geom &g)
 {
@@ -865,11 +903,16 @@ static size_t select_ksplit_bytes(const Geom &g)
 }
 static long long scan_tiles(const Geom &g) { return ((long long)g.S * g.Hq + SCAN_TILE - 1) / SCAN_TILE; }
 
-size_t select_workspace_bytes(const Geom &g)
+size_t select_status_offset(const Geom &g)
 {
     // the bf16 split of the mean keys, then the scan's tile sums
     const size_t tiles = (size_t)scan_tiles(g) * sizeof(long long);
     return select_ksplit_bytes(g) + ((tiles + 255) / 256) * 256;
+}
+
+size_t select_workspace_bytes(const Geom &g)
+{
+    return select_status_offset(g) + 256;  // and the status word (in a block of its own)
 }
 
 template <int D, bool TOPK>
@@ -923,7 +966,9 @@ hipError_t launch_cube_select(const Geom &g, const uint16_t *Q, const float *kba
     uint16_t *ksplit = reinterpret_cast<uint16_t *>(ws);
     const int NG = select_groups(g);
     const size_t total = (size_t)g.Hkv * NG * (g.D / 32) * 64;
-    hipLaunchKernelGGL(kbar_split_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, g, NG, kbar, ksplit);
+    int32_t *status = reinterpret_cast<int32_t *>(reinterpret_cast<char *>(ws) + select_status_offset(g));
+    hipLaunchKernelGGL(kbar_split_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, g, NG, kbar, ksplit,
+                       status);
     if (top_k >= 0) {
         if (g.D == 64) launch_select_d<64, true>(g, NG, Q, ksplit, top_p, top_k, sel_mask, sel_count, st);
         else launch_select_d<128, true>(g, NG, Q, ksplit, top_p, top_k, sel_mask, sel_count, st);
@@ -935,7 +980,7 @@ hipError_t launch_cube_select(const Geom &g, const uint16_t *Q, const float *kba
     if (row_ptr != nullptr) {
         launch_exclusive_scan(sel_count, R, tile_sum, row_ptr, st);
         hipLaunchKernelGGL(csr_fill_kernel, dim3((unsigned)((R + 255) / 256)), dim3(256), 0, st, g, R, sel_mask, row_ptr,
-                           cube_idx, (long long)capacity);
+                           cube_idx, (long long)capacity, status);
     }
     return hipGetLastError();
 }

@@ -102,6 +102,9 @@ SAMPLED_WORKLOADS = {
     "M_text16k": _wl("M_text16k", 20, (64, 16, 16), (4, 8, 8), 28, 4, 128, 0.9, 1.0, text=1000),
     # a 300-token system prompt, an 8,192-token video, a 500-token question
     "M_lead8k": _wl("M_lead8k", 23, (32, 16, 16), (4, 8, 8), 28, 4, 128, 0.9, 1.0, text=500, lead=300),
+    # a slice of the quarter-million-token geometry: 300 cubes of 256 tokens (more than one wavefront's 256 candidate
+    # cubes per row), the same heads and key statistics; small enough for every sparse kernel's scratch to fit a test
+    "M_c4slice": _wl("M_c4slice", 26, (300, 16, 16), (4, 8, 8), 28, 4, 128, 0.5, 0.5),
     # 256-token cubes (four key tiles each, the last cube half as long), a GQA group of seven: small enough for the
     # backward oracle to take every row
     "M_bwd256": _wl("M_bwd256", 24, (6, 16, 16), (4, 8, 8), 7, 1, 128, 0.8, 1.0),

@@ -46,7 +46,7 @@ def test_num_cubes_and_workspace_sizes(lib):
 
 def test_status_strings(lib):
     assert binding.status_string(0) == "ok"
-    for code in (-1, -2, -3, -4):
+    for code in (-1, -2, -3, -4, -5):
         assert binding.status_string(code) not in ("ok", "unknown status")
     assert binding.status_string(-99) == "unknown status"
 
@@ -146,10 +146,13 @@ def test_ffn_arguments_are_validated_before_launch(lib):
         ctypes.byref(cs), dims(256, 384), x, ctypes.c_float(p), ctypes.c_float(eps), keep, None, None, None)
     assert sel(1.5, 1e-6) == -1 and sel(float("nan"), 1e-6) == -1 and sel(0.7, -1.0) == -1
     assert sel(0.7, 1e-6, x=None) == -1 and sel(0.7, 1e-6, keep=ctypes.c_void_p(4097)) == -1
-    run = lambda ws, nbytes, x=ok_ptr, y=ctypes.c_void_p(8192): lib.adaspark_ffn_sparse(
+    xbytes = tokens * 256 * 2
+    run = lambda ws, nbytes, x=ok_ptr, y=ctypes.c_void_p(4096 + xbytes): lib.adaspark_ffn_sparse(
         ctypes.byref(cs), dims(256, 384), x, ok_ptr, ok_ptr, ok_ptr, None, y, ws, nbytes, None)
-    assert run(None, 1 << 30) == -3 and run(ok_ptr, 64) == -3
+    assert run(None, 1 << 30) == -3 and run(ok_ptr, 64) == -3                # Y right behind X: no overlap
     assert run(ok_ptr, 1 << 30, y=ok_ptr) == -1                              # Y aliases X
+    assert run(ok_ptr, 1 << 30, y=ctypes.c_void_p(4096 + xbytes - 16)) == -1  # Y starts inside X
+    assert run(ok_ptr, 1 << 30, x=ctypes.c_void_p(4096 + xbytes), y=ctypes.c_void_p(4096 + 512)) == -1  # X starts inside Y
     assert run(ok_ptr, 1 << 30, x=None) == -1
 
 
@@ -191,3 +194,25 @@ def test_allocation_free_selection_refuses_what_its_array_cannot_hold(lib):
     assert call(_raw_shape(head_dim=96)._c(), 0.5) == -2
     header = open(os.path.join(ROOT, "include", "adaspark.h")).read()
     assert "#define ADASPARK_NOALLOC_SCRATCH_BYTES (4u << 20)" in header and binding.NOALLOC_SCRATCH_BYTES == 4 << 20
+
+
+def test_compact_list_entries_validate_before_launch(lib):
+    cs = _raw_shape()._c()
+    ok_ptr = ctypes.c_void_p(4096)
+    off = ctypes.c_size_t(0)
+    assert lib.adaspark_select_status_offset(ctypes.byref(cs), ctypes.byref(off)) == 0
+    need = ctypes.c_size_t(0)
+    assert lib.adaspark_workspace_bytes(ctypes.byref(cs), binding.CALL_CUBE_SELECT, ctypes.byref(need)) == 0
+    assert off.value % 256 == 0 and off.value + 4 <= need.value
+    assert lib.adaspark_select_status_offset(ctypes.byref(cs), None) == -1
+    csr = lambda rp, ci, ws, n: lib.adaspark_sparse_attn_csr(ctypes.byref(cs), ok_ptr, ok_ptr, ok_ptr, rp, ci, 1, ok_ptr,
+                                                             None, ws, n, None)
+    assert csr(None, ok_ptr, ok_ptr, 1 << 30) == -1
+    assert csr(ok_ptr, None, ok_ptr, 1 << 30) == -1
+    assert csr(ok_ptr, ok_ptr, None, 0) == -3
+    plain, with_mask = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    assert lib.adaspark_workspace_bytes(ctypes.byref(cs), binding.CALL_SPARSE_ATTN, ctypes.byref(plain)) == 0
+    assert lib.adaspark_workspace_bytes(ctypes.byref(cs), binding.CALL_SPARSE_ATTN_CSR, ctypes.byref(with_mask)) == 0
+    rows, words = 4 * 8 * 8 * 4, 1
+    assert with_mask.value >= plain.value + rows * words * 4
+    assert csr(ok_ptr, ok_ptr, ok_ptr, plain.value) == -3           # room for the K/V copy but not for the mask rows

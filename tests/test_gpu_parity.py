@@ -204,13 +204,30 @@ def test_value_indicator_recovers_attended_set(B, oracle):
     assert np.abs(out.sum(1) - 1.0).max() < 2e-2
 
 
-def sampled_case(B, oracle, w, p_list, n_rows, check_dense=True, query_corr=0.0):
+def stratified_rows(oracle, osh, w, n_random):
+    """Rows that cover the corners of the launch configuration -- the first, second, middle, last-but-one and last
+    cube; in each the first, second, middle and last rank; every query head of each such token -- plus a seeded
+    uniform sample of n_random rows."""
+    cube_of, rank_of, size_of, _ = oracle.cube_map(osh)
+    N = size_of.size
+    picks = []
+    for c in sorted({0, 1, N // 2, N - 2, N - 1} & set(range(N))):
+        toks = np.nonzero(cube_of == c)[0]
+        by_rank = toks[np.argsort(rank_of[toks])]
+        for r in sorted({0, 1, len(by_rank) // 2, len(by_rank) - 1} & set(range(len(by_rank)))):
+            picks.extend(int(by_rank[r]) * w.Hq + a for a in range(w.Hq))
+    return np.unique(np.concatenate([np.asarray(picks, np.int64), synth.sample_rows(w, n_random)]))
+
+
+def sampled_case(B, oracle, w, p_list, n_rows, check_dense=True, query_corr=0.0, dense_rows=96, slow_kernels=True):
     print(f"case {w.name} grid={w.grid} cube={w.cube} heads={w.Hq}/{w.Hkv} D={w.D} sampled rows={n_rows} "
           f"query_corr={query_corr}", flush=True)
     sh, osh = B.Shape.of(w), oshape(oracle, w)
     Q, K, V = synth.generate(w, query_corr=query_corr)
     Qg, Kg, Vg = Q.cuda(), K.cuda(), V.cuda()
-    rows = synth.sample_rows(w, n_rows)
+    rows = stratified_rows(oracle, osh, w, n_rows)
+    print(f"[{w.name}] {len(rows)} rows compared (corners of the grid and of the cubes, every head, and a uniform sample)",
+          flush=True)
     kbar_ref = oracle.cube_pool(osh, K)
     kbar = B.cube_pool(sh, Kg)
     torch.cuda.synchronize()
@@ -237,7 +254,7 @@ def sampled_case(B, oracle, w, p_list, n_rows, check_dense=True, query_corr=0.0)
         got = rows_of(O, rows, w)
         check_outputs(f"{w.name} p={p} pipeline(sampled)", got[same], ref_out[same])
         # the sparse kernels, forced (the call above let the library choose)
-        for kern in (B.SPARSE_COMPACT, B.SPARSE_MASKED):
+        for kern in ((B.SPARSE_COMPACT, B.SPARSE_MASKED) if slow_kernels else (B.SPARSE_MASKED,)):
             Ok = B.sparse_attn_packed(sh, Qg, ws_att, mask, kernel=kern)
             torch.cuda.synchronize()
             check_outputs(f"{w.name} p={p} kernel {kern}(sampled)", rows_of(Ok, rows, w)[same], ref_out[same])
@@ -255,7 +272,7 @@ def sampled_case(B, oracle, w, p_list, n_rows, check_dense=True, query_corr=0.0)
     if check_dense:
         Od = B.dense_attn(sh, Qg, Kg, Vg, workspace=ws_att)
         torch.cuda.synchronize()
-        drows = rows[:: max(1, len(rows) // 96)]
+        drows = rows[:: max(1, len(rows) // dense_rows)]
         check_outputs(f"{w.name} dense(sampled)", rows_of(Od, drows, w), oracle.dense_attn(osh, Q, K, V, rows=drows))
 
 
@@ -362,11 +379,41 @@ def test_c5_entropy_stress_sampled(B, oracle):
 
 
 def test_c3_p_sweep_sampled(B, oracle):
-    sampled_case(B, oracle, synth.WORKLOADS["C3"], (0.5, 0.7, 0.9, 0.99), 384)
+    sampled_case(B, oracle, synth.WORKLOADS["C3"], (0.5, 0.7, 0.9, 0.99), 2048)
 
 
 def test_c4_sampled(B, oracle):
-    sampled_case(B, oracle, synth.WORKLOADS["C4"], (0.9,), 192, check_dense=False)
+    """262,144 tokens in 1,024 cubes: the wide selection kernel, the masked walk and the dense entry (a few dozen
+    rows of it: a late row attends a quarter of a million keys)."""
+    sampled_case(B, oracle, synth.WORKLOADS["C4"], (0.9,), 768, check_dense=True, dense_rows=48, slow_kernels=False)
+
+
+def test_many_large_cubes_through_every_kernel(B, oracle):
+    """300 cubes of 256 tokens, 28/4 heads -- a slice of the quarter-million-token geometry: rows with more than 256
+    candidate cubes go through the wide selection kernel, and the selection is small enough (p = 0.5) for the
+    key-stationary kernel's records to fit a test buffer, so that kernel runs on work lists of more than 256 key cubes
+    of full size; the compacting and masked kernels and the dense entry on the same rows."""
+    w = synth.SAMPLED_WORKLOADS["M_c4slice"]
+    assert B.num_cubes(B.Shape.of(w)) == 300
+    sampled_case(B, oracle, w, (0.5,), 1024, check_dense=True, dense_rows=48)
+
+
+@pytest.mark.parametrize("name,p", [("C3", 0.9), ("C5", 0.9)])
+def test_selection_every_row(B, oracle, name, p):
+    """Masks and counts of every row of the 65,536-token configuration and of the ragged entropy-stress one against
+    the oracle (the selection oracle is cheap next to the attention oracle: attention outputs stay sampled)."""
+    w = synth.WORKLOADS[name]
+    print(f"case {w.name} selection of every row, p={p}", flush=True)
+    sh, osh = B.Shape.of(w), oshape(oracle, w)
+    Q, K, _ = synth.generate(w)
+    Qg, Kg = Q.cuda(), K.cuda()
+    kbar_ref = oracle.cube_pool(osh, K)
+    kbar = B.cube_pool(sh, Kg)
+    p32 = float(np.float32(p))
+    mask, count, _, _ = B.cube_select(sh, Qg, kbar, p32)
+    torch.cuda.synchronize()
+    ref_mask, ref_count, near = oracle.cube_select(osh, Q, kbar_ref, p32)
+    check_selection(f"{w.name} p={p} every row", to_u32(mask), count.cpu().numpy(), ref_mask, ref_count, near)
 
 
 @pytest.mark.parametrize("name", ["T_gqa128", "T_manycubes", "T_cubes280", "T_cubes1100", "T_text64", "T_lead64",
@@ -730,3 +777,38 @@ def test_every_row(B, oracle, name, p):
     print(f"[{name} p={p} every row] rows={R} near-boundary(exempt)={n_near} differing={n_differ} (all exempt) "
           f"max-abs={worst:.3e} mean-abs={mean:.3e}", flush=True)
     assert worst <= MAX_ABS and mean <= MEAN_ABS
+
+
+@pytest.mark.parametrize("name", ["T_ragged", "T_lead64", "T_cubes280", "C2"])
+def test_attention_from_the_compact_list(B, oracle, name):
+    """The compact list that adaspark_cube_select writes, fed to adaspark_sparse_attn_csr: bit-identical output and
+    log-sum-exp to the mask-fed entry.  And the list's overflow signal: the device status word is ADASPARK_OK when
+    the capacity suffices and ADASPARK_ECAPACITY when it does not (mask and counts are complete either way)."""
+    w = synth.TEST_WORKLOADS.get(name) or synth.WORKLOADS[name]
+    print(f"case {w.name} attention from the compact list", flush=True)
+    sh = B.Shape.of(w)
+    Q, K, V = synth.generate(w)
+    Qg, Kg, Vg = Q.cuda(), K.cuda(), V.cuda()
+    kbar = B.cube_pool(sh, Kg)
+    p32 = float(np.float32(w.top_p[0]))
+    ws = B.alloc_workspace(sh, B.CALL_CUBE_SELECT)
+    mask, count, _, _ = B.cube_select(sh, Qg, kbar, p32, workspace=ws)
+    assert B.select_status(sh, ws) == 0                      # no list asked for: nothing can overflow
+    total = int(count.sum().item())
+    m2, c2, row_ptr, cube_idx = B.cube_select(sh, Qg, kbar, p32, csr_capacity=total, workspace=ws)
+    assert B.select_status(sh, ws) == 0 and int(row_ptr[-1].item()) == total
+    m3, c3, rp3, ci3 = B.cube_select(sh, Qg, kbar, p32, csr_capacity=max(total - 1, 0), workspace=ws)
+    assert B.select_status(sh, ws) == (B.ECAPACITY if total > 0 else 0)
+    assert torch.equal(m3, mask) and torch.equal(c3, count) and torch.equal(rp3, row_ptr)
+    assert torch.equal(ci3[: max(total - 1, 0)], cube_idx[: max(total - 1, 0)])
+    B.cube_select(sh, Qg, kbar, p32, csr_capacity=total, workspace=ws)
+    assert B.select_status(sh, ws) == 0                      # the word is rewritten by every call
+    O1, l1 = B.sparse_attn(sh, Qg, Kg, Vg, mask, return_lse=True)
+    O2, l2 = B.sparse_attn_csr(sh, Qg, Kg, Vg, row_ptr, cube_idx, return_lse=True)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O2) and torch.equal(l1, l2)
+    # and against the oracle on a sample of rows, for a result that does not lean on the mask-fed entry
+    osh = oshape(oracle, w)
+    rows = synth.sample_rows(w, 128)
+    ref_out, _ = oracle.sparse_attn(osh, Q, K, V, to_u32(mask)[rows], rows=rows)
+    check_outputs(f"{w.name} attention from the list", rows_of(O2, rows, w), ref_out)
