@@ -288,10 +288,17 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
         for (int e = 0; e < DT; ++e) oacc[s][e] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
     bool rsel[NS];
-    uint32_t mword[NS];
+    // The rows' mask words: the one in use, and the next one, fetched when the walk enters a word so that it has
+    // long arrived when the walk gets there 32 cubes later (read and used at the same cube boundary, every
+    // wavefront stood still for a memory latency once per 32 cubes).
+    uint32_t mword[NS], mword_ahead[NS];
     int mword_idx = -1;
 #pragma unroll
-    for (int s = 0; s < NS; ++s) { rsel[s] = true; mword[s] = 0; }
+    for (int s = 0; s < NS; ++s) { rsel[s] = true; mword[s] = 0; mword_ahead[s] = 0; }
+    if (MASKED) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) mword_ahead[s] = sel_mask[(size_t)rowid[lr[s]] * g.words];
+    }
     int jsize = 0;
     // per-cube constants of the softmax: key limits of every row, and (MASKED) whether the row attends the cube
     auto enter_cube = [&](int j) __attribute__((always_inline)) {
@@ -305,9 +312,15 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
                 for (int s = 0; s < NS; ++s) rsel[s] = true;
             } else {
                 if ((j >> 5) != mword_idx) {
+                    const bool ahead = (j >> 5) == mword_idx + 1;  // (the walk ascends; words can be skipped)
                     mword_idx = j >> 5;
+                    const int nxt = min(mword_idx + 1, g.words - 1);
 #pragma unroll
-                    for (int s = 0; s < NS; ++s) mword[s] = sel_mask[(size_t)rowid[lr[s]] * g.words + mword_idx];
+                    for (int s = 0; s < NS; ++s) {
+                        const uint32_t *mr = sel_mask + (size_t)rowid[lr[s]] * g.words;
+                        mword[s] = ahead ? mword_ahead[s] : mr[mword_idx];
+                        mword_ahead[s] = mr[nxt];
+                    }
                 }
 #pragma unroll
                 for (int s = 0; s < NS; ++s) rsel[s] = (mword[s] >> (j & 31)) & 1u;

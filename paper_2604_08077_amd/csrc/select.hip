@@ -257,17 +257,33 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
 #pragma unroll
     for (int s = 0; s < SELM_SLABS; ++s) {
         // ---- softmax numerators e = exp2(logit*log2(e)/sqrt(D) - max), 0 for non-candidates; kept in acc
+        // (a cube group whose 16 cubes are all candidates -- most are -- needs no test per value: the group-level
+        // conditions are the same in every lane and become scalar branches)
         float mx = -INFINITY;
 #pragma unroll
-        for (int cg = 0; cg < MAXG; ++cg)
+        for (int cg = 0; cg < MAXG; ++cg) {
+            const bool whole = 16 * cg >= g.Np && 16 * cg + 16 <= cend && (cr.skip >> 4) != cg;
+            if (whole) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int cube = 16 * cg + 4 * q4 + v;
-                const bool valid = cube >= g.Np && cube < cend && cube != cr.skip;
-                const float x = valid ? acc[s][cg][v] * scale : -INFINITY;
-                acc[s][cg][v] = x;
-                mx = fmaxf(mx, x);
+                for (int v = 0; v < 4; ++v) {
+                    const float x = acc[s][cg][v] * scale;
+                    acc[s][cg][v] = x;
+                    mx = fmaxf(mx, x);
+                }
+            } else if (16 * cg < cend) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int cube = 16 * cg + 4 * q4 + v;
+                    const bool valid = cube >= g.Np && cube < cend && cube != cr.skip;
+                    const float x = valid ? acc[s][cg][v] * scale : -INFINITY;
+                    acc[s][cg][v] = x;
+                    mx = fmaxf(mx, x);
+                }
+            } else {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[s][cg][v] = -INFINITY;
             }
+        }
         mx = selm_quad_max(mx);
         float target;
         if (TOPK) {
@@ -296,9 +312,7 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
 
         // ---- largest tau (as a bit pattern) with mass{e >= tau} >= target: positive floats order like
         // unsigned integers, so tau is found bit by bit; every row (four lanes) runs its own search
-        uint32_t tau = 0;
-        for (int b = TOPK ? 31 : 30; b >= 0; --b) {
-            const uint32_t cand = tau | (1u << b);
+        auto mass_at = [&](uint32_t cand) __attribute__((always_inline)) -> float {
             float sum = 0.f;
 #pragma unroll
             for (int k4 = 0; k4 < (MAXG + 3) / 4; ++k4)
@@ -311,35 +325,76 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
                             sum += (__float_as_uint(e) >= cand) ? (TOPK ? 1.f : e) : 0.f;
                         }
                 }
-            if (selm_quad_sum(sum) >= target) tau = cand;
+            return selm_quad_sum(sum);
+        };
+        uint32_t tau = 0;
+        int b_first = 31;
+        if (!TOPK) {
+            // The numerators lie in (0, 1]: bit 30 is never set.  And in all but very flat rows the threshold is
+            // above 2^-7 (pattern 0x3C000000: bits 29..26 set): if every row of the slab has its mass there, those
+            // four bits are settled in one step -- each of them would have been accepted in turn.
+            constexpr uint32_t guess = 0x3C000000u;
+            b_first = 29;
+            if (__all(mass_at(guess) >= target)) {
+                tau = guess;
+                b_first = 25;
+            }
+        }
+        bool single = false;  // the search ended early: every row has exactly one element equal to tau
+        for (int b = b_first; b >= 0; --b) {
+            const uint32_t cand = tau | (1u << b);
+            if (mass_at(cand) >= target) tau = cand;
             // tau is the value of one of the row's elements, the smallest kept one, and it lies in
-            // [tau, tau + 2^b).  Once that bucket holds a single distinct value for every row of the slab the
-            // remaining bits are known; looked at every fourth step once the exponent bits are settled.
+            // [tau, tau + 2^b).  Once that bucket holds a single element for every row of the slab the remaining
+            // bits are known; looked at every fourth step once the exponent bits are settled.
             if (b <= 22 && (b & 3) == 2) {
                 const uint32_t width = 1u << b;
-                uint32_t mn = 0xffffffffu, mxb = 0u;
+                int cnt = 0;
 #pragma unroll
                 for (int k4 = 0; k4 < (MAXG + 3) / 4; ++k4)
                     if (k4 < ng4) {
 #pragma unroll
                         for (int cg = 4 * k4; cg < 4 * k4 + 4 && cg < MAXG; ++cg)
 #pragma unroll
-                            for (int v = 0; v < 4; ++v) {
-                                const uint32_t bits = __float_as_uint(acc[s][cg][v]);
-                                const bool inb = bits - tau < width;
-                                mn = inb ? min(mn, bits) : mn;
-                                mxb = inb ? max(mxb, bits) : mxb;
-                            }
+                            for (int v = 0; v < 4; ++v)
+                                cnt += (__float_as_uint(acc[s][cg][v]) - tau < width) ? 1 : 0;
                     }
-                // min over the row's four lanes via max of the complement
-                mn = ~selm_quad_umax(~mn);
-                mxb = selm_quad_umax(mxb);
-                if (__all(mn == mxb)) {
-                    tau = mn;
+                if (__all((int)selm_quad_sum((float)cnt) == 1)) {  // small counts: exact in fp32
+                    uint32_t it = 0u;  // the one element of the bucket
+#pragma unroll
+                    for (int k4 = 0; k4 < (MAXG + 3) / 4; ++k4)
+                        if (k4 < ng4) {
+#pragma unroll
+                            for (int cg = 4 * k4; cg < 4 * k4 + 4 && cg < MAXG; ++cg)
+#pragma unroll
+                                for (int v = 0; v < 4; ++v) {
+                                    const uint32_t bits = __float_as_uint(acc[s][cg][v]);
+                                    it = (bits - tau < width) ? bits : it;
+                                }
+                        }
+                    tau = selm_quad_umax(it);
+                    single = true;
                     break;
                 }
             }
         }
+
+        // ---- kept flags.  An element equal to tau is kept while the mass before it (in cube order among the
+        // tied ones) is below the target; with a single such element that is always the case.
+        uint32_t nib[MAXG];  // bit v of nib[cg]: cube 16cg + 4q4 + v is kept
+        if (!TOPK && single) {
+            // kept <=> pattern >= tau <=> (tau - 1) - pattern is negative as a signed number (both are below
+            // 2^31): its sign bits are shifted into the nibble, no compare masks in scalar registers
+            const uint32_t tm1 = tau - 1u;
+#pragma unroll
+            for (int cg = 0; cg < MAXG; ++cg) {
+                uint32_t bitsk = 0u;
+#pragma unroll
+                for (int v = 3; v >= 0; --v)
+                    bitsk = __builtin_amdgcn_alignbit(bitsk, tm1 - __float_as_uint(acc[s][cg][v]), 31);
+                nib[cg] = bitsk;
+            }
+        } else {
         const float tauf = TOPK ? 1.f : __uint_as_float(tau);  // weight of an element equal to tau
         float sgt = 0.f;
         int neq = 0;
@@ -353,10 +408,6 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
             }
         const float mass_gt = selm_quad_sum(sgt);
         const int neq_row = (int)selm_quad_sum((float)neq);  // small counts: exact in fp32
-
-        // ---- kept flags.  An element equal to tau is kept while the mass before it (in cube order among the
-        // tied ones) is below the target; with a single such element that is always the case.
-        uint32_t nib[MAXG];  // bit v of nib[cg]: cube 16cg + 4q4 + v is kept
         if (__any(neq_row > 1)) {
             int running = 0;  // tied elements of this row in earlier cube groups
 #pragma unroll
@@ -399,6 +450,7 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
                 }
                 nib[cg] = bitsk;
             }
+        }
         }
 
         // ---- mask words: word w covers cube groups 2w, 2w+1; a lane's nibble of group cg sits at bit
