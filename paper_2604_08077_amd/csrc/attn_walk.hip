@@ -191,20 +191,24 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
             p.nt = tiles_of(p.j);
         }  // the last tile stays where it is: nothing is issued or computed past the end
     };
-    // The K and V^T tiles are fetched as two streams: a wave-uniform pointer to the current tile and a countdown
-    // to the end of its cube (cubes are padded to TPC tiles in memory; a ragged cube's padding tiles are skipped).
+    // The K and V^T tiles are fetched in the same order, V^T one tile behind K: one stream walks the list of cubes
+    // (cubes are padded to TPC tiles in memory; a ragged cube's padding tiles are skipped) and yields the byte
+    // offset of its current tile from the KV head's first tile, which is the same in the K and the V^T half of the
+    // packed copy; the V^T load of a slot takes the offset the K load of the slot before it used.  (Two independent
+    // streams cost twice the scalar registers and instructions, and this kernel has none to spare: what does not
+    // fit is kept in lanes of a vector register and read back with vector instructions.)
     struct Stream {
-        const unsigned char *head;  // first tile of the KV head
-        const unsigned char *tile;
+        uint32_t off;  // of the current tile
         int k, t, nt;  // position in the list of cubes, tile in the cube, tiles of the cube
         int next;      // the cube at position k + 1 (per lane, as read from the list)
     };
-    auto stream_begin = [&](const uint16_t *base) -> Stream {
+    const unsigned char *khead = reinterpret_cast<const unsigned char *>(Kp + (size_t)kv * g.N * g.TPC * (KEY_TILE * D));
+    const unsigned char *vhead = reinterpret_cast<const unsigned char *>(Vt + (size_t)kv * g.N * g.TPC * (KEY_TILE * D));
+    auto stream_begin = [&]() -> Stream {
         Stream q;
-        q.head = reinterpret_cast<const unsigned char *>(base + (size_t)kv * g.N * g.TPC * (KEY_TILE * D));
         q.k = 0;
         const int j = cube_at(0);
-        q.tile = q.head + (size_t)j * g.TPC * C::CHUNK;
+        q.off = (uint32_t)j * (uint32_t)(g.TPC * C::CHUNK);
         q.t = 0;
         q.nt = tiles_of(j);
         q.next = peek_after(0);
@@ -213,12 +217,12 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
     auto stream_next = [&](Stream &q) __attribute__((always_inline)) {
         if (q.t + 1 < q.nt) {
             ++q.t;
-            q.tile += C::CHUNK;
+            q.off += C::CHUNK;
         } else {
             q.k = min(q.k + 1, nlist - 1);  // past the end nothing is issued; the index only has to stay valid
             const int j = __builtin_amdgcn_readfirstlane(q.next);
             q.next = peek_after(q.k);
-            q.tile = q.head + (size_t)j * g.TPC * C::CHUNK;
+            q.off = (uint32_t)j * (uint32_t)(g.TPC * C::CHUNK);
             q.t = 0;
             q.nt = tiles_of(j);
         }
@@ -226,10 +230,11 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
     const uint32_t lds_piece =
         __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem + (uint32_t)(wave * C::DMA * 1024));
     const uint32_t src_piece = (uint32_t)(wave * C::DMA * 1024 + lane * 16);
-    auto issue = [&](const Stream &q, int off_bytes) __attribute__((always_inline)) {
+    auto issue = [&](const unsigned char *head, uint32_t off, int off_bytes) __attribute__((always_inline)) {
+        const void *tile = uniform_ptr(head + off);
 #pragma unroll
         for (int u = 0; u < C::DMA; ++u)
-            dma_1k_s(lds_piece + (uint32_t)(off_bytes + u * 1024), q.tile, src_piece + (uint32_t)(u * 1024));
+            dma_1k_s(lds_piece + (uint32_t)(off_bytes + u * 1024), tile, src_piece + (uint32_t)(u * 1024));
     };
     auto next_stage = [](int st) -> int { return st + 1 == NST ? 0 : st + 1; };
 
@@ -250,15 +255,15 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
     rank_lo = __builtin_amdgcn_readfirstlane(rank_lo == 0x7fffffff ? 0 : rank_lo);
 
     // prologue: K(0), K(1), V(0)
-    Stream sk = stream_begin(Kp), sv = stream_begin(Vt);
-    int tk = 0, tv = 0;  // index of the tile sk / sv points at
-    for (; tk < 2 && tk < ntiles; ++tk) {
-        issue(sk, C::OFF_K + tk * C::CHUNK);
+    Stream sk = stream_begin();
+    uint32_t klast = sk.off;  // offset of the K tile issued last
+    issue(khead, sk.off, C::OFF_K);  // (ntiles >= 1: the own cube has a tile)
+    issue(vhead, sk.off, C::OFF_V);
+    stream_next(sk);
+    if (ntiles > 1) {
+        klast = sk.off;
+        issue(khead, sk.off, C::OFF_K + C::CHUNK);
         stream_next(sk);
-    }
-    for (; tv < 1 && tv < ntiles; ++tv) {
-        issue(sv, C::OFF_V + tv * C::CHUNK);
-        stream_next(sv);
     }
 
     const float c2 = 1.44269504088896340736f / sqrtf((float)D);  // softmax scale in base 2, folded into Q
@@ -369,15 +374,12 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
         else dma_barrier<0>();
         const int st_v = kst == 0 ? 2 : kst - 1;  // (kst + 2) % 3: stage of V(t-1), and of K(t+2)
         const int st_n = kst == 2 ? 0 : kst + 1;  // (kst + 1) % 3: stage of V(t+1)
-        if (tk < ntiles) {
-            issue(sk, C::OFF_K + st_v * C::CHUNK);
+        if (t + 1 < ntiles)  // V^T(t+1): the tile K(t+1), whose offset the K load of the slot before this one used
+            issue(vhead, klast, C::OFF_V + st_n * C::CHUNK);
+        if (t + 2 < ntiles) {
+            klast = sk.off;
+            issue(khead, sk.off, C::OFF_K + st_v * C::CHUNK);
             stream_next(sk);
-            ++tk;
-        }
-        if (tv < ntiles) {
-            issue(sv, C::OFF_V + st_n * C::CHUNK);
-            stream_next(sv);
-            ++tv;
         }
     };
     auto k_tile = [&]() -> const unsigned char * { return smem + C::OFF_K + kst * C::CHUNK; };
