@@ -26,6 +26,8 @@ constexpr int SELM_THREADS = 256;
 constexpr int SELM_SLABS = 2;                                      // 16-row slabs per wavefront
 constexpr int SELM_ROWS = (SELM_THREADS / 64) * SELM_SLABS * 16;  // rows per workgroup
 constexpr int SELM_MAX_CUBES = 256;
+constexpr int SELM_SWITCH_BIT = 21;  // Top-p threshold search: bits down to this one on all candidates, the rest on a short list
+constexpr int SELM_SHORT = 16;       // entries of a lane's short list
 
 typedef __bf16 sel_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float sel_f32x4 __attribute__((ext_vector_type(4)));
@@ -166,6 +168,8 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
     int top_k, uint32_t *__restrict__ sel_mask, int32_t *__restrict__ sel_count)
 {
     constexpr int KS = D / 32;
+    // the threshold search's short lists (see below): SELM_SHORT entries and a dump slot per lane
+    __shared__ uint32_t shortlist[SELM_THREADS / 64][SELM_SHORT + 1][64];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n16 = lane & 15, q4 = lane >> 4;
@@ -341,7 +345,83 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
             }
         }
         bool single = false;  // the search ended early: every row has exactly one element equal to tau
-        for (int b = b_first; b >= 0; --b) {
+        // After bit b is settled, tau (the smallest kept element) lies in the bucket [tau, tau + 2^b), and of
+        // everything else only one number matters: `above`, the mass of the elements beyond the bucket.  On
+        // independent rows of a hundred-odd candidates the bucket is down to a twelfth of the row after bit
+        // SELM_SWITCH_BIT; the elements in it are then copied out (through LDS: a lane appends its own to a short
+        // list of its own) and the remaining bits are settled on those few instead of on all 4 * MAXG registers.
+        float above = 0.f;
+        int b_next = b_first;
+        if (!TOPK) {
+            for (; b_next >= SELM_SWITCH_BIT; --b_next) {
+                const uint32_t cand = tau | (1u << b_next);
+                const float m = mass_at(cand);
+                if (m >= target) tau = cand;
+                else above = m;
+            }
+            // ---- the bucket's elements, per lane, into shortlist[..][lane]; slot SELM_SHORT is a dump for the rest
+            uint32_t *mine = &shortlist[wave][0][lane];
+#pragma unroll
+            for (int k = 0; k < SELM_SHORT; ++k) mine[k * 64] = 0u;
+            constexpr uint32_t width = 1u << SELM_SWITCH_BIT;
+            int cnt = 0;
+#pragma unroll
+            for (int k4 = 0; k4 < (MAXG + 3) / 4; ++k4)
+                if (k4 < ng4) {
+#pragma unroll
+                    for (int cg = 4 * k4; cg < 4 * k4 + 4 && cg < MAXG; ++cg)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const uint32_t bits = __float_as_uint(acc[s][cg][v]);
+                            const bool inb = bits - tau < width;
+                            mine[(inb ? min(cnt, SELM_SHORT) : SELM_SHORT) * 64] = bits;
+                            cnt += inb ? 1 : 0;
+                        }
+                }
+            if (!__any(cnt > SELM_SHORT)) {  // (else: the plain search below goes on from where this one stands)
+                // the longest list of the wavefront, rounded up to four, bounds the loops over list entries
+                const int kmax = __any(cnt > 12) ? 16 : __any(cnt > 8) ? 12 : __any(cnt > 4) ? 8 : 4;
+                uint32_t c[SELM_SHORT];
+#pragma unroll
+                for (int k = 0; k < SELM_SHORT; ++k) c[k] = k < kmax ? mine[k * 64] : 0u;
+                for (; b_next >= 0; --b_next) {
+                    // the upper half of the bucket: [cand, cand + 2^b)
+                    const uint32_t cand = tau | (1u << b_next), half = 1u << b_next;
+                    float sum = 0.f;
+#pragma unroll
+                    for (int k4 = 0; k4 < SELM_SHORT / 4; ++k4)
+                        if (4 * k4 < kmax) {
+#pragma unroll
+                            for (int k = 4 * k4; k < 4 * k4 + 4; ++k)
+                                sum += (c[k] - cand < half) ? __uint_as_float(c[k]) : 0.f;
+                        }
+                    const float m = above + selm_quad_sum(sum);
+                    if (m >= target) tau = cand;
+                    else above = m;
+                    if ((b_next & 1) == 0) {  // one element left in every row's bucket: it is tau
+                        int left = 0;
+                        uint32_t it = 0u;
+#pragma unroll
+                        for (int k4 = 0; k4 < SELM_SHORT / 4; ++k4)
+                            if (4 * k4 < kmax) {
+#pragma unroll
+                                for (int k = 4 * k4; k < 4 * k4 + 4; ++k) {
+                                    const bool inb = c[k] - tau < half;
+                                    left += inb ? 1 : 0;
+                                    it = inb ? c[k] : it;
+                                }
+                            }
+                        if (__all((int)selm_quad_sum((float)left) == 1)) {  // small counts: exact in fp32
+                            tau = selm_quad_umax(it);
+                            single = true;
+                            break;
+                        }
+                    }
+                }
+                b_next = -1;
+            }
+        }
+        for (int b = b_next; b >= 0; --b) {
             const uint32_t cand = tau | (1u << b);
             if (mass_at(cand) >= target) tau = cand;
             // tau is the value of one of the row's elements, the smallest kept one, and it lies in

@@ -41,8 +41,9 @@ def run_both(B, w, p):
     torch.cuda.synchronize()
     assert torch.cuda.memory_allocated() == before
     print(f"[{w.name}] p={p} rows={sh.rows} selected pairs={cap}", flush=True)
-    assert torch.equal(m2, mask) and torch.equal(c2, count)
-    assert torch.equal(rp2, row_ptr) and torch.equal(ci2[:cap], cube_idx[:cap])
+    same = {"sel_mask": torch.equal(m2, mask), "sel_count": torch.equal(c2, count), "row_ptr": torch.equal(rp2, row_ptr),
+            "cube_idx": torch.equal(ci2[:cap], cube_idx[:cap])}
+    assert all(same.values()), same
     # without the compact list
     m3, c3 = torch.full_like(mask, -1), torch.full_like(count, -1)
     B.cube_select_noalloc(sh, Qg, kbar, p32, m3, c3)
