@@ -15,6 +15,7 @@
 // Streamed tiles come from packed, pre-swizzled copies (kvtile.h layouts) straight into LDS: K natural / V natural
 // / K transposed per 64 keys (two runs of the forward's pack kernel), Q, dO natural and transposed per 64 rows in
 // (cube, rank, head of the group) order (bwd_pack_rows_kernel, which also leaves log2-domain log-sum-exp and delta).
+#include <algorithm>
 #include <type_traits>
 
 #include "attn_tile.h"
@@ -26,10 +27,11 @@ constexpr int BWD_ROWS = 256;   // rows (dQ kernel) or keys (dK/dV kernel) per w
 constexpr float BWD_LOG2E = 1.44269504088896340736f;
 
 struct BwdWorkspace {
-    void *packA;             // launch_kv_pack(K, V): natural K first (its V^T half is not used here)
+    void *packA;             // launch_kv_pack(K, V): natural K first, turned into fp16 (its V^T half is not used here)
     void *packB;             // launch_kv_pack(V, K): natural V, then K transposed
-    uint16_t *Qn, *Qt, *dOn, *dOt;  // [Hkv][N][tpcr][64 * D]
-    float *lse2, *delta;     // [Hkv][N][tpcr * 64]; padding rows: +inf, 0
+    uint16_t *Qn, *Qt, *dOn, *dOt;  // [Hkv][N][tpcr][64 * D]; Qn: fp16, scaled (score operand), the others bf16
+    // minus the log-sum-exp in base 2 and minus delta per packed row (what the score and dP products start from)
+    float *lse2, *delta;     // [Hkv][N][tpcr * 64]; padding rows: -inf, 0
     unsigned long long *colmask;  // [Hkv][N (key cube j)][N (row cube i)][tpcr]: bit k = row 64 t + k of cube i selects j
     int tpcr;                // 64-row tiles per cube = ceil(Cmax * G / 64)
     size_t bytes;
@@ -91,6 +93,30 @@ __device__ __forceinline__ void dma_dword_s(uint32_t lds_addr, const void *sbase
                  : "memory", "m0");
 }
 
+// Score operands of the backward kernels: fp16.  The scores are rebuilt from Q with the softmax scale in base 2 folded
+// in (so that they leave the MFMAs as the exponents of the probabilities); rounded to bf16 that product would cost
+// every probability a relative error of the size of its own bf16 rounding, in fp16 (three more mantissa bits) an
+// eighth of that.  K converts exactly (bf16's 8 significant bits fit) as long as its magnitude lies in fp16's range;
+// beyond it both operands saturate at +-65504, below 6e-5 they lose bits no score can notice.
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ f16x8 to_f16(bf16x8 x, float scale)
+{
+    f16x8 r;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r[e] = (_Float16)fminf(fmaxf((float)x[e] * scale, -65504.f), 65504.f);
+    return r;
+}
+
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x4 mfma16(f16x8 a, f16x8 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
 // Row r of cube c in the packed row order: rank r / G, head r % G of the group.
 // Q, dO natural and transposed per 64-row tile; delta = dO.O; lse2 = lse * log2(e).
 template <int D>
@@ -113,7 +139,7 @@ __global__ __launch_bounds__(256) void bwd_pack_rows_kernel(Geom g, const uint16
         const int k = x / CPR, col = x % CPR;
         const int r = 64 * t + k;
         uint4 qq = make_uint4(0, 0, 0, 0), gg = make_uint4(0, 0, 0, 0);
-        float part = 0.f, l2 = INFINITY;
+        float part = 0.f, l2 = INFINITY;  // (padding rows: minus its log-sum-exp is -inf, its probabilities 0)
         if (r < mrows) {
             const int n = token_of(g, box, r / g.G);
             const size_t rowid = (size_t)n * g.Hq + kv * g.G + r % g.G;
@@ -131,11 +157,14 @@ __global__ __launch_bounds__(256) void bwd_pack_rows_kernel(Geom g, const uint16
         }
 #pragma unroll
         for (int d = CPR / 2; d >= 1; d >>= 1) part += __shfl_xor(part, d, 64);
-        if (col == 0) {
-            lse2p[tile * 64 + k] = l2;
-            deltap[tile * 64 + k] = part;
+        if (col == 0) {  // both with the sign the MFMA accumulators of the key-stationary kernels start from
+            lse2p[tile * 64 + k] = -l2;
+            deltap[tile * 64 + k] = -part;
         }
-        *reinterpret_cast<uint4 *>(reinterpret_cast<char *>(Qn + tile_base) + k_tile_off<D>(k, col)) = qq;
+        // The natural copy of Q feeds the score products of the key-stationary kernels only: fp16, with the softmax
+        // scale in base 2 folded in.  The transposed copy (dK^T += Q^T.dS) stays as it is.
+        *reinterpret_cast<f16x8 *>(reinterpret_cast<char *>(Qn + tile_base) + k_tile_off<D>(k, col)) =
+            to_f16(__builtin_bit_cast(bf16x8, qq), BWD_LOG2E / sqrtf((float)D));
         *reinterpret_cast<uint4 *>(reinterpret_cast<char *>(dOn + tile_base) + k_tile_off<D>(k, col)) = gg;
         *reinterpret_cast<uint4 *>(&qs[k][col * 8]) = qq;
         *reinterpret_cast<uint4 *>(&gs[k][col * 8]) = gg;
@@ -153,6 +182,16 @@ __global__ __launch_bounds__(256) void bwd_pack_rows_kernel(Geom g, const uint16
             make_uint4(wq[0], wq[1], wq[2], wq[3]);
         *reinterpret_cast<uint4 *>(reinterpret_cast<char *>(dOt + tile_base) + vt_tile_off(d, kc)) =
             make_uint4(wg[0], wg[1], wg[2], wg[3]);
+    }
+}
+
+// The packed natural copy of K, bf16 -> fp16 in place (same element size, so the tiles' layout stays): the score
+// operand of the row-stationary kernel.
+__global__ __launch_bounds__(256) void bwd_keys_to_f16_kernel(uint16_t *__restrict__ tiles, size_t chunks)
+{
+    for (size_t x = (size_t)blockIdx.x * 256 + threadIdx.x; x < chunks; x += (size_t)gridDim.x * 256) {
+        bf16x8 *p = reinterpret_cast<bf16x8 *>(tiles) + x;
+        *reinterpret_cast<f16x8 *>(p) = to_f16(*p, 1.0f);
     }
 }
 
@@ -180,26 +219,42 @@ __global__ __launch_bounds__(64) void bwd_colmask_kernel(Geom g, const uint32_t 
     }
 }
 
-// Half H of qk_tile: the products of a natural tile's rows 32 H .. 32 H + 31 with the B operands of NS slabs.
-// acc[s][k2][v] belongs to tile row 32 H + 8 q4 + 4 k2 + v.  Working a tile in two halves keeps half as many
-// accumulators alive.
-template <int D, int NS, int H>
-__device__ __forceinline__ void nat_half(const unsigned char *kt, int n16, int q4, const bf16x8 (&bf)[NS][D / 32],
-                                         f32x4 (&acc)[NS][2])
+// Half H of qk_tile: the products of a natural tile's rows 32 H .. 32 H + 31 with the B operands of NS slabs (OP:
+// bf16x8 or f16x8, the tile's element type with it).  acc[s][k2][v] belongs to tile row 32 H + 8 q4 + 4 k2 + v.
+// Working a tile in two halves keeps half as many accumulators alive.  The accumulators of slab s start from bias[s],
+// a value of the slab's row (the lane's column): the products come out with it added.
+template <int D, int NS, int H, typename OP>
+__device__ __forceinline__ void nat_half_bias(const unsigned char *kt, int n16, int q4, const OP (&bf)[NS][D / 32],
+                                              const float (&bias)[NS], f32x4 (&acc)[NS][2])
 {
+    f32x4 init[NS];
 #pragma unroll
-    for (int s = 0; s < NS; ++s)
-#pragma unroll
-        for (int k2 = 0; k2 < 2; ++k2) acc[s][k2] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < NS; ++s) init[s] = f32x4{bias[s], bias[s], bias[s], bias[s]};
 #pragma unroll
     for (int c = 0; c < D / 32; ++c)
 #pragma unroll
         for (int k2 = 0; k2 < 2; ++k2) {
             const int krow = 32 * H + 8 * (n16 >> 2) + 4 * k2 + (n16 & 3);
-            const bf16x8 af = *reinterpret_cast<const bf16x8 *>(kt + k_tile_off<D>(krow, 4 * c + q4));
+            const OP af = *reinterpret_cast<const OP *>(kt + k_tile_off<D>(krow, 4 * c + q4));
 #pragma unroll
-            for (int s = 0; s < NS; ++s)
-                acc[s][k2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bf[s][c], acc[s][k2], 0, 0, 0);
+            for (int s = 0; s < NS; ++s) acc[s][k2] = mfma16(af, bf[s][c], c == 0 ? init[s] : acc[s][k2]);
+        }
+}
+
+// The same with the accumulators started from init[k2]: four values, one per tile row 32 H + 8 q4 + 4 k2 + v, shared by
+// the slabs (minus a tile row's log-sum-exp or delta: the products then come out with it subtracted).
+template <int D, int NS, int H, typename OP>
+__device__ __forceinline__ void nat_half_from(const unsigned char *kt, int n16, int q4, const OP (&bf)[NS][D / 32],
+                                              const f32x4 (&init)[2], f32x4 (&acc)[NS][2])
+{
+#pragma unroll
+    for (int c = 0; c < D / 32; ++c)
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) {
+            const int krow = 32 * H + 8 * (n16 >> 2) + 4 * k2 + (n16 & 3);
+            const OP af = *reinterpret_cast<const OP *>(kt + k_tile_off<D>(krow, 4 * c + q4));
+#pragma unroll
+            for (int s = 0; s < NS; ++s) acc[s][k2] = mfma16(af, bf[s][c], c == 0 ? init[k2] : acc[s][k2]);
         }
 }
 
@@ -258,7 +313,8 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const 
     int rr[NS], rank[NS];
     size_t rowid[NS];
     bool valid[NS];
-    bf16x8 qf[NS][KSTEPS], gf[NS][KSTEPS];
+    f16x8 qf[NS][KSTEPS];
+    bf16x8 gf[NS][KSTEPS];
     float lse2[NS], delta[NS], psum[NS];
     size_t prow[NS];
 #pragma unroll
@@ -271,14 +327,15 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const 
         rowid[s] = (size_t)token_of(g, box, rank[s]) * g.Hq + kv * g.G + rr[s] % g.G;
 #pragma unroll
         for (int c = 0; c < KSTEPS; ++c) {
-            qf[s][c] = *reinterpret_cast<const bf16x8 *>(Q + rowid[s] * D + 32 * c + 8 * q4);
+            // Q in fp16 with the softmax scale in base 2: the scores then leave the MFMAs as exponents
+            qf[s][c] = to_f16(*reinterpret_cast<const bf16x8 *>(Q + rowid[s] * D + 32 * c + 8 * q4),
+                              BWD_LOG2E / sqrtf((float)D));
             gf[s][c] = *reinterpret_cast<const bf16x8 *>(dO + rowid[s] * D + 32 * c + 8 * q4);
         }
         prow[s] = ((size_t)kv * g.N + i) * tpcr * 64 + rr[s];
-        lse2[s] = lse2p[prow[s]];
-        delta[s] = deltap[prow[s]];
+        lse2[s] = -lse2p[prow[s]];   // (both stored with a minus sign, for the key-stationary kernels)
+        delta[s] = deltap[prow[s]];  // minus delta: what the dP products start from
     }
-    const float c2 = BWD_LOG2E / sqrtf((float)D);
 
     // tile stream: cubes 0..i, the tiles of each that hold keys
     const size_t head_tiles = (size_t)kv * g.N * g.TPC;
@@ -314,14 +371,15 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const 
     for (int j = 0; j <= i; ++j) {
         const int nt = tiles_of(j);
         const int size_j = csize[j];
-        // a row that did not select cube j takes no part: with +inf as its log-sum-exp its probabilities are 0
+        // What the score products start from: minus the row's log-sum-exp; -inf for a row that did not select cube
+        // j, which then takes no part (probabilities 0)
         float le[NS];
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            le[s] = lse2[s];
+            le[s] = -lse2[s];
             if (MASKED && j < i) {
                 if ((j & 31) == 0) mw[s] = sel_mask[rowid[s] * g.words + (j >> 5)];
-                if (!((mw[s] >> (j & 31)) & 1u)) le[s] = INFINITY;
+                if (!((mw[s] >> (j & 31)) & 1u)) le[s] = -INFINITY;
             }
         }
         for (int t = 0; t < nt; ++t) {
@@ -337,8 +395,8 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const 
                 constexpr int H = decltype(hc)::value;
                 f32x4 sacc[NS][2], pacc[NS][2];
                 __builtin_amdgcn_sched_barrier(0);  // phases are not overlapped: that would not fit the register file
-                nat_half<D, NS, H>(kt, n16, q4, qf, sacc);
-                nat_half<D, NS, H>(vt, n16, q4, gf, pacc);
+                nat_half_bias<D, NS, H>(kt, n16, q4, qf, le, sacc);
+                nat_half_bias<D, NS, H>(vt, n16, q4, gf, delta, pacc);
                 if (edge) {
                     int kb = 64 * t + 32 * H + 8 * q4;
                     asm volatile("" : "+v"(kb));
@@ -358,9 +416,9 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const 
                     for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
                         for (int v = 0; v < 4; ++v) {
-                            const float p = __builtin_amdgcn_exp2f(fmaf(sacc[s][k2][v], c2, -le[s]));
+                            const float p = __builtin_amdgcn_exp2f(sacc[s][k2][v]);
                             psum[s] += p;
-                            ds[s][H][4 * k2 + v] = (__bf16)(p * (pacc[s][k2][v] - delta[s]));
+                            ds[s][H][4 * k2 + v] = (__bf16)(p * pacc[s][k2][v]);
                         }
             };
             half(std::integral_constant<int, 0>{});
@@ -377,7 +435,7 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const 
     for (int s = 0; s < NS; ++s) {
         const float total = quad_sum(psum[s]);
         if (!valid[s]) continue;
-        if (q4 == 0) lse2p[prow[s]] = lse2[s] + log2f(total);
+        if (q4 == 0) lse2p[prow[s]] = -(lse2[s] + log2f(total));
         const float scale = 1.0f / (sqrtf((float)D) * total);
 #pragma unroll
         for (int e = 0; e < D / 16; ++e) {
@@ -436,7 +494,8 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
     int key[NS];
     bool valid[NS];
     size_t krow[NS];
-    bf16x8 kf[NS][KSTEPS], vf[NS][KSTEPS];
+    f16x8 kf[NS][KSTEPS];
+    bf16x8 vf[NS][KSTEPS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
         key[s] = kb * BWD_ROWS + wave * 32 + s * 16 + n16;
@@ -444,11 +503,10 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
         krow[s] = ((size_t)token_of(g, box, valid[s] ? key[s] : size_j - 1) * g.Hkv + kv) * D;
 #pragma unroll
         for (int c = 0; c < KSTEPS; ++c) {
-            kf[s][c] = *reinterpret_cast<const bf16x8 *>(K + krow[s] + 32 * c + 8 * q4);
+            kf[s][c] = to_f16(*reinterpret_cast<const bf16x8 *>(K + krow[s] + 32 * c + 8 * q4), 1.0f);
             if (WHICH == 1) vf[s][c] = *reinterpret_cast<const bf16x8 *>(V + krow[s] + 32 * c + 8 * q4);
         }
     }
-    const float c2 = BWD_LOG2E / sqrtf((float)D);
 
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem);
     const size_t head_tiles = (size_t)kv * g.N * tpcr;
@@ -515,11 +573,25 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
             auto half = [&](auto hc) __attribute__((always_inline)) {
                 constexpr int H = decltype(hc)::value;
                 f32x4 sacc[NS][2], pacc[NS][2];
-                __builtin_amdgcn_sched_barrier(0);  // phases are not overlapped: that would not fit the register file
-                nat_half<D, NS, H>(t0, n16, q4, kf, sacc);
-                if (WHICH == 1) nat_half<D, NS, H>(t0 + TILE, n16, q4, vf, pacc);
                 const int rb = 32 * H + 8 * q4;  // the lane's eight rows of this half: rb .. rb + 7
                 const uint32_t bits = (uint32_t)(cm >> rb);  // their selection bits
+                // What the products start from: minus the row's log-sum-exp (the streamed Q carries the softmax
+                // scale, so the scores then come out as the exponents of the probabilities), -inf for a row that did
+                // not select this key cube (probabilities 0); and minus the row's delta for dP.
+                f32x4 sinit[2], pinit[2];
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2) {
+                    sinit[k2] = *reinterpret_cast<const f32x4 *>(lv + rb + 4 * k2);
+                    if (MASKED) {
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            if (!((bits >> (4 * k2 + v)) & 1u)) sinit[k2][v] = -INFINITY;
+                    }
+                    if (WHICH == 1) pinit[k2] = *reinterpret_cast<const f32x4 *>(dv + rb + 4 * k2);
+                }
+                __builtin_amdgcn_sched_barrier(0);  // phases are not overlapped: that would not fit the register file
+                nat_half_from<D, NS, H>(t0, n16, q4, kf, sinit, sacc);
+                if (WHICH == 1) nat_half_from<D, NS, H>(t0 + TILE, n16, q4, vf, pinit, pacc);
                 if (i == j) {  // causal edge inside the own cube: a row attends keys up to its own rank
                     int r0 = 64 * t + rb;
                     asm volatile("" : "+v"(r0));
@@ -536,17 +608,12 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
 #pragma unroll
                 for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int rl = rb + 4 * k2 + v;
-                        float l2 = lv[rl];
-                        if (MASKED && !((bits >> (4 * k2 + v)) & 1u)) l2 = INFINITY;
-                        const float dl = WHICH == 1 ? dv[rl] : 0.f;
+                    for (int v = 0; v < 4; ++v)
 #pragma unroll
                         for (int s = 0; s < NS; ++s) {
-                            const float p = __builtin_amdgcn_exp2f(fmaf(sacc[s][k2][v], c2, -l2));
-                            pf[s][H][4 * k2 + v] = (__bf16)(WHICH == 1 ? p * (pacc[s][k2][v] - dl) : p);
+                            const float p = __builtin_amdgcn_exp2f(sacc[s][k2][v]);
+                            pf[s][H][4 * k2 + v] = (__bf16)(WHICH == 1 ? p * pacc[s][k2][v] : p);
                         }
-                    }
             };
             half(std::integral_constant<int, 0>{});
             half(std::integral_constant<int, 1>{});
@@ -585,6 +652,12 @@ static hipError_t launch_bwd_d(const Geom &g, const uint16_t *Q, const uint16_t 
     if (e != hipSuccess) return e;
     e = launch_kv_pack(g, V, K, w.packB, st);
     if (e != hipSuccess) return e;
+    {
+        const size_t chunks = (size_t)g.Hkv * g.N * g.TPC * KEY_TILE * D / 8;
+        hipLaunchKernelGGL(bwd_keys_to_f16_kernel, dim3((unsigned)std::min<size_t>((chunks + 255) / 256, 8192)), dim3(256),
+                           0, st, reinterpret_cast<uint16_t *>(w.packA), chunks);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
     hipLaunchKernelGGL((bwd_pack_rows_kernel<D>), dim3(w.tpcr, g.N, g.Hkv), dim3(256), 0, st, g, Q, dO, O, lse, w.tpcr,
                        w.Qn, w.Qt, w.dOn, w.dOt, w.lse2, w.delta);
     if ((e = hipGetLastError()) != hipSuccess) return e;

@@ -306,8 +306,8 @@ __global__ __launch_bounds__(SELM_THREADS, 2) void cube_select_mfma_kernel(
             for (int cg = 0; cg < MAXG; ++cg)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const float x = acc[s][cg][v];
-                    const float e = (x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(x - mx);
+                    // (non-candidates hold -inf and the maximum is finite -- there is a candidate: exp2 gives 0)
+                    const float e = __builtin_amdgcn_exp2f(acc[s][cg][v] - mx);
                     acc[s][cg][v] = e;
                     part += e;
                 }
@@ -572,8 +572,11 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
 {
     constexpr int KS = D / 32, MAXG = SELW_MAXG, SLABS = SELW_SLABS;
     constexpr int OPS = KS * 3;  // A operands (16 bytes per lane each) of one cube group
-    constexpr int XK = 2;        // values per row and wavefront in one exchange
+    constexpr int XK = 3;        // values per row and wavefront in one exchange
     __shared__ __attribute__((aligned(16))) uint32_t xch[2][SLABS][16][SPLIT * XK];
+    // the threshold search's short lists (see the kernel above): SELM_SHORT entries and a dump slot per lane; the
+    // two slabs of a wavefront fill it in turn
+    __shared__ uint32_t shortlist[SPLIT][SELM_SHORT + 1][64];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int part = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -682,6 +685,10 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
         xbuf ^= 1;
     };
     uint32_t xv[XK][SLABS], xa[SPLIT][XK][SLABS];
+#pragma unroll
+    for (int k = 0; k < XK; ++k)
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) xv[k][s] = 0u;
 
     // ---- softmax numerators e = exp2(logit*log2(e)/sqrt(D) - max), 0 for non-candidates; kept in acc
     const float scale = 1.44269504088896340736f / sqrtf((float)D);
@@ -689,15 +696,29 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
     for (int s = 0; s < SLABS; ++s) {
         float mx = -INFINITY;
 #pragma unroll
-        for (int lg = 0; lg < MAXG; ++lg)
+        for (int lg = 0; lg < MAXG; ++lg) {
+            // a cube group whose 16 cubes are all candidates (most are) needs no test per value: the group-level
+            // conditions are the same in every lane and become scalar branches
+            const int c0 = 16 * (g0 + lg);
+            const bool whole = c0 >= g.Np && c0 + 16 <= cend && (cr.skip >> 4) != g0 + lg;
+            if (whole) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int cube = 16 * (g0 + lg) + 4 * q4 + v;
-                const bool valid = cube >= g.Np && cube < cend && cube != cr.skip;
-                const float x = valid ? acc[s][lg][v] * scale : -INFINITY;
-                acc[s][lg][v] = x;
-                mx = fmaxf(mx, x);
+                for (int v = 0; v < 4; ++v) {
+                    const float x = acc[s][lg][v] * scale;
+                    acc[s][lg][v] = x;
+                    mx = fmaxf(mx, x);
+                }
+            } else {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int cube = c0 + 4 * q4 + v;
+                    const bool valid = cube >= g.Np && cube < cend && cube != cr.skip;
+                    const float x = valid ? acc[s][lg][v] * scale : -INFINITY;
+                    acc[s][lg][v] = x;
+                    mx = fmaxf(mx, x);
+                }
             }
+        }
         xv[0][s] = __float_as_uint(selm_quad_max(mx));
         xv[1][s] = 0;
     }
@@ -717,7 +738,8 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
                 if (TOPK) {  // rank the logits themselves: their order keys, 0 for non-candidates
                     acc[s][lg][v] = __uint_as_float((x == -INFINITY) ? 0u : sel_order_key(x));
                 } else {
-                    const float e = (x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(x - mx);
+                    // (non-candidates hold -inf and the row's maximum is finite: exp2 gives 0)
+                    const float e = __builtin_amdgcn_exp2f(x - mx);
                     acc[s][lg][v] = e;
                     sum += e;
                 }
@@ -733,11 +755,168 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
         target[s] = TOPK ? (float)top_k : top_p * z;
     }
 
-    // ---- largest tau (as a bit pattern) with mass{e >= tau} >= target, bit by bit, both slabs in step
+    // ---- largest tau (as a bit pattern) with mass{e >= tau} >= target, bit by bit, both slabs in step.  Every
+    // decision below is taken on exchanged values, which are the same in all wavefronts (they hold the same rows),
+    // so all of them follow the same path through the barriers.
     uint32_t tau[SLABS];
 #pragma unroll
     for (int s = 0; s < SLABS; ++s) tau[s] = 0;
-    for (int b = TOPK ? 31 : 30; b >= 0; --b) {
+    // the row's mass at or above cand[s]: one exchange
+    auto mass_at = [&](const uint32_t (&cand)[SLABS], float (&mass)[SLABS]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) {
+            float sum = 0.f;
+#pragma unroll
+            for (int lg = 0; lg < MAXG; ++lg)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float e = acc[s][lg][v];
+                    sum += (__float_as_uint(e) >= cand[s]) ? (TOPK ? 1.f : e) : 0.f;
+                }
+            xv[0][s] = __float_as_uint(selm_quad_sum(sum));
+        }
+        exchange(xv, xa);
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) {
+            mass[s] = 0.f;
+#pragma unroll
+            for (int p = 0; p < SPLIT; ++p) mass[s] += __uint_as_float(xa[p][0][s]);
+        }
+    };
+    bool single = false;  // the search ended early: every row has exactly one element equal to tau
+    int b_next = TOPK ? 31 : 29;  // (numerators lie in (0, 1]: bit 30 is never set)
+    if (!TOPK) {
+        // The same search as in the kernel for up to 256 candidates: a first trial that settles bits 29..26 at once,
+        // the bits down to SELM_SWITCH_BIT on all candidates while carrying `above`, the mass beyond the bucket
+        // [tau, tau + 2^b), and the rest on a short list of the bucket's elements per lane.
+        uint32_t cand[SLABS];
+        float mass[SLABS], above[SLABS];
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) {
+            cand[s] = 0x3C000000u;
+            above[s] = 0.f;
+        }
+        mass_at(cand, mass);
+        bool pass = true;
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) pass = pass && mass[s] >= target[s];
+        if (__all(pass)) {
+#pragma unroll
+            for (int s = 0; s < SLABS; ++s) tau[s] = cand[s];
+            b_next = 25;
+        }
+        for (; b_next >= SELM_SWITCH_BIT; --b_next) {
+#pragma unroll
+            for (int s = 0; s < SLABS; ++s) cand[s] = tau[s] | (1u << b_next);
+            mass_at(cand, mass);
+#pragma unroll
+            for (int s = 0; s < SLABS; ++s) {
+                if (mass[s] >= target[s]) tau[s] = cand[s];
+                else above[s] = mass[s];
+            }
+        }
+        // ---- the bucket's elements of this lane (its share of this wavefront's 256 cubes), slab by slab through
+        // the same LDS list into registers
+        uint32_t c[SLABS][SELM_SHORT];
+        uint32_t *mine = &shortlist[part][0][lane];
+        constexpr uint32_t width = 1u << SELM_SWITCH_BIT;
+        int cmax = 0;
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) {
+#pragma unroll
+            for (int k = 0; k < SELM_SHORT; ++k) mine[k * 64] = 0u;
+            int cnt = 0;
+#pragma unroll
+            for (int lg = 0; lg < MAXG; ++lg)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const uint32_t bits = __float_as_uint(acc[s][lg][v]);
+                    const bool inb = bits - tau[s] < width;
+                    mine[(inb ? min(cnt, SELM_SHORT) : SELM_SHORT) * 64] = bits;
+                    cnt += inb ? 1 : 0;
+                }
+#pragma unroll
+            for (int k = 0; k < SELM_SHORT; ++k) c[s][k] = mine[k * 64];
+            cmax = max(cmax, cnt);
+        }
+        // a list that overflowed anywhere in the workgroup: all wavefronts go on with the plain search below
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) xv[0][s] = __any(cmax > SELM_SHORT) ? 1u : 0u;
+        exchange(xv, xa);
+        uint32_t over = 0u;
+#pragma unroll
+        for (int p = 0; p < SPLIT; ++p) over |= xa[p][0][0];
+        if (!over) {
+            // the longest list of the wavefront, rounded up to four, bounds the loops over list entries
+            const int kmax = __any(cmax > 12) ? 16 : __any(cmax > 8) ? 12 : __any(cmax > 4) ? 8 : 4;
+            for (; b_next >= 0; --b_next) {
+                // the bucket's upper half [cand, cand + 2^b): its mass and its number of elements; the lower
+                // half's number of elements -- whichever half the bucket becomes, its count is known after the
+                // one exchange
+                const uint32_t half = 1u << b_next;
+#pragma unroll
+                for (int s = 0; s < SLABS; ++s) {
+                    cand[s] = tau[s] | half;
+                    float sum = 0.f;
+                    int nup = 0, nlo = 0;
+#pragma unroll
+                    for (int k4 = 0; k4 < SELM_SHORT / 4; ++k4)
+                        if (4 * k4 < kmax) {
+#pragma unroll
+                            for (int k = 4 * k4; k < 4 * k4 + 4; ++k) {
+                                const bool up = c[s][k] - cand[s] < half;
+                                sum += up ? __uint_as_float(c[s][k]) : 0.f;
+                                nup += up ? 1 : 0;
+                                nlo += (c[s][k] - tau[s] < half) ? 1 : 0;
+                            }
+                        }
+                    xv[0][s] = __float_as_uint(selm_quad_sum(sum));
+                    xv[1][s] = (uint32_t)selm_quad_sum((float)nup);  // small counts: exact in fp32
+                    xv[2][s] = (uint32_t)selm_quad_sum((float)nlo);
+                }
+                exchange(xv, xa);
+                bool one = true;
+#pragma unroll
+                for (int s = 0; s < SLABS; ++s) {
+                    float m = above[s];
+                    uint32_t nup = 0u, nlo = 0u;
+#pragma unroll
+                    for (int p = 0; p < SPLIT; ++p) {
+                        m += __uint_as_float(xa[p][0][s]);
+                        nup += xa[p][1][s];
+                        nlo += xa[p][2][s];
+                    }
+                    const bool take = m >= target[s];
+                    if (take) tau[s] = cand[s];
+                    else above[s] = m;
+                    one = one && (take ? nup : nlo) == 1u;
+                }
+                if (__all(one)) {  // one element left in every row's bucket: it is tau
+#pragma unroll
+                    for (int s = 0; s < SLABS; ++s) {
+                        uint32_t it = 0u;
+#pragma unroll
+                        for (int k = 0; k < SELM_SHORT; ++k) it = (c[s][k] - tau[s] < half) ? c[s][k] : it;
+                        xv[0][s] = selm_quad_umax(it);
+                    }
+                    exchange(xv, xa);
+#pragma unroll
+                    for (int s = 0; s < SLABS; ++s) {
+                        uint32_t it = 0u;
+#pragma unroll
+                        for (int p = 0; p < SPLIT; ++p) it = max(it, xa[p][0][s]);
+                        tau[s] = it;
+                    }
+                    single = true;
+                    break;
+                }
+            }
+            b_next = -1;
+        }
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) xv[1][s] = xv[2][s] = 0u;
+    }
+    for (int b = b_next; b >= 0; --b) {
 #pragma unroll
         for (int s = 0; s < SLABS; ++s) {
             const uint32_t cand = tau[s] | (1u << b);
@@ -779,7 +958,7 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
                 xv[1][s] = selm_quad_umax(mxb);
             }
             exchange(xv, xa);
-            bool single = true;
+            bool one_value = true;
             uint32_t only[SLABS];
 #pragma unroll
             for (int s = 0; s < SLABS; ++s) {
@@ -790,9 +969,9 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
                     mxb = max(mxb, xa[p][1][s]);
                 }
                 only[s] = ~nmn;
-                single = single && (only[s] == mxb);
+                one_value = one_value && (only[s] == mxb);
             }
-            if (__all(single)) {  // the same in every wavefront: they hold the same rows
+            if (__all(one_value)) {  // the same in every wavefront: they hold the same rows
 #pragma unroll
                 for (int s = 0; s < SLABS; ++s) tau[s] = only[s];
                 break;
@@ -801,7 +980,9 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
     }
 
     // ---- mass above tau and the number of elements equal to it: in the whole row, and in the blocks before this
-    // wavefront's (ties are kept in cube order)
+    // wavefront's (ties are kept in cube order).  With a single element equal to tau in every row (`single`) none of
+    // that is needed: kept <=> pattern >= tau.
+    if (!single) {
 #pragma unroll
     for (int s = 0; s < SLABS; ++s) {
         float sgt = 0.f;
@@ -818,6 +999,7 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
         xv[1][s] = (uint32_t)selm_quad_sum((float)neq);  // small counts: exact in fp32
     }
     exchange(xv, xa);
+    }
     uint32_t kept_part[SLABS];
 #pragma unroll
     for (int s = 0; s < SLABS; ++s) {
@@ -831,7 +1013,19 @@ __global__ __launch_bounds__(64 * SPLIT, 2) void cube_select_wide_kernel(
         }
         const float tauf = TOPK ? 1.f : __uint_as_float(tau[s]);  // weight of an element equal to tau
         uint32_t nib[MAXG];  // bit v of nib[lg]: cube 16(g0+lg) + 4q4 + v is kept
-        if (__any(neq_row > 1)) {
+        if (single) {
+            // (tau - 1) - pattern is negative as a signed number exactly when pattern >= tau (both are below 2^31):
+            // its sign bits are shifted into the nibble
+            const uint32_t tm1 = tau[s] - 1u;
+#pragma unroll
+            for (int lg = 0; lg < MAXG; ++lg) {
+                uint32_t bitsk = 0u;
+#pragma unroll
+                for (int v = 3; v >= 0; --v)
+                    bitsk = __builtin_amdgcn_alignbit(bitsk, tm1 - __float_as_uint(acc[s][lg][v]), 31);
+                nib[lg] = bitsk;
+            }
+        } else if (__any(neq_row > 1)) {
             int running = neq_before;  // tied elements of this row in earlier cube groups
 #pragma unroll
             for (int lg = 0; lg < MAXG; ++lg) {
