@@ -239,12 +239,13 @@ __global__ void pairs_scale_q_kernel(Geom g, long long chunks, float c2, const i
                                      const uint16_t *__restrict__ Q, uint16_t *__restrict__ qs)
 {
     if (!flags[FLAG_ACTIVE]) return;
-    const long long x = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (x >= chunks) return;
-    const long long row = x / (g.D / 8);
-    if (flags[FLAG_KV + (int)(row % g.Hq) / g.G] != 3) return;
-    const bf16x8 q = *reinterpret_cast<const bf16x8 *>(Q + x * 8);
-    *reinterpret_cast<bf16x8 *>(qs + x * 8) = prescale_q(q, c2);
+    // grid-stride: the grid is bounded, so that a launch that has nothing to do costs little
+    for (long long x = (long long)blockIdx.x * blockDim.x + threadIdx.x; x < chunks; x += (long long)gridDim.x * blockDim.x) {
+        const long long row = x / (g.D / 8);
+        if (flags[FLAG_KV + (int)(row % g.Hq) / g.G] != 3) continue;
+        const bf16x8 q = *reinterpret_cast<const bf16x8 *>(Q + x * 8);
+        *reinterpret_cast<bf16x8 *>(qs + x * 8) = prescale_q(q, c2);
+    }
 }
 
 // Transposition of the selection, two passes over the set bits of PAIRS_HIST_ROWS rows per workgroup.
@@ -661,7 +662,7 @@ static hipError_t launch_pairs_d(const Geom &g, const uint16_t *Q, const void *p
     const long long chunks = most / PAIRS_CHUNK + segs;
     const int own_chunks = (g.G * g.Cmax + PAIRS_CHUNK - 1) / PAIRS_CHUNK;
     const long long q_chunks = R * (D / 8);
-    hipLaunchKernelGGL(pairs_scale_q_kernel, dim3((unsigned)((q_chunks + 255) / 256)), dim3(256), 0, st, g, q_chunks,
+    hipLaunchKernelGGL(pairs_scale_q_kernel, dim3((unsigned)std::min<long long>((q_chunks + 255) / 256, 256 * 32)), dim3(256), 0, st, g, q_chunks,
                        1.44269504088896340736f / sqrtf((float)D), flag, Q, sc.qs);
     hipLaunchKernelGGL((attn_pairs_kernel<D, false>), dim3((unsigned)chunks), dim3(C::THREADS), C::BYTES, st, g, 1, sc.qs, Kp, Vt,
                        csize, sc.pair_ptr, sc.seg_count, sc.seg_start, sc.seg_chunk, sc.entries, flag, sc.rec, sc.ml);
