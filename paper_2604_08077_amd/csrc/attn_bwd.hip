@@ -394,7 +394,6 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const 
             auto half = [&](auto hc) __attribute__((always_inline)) {
                 constexpr int H = decltype(hc)::value;
                 f32x4 sacc[NS][2], pacc[NS][2];
-                __builtin_amdgcn_sched_barrier(0);  // phases are not overlapped: that would not fit the register file
                 nat_half_bias<D, NS, H>(kt, n16, q4, qf, le, sacc);
                 nat_half_bias<D, NS, H>(vt, n16, q4, gf, delta, pacc);
                 if (edge) {
@@ -423,7 +422,6 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const 
             };
             half(std::integral_constant<int, 0>{});
             half(std::integral_constant<int, 1>{});
-            __builtin_amdgcn_sched_barrier(0);
             tn_tile<D, NS>(ktt, n16, q4, ds, acc);
             stage ^= 1;
         }
@@ -589,7 +587,6 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
                     }
                     if (WHICH == 1) pinit[k2] = *reinterpret_cast<const f32x4 *>(dv + rb + 4 * k2);
                 }
-                __builtin_amdgcn_sched_barrier(0);  // phases are not overlapped: that would not fit the register file
                 nat_half_from<D, NS, H>(t0, n16, q4, kf, sinit, sacc);
                 if (WHICH == 1) nat_half_from<D, NS, H>(t0 + TILE, n16, q4, vf, pinit, pacc);
                 if (i == j) {  // causal edge inside the own cube: a row attends keys up to its own rank
@@ -617,7 +614,6 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
             };
             half(std::integral_constant<int, 0>{});
             half(std::integral_constant<int, 1>{});
-            __builtin_amdgcn_sched_barrier(0);
             tn_tile<D, NS>(t0 + (WHICH == 0 ? TILE : 2 * TILE), n16, q4, pf, acc);
             };
             tile_work(0);
