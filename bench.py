@@ -204,13 +204,14 @@ def bwd_leg(B, w, sh, Qg, Kg, Vg, ws_att, mask, eff_flops, dense_flops, steps, t
     }
 
 
-def workload_line(B, w, steps):
-    """One of the configuration's other workloads at its first Top-p value, measured like the headline step (pool +
-    select + pack + sparse attention, host clock; dense entry beside it) but reported in a few figures only."""
-    p = float(np.float32(w.top_p[0]))
+def workload_line(B, w, steps, query_corr=0.0, top_p=None):
+    """One of the configuration's other workloads at its first Top-p value (or top_p), measured like the headline
+    step (pool + select + pack + sparse attention, host clock; dense entry beside it) but reported in a few figures
+    only.  query_corr > 0: synth.generate's variant with queries that neighbouring tokens share."""
+    p = float(np.float32(w.top_p[0] if top_p is None else top_p))
     sh = B.Shape.of(w)
     N = B.num_cubes(sh)
-    Q, K, V = synth.generate(w)
+    Q, K, V = synth.generate(w, query_corr=query_corr)
     Qg, Kg, Vg = Q.cuda(), K.cuda(), V.cuda()
     del Q, K, V
     R, words = sh.rows, (N + 31) // 32
@@ -269,7 +270,7 @@ def workload_line(B, w, steps):
     dense_keys = int((np.cumsum(np.concatenate([[0], sizes[:-1]]))[cube] + rank + 1).sum()) * w.Hq
     tf = 4.0 * w.D * keys_total / (att_ms * 1e-3) / 1e12
     return {"workload": f"{w.T}x{w.H}x{w.W} tokens={w.S}, cube {w.ct}x{w.ch}x{w.cw} ({N} cubes), {w.Hq}q/{w.Hkv}kv "
-                        f"heads, head_dim {w.D}, top_p {w.top_p[0]}",
+                        f"heads, head_dim {w.D}, top_p {p:g}" + (f", query correlation {query_corr:g}" if query_corr else ""),
             "ms_per_step": ms, "tokens_per_s": w.S / (ms * 1e-3), "graph_replay_ms_per_step": graph_ms,
             "sparse_attn_ms": att_ms,
             "selected_fraction_of_preceding_cubes": pairs / max(1, preceding),
@@ -529,6 +530,14 @@ def main():
             if name != "C3":
                 out["other_workloads"][name] = workload_line(B, synth.WORKLOADS[name], 3 if name == "C4" else args.steps)
                 torch.cuda.empty_cache()
+        # The headline workload once more with queries that the video tokens of a cube share a component of
+        # (synth.generate's query_corr: a variant outside the configuration's recipe, whose rows select independently
+        # of each other -- the hardest case for a kernel that can only leave out what a whole group of rows skips).
+        # The selected share per row stays what it is; what changes is how much neighbouring rows agree.
+        out["correlated_queries"] = {
+            str(rho): workload_line(B, synth.WORKLOADS["C3"], max(2, args.steps // 2), query_corr=rho, top_p=p)
+            for rho in (0.9, 0.99)}
+        torch.cuda.empty_cache()
     print(json.dumps(out), flush=True)
 
 
