@@ -305,18 +305,6 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
         for (int s = 0; s < NS; ++s) mword_ahead[s] = sel_mask[(size_t)rowid[lr[s]] * g.words];
     }
     int jsize = 0;
-    // Wave-uniform: no row of the wavefront that takes part in the current cube is still without a reference point
-    // (fresh), so softmax_tile_fast may be tried.  A fresh row that did not select the cube does not stand in the way:
-    // its scores start from -inf, its probabilities are 0 whatever the reference.  (With a selection, rows stay fresh
-    // until the first cube they selected; waiting for the last of a wavefront's 32 rows kept the first cubes of every
-    // walk on the long path.)
-    bool quick = false;
-    auto update_quick = [&]() __attribute__((always_inline)) {
-        bool open = false;
-#pragma unroll
-        for (int s = 0; s < NS; ++s) open = open || (fresh[s] && (!MASKED || rsel[s]));
-        quick = __ballot(open) == 0ull;
-    };
     // per-cube constants of the softmax: key limits of every row, and (MASKED) whether the row attends the cube
     auto enter_cube = [&](int j) __attribute__((always_inline)) {
         const bool own = (j == i);
@@ -342,7 +330,6 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
 #pragma unroll
                 for (int s = 0; s < NS; ++s) rsel[s] = (mword[s] >> (j & 31)) & 1u;
             }
-            update_quick();
         }
     };
     TilePos cc = first_tile();  // the tile whose softmax comes next
@@ -350,13 +337,17 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
 
     f32x4 sacc[NS][4];
     bf16x8 pf[NS][2];
+    bool settled = false;  // wave-uniform: no row of the wavefront is fresh any more (softmax_tile_fast may be tried)
     auto softmax_step = [&]() __attribute__((always_inline)) {
         const bool own = (cc.j == i);
         const int key0 = KEY_TILE * cc.t;
         const bool need_mask = (key0 + KEY_TILE > jsize) || (own && g.causal && key0 + KEY_TILE - 1 > rank_lo);
-        if (need_mask || !softmax_tile_fast<NS>(sacc, pf, quick)) {
+        if (need_mask || !softmax_tile_fast<NS>(sacc, pf, settled)) {
             softmax_tile_folded<D, NS>(sacc, pf, oacc, m_run, l_run, fresh, lim, key0, need_mask, q4);
-            update_quick();  // the rows that took part have a reference point now
+            bool open = false;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) open = open || fresh[s];
+            settled = __ballot(open) == 0ull;  // every row of the wavefront has a reference point by now
         }
         const int j0 = cc.j;
         advance(cc);
