@@ -10,7 +10,9 @@
  * Conventions shared by all entry points
  *   - Every data pointer is a DEVICE pointer owned by the caller, contiguous,
  *     16-byte aligned.  The library never allocates or frees device memory and
- *     keeps no state between calls; scratch space is the caller's `workspace`
+ *     keeps no state between calls (beyond remembering, per device, which of its
+ *     kernels have been granted their large LDS and where its one static scratch
+ *     array lies); scratch space is the caller's `workspace`
  *     (size from adaspark_workspace_bytes; contents need not be initialised and
  *     are undefined afterwards).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).

@@ -66,5 +66,24 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     return LIB
 
 
+C_CLIENT_SRC = os.path.join(os.path.dirname(_HERE), "tests", "c_client", "abi_client.c")
+C_CLIENT = os.path.join(os.path.dirname(_HERE), "tests", "c_client", "abi_client")
+
+
+def build_c_client() -> str:
+    """The plain-C client of the C ABI (tests/c_client/abi_client.c): gcc in C99 mode, linked against the built
+    library and the HIP runtime; tests/test_gpu_c_client.py runs it on the GPU machine."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    include = os.path.join(os.path.dirname(_HERE), "include")
+    tmp = C_CLIENT + f".tmp{os.getpid()}"
+    subprocess.check_call(["gcc", "-std=c99", "-O1", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I" + include,
+                           "-I" + os.path.join(rocm, "include"), C_CLIENT_SRC, "-o", tmp, "-L" + _HERE, "-ladaspark",
+                           "-L" + os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
+                           "-Wl,-rpath,$ORIGIN/../../paper_2604_08077_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")])
+    os.replace(tmp, C_CLIENT)
+    return C_CLIENT
+
+
 if __name__ == "__main__":
     print(build(verbose="-v" in sys.argv))
+    print(build_c_client())
