@@ -14,7 +14,11 @@
 // In both, a row's selection bit for the key cube acts as a mask (dense work, like the forward's masked walk).
 // Streamed tiles come from packed, pre-swizzled copies (kvtile.h layouts) straight into LDS: K natural / V natural
 // / K transposed per 64 keys (two runs of the forward's pack kernel), Q, dO natural and transposed per 64 rows in
-// (cube, rank, head of the group) order (bwd_pack_rows_kernel, which also leaves log2-domain log-sum-exp and delta).
+// (cube, rank, head of the group) order (bwd_pack_rows_kernel).
+// The probabilities come out of the MFMAs as exponents: the score products take fp16 operands, Q with the softmax
+// scale in base 2 folded in (the natural copy of Q and the natural copy of K are stored that way), and their
+// accumulators start from minus the row's log-sum-exp in base 2, -inf for a row that did not select the key cube;
+// the dP accumulators start from minus delta.  bwd_pack_rows_kernel leaves both per packed row with that sign.
 #include <algorithm>
 #include <type_traits>
 
@@ -118,7 +122,7 @@ __device__ __forceinline__ f32x4 mfma16(f16x8 a, f16x8 b, f32x4 c)
 }
 
 // Row r of cube c in the packed row order: rank r / G, head r % G of the group.
-// Q, dO natural and transposed per 64-row tile; delta = dO.O; lse2 = lse * log2(e).
+// Q, dO natural and transposed per 64-row tile; deltap = -dO.O; lse2p = -lse * log2(e) (-inf for padding rows).
 template <int D>
 __global__ __launch_bounds__(256) void bwd_pack_rows_kernel(Geom g, const uint16_t *__restrict__ Q,
                                                             const uint16_t *__restrict__ dO,
