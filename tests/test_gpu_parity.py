@@ -398,10 +398,11 @@ def test_many_large_cubes_through_every_kernel(B, oracle):
     sampled_case(B, oracle, w, (0.5,), 1024, check_dense=True, dense_rows=48)
 
 
-@pytest.mark.parametrize("name,p", [("C3", 0.9), ("C5", 0.9)])
+@pytest.mark.parametrize("name,p", [("C3", 0.9), ("C5", 0.9), ("C4", 0.9)])
 def test_selection_every_row(B, oracle, name, p):
-    """Masks and counts of every row of the 65,536-token configuration and of the ragged entropy-stress one against
-    the oracle (the selection oracle is cheap next to the attention oracle: attention outputs stay sampled)."""
+    """Masks and counts of every row of the 65,536-token configuration, of the ragged entropy-stress one and of the
+    262,144-token one (7.3 M rows through the kernel for more than 256 candidates) against the oracle (the selection
+    oracle is cheap next to the attention oracle: attention outputs stay sampled)."""
     w = synth.WORKLOADS[name]
     print(f"case {w.name} selection of every row, p={p}", flush=True)
     sh, osh = B.Shape.of(w), oshape(oracle, w)
