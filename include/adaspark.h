@@ -168,7 +168,9 @@ int adaspark_select_status_offset(const adaspark_shape *shape, size_t *offset);
  * anything is enqueued; 4 MiB covers 262,144 tokens in 1,024 cubes with 4 KV heads of 128.  All calls on one GPU share
  * that GPU's array: it holds whatever the last call left, every call rewrites what it reads, and two calls that
  * overlap in time on one GPU (different streams or threads) race -- serialise them, or use adaspark_cube_select
- * with a workspace each.  Other arguments and outputs as adaspark_cube_select.
+ * with a workspace each.  Other arguments and outputs as adaspark_cube_select, except that the status word of the
+ * call lies in the library's array, out of the caller's reach: whether the compact list fitted is read off the list
+ * itself (row_ptr[tokens*q_heads] <= capacity).
  */
 #define ADASPARK_NOALLOC_SCRATCH_BYTES (4u << 20)
 int adaspark_cube_select_noalloc(const adaspark_shape *shape, const void *Q, const float *kbar, float top_p, int causal,
