@@ -212,9 +212,11 @@ int adaspark_cube_select_shared(const adaspark_shape *shape, const void *Q, cons
  *   Q,K,V     in   bf16 (layouts above)
  *   sel_mask  in   as written by adaspark_cube_select
  *   O         out  bf16 [tokens][q_heads][head_dim]
- *   lse       out  fp32 [tokens*q_heads] natural-log sum-exp of the scaled logits, or NULL.  (The masked-walk and
- *                  dense kernels multiply Q by the softmax scale and round it to bf16 once more: a score, and
- *                  with it this value, is accurate to about 2^-9 * sum_d |q_d k_d| / sqrt(head_dim).)
+ *   lse       out  fp32 [tokens*q_heads] natural-log sum-exp of the scaled logits, or NULL.  (The masked-walk,
+ *                  dense and key-stationary kernels multiply Q by the softmax scale and round it to fp16: a score,
+ *                  and with it this value, is accurate to about 2^-12 * sum_d |q_d k_d| / sqrt(head_dim).)
+ * The score products q.k take fp16 operands: K converts exactly while |k| <= 65504, the limit of that format; larger
+ * magnitudes, in K or in the scaled Q, saturate there.  P.V takes bf16 operands as they are.
  *   workspace      adaspark_workspace_bytes(ADASPARK_CALL_SPARSE_ATTN), or more: with
  *                  adaspark_pairs_workspace_bytes(...) the key-stationary kernel becomes a candidate
  */

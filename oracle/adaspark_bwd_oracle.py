@@ -92,12 +92,13 @@ def row_backward(shape: base.Shape, Q, K, V, sel_mask_row, r: int, do, o_given, 
 def delta_error_bound(do, o, p, Va, absdot):
     """Tolerance model, not part of the gradient: how far delta = do.O can lie from the exact do.o when O comes from a
     forward that rounds every probability and the output to bf16 and whose scores carry a relative perturbation of
-    2^-9 in every product q_d k_d (`absdot`: the row's largest sum_d |q_d k_d| / sqrt(D)).  Element d of such an O is a
-    sum of terms p_j v_jd, each off by about 2^-9 (1 + absdot) of itself, independently: about seven standard
-    deviations of that, 2^-7 (1 + absdot) sqrt(sum_j p_j^2 v_jd^2), plus the output's own rounding 2^-8 |o_d|; the
-    elements' bounds are added up with the weights |do_d|."""
+    2^-12 in every product q_d k_d -- a query operand rounded to fp16 -- (`absdot`: the row's largest
+    sum_d |q_d k_d| / sqrt(D)).  Element d of such an O is a sum of terms p_j v_jd, each off by about
+    2^-9 (1 + absdot / 8) of itself, independently: about seven standard deviations of that,
+    2^-7 (1 + absdot / 8) sqrt(sum_j p_j^2 v_jd^2), plus the output's own rounding 2^-8 |o_d|; the elements' bounds are
+    added up with the weights |do_d|."""
     t_o = np.sqrt((p * p) @ (Va * Va))
-    return float(np.abs(do) @ (2.0 ** -8 * np.abs(o) + 2.0 ** -7 * (1.0 + absdot) * t_o))
+    return float(np.abs(do) @ (2.0 ** -8 * np.abs(o) + 2.0 ** -7 * (1.0 + absdot / 8.0) * t_o))
 
 
 def sparse_attn_bwd(shape: base.Shape, Q, K, V, sel_mask, dO, O=None, scales=None):

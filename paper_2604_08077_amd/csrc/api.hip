@@ -260,7 +260,7 @@ int adaspark_kv_pack(const adaspark_shape *shape, const void *K, const void *V, 
     const Geom g = make_geom(*shape);
     if ((rc = workspace_check(g, workspace, workspace_bytes)) != ADASPARK_OK) return rc;
     const hipError_t e = launch_kv_pack(g, static_cast<const uint16_t *>(K), static_cast<const uint16_t *>(V), workspace,
-                                        static_cast<hipStream_t>(stream));
+                                        true, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? ADASPARK_OK : ADASPARK_EHIP;
 }
 

@@ -31,7 +31,7 @@ constexpr int BWD_ROWS = 256;   // rows (dQ kernel) or keys (dK/dV kernel) per w
 constexpr float BWD_LOG2E = 1.44269504088896340736f;
 
 struct BwdWorkspace {
-    void *packA;             // launch_kv_pack(K, V): natural K first, turned into fp16 (its V^T half is not used here)
+    void *packA;             // launch_kv_pack(K, V): natural K first, in fp16 (its V^T half is not used here)
     void *packB;             // launch_kv_pack(V, K): natural V, then K transposed
     uint16_t *Qn, *Qt, *dOn, *dOt;  // [Hkv][N][tpcr][64 * D]; Qn: fp16, scaled (score operand), the others bf16
     // minus the log-sum-exp in base 2 and minus delta per packed row (what the score and dP products start from)
@@ -97,21 +97,8 @@ __device__ __forceinline__ void dma_dword_s(uint32_t lds_addr, const void *sbase
                  : "memory", "m0");
 }
 
-// Score operands of the backward kernels: fp16.  The scores are rebuilt from Q with the softmax scale in base 2 folded
-// in (so that they leave the MFMAs as the exponents of the probabilities); rounded to bf16 that product would cost
-// every probability a relative error of the size of its own bf16 rounding, in fp16 (three more mantissa bits) an
-// eighth of that.  K converts exactly (bf16's 8 significant bits fit) as long as its magnitude lies in fp16's range;
-// beyond it both operands saturate at +-65504, below 6e-5 they lose bits no score can notice.
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-
-__device__ __forceinline__ f16x8 to_f16(bf16x8 x, float scale)
-{
-    f16x8 r;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) r[e] = (_Float16)fminf(fmaxf((float)x[e] * scale, -65504.f), 65504.f);
-    return r;
-}
-
+// Score operands of the backward kernels: fp16, as in the forward (attn_tile.h: to_f16).  The scores are rebuilt from
+// Q with the softmax scale in base 2 folded in, so that they leave the MFMAs as the exponents of the probabilities.
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c)
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
@@ -186,16 +173,6 @@ __global__ __launch_bounds__(256) void bwd_pack_rows_kernel(Geom g, const uint16
             make_uint4(wq[0], wq[1], wq[2], wq[3]);
         *reinterpret_cast<uint4 *>(reinterpret_cast<char *>(dOt + tile_base) + vt_tile_off(d, kc)) =
             make_uint4(wg[0], wg[1], wg[2], wg[3]);
-    }
-}
-
-// The packed natural copy of K, bf16 -> fp16 in place (same element size, so the tiles' layout stays): the score
-// operand of the row-stationary kernel.
-__global__ __launch_bounds__(256) void bwd_keys_to_f16_kernel(uint16_t *__restrict__ tiles, size_t chunks)
-{
-    for (size_t x = (size_t)blockIdx.x * 256 + threadIdx.x; x < chunks; x += (size_t)gridDim.x * 256) {
-        bf16x8 *p = reinterpret_cast<bf16x8 *>(tiles) + x;
-        *reinterpret_cast<f16x8 *>(p) = to_f16(*p, 1.0f);
     }
 }
 
@@ -648,16 +625,10 @@ static hipError_t launch_bwd_d(const Geom &g, const uint16_t *Q, const uint16_t 
                                uint16_t *dQ, uint16_t *dK, uint16_t *dV, void *ws, hipStream_t st)
 {
     const BwdWorkspace w = bwd_workspace(g, ws);
-    hipError_t e = launch_kv_pack(g, K, V, w.packA, st);
+    hipError_t e = launch_kv_pack(g, K, V, w.packA, true, st);   // natural K as fp16: the score operand
     if (e != hipSuccess) return e;
-    e = launch_kv_pack(g, V, K, w.packB, st);
+    e = launch_kv_pack(g, V, K, w.packB, false, st);             // natural V stays bf16
     if (e != hipSuccess) return e;
-    {
-        const size_t chunks = (size_t)g.Hkv * g.N * g.TPC * KEY_TILE * D / 8;
-        hipLaunchKernelGGL(bwd_keys_to_f16_kernel, dim3((unsigned)std::min<size_t>((chunks + 255) / 256, 8192)), dim3(256),
-                           0, st, reinterpret_cast<uint16_t *>(w.packA), chunks);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-    }
     hipLaunchKernelGGL((bwd_pack_rows_kernel<D>), dim3(w.tpcr, g.N, g.Hkv), dim3(256), 0, st, g, Q, dO, O, lse, w.tpcr,
                        w.Qn, w.Qt, w.dOn, w.dOt, w.lse2, w.delta);
     if ((e = hipGetLastError()) != hipSuccess) return e;

@@ -271,9 +271,13 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_compact_kernel(
     // The compiler places the wait for a load in front of the first use of its result.  Naming the registers
     // here puts that wait here, once, instead of in front of every S^T of the main loop (where it would also
     // hold up the direct-to-LDS loads in flight).
+    // Settled, the operands are turned into the score products' fp16 (attn_tile.h; this kernel applies the softmax
+    // scale to the scores afterwards, so the conversion is exact within fp16's range).
     auto settle_q = [&](bf16x8 (&q)[KSTEPS]) __attribute__((always_inline)) {
 #pragma unroll
         for (int c = 0; c < KSTEPS; ++c) asm volatile("" : "+v"(q[c]));
+#pragma unroll
+        for (int c = 0; c < KSTEPS; ++c) q[c] = score_operand(q[c], 1.0f);
     };
 
     const float c2 = 1.44269504088896340736f / sqrtf((float)D);
@@ -359,7 +363,7 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_compact_kernel(
             for (int s = 0; s < NS; ++s) lr[s] = lr_n[s];
             if (ns > 0) {
 #pragma unroll
-                for (int c = 0; c < KSTEPS; ++c) qf[0][c] = qf_n[c];
+                for (int c = 0; c < KSTEPS; ++c) qf[0][c] = score_operand(qf_n[c], 1.0f);
             }
             // a second slab is rare (own cube, unusually popular cube): its Q operands come late
 #pragma unroll

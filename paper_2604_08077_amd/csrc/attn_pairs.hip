@@ -57,8 +57,8 @@ bool pairs_supported(const Geom &g)
 // Scratch memory of the pair path, carved from `bytes` bytes at `base` (256-byte aligned):
 //   flags      i32 [4 + Hkv]  the kernel-choice flags (geom.h)
 //   kv_sel     u64 [Hkv]      selected (row, cube) pairs per KV head
-//   qs         bf16 [R][D]    Q times the softmax scale in base 2, rounded to bf16 again (rows of the heads this
-//                             path takes): the operand of the score MFMAs, see softmax_tile_folded
+//   qs         fp16 [R][D]    Q times the softmax scale in base 2 (rows of the heads this path takes): the operand of
+//                             the score MFMAs, see softmax_tile_folded
 //   cnt        i32 [R]        records per row = selected cubes + 1 (the own cube); 0 for rows of heads left to a
 //                             row-stationary kernel
 //   pair_ptr   i64 [R + 1]    exclusive scan of cnt: a row's records, in cube order, the own cube last
@@ -234,7 +234,8 @@ __global__ void pair_keep_kernel(Geom g, long long R, const int *__restrict__ fl
     if (r < R && flags[FLAG_KV + (int)(r % g.Hq) / g.G] != 3) cnt[r] = 0;
 }
 
-// qs = bf16(Q * log2(e)/sqrt(D)) for the rows of the heads this path takes; 8 elements per thread.
+// qs = fp16(Q * log2(e)/sqrt(D)) for the rows of the heads this path takes (the score operand: attn_tile.h); 8 elements
+// per thread.
 __global__ void pairs_scale_q_kernel(Geom g, long long chunks, float c2, const int *__restrict__ flags,
                                      const uint16_t *__restrict__ Q, uint16_t *__restrict__ qs)
 {
@@ -244,7 +245,7 @@ __global__ void pairs_scale_q_kernel(Geom g, long long chunks, float c2, const i
         const long long row = x / (g.D / 8);
         if (flags[FLAG_KV + (int)(row % g.Hq) / g.G] != 3) continue;
         const bf16x8 q = *reinterpret_cast<const bf16x8 *>(Q + x * 8);
-        *reinterpret_cast<bf16x8 *>(qs + x * 8) = prescale_q(q, c2);
+        *reinterpret_cast<bf16x8 *>(qs + x * 8) = score_operand(q, c2);
     }
 }
 

@@ -78,6 +78,28 @@ __device__ __forceinline__ float quad_sum(float x)
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
+// Score operands are fp16.  The score products S^T = K.Q^T take the packed natural K tile, which kv_pack writes as
+// fp16 (K's bf16 values have 8 significant bits and convert exactly while |k| <= 65504, the limit of the format;
+// beyond it they saturate there), and Q converted here: times `scale` -- the softmax scale in base 2,
+// log2(e)/sqrt(D), in the kernels that fold it in, so that the scores leave the MFMAs in the exponent's units -- and
+// rounded to fp16's 11 significant bits (relative 2^-12: an eighth of what a second bf16 rounding would cost every
+// product of a score).  The 128-bit operand registers keep the type bf16x8 whatever they hold; score_mfma reads both
+// of its operands as fp16.
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ f16x8 to_f16(bf16x8 x, float scale)
+{
+    f16x8 r;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r[e] = (_Float16)fminf(fmaxf((float)x[e] * scale, -65504.f), 65504.f);
+    return r;
+}
+__device__ __forceinline__ bf16x8 score_operand(bf16x8 q, float scale) { return __builtin_bit_cast(bf16x8, to_f16(q, scale)); }
+__device__ __forceinline__ f32x4 score_mfma(bf16x8 k, bf16x8 q, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, k), __builtin_bit_cast(f16x8, q), c, 0, 0, 0);
+}
+
 // S^T = K.Q^T for one 64-key tile and slabs S0..S1-1 of a wavefront.  MFMA M-row m of key group kg carries
 // tile key 32*(kg/2) + 8*(m/4) + 4*(kg%2) + m%4, so that a lane's registers of groups 2sl, 2sl+1 hold keys
 // 32sl + 8*q4 + 0..7: the operand order of the P.V MFMA.  One K operand load serves all slabs of the range.
@@ -97,7 +119,7 @@ __device__ __forceinline__ void qk_tile(const unsigned char *kt, int n16, int q4
             const bf16x8 af = *reinterpret_cast<const bf16x8 *>(kt + k_tile_off<D>(krow, 4 * c + q4));
 #pragma unroll
             for (int s = S0; s < S1; ++s)
-                sacc[s][kg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, qf[s][c], sacc[s][kg], 0, 0, 0);
+                sacc[s][kg] = score_mfma(af, qf[s][c], sacc[s][kg]);
         }
 }
 
@@ -173,16 +195,6 @@ __device__ __forceinline__ void softmax_tile(f32x4 (&sacc)[NS][4], bf16x8 (&pf)[
 #pragma unroll
         for (int s = S0; s < S1; ++s) l_run[s] *= alpha[s];
     }
-}
-
-// Q operand times the softmax scale in base 2, log2(e)/sqrt(D), rounded to bf16 again: the scores then come out of
-// the MFMAs in the exponent's units (the rounding adds an error of the size of the bf16 rounding of the output).
-__device__ __forceinline__ bf16x8 prescale_q(bf16x8 q, float c2)
-{
-    bf16x8 r;
-#pragma unroll
-    for (int x = 0; x < 8; ++x) r[x] = (__bf16)((float)q[x] * c2);
-    return r;
 }
 
 // Online softmax with the running maximum folded into the MFMA accumulator: the scores arrive as
@@ -355,8 +367,7 @@ __device__ __forceinline__ void mfma_phase_from(const unsigned char *vt, const u
             const int c = (r - RV) / 4, kg = (r - RV) % 4;
 #pragma unroll
             for (int s = 0; s < NS; ++s)
-                sacc[s][kg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                    af, qf[s][c], c == 0 ? sinit[s] : sacc[s][kg], 0, 0, 0);
+                sacc[s][kg] = score_mfma(af, qf[s][c], c == 0 ? sinit[s] : sacc[s][kg]);
         }
         if (r + PF < R) ring[r % PF] = phase_operand<D, DO_PV, DO_QK>(vt, kt, n16, q4, r + PF);
         __builtin_amdgcn_sched_barrier(0);

@@ -272,7 +272,7 @@ __global__ __launch_bounds__(FWD_MAX_THREADS) void attn_walk_kernel(
     for (int s = 0; s < NS; ++s) {
         const uint16_t *qrow = Q + (size_t)rowid[lr[s]] * D + 8 * q4;
 #pragma unroll
-        for (int c = 0; c < KSTEPS; ++c) qf[s][c] = prescale_q(*reinterpret_cast<const bf16x8 *>(qrow + 32 * c), c2);
+        for (int c = 0; c < KSTEPS; ++c) qf[s][c] = score_operand(*reinterpret_cast<const bf16x8 *>(qrow + 32 * c), c2);
     }
 #pragma unroll
     for (int s = 0; s < NS; ++s)

@@ -132,7 +132,7 @@ hipError_t launch_cube_select_shared(const Geom &g, const uint16_t *Q, const flo
 size_t scan_tile_sum_bytes(long long n);
 void launch_exclusive_scan(const int32_t *count, long long n, long long *tile_sum, int64_t *out, hipStream_t st);
 size_t attn_workspace_bytes(const Geom &g);
-hipError_t launch_kv_pack(const Geom &g, const uint16_t *K, const uint16_t *V, void *ws, hipStream_t st);
+hipError_t launch_kv_pack(const Geom &g, const uint16_t *K, const uint16_t *V, void *ws, bool natural_f16, hipStream_t st);
 // Kernel-choice flags of the sparse attention entries (ints, written and read on the device only):
 //   [FLAG_MODE]      the row-stationary kernel that runs: 1 compaction, 2 masked walk
 //   [FLAG_ESTIMATE]  smallest share of selected candidate cubes over the KV heads, permille, from a sample of rows

@@ -169,7 +169,7 @@ def test_delta_sensitivity_diagnostics(oracle):
     for r in range(R):
         n, a, g, att, s, p, o, ds = _explicit_row(oracle, sh, w, q, k, v, mask, r, dO[r])
         absdot = max(sum(abs(float(q[n, a, d]) * float(k[m, g, d])) for d in range(w.D)) for m in att) * c
-        derr[r] = sum(abs(float(dO[r, d])) * (2.0 ** -8 * abs(o[d]) + 2.0 ** -7 * (1.0 + absdot) *
+        derr[r] = sum(abs(float(dO[r, d])) * (2.0 ** -8 * abs(o[d]) + 2.0 ** -7 * (1.0 + absdot / 8.0) *
                                               np.sqrt(sum((p[x] * float(v[m, g, d])) ** 2 for x, m in enumerate(att))))
                       for d in range(w.D))
         if r % 37 == 0:

@@ -68,12 +68,12 @@ def check_outputs(name, gpu_out, ref_out):
 def lse_bound(absdot, rounded_q=True):
     """Per-row tolerance of the optional log-sum-exp output, from the kernels' arithmetic.  The row sum is a sum of
     probabilities rounded to bf16, each off by at most 2^-9 of itself: the logarithm moves by at most 2^-9.  The
-    masked-walk, dense and key-stationary kernels also round the query, times the softmax scale, to bf16 once more:
-    every product q_d k_d of a score is then off by at most 2^-9 of itself, a score by at most 2^-9 times
-    `absdot` = sum_d |q_d k_d| / sqrt(D) maximised over the row's attended keys (the oracle computes it), and the
-    log-sum-exp, whose derivative in the scores is a probability vector, by no more than the largest such movement.
-    1e-4 covers the fp32 accumulation and the hardware exponential and logarithm."""
-    return 2.0 ** -9 * (1.0 + (np.asarray(absdot) if rounded_q else 0.0)) + 1e-4
+    masked-walk, dense and key-stationary kernels also round the query, times the softmax scale, to fp16: every
+    product q_d k_d of a score is then off by at most 2^-12 of itself, a score by at most 2^-12 times `absdot` =
+    sum_d |q_d k_d| / sqrt(D) maximised over the row's attended keys (the oracle computes it), and the log-sum-exp,
+    whose derivative in the scores is a probability vector, by no more than the largest such movement.  1e-4 covers
+    the fp32 accumulation and the hardware exponential and logarithm."""
+    return 2.0 ** -9 + 2.0 ** -12 * (np.asarray(absdot) if rounded_q else 0.0) + 1e-4
 
 
 PAIRS_TEST_BYTES = 48e9  # largest workspace the tests allocate for the key-stationary kernel

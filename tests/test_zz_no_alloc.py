@@ -41,14 +41,25 @@ def run_both(B, w, p):
     torch.cuda.synchronize()
     assert torch.cuda.memory_allocated() == before
     print(f"[{w.name}] p={p} rows={sh.rows} selected pairs={cap}", flush=True)
-    same = {"sel_mask": torch.equal(m2, mask), "sel_count": torch.equal(c2, count), "row_ptr": torch.equal(rp2, row_ptr),
-            "cube_idx": torch.equal(ci2[:cap], cube_idx[:cap])}
-    assert all(same.values()), same
+    assert differences({"sel_mask": (m2, mask), "sel_count": (c2, count), "row_ptr": (rp2, row_ptr),
+                        "cube_idx": (ci2[:cap], cube_idx[:cap])}) == {}
     # without the compact list
     m3, c3 = torch.full_like(mask, -1), torch.full_like(count, -1)
     B.cube_select_noalloc(sh, Qg, kbar, p32, m3, c3)
     torch.cuda.synchronize()
-    assert torch.equal(m3, mask) and torch.equal(c3, count)
+    assert differences({"sel_mask, no list": (m3, mask), "sel_count, no list": (c3, count)}) == {}
+
+
+def differences(pairs):
+    """{name: (number of differing elements, first differing flat index, the two values there)} for the pairs that
+    differ: what a failure report needs to name the output and the place."""
+    out = {}
+    for name, (got, want) in pairs.items():
+        if not torch.equal(got, want):
+            ne = (got != want).reshape(-1)
+            first = int(torch.nonzero(ne)[0].item())
+            out[name] = (int(ne.sum().item()), first, int(got.reshape(-1)[first].item()), int(want.reshape(-1)[first].item()))
+    return out
 
 
 def test_two_calls_in_a_row_the_second_smaller(B):
