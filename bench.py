@@ -452,6 +452,8 @@ def main():
                         f"{w.Hq}q/{w.Hkv}kv heads, head_dim {w.D}, top_p {args.top_p}, causal, batch 1",
             "top_p": args.top_p,
             "selection": "shared by the GQA group" if args.shared_selection else "per query head",
+            "arithmetic": "bf16 in and out; q.k products fp16 x fp16 -> fp32 (MFMA), p.v products bf16 x bf16 -> fp32, "
+                          "softmax fp32; selection logits fp32-accurate (three bf16 MFMA terms)",
             "query_corr": args.query_corr,
         },
         "effective_tflops": attn_tflops,
