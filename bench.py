@@ -179,7 +179,7 @@ def ffn_leg(B, w, steps, dense=True):
 
 # Bytes the three backward kernels of one call move between the L2 caches and the fabric (rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE, scaled by a copy of known size; see profiles/), keyed by (workload, top_p).
-BWD_MEASURED_TRAFFIC_BYTES = {("C3", 0.9): 4.82e10}
+BWD_MEASURED_TRAFFIC_BYTES = {("C3", 0.9): 4.58e10}
 
 
 def bwd_leg(B, w, sh, Qg, Kg, Vg, ws_att, mask, eff_flops, dense_flops, steps, top_p):

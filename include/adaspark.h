@@ -287,10 +287,9 @@ int adaspark_dense_attn_packed(const adaspark_shape *shape, const void *Q, const
  *   dQ         out  bf16 [tokens][q_heads][head_dim];  dK, dV  out  bf16 [tokens][kv_heads][head_dim]
  *   workspace       adaspark_workspace_bytes(ADASPARK_CALL_ATTN_BWD): packed copies of K, V (natural and
  *                   transposed), of Q and dO (natural and transposed, in cube order) and two floats per row
- * p is rebuilt from lse in fp32; the score products that rebuild it take Q (times the softmax scale) and K in fp16
- * -- K converts exactly while |k| <= 65504, the limit of that format; larger magnitudes, in K or in the scaled Q,
- * saturate there -- p and dS are rounded to bf16 for the other MFMA products, sums are fp32, outputs are rounded to
- * bf16 once.  Limits as for the forward, and tokens*q_heads*ceil(cubes/32) < 2^30; causal != 0 only.
+ * p is rebuilt from lse in fp32 from exact score products (bf16 x bf16 accumulated in fp32, the softmax scale applied
+ * in fp32); p and dS are rounded to bf16 for the other MFMA products, sums are fp32, outputs are rounded to bf16
+ * once.  Limits as for the forward, and tokens*q_heads*ceil(cubes/32) < 2^30; causal != 0 only.
  */
 int adaspark_sparse_attn_bwd(const adaspark_shape *shape, const void *Q, const void *K, const void *V, const void *O,
                              const float *lse, const void *dO, const uint32_t *sel_mask, int causal, void *dQ,

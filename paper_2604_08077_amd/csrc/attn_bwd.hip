@@ -15,10 +15,11 @@
 // Streamed tiles come from packed, pre-swizzled copies (kvtile.h layouts) straight into LDS: K natural / V natural
 // / K transposed per 64 keys (two runs of the forward's pack kernel), Q, dO natural and transposed per 64 rows in
 // (cube, rank, head of the group) order (bwd_pack_rows_kernel).
-// The probabilities come out of the MFMAs as exponents: the score products take fp16 operands, Q with the softmax
-// scale in base 2 folded in (the natural copy of Q and the natural copy of K are stored that way), and their
-// accumulators start from minus the row's log-sum-exp in base 2, -inf for a row that did not select the key cube;
-// the dP accumulators start from minus delta.  bwd_pack_rows_kernel leaves both per packed row with that sign.
+// The score products take Q and K as they are (bf16 x bf16 -> fp32: exact products, so the rebuilt probabilities
+// carry nothing but their own rounding, whatever the size of the scores) and their accumulators start from
+// -lse * sqrt(D), -inf for a row that did not select the key cube: the accumulator times the softmax scale in base
+// 2 is then the exponent of the probability, and the selection costs no instruction per score.  The dP accumulators
+// start from minus delta.  bwd_pack_rows_kernel leaves both start values per packed row.
 #include <algorithm>
 #include <type_traits>
 
@@ -31,10 +32,10 @@ constexpr int BWD_ROWS = 256;   // rows (dQ kernel) or keys (dK/dV kernel) per w
 constexpr float BWD_LOG2E = 1.44269504088896340736f;
 
 struct BwdWorkspace {
-    void *packA;             // launch_kv_pack(K, V): natural K first, in fp16 (its V^T half is not used here)
+    void *packA;             // launch_kv_pack(K, V): natural K first (its V^T half is not used here)
     void *packB;             // launch_kv_pack(V, K): natural V, then K transposed
-    uint16_t *Qn, *Qt, *dOn, *dOt;  // [Hkv][N][tpcr][64 * D]; Qn: fp16, scaled (score operand), the others bf16
-    // minus the log-sum-exp in base 2 and minus delta per packed row (what the score and dP products start from)
+    uint16_t *Qn, *Qt, *dOn, *dOt;  // [Hkv][N][tpcr][64 * D]
+    // -lse * sqrt(D) and -delta per packed row (what the score and dP products start from)
     float *lse2, *delta;     // [Hkv][N][tpcr * 64]; padding rows: -inf, 0
     unsigned long long *colmask;  // [Hkv][N (key cube j)][N (row cube i)][tpcr]: bit k = row 64 t + k of cube i selects j
     int tpcr;                // 64-row tiles per cube = ceil(Cmax * G / 64)
@@ -97,19 +98,13 @@ __device__ __forceinline__ void dma_dword_s(uint32_t lds_addr, const void *sbase
                  : "memory", "m0");
 }
 
-// Score operands of the backward kernels: fp16, as in the forward (attn_tile.h: to_f16).  The scores are rebuilt from
-// Q with the softmax scale in base 2 folded in, so that they leave the MFMAs as the exponents of the probabilities.
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c)
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
-__device__ __forceinline__ f32x4 mfma16(f16x8 a, f16x8 b, f32x4 c)
-{
-    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
-}
 
 // Row r of cube c in the packed row order: rank r / G, head r % G of the group.
-// Q, dO natural and transposed per 64-row tile; deltap = -dO.O; lse2p = -lse * log2(e) (-inf for padding rows).
+// Q, dO natural and transposed per 64-row tile; deltap = -dO.O; lse2p = -lse * sqrt(D) (-inf for padding rows).
 template <int D>
 __global__ __launch_bounds__(256) void bwd_pack_rows_kernel(Geom g, const uint16_t *__restrict__ Q,
                                                             const uint16_t *__restrict__ dO,
@@ -144,7 +139,7 @@ __global__ __launch_bounds__(256) void bwd_pack_rows_kernel(Geom g, const uint16
                 part = fmaf(__uint_as_float(gw[e] << 16), __uint_as_float(ow[e] << 16), part);
                 part = fmaf(__uint_as_float(gw[e] & 0xffff0000u), __uint_as_float(ow[e] & 0xffff0000u), part);
             }
-            l2 = lse[rowid] * BWD_LOG2E;
+            l2 = lse[rowid] * sqrtf((float)D);  // = (lse in base 2) / (softmax scale in base 2)
         }
 #pragma unroll
         for (int d = CPR / 2; d >= 1; d >>= 1) part += __shfl_xor(part, d, 64);
@@ -152,10 +147,7 @@ __global__ __launch_bounds__(256) void bwd_pack_rows_kernel(Geom g, const uint16
             lse2p[tile * 64 + k] = -l2;
             deltap[tile * 64 + k] = -part;
         }
-        // The natural copy of Q feeds the score products of the key-stationary kernels only: fp16, with the softmax
-        // scale in base 2 folded in.  The transposed copy (dK^T += Q^T.dS) stays as it is.
-        *reinterpret_cast<f16x8 *>(reinterpret_cast<char *>(Qn + tile_base) + k_tile_off<D>(k, col)) =
-            to_f16(__builtin_bit_cast(bf16x8, qq), BWD_LOG2E / sqrtf((float)D));
+        *reinterpret_cast<uint4 *>(reinterpret_cast<char *>(Qn + tile_base) + k_tile_off<D>(k, col)) = qq;
         *reinterpret_cast<uint4 *>(reinterpret_cast<char *>(dOn + tile_base) + k_tile_off<D>(k, col)) = gg;
         *reinterpret_cast<uint4 *>(&qs[k][col * 8]) = qq;
         *reinterpret_cast<uint4 *>(&gs[k][col * 8]) = gg;
@@ -201,7 +193,7 @@ __global__ __launch_bounds__(64) void bwd_colmask_kernel(Geom g, const uint32_t 
 }
 
 // Half H of qk_tile: the products of a natural tile's rows 32 H .. 32 H + 31 with the B operands of NS slabs (OP:
-// bf16x8 or f16x8, the tile's element type with it).  acc[s][k2][v] belongs to tile row 32 H + 8 q4 + 4 k2 + v.
+// the operand type, bf16x8).  acc[s][k2][v] belongs to tile row 32 H + 8 q4 + 4 k2 + v.
 // Working a tile in two halves keeps half as many accumulators alive.  The accumulators of slab s start from bias[s],
 // a value of the slab's row (the lane's column): the products come out with it added.
 template <int D, int NS, int H, typename OP>
@@ -294,8 +286,7 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const 
     int rr[NS], rank[NS];
     size_t rowid[NS];
     bool valid[NS];
-    f16x8 qf[NS][KSTEPS];
-    bf16x8 gf[NS][KSTEPS];
+    bf16x8 qf[NS][KSTEPS], gf[NS][KSTEPS];
     float lse2[NS], delta[NS], psum[NS];
     size_t prow[NS];
 #pragma unroll
@@ -308,15 +299,15 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const 
         rowid[s] = (size_t)token_of(g, box, rank[s]) * g.Hq + kv * g.G + rr[s] % g.G;
 #pragma unroll
         for (int c = 0; c < KSTEPS; ++c) {
-            // Q in fp16 with the softmax scale in base 2: the scores then leave the MFMAs as exponents
-            qf[s][c] = to_f16(*reinterpret_cast<const bf16x8 *>(Q + rowid[s] * D + 32 * c + 8 * q4),
-                              BWD_LOG2E / sqrtf((float)D));
+            qf[s][c] = *reinterpret_cast<const bf16x8 *>(Q + rowid[s] * D + 32 * c + 8 * q4);
             gf[s][c] = *reinterpret_cast<const bf16x8 *>(dO + rowid[s] * D + 32 * c + 8 * q4);
         }
         prow[s] = ((size_t)kv * g.N + i) * tpcr * 64 + rr[s];
-        lse2[s] = -lse2p[prow[s]];   // (both stored with a minus sign, for the key-stationary kernels)
+        lse2[s] = lse2p[prow[s]];    // -lse * sqrt(D): what the score products start from
         delta[s] = deltap[prow[s]];  // minus delta: what the dP products start from
     }
+
+    const float c2 = BWD_LOG2E / sqrtf((float)D);  // softmax scale in base 2
 
     // tile stream: cubes 0..i, the tiles of each that hold keys
     const size_t head_tiles = (size_t)kv * g.N * g.TPC;
@@ -357,7 +348,7 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const 
         float le[NS];
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            le[s] = -lse2[s];
+            le[s] = lse2[s];
             if (MASKED && j < i) {
                 if ((j & 31) == 0) mw[s] = sel_mask[rowid[s] * g.words + (j >> 5)];
                 if (!((mw[s] >> (j & 31)) & 1u)) le[s] = -INFINITY;
@@ -396,7 +387,7 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const 
                     for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
                         for (int v = 0; v < 4; ++v) {
-                            const float p = __builtin_amdgcn_exp2f(sacc[s][k2][v]);
+                            const float p = __builtin_amdgcn_exp2f(sacc[s][k2][v] * c2);
                             psum[s] += p;
                             ds[s][H][4 * k2 + v] = (__bf16)(p * pacc[s][k2][v]);
                         }
@@ -414,7 +405,7 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dq_kernel(Geom g, const 
     for (int s = 0; s < NS; ++s) {
         const float total = quad_sum(psum[s]);
         if (!valid[s]) continue;
-        if (q4 == 0) lse2p[prow[s]] = -(lse2[s] + log2f(total));
+        if (q4 == 0) lse2p[prow[s]] = lse2[s] - log2f(total) / c2;
         const float scale = 1.0f / (sqrtf((float)D) * total);
 #pragma unroll
         for (int e = 0; e < D / 16; ++e) {
@@ -473,8 +464,7 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
     int key[NS];
     bool valid[NS];
     size_t krow[NS];
-    f16x8 kf[NS][KSTEPS];
-    bf16x8 vf[NS][KSTEPS];
+    bf16x8 kf[NS][KSTEPS], vf[NS][KSTEPS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
         key[s] = kb * BWD_ROWS + wave * 32 + s * 16 + n16;
@@ -482,10 +472,11 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
         krow[s] = ((size_t)token_of(g, box, valid[s] ? key[s] : size_j - 1) * g.Hkv + kv) * D;
 #pragma unroll
         for (int c = 0; c < KSTEPS; ++c) {
-            kf[s][c] = to_f16(*reinterpret_cast<const bf16x8 *>(K + krow[s] + 32 * c + 8 * q4), 1.0f);
+            kf[s][c] = *reinterpret_cast<const bf16x8 *>(K + krow[s] + 32 * c + 8 * q4);
             if (WHICH == 1) vf[s][c] = *reinterpret_cast<const bf16x8 *>(V + krow[s] + 32 * c + 8 * q4);
         }
     }
+    const float c2 = BWD_LOG2E / sqrtf((float)D);  // softmax scale in base 2
 
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)smem);
     const size_t head_tiles = (size_t)kv * g.N * tpcr;
@@ -554,9 +545,9 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
                 f32x4 sacc[NS][2], pacc[NS][2];
                 const int rb = 32 * H + 8 * q4;  // the lane's eight rows of this half: rb .. rb + 7
                 const uint32_t bits = (uint32_t)(cm >> rb);  // their selection bits
-                // What the products start from: minus the row's log-sum-exp (the streamed Q carries the softmax
-                // scale, so the scores then come out as the exponents of the probabilities), -inf for a row that did
-                // not select this key cube (probabilities 0); and minus the row's delta for dP.
+                // What the products start from: -lse * sqrt(D) of the row (times the softmax scale in base 2 the
+                // accumulator is then the exponent of the probability), -inf for a row that did not select this key
+                // cube (probabilities 0); and minus the row's delta for dP.
                 f32x4 sinit[2], pinit[2];
 #pragma unroll
                 for (int k2 = 0; k2 < 2; ++k2) {
@@ -589,7 +580,7 @@ __global__ __launch_bounds__(BWD_THREADS) void attn_bwd_dkv_kernel(Geom g, const
                     for (int v = 0; v < 4; ++v)
 #pragma unroll
                         for (int s = 0; s < NS; ++s) {
-                            const float p = __builtin_amdgcn_exp2f(sacc[s][k2][v]);
+                            const float p = __builtin_amdgcn_exp2f(sacc[s][k2][v] * c2);
                             pf[s][H][4 * k2 + v] = (__bf16)(WHICH == 1 ? p * pacc[s][k2][v] : p);
                         }
             };
@@ -625,9 +616,9 @@ static hipError_t launch_bwd_d(const Geom &g, const uint16_t *Q, const uint16_t 
                                uint16_t *dQ, uint16_t *dK, uint16_t *dV, void *ws, hipStream_t st)
 {
     const BwdWorkspace w = bwd_workspace(g, ws);
-    hipError_t e = launch_kv_pack(g, K, V, w.packA, true, st);   // natural K as fp16: the score operand
+    hipError_t e = launch_kv_pack(g, K, V, w.packA, false, st);  // natural K as it is: exact score products
     if (e != hipSuccess) return e;
-    e = launch_kv_pack(g, V, K, w.packB, false, st);             // natural V stays bf16
+    e = launch_kv_pack(g, V, K, w.packB, false, st);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((bwd_pack_rows_kernel<D>), dim3(w.tpcr, g.N, g.Hkv), dim3(256), 0, st, g, Q, dO, O, lse, w.tpcr,
                        w.Qn, w.Qt, w.dOn, w.dOt, w.lse2, w.delta);
