@@ -682,7 +682,27 @@ def _large_key_workloads():
             synth.Workload("L221", 221, 5, 7, 7, 1, 1, 1, 3, 3, 64, (0.6,), (3.0, 3.0, 3.0), 37, 0)]
 
 
-@pytest.mark.parametrize("w", _random_workloads(16, 2604) + _large_key_workloads(), ids=lambda w: f"{w.name}-{w.T}x{w.H}x{w.W}-c{w.ct}x{w.ch}x{w.cw}-h{w.Hq}/{w.Hkv}-d{w.D}-t{w.text}-l{w.lead}")
+def _random_mid_workloads(count, seed):
+    """Seeded mid-sized geometries: tens to hundreds of cubes (past 256: the wide selection kernel), cubes of up to
+    256 tokens (several key tiles), up to a few tens of thousands of rows."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        T, H, W = int(rng.integers(4, 41)), int(rng.integers(3, 13)), int(rng.integers(3, 13))
+        ct, ch, cw = int(rng.integers(1, 5)), int(rng.integers(1, min(H, 8) + 1)), int(rng.integers(1, min(W, 8) + 1))
+        hkv, grp, D = int(rng.choice([1, 2, 4])), int(rng.choice([1, 2, 7])), int(rng.choice([64, 128]))
+        text = int(rng.choice([0, int(rng.integers(1, 300))]))
+        lead = int(rng.choice([0, int(rng.integers(1, 200))]))
+        p, scale = float(rng.choice([0.3, 0.6, 0.9])), float(rng.choice([0.0, 1.0, 3.0]))
+        cubes = -(-T // ct) * -(-H // ch) * -(-W // cw)
+        if cubes > 700 or T * H * W * hkv * grp > 40000:
+            continue
+        out.append(synth.Workload(f"M{len(out)}", 300 + len(out), T, H, W, ct, ch, cw, hkv * grp, hkv, D, (p,), (scale,) * hkv,
+                                  text, lead))
+    return out
+
+
+@pytest.mark.parametrize("w", _random_workloads(48, 2604) + _large_key_workloads() + _random_mid_workloads(6, 5), ids=lambda w: f"{w.name}-{w.T}x{w.H}x{w.W}-c{w.ct}x{w.ch}x{w.cw}-h{w.Hq}/{w.Hkv}-d{w.D}-t{w.text}-l{w.lead}")
 def test_random_small_geometries(B, oracle, w):
     """Seeded random grids, cube shapes (down to single-token cubes), head groupings and text spans: selection,
     sparse attention through every kernel that takes the geometry, the backward pass and the token-selective FFN,
